@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the embedding-cache step on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic minibatch: het_lookup (dedup, probe,
+stale refresh, miss fill, gather) followed by het_update (dedup, gradient coalescing, optimizer
+apply with clock increment, policy trim with write-back).  The workload is configuration 2
+(1M ids, dim 64, 4096 x 26 lookups per batch, Zipf 1.05, LFU cache of 100k rows, s = 100,
+Adagrad, backing table in HBM).  Inputs are resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+
+Prints one JSON line: lookups+updates per second, plus the roofline position of the dominant
+kernel (timed with HIP events inside this script) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(w, c):
+    """HBM bytes one step must move, from device counters `c` (per-step averages):
+    ids read twice, out written, cached rows read for the gather, grads read, apply read+write
+    of value (+accumulator), both ends of every fill / refresh / write-back, keys-clocks-policy
+    metadata and the victim scan."""
+    R = 4 * w.dim
+    Q = 2 if w.optimizer else 1
+    n, U = w.n, c["unique_lookup"]
+    rows_io = w.n_grad_rows * R
+    moved = c["miss"] + c["stale_dirty"] + c["evicted_dirty"]
+    P = w.capacity + w.n
+    return (16 * n + rows_io + U * R + rows_io + 2 * U * Q * R + 2 * moved * Q * R + 32 * U + 8 * P)
+
+
+def kernel_bytes(w, c, name):
+    """Algorithmic bytes of one launch of the kernels the roofline line may name."""
+    R = 4 * w.dim
+    Q = 2 if w.optimizer else 1
+    U = c["unique_lookup"]
+    if name == "apply_kernel":      # grads read, value (+accumulator) read and written, index arrays
+        return w.n_grad_rows * R + 2 * U * Q * R + 4 * w.n + 12 * U
+    if name == "gather_kernel":     # cached rows read once per key, out written, index arrays
+        return U * R + w.n * R + 8 * w.n + 4 * U
+    if name == "pooled_gather_kernel":
+        return U * R + w.batch * R + 4 * w.n + 4 * U
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=900)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--profile-steps", type=int, default=50)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2112_07221_amd import hetcache as hc
+    from paper_2112_07221_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.config]
+    dev = torch.device("cuda:0")
+    K, W = args.steps, args.warmup
+    total = W + K + args.profile_steps
+
+    # ---- inputs, staged on the device before anything is timed
+    table = wl.table_init(w)
+    ids_np = wl.IdStream(w).batches(total)
+    grads_np = wl.grad_pool(w)
+    ids = torch.from_numpy(ids_np).to(dev)
+    grads = torch.from_numpy(grads_np).to(dev)
+    host = w.backing == "host"
+    if host:
+        Wt = torch.from_numpy(table).pin_memory()
+        At = torch.zeros_like(Wt).pin_memory() if w.optimizer else None
+        Cg = torch.zeros(w.vocab, dtype=torch.int32).pin_memory()
+    else:
+        Wt = torch.from_numpy(table).to(dev)
+        At = torch.zeros_like(Wt) if w.optimizer else None
+        Cg = torch.zeros(w.vocab, dtype=torch.int32, device=dev)
+    offsets = torch.from_numpy(wl.bag_offsets(w)).to(dev) if w.pooled else None
+    out = torch.empty(w.n_grad_rows, w.dim, device=dev)
+
+    cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps)
+    cache.attach_backing(Wt, At, Cg, hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
+
+    def step(t):
+        if w.pooled:
+            cache.lookup_pooled(ids[t], offsets, out)
+            cache.update_pooled(ids[t], offsets, grads[t % w.grad_pool], w.lr)
+        else:
+            cache.lookup(ids[t], out)
+            cache.update(ids[t], grads[t % w.grad_pool], w.lr)
+
+    # ---- warm-up (cold cache), then the timed region
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(W):
+        step(t)
+    torch.cuda.synchronize()
+    warm_ms = (time.perf_counter() - t0) * 1e3 / max(W, 1)
+    before = cache.stats()["total"]
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    e0.record()
+    for t in range(W, W + K):
+        step(t)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - wall0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = max(gpu_ms, wall_ms) / K
+    after = cache.stats()
+    assert after["error_bits"] == 0, "device error bits set during the run"
+    tot = after["total"]
+    per_step = {k: (tot[k] - before[k]) / K for k in tot}
+    per_step["unique_lookup"] = per_step["unique"] / 2.0      # counted by lookup and by update
+
+    # ---- per-kernel durations, HIP events around every launch (outside the timed region)
+    cache.profile_begin()
+    for t in range(W + K, total):
+        step(t)
+    prof = cache.profile_end()
+    kern = {k: {"avg_us": ms * 1e3 / cnt, "launches_per_step": cnt / args.profile_steps}
+            for k, (ms, cnt) in prof.items()}
+    per_step_us = {k: v["avg_us"] * v["launches_per_step"] for k, v in kern.items()}
+    candidates = [k for k in per_step_us if kernel_bytes(w, per_step, k) is not None]
+    dominant = max(candidates, key=lambda k: per_step_us[k])
+    dom_bytes = kernel_bytes(w, per_step, dominant)
+    achieved = dom_bytes / (kern[dominant]["avg_us"] * 1e-6) / 1e9
+    step_bytes = algorithmic_bytes(w, per_step)
+
+    result = {
+        "metric": "embedding lookups+updates/sec and achieved HBM GB/s (% peak), 1 MI355X",
+        "value": 2.0 * w.n / (ms_per_step * 1e-3),
+        "unit": "lookups+updates/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {w.index} ({w.name}): vocab {w.vocab}, dim {w.dim}, "
+                               f"{w.batch}x{w.width} ids/batch, Zipf {w.alpha}, cache {w.capacity} "
+                               f"{'LFU' if w.policy else 'LRU'}, s={w.s}, "
+                               f"{'Adagrad' if w.optimizer else 'SGD'}, backing {w.backing}",
+                   "ids_per_step": w.n, "unique_per_step": per_step["unique_lookup"],
+                   "miss_per_step": per_step["miss"], "stale_per_step": per_step["stale"],
+                   "evicted_dirty_per_step": per_step["evicted_dirty"],
+                   "warmup_ms_per_step": warm_ms},
+        "step_hbm": {"algorithmic_bytes": step_bytes,
+                     "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                     "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "bytes_per_launch": dom_bytes, "avg_us": kern[dominant]["avg_us"]},
+        "kernels_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda x: -x[1])},
+    }
+    if host:
+        link = (per_step["miss"] + per_step["stale_dirty"] + per_step["evicted_dirty"]) * 4 * w.dim \
+            * (2 if w.optimizer else 1)
+        result["host_link"] = {"bytes_per_step": link, "achieved_GBps": link / (ms_per_step * 1e-3) / 1e9}
+
+    # ---- CPU oracle on a bounded sample of the same stream (reported baseline, not a target)
+    if not args.no_cpu_baseline:
+        from oracle.het_oracle import Oracle
+        o = Oracle(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps, table)
+        offs = wl.bag_offsets(w) if w.pooled else None
+        n_cpu = args.cpu_iters or min(total, 200)
+        budget_s = 20.0
+        done = 0
+        c0 = time.perf_counter()
+        for t in range(n_cpu):
+            if w.pooled:
+                o.lookup_pooled(ids_np[t], offs)
+                o.update_pooled(ids_np[t], offs, grads_np[t % w.grad_pool], w.lr)
+            else:
+                o.lookup(ids_np[t])
+                o.update(ids_np[t], grads_np[t % w.grad_pool], w.lr)
+            done += 1
+            if time.perf_counter() - c0 > budget_s:
+                break
+        cpu_s = time.perf_counter() - c0
+        result["cpu_baseline"] = {
+            "value": 2.0 * w.n * done / cpu_s, "unit": "lookups+updates/s", "cores": 1,
+            "kind": "oracle",
+            "sample": f"first {done} iterations of the same stream from a cold cache, fp64 oracle, "
+                      f"{cpu_s:.1f} s on one host core (of {os.cpu_count()} visible)"}
+    cache.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

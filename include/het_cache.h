@@ -1,0 +1,195 @@
+/*
+ * het_cache.h - C ABI of the MI355X embedding-cache step.
+ *
+ * One cache object serves one worker's share of a huge embedding table: the global
+ * ("server") table stays in a backing store, a bounded number of rows is cached in HBM, and
+ * every cached row carries a start clock c_s and a local clock c_c next to the global clock
+ * c_g of its global row (HET, arXiv 2112.07221, Section 3.1).  het_lookup is the client's
+ * Read (Algorithm 2) on the unique key set of a minibatch (Algorithm 1), het_update is its
+ * Write (Algorithm 3), including the policy-driven Evict() of the overflow (Section 3.1,
+ * Section 4.3).  All steps run in HIP kernels on the configured stream.
+ *
+ * Conventions
+ *   - Every function returns an int status: HET_OK (0) or a negative het_status.
+ *   - "device" pointers are HIP device allocations of the current device, owned by the caller
+ *     and only borrowed for the duration stated; "host" pointers are ordinary host memory.
+ *   - het_lookup* / het_update* only enqueue work on the configured stream and return; their
+ *     results are valid in stream order.  het_flush, het_stats, het_export_*, het_last_* and
+ *     het_cache_destroy wait for the stream.
+ *   - Errors the host can see (NULL, sizes out of range, wrong call order) are returned at
+ *     once and change nothing.  Errors only the device can see (an id outside [0, vocab), an
+ *     update of an id that is not cached) set a sticky bit that the next waiting call returns
+ *     (HET_ERANGE / HET_ESTATE) and het_stats reports; the offending ids are skipped (their
+ *     lookup rows are zero).  het_clear_error resets the bits.
+ *   - The library allocates device memory only in het_cache_configure / het_attach_backing and
+ *     frees it in het_cache_destroy; lookup/update/flush allocate nothing.
+ *   - A cache object is not thread-safe; use it from one host thread at a time.
+ */
+#ifndef HET_CACHE_H
+#define HET_CACHE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct het_cache het_cache;
+
+typedef enum het_status {
+    HET_OK = 0,
+    HET_EINVAL = -1,  /* bad argument or call order; nothing was done */
+    HET_ENOMEM = -2,  /* a device or host allocation failed */
+    HET_EHIP = -3,    /* a HIP runtime call failed */
+    HET_ERANGE = -4,  /* sticky: some id was outside [0, vocab) */
+    HET_ESTATE = -5   /* sticky: het_update saw an id that is not cached (no het_lookup before) */
+} het_status;
+
+enum { HET_POLICY_LRU = 0, HET_POLICY_LFU = 1 };       /* Section 4.3 */
+enum { HET_OPT_SGD = 0, HET_OPT_ADAGRAD = 1 };
+enum { HET_BACKING_HBM = 0, HET_BACKING_PINNED_HOST = 1 };
+enum { HET_CLASS_HIT = 0, HET_CLASS_STALE = 1, HET_CLASS_MISS = 2 };
+#define HET_S_INFINITE INT64_MAX /* staleness bound that never invalidates a row */
+
+/* Counters of the most recent lookup/update/flush call and running totals since creation. */
+typedef struct het_counters {
+    int64_t n;             /* ids passed in */
+    int64_t unique;        /* distinct valid ids (size of the key set K) */
+    int64_t hit;           /* keys found valid in the cache */
+    int64_t stale;         /* keys found but failing CheckValid: synchronised in place */
+    int64_t miss;          /* keys fetched from the backing store into a new slot */
+    int64_t evicted;       /* rows dropped by the policy trim */
+    int64_t evicted_dirty; /* ... of which were written back (c_c > c_s) */
+    int64_t stale_dirty;   /* stale rows written back before their refresh */
+    int64_t flushed;       /* rows written back by het_flush */
+} het_counters;
+
+typedef struct het_stats_t {
+    het_counters last;
+    het_counters total;
+    int64_t resident;      /* rows in the cache now */
+    int64_t iteration;     /* number of non-empty lookups so far (the LRU time stamp) */
+    int32_t error_bits;    /* 1: id out of range, 2: update of an id that is not cached */
+} het_stats_t;
+
+/*
+ * Creates an empty cache for `capacity` rows of `dim` floats with staleness bound `s`
+ * (CheckValid, Section 3.1: a cached row is valid iff c_c <= c_s + s and c_g <= c_c + s) and
+ * eviction `policy`.  s may be HET_S_INFINITE.  No device memory is taken yet.
+ * HET_EINVAL: out == NULL, capacity <= 0, dim <= 0, s < 0, unknown policy.
+ */
+int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, int32_t policy);
+
+/*
+ * Fixes the largest number of ids one call may carry, the optimizer het_update applies and the
+ * HIP stream (a hipStream_t, NULL = the default stream) all work is enqueued on, and allocates
+ * the cache in HBM: capacity + max_batch_ids row slots (rows fetched on a miss are added beyond
+ * the capacity and the overflow is trimmed at the end of the update, Algorithm 2 / 3), the
+ * id->slot hash table and the per-call workspaces.  Must be called once, before attach.
+ * eps is Adagrad's epsilon (ignored for SGD).
+ */
+int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps,
+                        void *hip_stream);
+
+/*
+ * Names the global embedding table this cache fronts (Section 3.1):
+ *   table  float[vocab][dim], row-major: the global rows;
+ *   state  float[vocab][dim]: Adagrad accumulators, travelling with the rows (NULL for SGD);
+ *   cg     uint32[vocab]: global clock c_g per row, zero-initialised by the caller.
+ * location HET_BACKING_HBM: device pointers.  HET_BACKING_PINNED_HOST: pointers to pinned,
+ * device-mapped host memory (hipHostMalloc); kernels read and write it over the host link.
+ * The caller owns the arrays; the library reads and writes them during lookup/update/flush and
+ * they must outlive the cache.  vocab must be below 2^32 - 1.
+ */
+int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, int64_t vocab,
+                       int32_t location);
+
+/*
+ * Read (Algorithm 2) of the unique keys of ids[n] (device, int64), then out[i][:] = cached row
+ * of ids[i] (device, float[n][dim], row-major).  Keys not cached are fetched from the backing
+ * store into the smallest free slots in ascending key order with c_s = c_c = c_g (Fetch); keys
+ * cached but invalid are written back if they hold updates (Evict: c_g = max(c_g, c_c)) and
+ * refreshed in place; every key of the batch counts as one use for LRU/LFU.  n == 0 is a
+ * complete no-op.  n > max_batch_ids: HET_EINVAL.  If the previous call was also a lookup, the
+ * overflow it left is trimmed first.
+ */
+int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out);
+
+/*
+ * Pooled Read for multi-hot inputs: bag b holds ids[offsets[b] .. offsets[b+1]) and
+ * out[b][:] = sum of its rows, added in bag order in fp32 (device, float[n_bags][dim]).
+ * offsets: device, int64[n_bags + 1], non-decreasing, offsets[0] = 0, offsets[n_bags] = n.
+ */
+int het_lookup_pooled(het_cache *c, const int64_t *ids, int64_t n, const int64_t *offsets,
+                      int64_t n_bags, float *out);
+
+/*
+ * Write (Algorithm 3) for the ids of the preceding lookup: per unique key k the gradients
+ * grads[i][:] (device, float[n][dim]) of all positions i with ids[i] == k are summed in order
+ * of increasing i, the optimizer step is applied to the cached row
+ *   SGD      x -= lr * G
+ *   Adagrad  a += G*G;  x -= lr * G / (sqrt(a) + eps)
+ * and c_c grows by one (once per key per call).  Then Evict(): while more than `capacity` rows
+ * are cached, the rows smallest in (last_use, slot) for LRU or (freq, last_use, slot) for LFU
+ * are dropped, those with c_c > c_s being written back first (c_g = max(c_g, c_c)).
+ */
+int het_update(het_cache *c, const int64_t *ids, const float *grads, int64_t n, float lr);
+
+/* Pooled Write: the gradient of every position of bag b is bag_grads[b][:] (device,
+ * float[n_bags][dim]); ids/offsets as in het_lookup_pooled. */
+int het_update_pooled(het_cache *c, const int64_t *ids, int64_t n, const int64_t *offsets,
+                      const float *bag_grads, int64_t n_bags, float lr);
+
+/*
+ * Writes every cached row that holds updates back to the backing store (as Evict does) and
+ * marks it clean (c_s = c_c = c_g); rows stay cached.  Afterwards the backing store alone holds
+ * the trained table.  (The paper lets updates left in the cache at the end of training be
+ * dropped, Section 3.3; this call keeps them instead.)  Waits for the stream.
+ */
+int het_flush(het_cache *c);
+
+/* Waits for the stream and fills *out (host). */
+int het_stats(het_cache *c, het_stats_t *out);
+
+/* Resets the sticky device error bits. */
+int het_clear_error(het_cache *c);
+
+/*
+ * Parity helpers (wait for the stream; all pointers are host memory; any may be NULL).
+ * het_export_state: the cached rows in ascending slot order; arrays need room for
+ *   capacity + max_batch_ids entries; *n_resident receives the count.
+ * het_export_rows: their values (and Adagrad accumulators), float[n_resident][dim], same order.
+ * het_last_lookup: the sorted unique keys of the last lookup with class (HET_CLASS_*) and slot;
+ *   arrays need room for max_batch_ids entries.
+ * het_last_evicted: the ids dropped by the most recent trim, in no particular order; room for
+ *   capacity + max_batch_ids entries.
+ */
+int het_export_state(het_cache *c, int64_t *keys, int32_t *slots, uint32_t *cs, uint32_t *cc,
+                     uint32_t *last_use, uint32_t *freq, int64_t *n_resident);
+int het_export_rows(het_cache *c, float *rows, float *acc);
+int het_last_lookup(het_cache *c, int64_t *keys, int32_t *cls, int32_t *slots, int64_t *n_unique);
+int het_last_evicted(het_cache *c, int64_t *ids, int64_t *n);
+
+/*
+ * Per-kernel timing for benchmarks.  Between het_profile_begin and het_profile_end every kernel
+ * the library launches for this cache is bracketed by a pair of HIP events on the cache's
+ * stream (this slows the calls down slightly and creates events: not for timed regions).
+ * het_profile_end waits for the stream and adds up, per kernel index, the elapsed milliseconds
+ * into total_ms[n_kernels] and the launch count into launches[n_kernels] (host arrays).
+ * het_profile_kernel_count / het_profile_kernel_name give the index space.
+ */
+int het_profile_begin(het_cache *c);
+int het_profile_end(het_cache *c, double *total_ms, int64_t *launches, int32_t n_kernels);
+int het_profile_kernel_count(void);
+const char *het_profile_kernel_name(int index);
+
+/* Waits for the stream, frees everything the library allocated.  NULL is allowed. */
+int het_cache_destroy(het_cache *c);
+
+/* Static description of a status code. */
+const char *het_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HET_CACHE_H */

@@ -1,0 +1,574 @@
+// Host side of the C ABI declared in include/het_cache.h: argument checks, device memory
+// owned by the cache, and the kernel sequence of each call.  No step of the method runs on the
+// host; the host only decides launch shapes from sizes it already knows (n, max_batch_ids,
+// capacity) and never waits for the device inside het_lookup / het_update.
+#include "../../include/het_cache.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "cache_kernels.hpp"
+
+using namespace het;
+
+// Kernels of the path, as named in profiles and by het_profile_kernel_name.
+enum KernelId {
+    K_SORT_COUNT, K_SORT_SCAN, K_SORT_SCATTER, K_UNIQUE_COUNT, K_RANK_PROBE, K_FILL, K_GATHER, K_INVERT,
+    K_POOLED_GATHER, K_BAG_OF, K_APPLY, K_TRIM_BEGIN, K_TRIM_HIST, K_TRIM_COUNT, K_TRIM_EVICT, K_TRIM_FREE,
+    K_FLUSH, K_MISC, K_NUM
+};
+static const char *const kKernelNames[K_NUM] = {
+    "sort_count_kernel", "sort_scan_kernel", "sort_scatter_kernel", "unique_count_kernel", "rank_probe_kernel",
+    "fill_kernel", "gather_kernel", "invert_kernel", "pooled_gather_kernel", "bag_of_kernel", "apply_kernel",
+    "trim_begin_kernel", "trim_hist_kernel", "trim_count_kernel", "trim_evict_kernel", "trim_free_kernel",
+    "flush_kernel", "misc"};
+
+struct ProfSpan { int id; hipEvent_t start, stop; };
+
+struct het_cache {
+    // creation parameters
+    int64_t capacity = 0, s = 0;
+    int32_t dim = 0, policy = 0;
+    // configuration
+    bool configured = false, attached = false;
+    int64_t max_ids = 0;
+    int32_t optimizer = 0;
+    float eps = 0.f;
+    hipStream_t stream = nullptr;
+    int location = 0;
+    // device state
+    CacheView cv{};
+    Workspace ws{};
+    TrimPlan tp{};
+    uint32_t *keys_a = nullptr, *keys_b = nullptr, *idx_a = nullptr, *idx_b = nullptr;
+    uint32_t *tile_hist = nullptr;
+    uint32_t *bag_of = nullptr;
+    uint32_t n_buckets = 0;
+    std::vector<void *> owned;       // every device allocation, for destroy
+    // host-side bookkeeping
+    uint64_t t_host = 0;             // non-empty lookups so far (equals the device's t)
+    bool overflow_pending = false;   // a lookup ran and no trim since
+    uint32_t last_lookup_n = 0;
+    // optional per-kernel timing (het_profile_begin / het_profile_end)
+    bool profiling = false;
+    std::vector<ProfSpan> spans;
+};
+
+namespace {
+
+// With HET_DEBUG set in the environment, a failing HIP call is named on stderr.
+void report(const char *what, hipError_t e)
+{
+    if (std::getenv("HET_DEBUG")) std::fprintf(stderr, "[het_cache] %s: %s\n", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) { report(#expr, e_); return HET_EHIP; } \
+    } while (0)
+
+template <typename T>
+int dev_alloc(het_cache *c, T **p, size_t count)
+{
+    void *q = nullptr;
+    const hipError_t e = hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T));
+    if (e != hipSuccess) { report("hipMalloc", e); return HET_ENOMEM; }
+    c->owned.push_back(q);
+    *p = static_cast<T *>(q);
+    return HET_OK;
+}
+
+inline uint32_t cdiv(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
+
+inline int bit_width(uint64_t v)
+{
+    int b = 0;
+    while (v) { ++b; v >>= 1; }
+    return b;
+}
+
+inline uint32_t pow2_at_least(uint64_t v)
+{
+    uint64_t p = 1;
+    while (p < v) p <<= 1;
+    return (uint32_t)p;
+}
+
+int status_from_bits(uint32_t bits)
+{
+    if (bits & ERRBIT_INTERNAL) return HET_EHIP;
+    if (bits & ERRBIT_RANGE) return HET_ERANGE;
+    if (bits & ERRBIT_STATE) return HET_ESTATE;
+    return HET_OK;
+}
+
+// While profiling, every launch is bracketed by a pair of events on the cache's stream.
+struct LaunchScope {
+    het_cache *c;
+    ProfSpan sp{};
+    bool on;
+    LaunchScope(het_cache *cache, int id) : c(cache), on(cache->profiling)
+    {
+        if (!on) return;
+        sp.id = id;
+        if (hipEventCreate(&sp.start) != hipSuccess || hipEventCreate(&sp.stop) != hipSuccess) { on = false; return; }
+        (void)hipEventRecord(sp.start, c->stream);
+    }
+    ~LaunchScope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(sp.stop, c->stream);
+        c->spans.push_back(sp);
+    }
+};
+#define LAUNCH(cache, id, ...)            \
+    do {                                  \
+        LaunchScope scope_(cache, id);    \
+        __VA_ARGS__;                      \
+    } while (0)
+
+int launch_ok()
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { report("kernel launch", e); return HET_EHIP; }
+    return HET_OK;
+}
+
+// Groups of `lanes` threads work on one row; how many 256-thread blocks for `items` rows.
+uint32_t row_grid(const RowGeom &g, uint64_t items)
+{
+    const uint32_t per_block = 256u / (uint32_t)g.lanes;
+    return std::max(1u, std::min(cdiv(items, per_block), 256u * 16u));
+}
+
+// Sort + unique of ids[n]: leaves ws.skey / ws.perm / ws.rank / ws.ukey / ws.seg / ws.uslot and,
+// for a lookup, the classes and the staged miss / stale lists.
+template <bool LOOKUP>
+int dedup_and_probe(het_cache *c, const int64_t *ids, uint32_t n, bool reset_last = true)
+{
+    const uint32_t vocab = c->cv.vocab;
+    const int bits = bit_width(vocab);                 // the key `vocab` itself marks a bad id
+    const int passes = std::max(1, (bits + RADIX_BITS - 1) / RADIX_BITS);
+    const uint32_t ntiles = cdiv(n, SORT_TILE);
+    uint32_t *kin = c->keys_a, *kout = c->keys_b, *iin = c->idx_a, *iout = c->idx_b;
+    for (int p = 0; p < passes; ++p) {
+        const uint32_t shift = (uint32_t)(p * RADIX_BITS);
+        if (p == 0) {
+            LAUNCH(c, K_SORT_COUNT, sort_count_kernel<true><<<ntiles, SORT_THREADS, 0, c->stream>>>(ids, nullptr, kin, n, vocab, shift,
+                                                                            c->tile_hist, ntiles, c->cv.ds,
+                                                                            (LOOKUP ? CALL_BUMP_ITERATION : 0) | (reset_last ? CALL_RESET_LAST : 0)));
+        } else {
+            LAUNCH(c, K_SORT_COUNT, sort_count_kernel<false><<<ntiles, SORT_THREADS, 0, c->stream>>>(nullptr, kin, nullptr, n, vocab, shift,
+                                                                             c->tile_hist, ntiles, c->cv.ds, 0));
+        }
+        LAUNCH(c, K_SORT_SCAN, sort_scan_kernel<<<1, SCAN_THREADS, 0, c->stream>>>(c->tile_hist, ntiles * RADIX));
+        if (p == 0)
+            LAUNCH(c, K_SORT_SCATTER, sort_scatter_kernel<true><<<ntiles, SORT_THREADS, 0, c->stream>>>(kin, nullptr, kout, iout, n, shift, c->tile_hist, ntiles));
+        else
+            LAUNCH(c, K_SORT_SCATTER, sort_scatter_kernel<false><<<ntiles, SORT_THREADS, 0, c->stream>>>(kin, iin, kout, iout, n, shift, c->tile_hist, ntiles));
+        std::swap(kin, kout);
+        std::swap(iin, iout);
+    }
+    c->ws.skey = kin;      // after the last swap the inputs of a further pass are the result
+    c->ws.perm = iin;
+    const uint32_t utiles = cdiv(n, UQ_TILE);
+    LAUNCH(c, K_UNIQUE_COUNT, unique_count_kernel<<<utiles, UQ_THREADS, 0, c->stream>>>(c->ws.skey, n, vocab, c->ws.tile_heads));
+    LAUNCH(c, K_RANK_PROBE, rank_probe_kernel<LOOKUP><<<utiles, UQ_THREADS, 0, c->stream>>>(c->cv, c->ws, n));
+    return launch_ok();
+}
+
+template <int VEC>
+int run_trim(het_cache *c)
+{
+    TrimPlan tp = c->tp;
+    tp.lfu = c->policy == HET_POLICY_LFU;
+    tp.bits = std::max(1, bit_width(c->t_host));
+    tp.key_bits = tp.lfu ? 2 * tp.bits : tp.bits;
+    tp.passes = (tp.key_bits + SEL_BITS - 1) / SEL_BITS;
+    const uint32_t stiles = cdiv(c->cv.n_slots, TRIM_TILE);
+    const uint32_t hist_blocks = std::min(stiles, 1024u);
+    LAUNCH(c, K_TRIM_BEGIN, trim_begin_kernel<<<4, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    for (int p = 0; p < tp.passes; ++p) LAUNCH(c, K_TRIM_HIST, trim_hist_kernel<<<hist_blocks, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, p));
+    LAUNCH(c, K_TRIM_COUNT, trim_count_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC><<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    LAUNCH(c, K_TRIM_FREE, trim_free_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    c->overflow_pending = false;
+    return launch_ok();
+}
+
+template <int VEC>
+int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offsets, uint32_t n_bags, float *out)
+{
+    c->t_host += 1;
+    int rc;
+    const bool pre_trim = c->overflow_pending;                  // a Read that follows a Read
+    if (pre_trim) {
+        LAUNCH(c, K_MISC, reset_last_kernel<<<1, 64, 0, c->stream>>>(c->cv.ds));
+        if ((rc = run_trim<VEC>(c)) != HET_OK) return rc;
+    }
+    if ((rc = dedup_and_probe<true>(c, ids, n, !pre_trim)) != HET_OK) return rc;
+    const uint32_t utiles = cdiv(n, UQ_TILE);
+    LAUNCH(c, K_FILL, fill_kernel<VEC><<<utiles, UQ_THREADS, 0, c->stream>>>(c->cv, c->ws));
+    if (!offsets) {
+        LAUNCH(c, K_GATHER, gather_kernel<VEC><<<row_grid(c->cv.geom, n), 256, 0, c->stream>>>(c->cv, c->ws, n, out));
+    } else {
+        LAUNCH(c, K_INVERT, invert_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n));
+        LAUNCH(c, K_POOLED_GATHER, pooled_gather_kernel<VEC><<<row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(c->cv, c->ws, offsets, n, n_bags, out));
+    }
+    c->overflow_pending = true;
+    c->last_lookup_n = n;
+    return launch_ok();
+}
+
+template <int VEC>
+int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offsets, uint32_t n_bags,
+               const float *grads, float lr)
+{
+    int rc;
+    if ((rc = dedup_and_probe<false>(c, ids, n)) != HET_OK) return rc;
+    const uint32_t *grad_row = nullptr;
+    if (offsets) {
+        LAUNCH(c, K_BAG_OF, bag_of_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(offsets, n, n_bags, c->bag_of));
+        grad_row = c->bag_of;
+    }
+    LAUNCH(c, K_APPLY, apply_kernel<VEC><<<row_grid(c->cv.geom, n), 256, 0, c->stream>>>(c->cv, c->ws, grads, grad_row, lr, c->eps));
+    if ((rc = launch_ok()) != HET_OK) return rc;
+    return run_trim<VEC>(c);
+}
+
+int sync_and_status(het_cache *c, DState *host_copy)
+{
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    DState h;
+    HIP_TRY(hipMemcpy(&h, c->cv.ds, sizeof(DState), hipMemcpyDeviceToHost));
+    if (host_copy) *host_copy = h;
+    return status_from_bits(h.err);
+}
+
+void to_public(const Counters &in, het_counters *out)
+{
+    out->n = (int64_t)in.n; out->unique = (int64_t)in.unique; out->hit = (int64_t)in.hit;
+    out->stale = (int64_t)in.stale; out->miss = (int64_t)in.miss; out->evicted = (int64_t)in.evicted;
+    out->evicted_dirty = (int64_t)in.evicted_dirty; out->stale_dirty = (int64_t)in.stale_dirty;
+    out->flushed = (int64_t)in.flushed;
+}
+
+bool ready(const het_cache *c) { return c && c->configured && c->attached; }
+
+} // namespace
+
+extern "C" {
+
+int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, int32_t policy)
+{
+    if (!out || capacity <= 0 || dim <= 0 || s < 0) return HET_EINVAL;
+    if (policy != HET_POLICY_LRU && policy != HET_POLICY_LFU) return HET_EINVAL;
+    if (capacity >= (1ll << 30) || dim > (1 << 20)) return HET_EINVAL;
+    het_cache *c = new (std::nothrow) het_cache();
+    if (!c) return HET_ENOMEM;
+    c->capacity = capacity; c->dim = dim; c->s = s; c->policy = policy;
+    *out = c;
+    return HET_OK;
+}
+
+int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps, void *hip_stream)
+{
+    if (!c || c->configured || max_batch_ids <= 0 || max_batch_ids >= (1ll << 30)) return HET_EINVAL;
+    if (optimizer != HET_OPT_SGD && optimizer != HET_OPT_ADAGRAD) return HET_EINVAL;
+    if (!(eps >= 0.f)) return HET_EINVAL;
+    c->max_ids = max_batch_ids; c->optimizer = optimizer; c->eps = eps;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+
+    CacheView &cv = c->cv;
+    const uint64_t P = (uint64_t)c->capacity + (uint64_t)max_batch_ids;
+    cv.n_slots = (uint32_t)P; cv.capacity = (uint32_t)c->capacity; cv.max_ids = (uint32_t)max_batch_ids;
+    cv.s = c->s; cv.adagrad = optimizer == HET_OPT_ADAGRAD;
+    RowGeom g;
+    g.dim = c->dim; g.vec = (c->dim % 4 == 0) ? 4 : 1; g.chunks = c->dim / g.vec;
+    g.lanes = (int)std::min<uint32_t>(64u, pow2_at_least((uint64_t)g.chunks));
+    cv.geom = g;
+
+    int rc = HET_OK;
+    const size_t row_elems = (size_t)P * (size_t)c->dim;
+    if ((rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
+    if (cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
+    if ((rc = dev_alloc(c, &cv.slot_key, P)) || (rc = dev_alloc(c, &cv.cs, P)) || (rc = dev_alloc(c, &cv.cc, P)) ||
+        (rc = dev_alloc(c, &cv.last_use, P)) || (rc = dev_alloc(c, &cv.freq, P)))
+        return rc;
+    if ((rc = dev_alloc(c, &cv.free_list, (size_t)max_batch_ids))) return rc;
+    if ((rc = dev_alloc(c, &cv.ds, 1))) return rc;
+    // hash table: at most a quarter of the entries are ever used
+    c->n_buckets = pow2_at_least(std::max<uint64_t>(1, cdiv(P * 4, BUCKET_ENTRIES)));
+    cv.ht.bucket_mask = c->n_buckets - 1;
+    cv.ht.shift = 32u - (uint32_t)(bit_width(c->n_buckets) - 1);
+    if ((rc = dev_alloc(c, &cv.ht.entries, (size_t)c->n_buckets * BUCKET_ENTRIES)) ||
+        (rc = dev_alloc(c, &cv.ht.reach, c->n_buckets)))
+        return rc;
+
+    // workspaces
+    Workspace &ws = c->ws;
+    const size_t N = (size_t)max_batch_ids;
+    const size_t utiles = cdiv(N, UQ_TILE), stiles_sort = cdiv(N, SORT_TILE);
+    if ((rc = dev_alloc(c, &c->keys_a, N)) || (rc = dev_alloc(c, &c->keys_b, N)) ||
+        (rc = dev_alloc(c, &c->idx_a, N)) || (rc = dev_alloc(c, &c->idx_b, N)) ||
+        (rc = dev_alloc(c, &c->tile_hist, stiles_sort * RADIX)) || (rc = dev_alloc(c, &ws.rank, N)) ||
+        (rc = dev_alloc(c, &ws.ukey, N)) || (rc = dev_alloc(c, &ws.seg, N + 1)) ||
+        (rc = dev_alloc(c, &ws.uslot, N)) || (rc = dev_alloc(c, &ws.ucls, N)) ||
+        (rc = dev_alloc(c, &ws.tile_heads, utiles)) || (rc = dev_alloc(c, &ws.tile_miss, utiles)) ||
+        (rc = dev_alloc(c, &ws.tile_stale, utiles)) || (rc = dev_alloc(c, &ws.miss_stage, utiles * UQ_TILE)) ||
+        (rc = dev_alloc(c, &ws.stale_stage, utiles * UQ_TILE)) || (rc = dev_alloc(c, &ws.inv, N)) ||
+        (rc = dev_alloc(c, &c->bag_of, N)))
+        return rc;
+    const size_t slot_tiles = cdiv(P, TRIM_TILE);
+    if ((rc = dev_alloc(c, &c->tp.hist, (size_t)SEL_MAX_PASSES * SEL_BINS)) ||
+        (rc = dev_alloc(c, &c->tp.tile_eq, slot_tiles)) || (rc = dev_alloc(c, &c->tp.tile_free, slot_tiles)) ||
+        (rc = dev_alloc(c, &c->tp.ev_ids, P)))
+        return rc;
+
+    HIP_TRY(hipMemsetAsync(cv.ds, 0, sizeof(DState), c->stream));
+    init_cache_kernel<<<1024, 256, 0, c->stream>>>(cv, c->n_buckets * BUCKET_ENTRIES, c->n_buckets);
+    if ((rc = launch_ok())) return rc;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    c->configured = true;
+    return HET_OK;
+}
+
+int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, int64_t vocab, int32_t location)
+{
+    if (!c || !c->configured || !table || !cg || vocab <= 0 || vocab >= 0xFFFFFFFFll) return HET_EINVAL;
+    if (location != HET_BACKING_HBM && location != HET_BACKING_PINNED_HOST) return HET_EINVAL;
+    if (c->optimizer == HET_OPT_ADAGRAD && !state) return HET_EINVAL;
+    if (c->attached) return HET_EINVAL;
+    if (location == HET_BACKING_PINNED_HOST) {
+        // kernels need the device-side alias of the mapped host memory
+        void *dt = nullptr, *dst = nullptr, *dcg = nullptr;
+        HIP_TRY(hipHostGetDevicePointer(&dt, table, 0));
+        HIP_TRY(hipHostGetDevicePointer(&dcg, cg, 0));
+        if (state) HIP_TRY(hipHostGetDevicePointer(&dst, state, 0));
+        table = static_cast<float *>(dt); cg = static_cast<uint32_t *>(dcg); state = static_cast<float *>(dst);
+    }
+    c->cv.W = table; c->cv.A = state; c->cv.Cg = cg; c->cv.vocab = (uint32_t)vocab;
+    c->location = location;
+    c->attached = true;
+    return HET_OK;
+}
+
+int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out)
+{
+    if (!ready(c) || n < 0 || n > c->max_ids) return HET_EINVAL;
+    if (n == 0) return HET_OK;
+    if (!ids || !out) return HET_EINVAL;
+    return c->cv.geom.vec == 4 ? run_lookup<4>(c, ids, (uint32_t)n, nullptr, 0, out)
+                               : run_lookup<1>(c, ids, (uint32_t)n, nullptr, 0, out);
+}
+
+int het_lookup_pooled(het_cache *c, const int64_t *ids, int64_t n, const int64_t *offsets, int64_t n_bags, float *out)
+{
+    if (!ready(c) || n < 0 || n > c->max_ids) return HET_EINVAL;
+    if (n == 0) return HET_OK;
+    if (!ids || !out || !offsets || n_bags <= 0 || n_bags >= (1ll << 31)) return HET_EINVAL;
+    return c->cv.geom.vec == 4 ? run_lookup<4>(c, ids, (uint32_t)n, offsets, (uint32_t)n_bags, out)
+                               : run_lookup<1>(c, ids, (uint32_t)n, offsets, (uint32_t)n_bags, out);
+}
+
+int het_update(het_cache *c, const int64_t *ids, const float *grads, int64_t n, float lr)
+{
+    if (!ready(c) || n < 0 || n > c->max_ids) return HET_EINVAL;
+    if (n == 0) return HET_OK;
+    if (!ids || !grads) return HET_EINVAL;
+    return c->cv.geom.vec == 4 ? run_update<4>(c, ids, (uint32_t)n, nullptr, 0, grads, lr)
+                               : run_update<1>(c, ids, (uint32_t)n, nullptr, 0, grads, lr);
+}
+
+int het_update_pooled(het_cache *c, const int64_t *ids, int64_t n, const int64_t *offsets, const float *bag_grads,
+                      int64_t n_bags, float lr)
+{
+    if (!ready(c) || n < 0 || n > c->max_ids) return HET_EINVAL;
+    if (n == 0) return HET_OK;
+    if (!ids || !bag_grads || !offsets || n_bags <= 0 || n_bags >= (1ll << 31)) return HET_EINVAL;
+    return c->cv.geom.vec == 4 ? run_update<4>(c, ids, (uint32_t)n, offsets, (uint32_t)n_bags, bag_grads, lr)
+                               : run_update<1>(c, ids, (uint32_t)n, offsets, (uint32_t)n_bags, bag_grads, lr);
+}
+
+int het_flush(het_cache *c)
+{
+    if (!ready(c)) return HET_EINVAL;
+    LAUNCH(c, K_MISC, reset_last_kernel<<<1, 64, 0, c->stream>>>(c->cv.ds));
+    const uint32_t grid = row_grid(c->cv.geom, c->cv.n_slots);
+    if (c->cv.geom.vec == 4) LAUNCH(c, K_FLUSH, flush_kernel<4><<<grid, 256, 0, c->stream>>>(c->cv));
+    else LAUNCH(c, K_FLUSH, flush_kernel<1><<<grid, 256, 0, c->stream>>>(c->cv));
+    int rc = launch_ok();
+    if (rc) return rc;
+    return sync_and_status(c, nullptr);
+}
+
+int het_stats(het_cache *c, het_stats_t *out)
+{
+    if (!c || !c->configured || !out) return HET_EINVAL;
+    DState h;
+    int rc = sync_and_status(c, &h);
+    if (rc == HET_EHIP) return rc;
+    to_public(h.last, &out->last);
+    to_public(h.total, &out->total);
+    out->resident = h.size;
+    out->iteration = h.t;
+    out->error_bits = (int32_t)h.err;
+    return HET_OK;
+}
+
+int het_clear_error(het_cache *c)
+{
+    if (!c || !c->configured) return HET_EINVAL;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    HIP_TRY(hipMemset(&c->cv.ds->err, 0, sizeof(uint32_t)));
+    return HET_OK;
+}
+
+int het_export_state(het_cache *c, int64_t *keys, int32_t *slots, uint32_t *cs, uint32_t *cc, uint32_t *last_use,
+                     uint32_t *freq, int64_t *n_resident)
+{
+    if (!c || !c->configured) return HET_EINVAL;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    const size_t P = c->cv.n_slots;
+    std::vector<uint32_t> k(P), a(P), b(P), l(P), f(P);
+    HIP_TRY(hipMemcpy(k.data(), c->cv.slot_key, P * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(a.data(), c->cv.cs, P * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(b.data(), c->cv.cc, P * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(l.data(), c->cv.last_use, P * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(f.data(), c->cv.freq, P * 4, hipMemcpyDeviceToHost));
+    int64_t r = 0;
+    for (size_t slot = 0; slot < P; ++slot) {
+        if (k[slot] == KEY_NONE) continue;
+        if (keys) keys[r] = k[slot];
+        if (slots) slots[r] = (int32_t)slot;
+        if (cs) cs[r] = a[slot];
+        if (cc) cc[r] = b[slot];
+        if (last_use) last_use[r] = l[slot];
+        if (freq) freq[r] = f[slot];
+        ++r;
+    }
+    if (n_resident) *n_resident = r;
+    return HET_OK;
+}
+
+int het_export_rows(het_cache *c, float *rows, float *acc)
+{
+    if (!c || !c->configured) return HET_EINVAL;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    const size_t P = c->cv.n_slots, D = (size_t)c->dim;
+    std::vector<uint32_t> k(P);
+    HIP_TRY(hipMemcpy(k.data(), c->cv.slot_key, P * 4, hipMemcpyDeviceToHost));
+    size_t r = 0;
+    for (size_t slot = 0; slot < P; ++slot) {
+        if (k[slot] == KEY_NONE) continue;
+        if (rows) HIP_TRY(hipMemcpy(rows + r * D, c->cv.rows + slot * D, D * 4, hipMemcpyDeviceToHost));
+        if (acc && c->cv.acc) HIP_TRY(hipMemcpy(acc + r * D, c->cv.acc + slot * D, D * 4, hipMemcpyDeviceToHost));
+        ++r;
+    }
+    return HET_OK;
+}
+
+int het_last_lookup(het_cache *c, int64_t *keys, int32_t *cls, int32_t *slots, int64_t *n_unique)
+{
+    if (!c || !c->configured) return HET_EINVAL;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    DState h;
+    HIP_TRY(hipMemcpy(&h, c->cv.ds, sizeof(DState), hipMemcpyDeviceToHost));
+    const size_t U = c->last_lookup_n ? h.n_unique : 0;
+    std::vector<uint32_t> k(U);
+    std::vector<int32_t> sl(U);
+    std::vector<uint8_t> cl(U);
+    if (U) {
+        HIP_TRY(hipMemcpy(k.data(), c->ws.ukey, U * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(sl.data(), c->ws.uslot, U * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(cl.data(), c->ws.ucls, U, hipMemcpyDeviceToHost));
+    }
+    for (size_t u = 0; u < U; ++u) {
+        if (keys) keys[u] = k[u];
+        if (cls) cls[u] = cl[u];
+        if (slots) slots[u] = sl[u];
+    }
+    if (n_unique) *n_unique = (int64_t)U;
+    return HET_OK;
+}
+
+int het_last_evicted(het_cache *c, int64_t *ids, int64_t *n)
+{
+    if (!c || !c->configured) return HET_EINVAL;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    DState h;
+    HIP_TRY(hipMemcpy(&h, c->cv.ds, sizeof(DState), hipMemcpyDeviceToHost));
+    std::vector<uint32_t> e(h.ev_n);
+    if (h.ev_n) HIP_TRY(hipMemcpy(e.data(), c->tp.ev_ids, (size_t)h.ev_n * 4, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < e.size(); ++i)
+        if (ids) ids[i] = e[i];
+    if (n) *n = (int64_t)h.ev_n;
+    return HET_OK;
+}
+
+int het_profile_begin(het_cache *c)
+{
+    if (!c || !c->configured || c->profiling) return HET_EINVAL;
+    c->profiling = true;
+    return HET_OK;
+}
+
+int het_profile_end(het_cache *c, double *total_ms, int64_t *launches, int32_t n_kernels)
+{
+    if (!c || !c->profiling) return HET_EINVAL;
+    c->profiling = false;
+    int rc = HET_OK;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) rc = HET_EHIP;
+    for (int i = 0; i < n_kernels; ++i) {
+        if (total_ms) total_ms[i] = 0.0;
+        if (launches) launches[i] = 0;
+    }
+    for (ProfSpan &sp : c->spans) {
+        float ms = 0.f;
+        if (rc == HET_OK && hipEventElapsedTime(&ms, sp.start, sp.stop) == hipSuccess && sp.id < n_kernels) {
+            if (total_ms) total_ms[sp.id] += ms;
+            if (launches) launches[sp.id] += 1;
+        }
+        (void)hipEventDestroy(sp.start);
+        (void)hipEventDestroy(sp.stop);
+    }
+    c->spans.clear();
+    return rc;
+}
+
+int het_profile_kernel_count(void) { return K_NUM; }
+
+const char *het_profile_kernel_name(int index) { return index >= 0 && index < K_NUM ? kKernelNames[index] : ""; }
+
+int het_cache_destroy(het_cache *c)
+{
+    if (!c) return HET_OK;
+    int rc = HET_OK;
+    if (c->configured && hipStreamSynchronize(c->stream) != hipSuccess) rc = HET_EHIP;
+    for (void *p : c->owned)
+        if (hipFree(p) != hipSuccess) rc = HET_EHIP;
+    delete c;
+    return rc;
+}
+
+const char *het_strerror(int status)
+{
+    switch (status) {
+    case HET_OK: return "ok";
+    case HET_EINVAL: return "invalid argument or call order";
+    case HET_ENOMEM: return "out of memory";
+    case HET_EHIP: return "HIP runtime error";
+    case HET_ERANGE: return "an id was outside [0, vocab)";
+    case HET_ESTATE: return "update of an id that is not cached";
+    default: return "unknown status";
+    }
+}
+
+} // extern "C"

@@ -1,0 +1,156 @@
+"""HIP path against the CPU oracle, through the C ABI, on an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2112_07221_amd import hetcache as hc
+from paper_2112_07221_amd import workloads as wl
+from parity import Pair, close, run_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_config_full_length():
+    """Config 1 as stated: 10k ids, dim 16, 128 x 26 lookups, LRU cache of 1000, s = 10, SGD,
+    100 iterations, every integer of the state compared after every iteration."""
+    st = run_workload(wl.WORKLOADS[1], 100, state_every=1, values_every=10)
+    assert st["total"]["stale"] > 0 and st["total"]["evicted"] > 0
+
+
+@pytest.mark.parametrize("policy", [wl.LRU, wl.LFU])
+@pytest.mark.parametrize("opt", [wl.SGD, wl.ADAGRAD])
+@pytest.mark.parametrize("s", [0, 3, hc.S_INFINITE])
+def test_policies_optimizers_staleness(policy, opt, s):
+    w = wl.WORKLOADS[1].scaled(policy=policy, optimizer=opt, s=s, eps=1e-8, lr=0.05)
+    run_workload(w, 30, state_every=1, values_every=7)
+
+
+@pytest.mark.parametrize("dim", [1, 10, 16, 64, 128, 256, 260])
+def test_row_widths(dim):
+    """Row groups of 1..64 lanes, the vector and the scalar row path."""
+    w = wl.WORKLOADS[1].scaled(dim=dim, optimizer=wl.ADAGRAD, eps=1e-8, policy=wl.LFU, s=2)
+    run_workload(w, 12, state_every=3, values_every=3)
+
+
+def test_config2_shape_reduced():
+    """Config 2's structure (26 fields, Zipf 1.05, LFU, Adagrad, s = 100) at a tenth of its
+    size, long enough for rows to go stale: several sort tiles, ragged last tile."""
+    w = wl.WORKLOADS[2].scaled(vocab=100_000, batch=411, capacity=10_000, s=20)
+    st = run_workload(w, 120, state_every=10, values_every=40)
+    assert st["total"]["stale"] > 0
+
+
+def test_config2_full_size():
+    """Config 2 at full size in the launch configuration the benchmark times: 1M ids, dim 64,
+    4096 x 26 lookups, LFU cache of 100k, Adagrad."""
+    w = wl.WORKLOADS[2].scaled(s=5)
+    st = run_workload(w, 24, state_every=6, values_every=12)
+    assert st["total"]["stale"] > 0 and st["total"]["evicted"] > 0
+
+
+def test_config4_shape_reduced():
+    w = wl.WORKLOADS[4].scaled(vocab=400_000, batch=2048, capacity=40_000, s=4)
+    run_workload(w, 30, state_every=5, values_every=10)
+
+
+def test_config5_pooled_more_uniques_than_capacity():
+    """Bag-of-words shape: pooled lookup, and more unique ids per batch than cache rows, so
+    rows of the current batch are evicted at the end of the update."""
+    w = wl.WORKLOADS[5].scaled(vocab=100_000, batch=256, capacity=5_000, s=3)
+    st = run_workload(w, 20, state_every=4, values_every=8)
+    assert st["total"]["unique"] // 40 > w.capacity        # 20 lookups + 20 updates
+
+
+def test_config3_pinned_host_backing_reduced():
+    """Config 3's structure with the global table in pinned host memory."""
+    w = wl.WORKLOADS[3].scaled(vocab=2_000_000, batch=2048, capacity=100_000, s=5)
+    run_workload(w, 16, state_every=4, values_every=8)
+
+
+def test_ragged_and_degenerate_batches():
+    """Batches of 1, 63, 64, 65, 1023, 1025, 2047, 2049 ids, all-equal ids, already-unique ids."""
+    w = wl.WORKLOADS[1].scaled(capacity=300, s=1)
+    table = wl.table_init(w)
+    rng = np.random.default_rng(5)
+    p = Pair(w, table, max_ids=4096)
+    try:
+        for n in (1, 63, 64, 65, 1023, 1025, 2047, 2049, 4096):
+            for kind in ("zipf", "same", "unique"):
+                if kind == "zipf":
+                    ids = (rng.zipf(1.3, size=n) % w.vocab).astype(np.int64)
+                elif kind == "same":
+                    ids = np.full(n, int(rng.integers(w.vocab)), dtype=np.int64)
+                else:
+                    ids = rng.permutation(w.vocab)[:n].astype(np.int64)
+                g = rng.standard_normal((n, w.dim)).astype(np.float32)
+                p.lookup(ids)
+                p.update(ids, g)
+                p.compare_state(values=True)
+                p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
+def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
+    w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
+    ids = wl.IdStream(w).batches(6)
+    g = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        p.lookup(ids[0]); p.update(ids[0], g[0])
+        p.lookup(ids[1])
+        p.lookup(ids[2])                      # overflow of the first lookup is trimmed here
+        assert np.array_equal(np.sort(p.cache.last_evicted()), np.sort(p.oracle.last_evicted()))
+        p.compare_state(values=True); p.compare_counters()
+        p.update(ids[2], g[2])
+        empty = torch.zeros(0, dtype=torch.int64, device="cuda")
+        p.cache.lookup(empty, torch.zeros(0, w.dim, device="cuda"))
+        p.cache.update(empty, torch.zeros(0, w.dim, device="cuda"), 0.1)
+        p.oracle.lookup(np.zeros(0, np.int64))
+        p.compare_state(values=True); p.compare_counters()
+        p.lookup(ids[3]); p.update(ids[3], g[3])
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
+def test_bad_ids_and_update_without_lookup_are_reported_not_fatal():
+    w = wl.WORKLOADS[1].scaled(capacity=100)
+    p = Pair(w, wl.table_init(w), max_ids=64)
+    try:
+        ids = np.array([5, -1, 7, w.vocab, 5, 2**40, 9], dtype=np.int64)
+        out = p.lookup(ids, expect_rc=1)
+        assert torch.all(out[[1, 3, 5]] == 0)
+        st = p.cache.stats()
+        assert st["error_bits"] & 1 and st["last"]["unique"] == 3
+        assert p.cache.flush() == hc.HET_ERANGE
+        p.oracle.flush()
+        p.cache.clear_error(); p.oracle.clear_error()
+        g = np.ones((len(ids), w.dim), np.float32)
+        p.update(ids, g)
+        assert p.cache.stats()["error_bits"] & 1
+        p.cache.clear_error(); p.oracle.clear_error()
+        # an id that was never looked up: skipped and flagged
+        ids2 = np.array([5, 11], dtype=np.int64)
+        p.cache.update(torch.from_numpy(ids2).cuda(), torch.ones(2, w.dim, device="cuda"), w.lr)
+        p.oracle.update(ids2, np.ones((2, w.dim)), w.lr)
+        assert p.cache.stats()["error_bits"] & 2
+        assert p.cache.flush() == hc.HET_ESTATE
+        p.oracle.flush()
+        p.cache.clear_error(); p.oracle.clear_error()
+        p.flush_and_compare()
+        # host-visible argument errors change nothing
+        too_many = torch.zeros(65, dtype=torch.int64, device="cuda")
+        with pytest.raises(hc.HetError):
+            p.cache.lookup(too_many, torch.zeros(65, w.dim, device="cuda"))
+        p.compare_counters()
+    finally:
+        p.close()
+
+
+def test_everything_fits_no_eviction():
+    """Capacity >= vocabulary: misses are first touches only and nothing is ever evicted."""
+    w = wl.WORKLOADS[1].scaled(vocab=2000, capacity=2000, s=1)
+    st = run_workload(w, 25, state_every=5, values_every=5)
+    assert st["total"]["evicted"] == 0
