@@ -36,22 +36,32 @@ __device__ __forceinline__ uint64_t ht_pack(uint32_t key, uint32_t slot)
     return ((uint64_t)key << 32) | slot;
 }
 
+// Looks for `key` in bucket b: all eight 16-byte loads are issued before the first compare.
+__device__ __forceinline__ int32_t ht_scan_bucket(const HashTable &ht, uint32_t b, uint32_t key, uint32_t *entry_index)
+{
+    const uint4 *line = reinterpret_cast<const uint4 *>(ht.entries + (size_t)b * BUCKET_ENTRIES);
+    uint4 v[BUCKET_ENTRIES / 2];
+#pragma unroll
+    for (int q = 0; q < BUCKET_ENTRIES / 2; ++q) v[q] = line[q];      // two entries each: (slot, key), (slot, key)
+    int32_t slot = SLOT_NONE;
+    uint32_t at = 0;
+#pragma unroll
+    for (int q = 0; q < BUCKET_ENTRIES / 2; ++q) {
+        if (v[q].y == key) { slot = (int32_t)v[q].x; at = 2 * q; }
+        if (v[q].w == key) { slot = (int32_t)v[q].z; at = 2 * q + 1; }
+    }
+    if (entry_index && slot != SLOT_NONE) *entry_index = b * BUCKET_ENTRIES + at;
+    return slot;
+}
+
 // Slot of `key`, or SLOT_NONE.  If entry_index is given it receives the entry's position.
 __device__ __forceinline__ int32_t ht_find(const HashTable &ht, uint32_t key, uint32_t *entry_index = nullptr)
 {
     const uint32_t h = ht_home(ht, key);
-    const uint32_t reach = ht.reach[h];
-    for (uint32_t d = 0; d <= reach; ++d) {
-        const uint32_t b = (h + d) & ht.bucket_mask;
-        const uint4 *line = reinterpret_cast<const uint4 *>(ht.entries + (size_t)b * BUCKET_ENTRIES);
-#pragma unroll
-        for (int q = 0; q < BUCKET_ENTRIES / 2; ++q) {
-            const uint4 v = line[q];   // two entries: (x = slot, y = key), (z = slot, w = key)
-            if (v.y == key) { if (entry_index) *entry_index = b * BUCKET_ENTRIES + 2 * q; return (int32_t)v.x; }
-            if (v.w == key) { if (entry_index) *entry_index = b * BUCKET_ENTRIES + 2 * q + 1; return (int32_t)v.z; }
-        }
-    }
-    return SLOT_NONE;
+    const uint32_t reach = ht.reach[h];                  // in flight together with the home bucket
+    int32_t slot = ht_scan_bucket(ht, h, key, entry_index);
+    for (uint32_t d = 1; slot == SLOT_NONE && d <= reach; ++d) slot = ht_scan_bucket(ht, (h + d) & ht.bucket_mask, key, entry_index);
+    return slot;
 }
 
 // Inserts a key known to be absent.  Returns false only if every bucket is full.

@@ -19,15 +19,13 @@ using namespace het;
 
 // Kernels of the path, as named in profiles and by het_profile_kernel_name.
 enum KernelId {
-    K_SORT_COUNT, K_SORT_SCAN, K_SORT_SCATTER, K_UNIQUE_COUNT, K_RANK_PROBE, K_FILL, K_GATHER, K_INVERT,
-    K_POOLED_GATHER, K_BAG_OF, K_APPLY, K_TRIM_BEGIN, K_TRIM_HIST, K_TRIM_COUNT, K_TRIM_EVICT, K_TRIM_FREE,
-    K_FLUSH, K_MISC, K_NUM
+    K_DEDUP_HIST, K_SORT_PASS, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_APPLY_FINISH, K_TRIM_BEGIN, K_TRIM_HIST,
+    K_TRIM_COUNT, K_TRIM_EVICT, K_TRIM_FREE, K_FLUSH, K_MISC, K_NUM
 };
 static const char *const kKernelNames[K_NUM] = {
-    "sort_count_kernel", "sort_scan_kernel", "sort_scatter_kernel", "unique_count_kernel", "rank_probe_kernel",
-    "fill_kernel", "gather_kernel", "invert_kernel", "pooled_gather_kernel", "bag_of_kernel", "apply_kernel",
-    "trim_begin_kernel", "trim_hist_kernel", "trim_count_kernel", "trim_evict_kernel", "trim_free_kernel",
-    "flush_kernel", "misc"};
+    "dedup_hist_kernel", "sort_pass_kernel", "probe_kernel", "pooled_index_kernel", "fill_gather_kernel",
+    "apply_kernel", "apply_finish_kernel", "trim_begin_kernel", "trim_hist_kernel", "trim_count_kernel", "trim_evict_kernel",
+    "trim_free_kernel", "flush_kernel", "misc"};
 
 struct ProfSpan { int id; hipEvent_t start, stop; };
 
@@ -46,15 +44,21 @@ struct het_cache {
     CacheView cv{};
     Workspace ws{};
     TrimPlan tp{};
-    uint32_t *keys_a = nullptr, *keys_b = nullptr, *idx_a = nullptr, *idx_b = nullptr;
-    uint32_t *tile_hist = nullptr;
-    uint32_t *bag_of = nullptr;
+    uint32_t *keys[2] = {nullptr, nullptr}, *idx[2] = {nullptr, nullptr};
+    uint32_t *sort_hist[SORT_MAX_PASSES] = {nullptr, nullptr, nullptr};
+    uint32_t *inv = nullptr;
+    uint32_t *tile_free[2] = {nullptr, nullptr};   // alternate between trims: one in use, one being cleared
+    int tile_free_cur = 0;
     uint32_t n_buckets = 0;
+    int max_chunks_per_lane = 1;     // row chunks one lane handles in the apply kernel
     std::vector<void *> owned;       // every device allocation, for destroy
     // host-side bookkeeping
     uint64_t t_host = 0;             // non-empty lookups so far (equals the device's t)
     bool overflow_pending = false;   // a lookup ran and no trim since
     uint32_t last_lookup_n = 0;
+    const int64_t *order_ids = nullptr;   // ids the current sorted order was built from (by a lookup)
+    uint32_t order_n = 0;
+    bool order_valid = false;
     // optional per-kernel timing (het_profile_begin / het_profile_end)
     bool profiling = false;
     std::vector<ProfSpan> spans;
@@ -145,61 +149,78 @@ int launch_ok()
 uint32_t row_grid(const RowGeom &g, uint64_t items)
 {
     const uint32_t per_block = 256u / (uint32_t)g.lanes;
-    return std::max(1u, std::min(cdiv(items, per_block), 256u * 16u));
+    return std::max(1u, std::min(cdiv(items, per_block), 256u * 8u));      // at most 8 workgroups per CU
 }
 
-// Sort + unique of ids[n]: leaves ws.skey / ws.perm / ws.rank / ws.ukey / ws.seg / ws.uslot and,
-// for a lookup, the classes and the staged miss / stale lists.
+SortPlan make_sort_plan(const het_cache *c, uint32_t n)
+{
+    SortPlan sp{};
+    sp.n = n;
+    sp.vocab = c->cv.vocab;
+    const int bits = bit_width(sp.vocab);               // the key `vocab` itself marks a bad id
+    sp.passes = std::max(1, (bits + SORT_MAX_BITS - 1) / SORT_MAX_BITS);
+    sp.width = std::max(2, (bits + sp.passes - 1) / sp.passes);      // the pass kernel reads four digits' counts at a time
+    const int items = n <= 64u * 2048u ? 8 : (n <= 64u * 4096u ? 16 : 32);   // keep the tile count small
+    sp.tile = SORT_THREADS * items;
+    sp.ntiles = cdiv(n, sp.tile);
+    for (int p = 0; p < SORT_MAX_PASSES; ++p) sp.hist[p] = c->sort_hist[p];
+    return sp;
+}
+
+template <int ITEMS>
+void launch_sort(het_cache *c, const int64_t *ids, const SortPlan &sp, int call_flags)
+{
+    LAUNCH(c, K_DEDUP_HIST, dedup_hist_kernel<ITEMS><<<sp.ntiles, SORT_THREADS, 0, c->stream>>>(ids, sp, c->cv.ds, call_flags));
+    int in = 0;
+    for (int p = 0; p < sp.passes; ++p) {
+        const int out = p == 0 ? 0 : 1 - in;
+        if (p == 0)
+            LAUNCH(c, K_SORT_PASS, sort_pass_kernel<ITEMS, true><<<sp.ntiles, SORT_THREADS, 0, c->stream>>>(
+                                       ids, nullptr, nullptr, c->keys[out], c->idx[out], sp, p));
+        else
+            LAUNCH(c, K_SORT_PASS, sort_pass_kernel<ITEMS, false><<<sp.ntiles, SORT_THREADS, 0, c->stream>>>(
+                                       nullptr, c->keys[in], c->idx[in], c->keys[out], c->idx[out], sp, p));
+        in = out;
+    }
+    c->ws.skey = c->keys[in];
+    c->ws.perm = c->idx[in];
+}
+
+// Sort of ids[n] and Find of every position; for a lookup also the classes and the staged miss
+// and stale lists.
 template <bool LOOKUP>
 int dedup_and_probe(het_cache *c, const int64_t *ids, uint32_t n, bool reset_last = true)
 {
-    const uint32_t vocab = c->cv.vocab;
-    const int bits = bit_width(vocab);                 // the key `vocab` itself marks a bad id
-    const int passes = std::max(1, (bits + RADIX_BITS - 1) / RADIX_BITS);
-    const uint32_t ntiles = cdiv(n, SORT_TILE);
-    uint32_t *kin = c->keys_a, *kout = c->keys_b, *iin = c->idx_a, *iout = c->idx_b;
-    for (int p = 0; p < passes; ++p) {
-        const uint32_t shift = (uint32_t)(p * RADIX_BITS);
-        if (p == 0) {
-            LAUNCH(c, K_SORT_COUNT, sort_count_kernel<true><<<ntiles, SORT_THREADS, 0, c->stream>>>(ids, nullptr, kin, n, vocab, shift,
-                                                                            c->tile_hist, ntiles, c->cv.ds,
-                                                                            (LOOKUP ? CALL_BUMP_ITERATION : 0) | (reset_last ? CALL_RESET_LAST : 0)));
-        } else {
-            LAUNCH(c, K_SORT_COUNT, sort_count_kernel<false><<<ntiles, SORT_THREADS, 0, c->stream>>>(nullptr, kin, nullptr, n, vocab, shift,
-                                                                             c->tile_hist, ntiles, c->cv.ds, 0));
-        }
-        LAUNCH(c, K_SORT_SCAN, sort_scan_kernel<<<1, SCAN_THREADS, 0, c->stream>>>(c->tile_hist, ntiles * RADIX));
-        if (p == 0)
-            LAUNCH(c, K_SORT_SCATTER, sort_scatter_kernel<true><<<ntiles, SORT_THREADS, 0, c->stream>>>(kin, nullptr, kout, iout, n, shift, c->tile_hist, ntiles));
-        else
-            LAUNCH(c, K_SORT_SCATTER, sort_scatter_kernel<false><<<ntiles, SORT_THREADS, 0, c->stream>>>(kin, iin, kout, iout, n, shift, c->tile_hist, ntiles));
-        std::swap(kin, kout);
-        std::swap(iin, iout);
-    }
-    c->ws.skey = kin;      // after the last swap the inputs of a further pass are the result
-    c->ws.perm = iin;
-    const uint32_t utiles = cdiv(n, UQ_TILE);
-    LAUNCH(c, K_UNIQUE_COUNT, unique_count_kernel<<<utiles, UQ_THREADS, 0, c->stream>>>(c->ws.skey, n, vocab, c->ws.tile_heads));
-    LAUNCH(c, K_RANK_PROBE, rank_probe_kernel<LOOKUP><<<utiles, UQ_THREADS, 0, c->stream>>>(c->cv, c->ws, n));
+    const SortPlan sp = make_sort_plan(c, n);
+    const int flags = (LOOKUP ? CALL_BUMP_ITERATION : 0) | (reset_last ? CALL_RESET_LAST : 0);
+    if (sp.tile == SORT_THREADS * 8) launch_sort<8>(c, ids, sp, flags);
+    else if (sp.tile == SORT_THREADS * 16) launch_sort<16>(c, ids, sp, flags);
+    else launch_sort<32>(c, ids, sp, flags);
+    LAUNCH(c, K_PROBE, probe_kernel<LOOKUP><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n));
     return launch_ok();
 }
 
 template <int VEC>
-int run_trim(het_cache *c)
+int run_trim(het_cache *c, bool prepared = false)
 {
     TrimPlan tp = c->tp;
     tp.lfu = c->policy == HET_POLICY_LFU;
     tp.bits = std::max(1, bit_width(c->t_host));
     tp.key_bits = tp.lfu ? 2 * tp.bits : tp.bits;
     tp.passes = (tp.key_bits + SEL_BITS - 1) / SEL_BITS;
+    tp.tile_free = c->tile_free[c->tile_free_cur];
+    uint32_t *tile_free_next = c->tile_free[1 - c->tile_free_cur];
+    c->tile_free_cur = 1 - c->tile_free_cur;
     const uint32_t stiles = cdiv(c->cv.n_slots, TRIM_TILE);
     const uint32_t hist_blocks = std::min(stiles, 1024u);
-    LAUNCH(c, K_TRIM_BEGIN, trim_begin_kernel<<<4, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
-    for (int p = 0; p < tp.passes; ++p) LAUNCH(c, K_TRIM_HIST, trim_hist_kernel<<<hist_blocks, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, p));
+    if (!prepared) LAUNCH(c, K_TRIM_BEGIN, trim_begin_kernel<<<4, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    for (int p = 0; p < tp.passes; ++p)
+        LAUNCH(c, K_TRIM_HIST, trim_hist_kernel<<<hist_blocks, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, p));
     LAUNCH(c, K_TRIM_COUNT, trim_count_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
-    LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC><<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
-    LAUNCH(c, K_TRIM_FREE, trim_free_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC><<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    LAUNCH(c, K_TRIM_FREE, trim_free_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, tile_free_next));
     c->overflow_pending = false;
+    c->order_valid = false;          // slots recorded for the sorted order may be gone now
     return launch_ok();
 }
 
@@ -214,17 +235,31 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         if ((rc = run_trim<VEC>(c)) != HET_OK) return rc;
     }
     if ((rc = dedup_and_probe<true>(c, ids, n, !pre_trim)) != HET_OK) return rc;
-    const uint32_t utiles = cdiv(n, UQ_TILE);
-    LAUNCH(c, K_FILL, fill_kernel<VEC><<<utiles, UQ_THREADS, 0, c->stream>>>(c->cv, c->ws));
+    const uint32_t ptiles = cdiv(n, PT_TILE);
     if (!offsets) {
-        LAUNCH(c, K_GATHER, gather_kernel<VEC><<<row_grid(c->cv.geom, n), 256, 0, c->stream>>>(c->cv, c->ws, n, out));
+        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
+                                     c->cv, c->ws, n, ptiles, out, nullptr, 0, nullptr));
     } else {
-        LAUNCH(c, K_INVERT, invert_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n));
-        LAUNCH(c, K_POOLED_GATHER, pooled_gather_kernel<VEC><<<row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(c->cv, c->ws, offsets, n, n_bags, out));
+        LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
+        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<row_grid(c->cv.geom, std::max(n_bags, n / 8)), 256, 0, c->stream>>>(
+                                     c->cv, c->ws, n, ptiles, out, offsets, n_bags, c->inv));
     }
     c->overflow_pending = true;
     c->last_lookup_n = n;
+    c->order_ids = ids; c->order_n = n; c->order_valid = true;
     return launch_ok();
+}
+
+template <int VEC, int MAXC>
+void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr)
+{
+    const uint32_t grid = row_grid(c->cv.geom, cdiv(n, CHUNK));
+    if (verify)
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
+    else
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, c->tp.hist,
+                                                                                          (uint32_t)(SEL_MAX_PASSES * SEL_BINS)));
 }
 
 template <int VEC>
@@ -232,15 +267,23 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
                const float *grads, float lr)
 {
     int rc;
-    if ((rc = dedup_and_probe<false>(c, ids, n)) != HET_OK) return rc;
+    // The ids of the preceding lookup, passed again: reuse its sorted order (the apply kernel
+    // checks every id against it).  Anything else is sorted and probed afresh.
+    const bool reuse = c->order_valid && ids == c->order_ids && n == c->order_n;
+    if (!reuse && (rc = dedup_and_probe<false>(c, ids, n)) != HET_OK) return rc;
     const uint32_t *grad_row = nullptr;
     if (offsets) {
-        LAUNCH(c, K_BAG_OF, bag_of_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(offsets, n, n_bags, c->bag_of));
-        grad_row = c->bag_of;
+        LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
+        grad_row = c->ws.bag_of;
     }
-    LAUNCH(c, K_APPLY, apply_kernel<VEC><<<row_grid(c->cv.geom, n), 256, 0, c->stream>>>(c->cv, c->ws, grads, grad_row, lr, c->eps));
+    switch (c->max_chunks_per_lane) {
+    case 1: launch_apply<VEC, 1>(c, reuse, ids, n, grads, grad_row, lr); break;
+    case 2: launch_apply<VEC, 2>(c, reuse, ids, n, grads, grad_row, lr); break;
+    case 4: launch_apply<VEC, 4>(c, reuse, ids, n, grads, grad_row, lr); break;
+    default: launch_apply<VEC, 16>(c, reuse, ids, n, grads, grad_row, lr); break;
+    }
     if ((rc = launch_ok()) != HET_OK) return rc;
-    return run_trim<VEC>(c);
+    return run_trim<VEC>(c, true);        // apply_finish_kernel has cleared the select histograms
 }
 
 int sync_and_status(het_cache *c, DState *host_copy)
@@ -280,7 +323,7 @@ int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, 
 
 int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps, void *hip_stream)
 {
-    if (!c || c->configured || max_batch_ids <= 0 || max_batch_ids >= (1ll << 30)) return HET_EINVAL;
+    if (!c || c->configured || max_batch_ids <= 0 || max_batch_ids > (int64_t)MAX_PROBE_TILES * PT_TILE) return HET_EINVAL;
     if (optimizer != HET_OPT_SGD && optimizer != HET_OPT_ADAGRAD) return HET_EINVAL;
     if (!(eps >= 0.f)) return HET_EINVAL;
     c->max_ids = max_batch_ids; c->optimizer = optimizer; c->eps = eps;
@@ -294,6 +337,9 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     g.dim = c->dim; g.vec = (c->dim % 4 == 0) ? 4 : 1; g.chunks = c->dim / g.vec;
     g.lanes = (int)std::min<uint32_t>(64u, pow2_at_least((uint64_t)g.chunks));
     cv.geom = g;
+    const int per_lane = (g.chunks + g.lanes - 1) / g.lanes;
+    c->max_chunks_per_lane = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : 16));
+    if (per_lane > 16) return HET_EINVAL;               // rows wider than 64 lanes x 16 chunks
 
     int rc = HET_OK;
     const size_t row_elems = (size_t)P * (size_t)c->dim;
@@ -315,22 +361,26 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     // workspaces
     Workspace &ws = c->ws;
     const size_t N = (size_t)max_batch_ids;
-    const size_t utiles = cdiv(N, UQ_TILE), stiles_sort = cdiv(N, SORT_TILE);
-    if ((rc = dev_alloc(c, &c->keys_a, N)) || (rc = dev_alloc(c, &c->keys_b, N)) ||
-        (rc = dev_alloc(c, &c->idx_a, N)) || (rc = dev_alloc(c, &c->idx_b, N)) ||
-        (rc = dev_alloc(c, &c->tile_hist, stiles_sort * RADIX)) || (rc = dev_alloc(c, &ws.rank, N)) ||
-        (rc = dev_alloc(c, &ws.ukey, N)) || (rc = dev_alloc(c, &ws.seg, N + 1)) ||
-        (rc = dev_alloc(c, &ws.uslot, N)) || (rc = dev_alloc(c, &ws.ucls, N)) ||
-        (rc = dev_alloc(c, &ws.tile_heads, utiles)) || (rc = dev_alloc(c, &ws.tile_miss, utiles)) ||
-        (rc = dev_alloc(c, &ws.tile_stale, utiles)) || (rc = dev_alloc(c, &ws.miss_stage, utiles * UQ_TILE)) ||
-        (rc = dev_alloc(c, &ws.stale_stage, utiles * UQ_TILE)) || (rc = dev_alloc(c, &ws.inv, N)) ||
-        (rc = dev_alloc(c, &c->bag_of, N)))
+    const size_t ptiles = cdiv(N, PT_TILE);
+    const size_t sort_tiles = std::max<size_t>(64, cdiv(N, SORT_THREADS * 32));
+    const size_t chunks = cdiv(N, CHUNK);
+    for (int i = 0; i < 2; ++i)
+        if ((rc = dev_alloc(c, &c->keys[i], N)) || (rc = dev_alloc(c, &c->idx[i], N))) return rc;
+    for (int p = 0; p < SORT_MAX_PASSES; ++p)
+        if ((rc = dev_alloc(c, &c->sort_hist[p], sort_tiles * SORT_MAX_BINS))) return rc;
+    if ((rc = dev_alloc(c, &ws.src, N)) || (rc = dev_alloc(c, &ws.head_slot, N)) || (rc = dev_alloc(c, &ws.cls, N)) ||
+        (rc = dev_alloc(c, &ws.tile_miss, ptiles)) || (rc = dev_alloc(c, &ws.tile_stale, ptiles)) ||
+        (rc = dev_alloc(c, &ws.miss_stage, ptiles * PT_TILE)) || (rc = dev_alloc(c, &ws.stale_stage, ptiles * PT_TILE)) ||
+        (rc = dev_alloc(c, &c->inv, N)) || (rc = dev_alloc(c, &ws.bag_of, N)) ||
+        (rc = dev_alloc(c, &ws.partial, chunks * 2 * (size_t)c->dim)))
         return rc;
     const size_t slot_tiles = cdiv(P, TRIM_TILE);
     if ((rc = dev_alloc(c, &c->tp.hist, (size_t)SEL_MAX_PASSES * SEL_BINS)) ||
-        (rc = dev_alloc(c, &c->tp.tile_eq, slot_tiles)) || (rc = dev_alloc(c, &c->tp.tile_free, slot_tiles)) ||
-        (rc = dev_alloc(c, &c->tp.ev_ids, P)))
+        (rc = dev_alloc(c, &c->tp.tile_eq, slot_tiles)) || (rc = dev_alloc(c, &c->tile_free[0], slot_tiles)) ||
+        (rc = dev_alloc(c, &c->tile_free[1], slot_tiles)) || (rc = dev_alloc(c, &c->tp.ev_ids, P)))
         return rc;
+    HIP_TRY(hipMemsetAsync(c->tile_free[0], 0, slot_tiles * sizeof(uint32_t), c->stream));
+    HIP_TRY(hipMemsetAsync(c->tile_free[1], 0, slot_tiles * sizeof(uint32_t), c->stream));
 
     HIP_TRY(hipMemsetAsync(cv.ds, 0, sizeof(DState), c->stream));
     init_cache_kernel<<<1024, 256, 0, c->stream>>>(cv, c->n_buckets * BUCKET_ENTRIES, c->n_buckets);
@@ -479,23 +529,24 @@ int het_last_lookup(het_cache *c, int64_t *keys, int32_t *cls, int32_t *slots, i
 {
     if (!c || !c->configured) return HET_EINVAL;
     HIP_TRY(hipStreamSynchronize(c->stream));
-    DState h;
-    HIP_TRY(hipMemcpy(&h, c->cv.ds, sizeof(DState), hipMemcpyDeviceToHost));
-    const size_t U = c->last_lookup_n ? h.n_unique : 0;
-    std::vector<uint32_t> k(U);
-    std::vector<int32_t> sl(U);
-    std::vector<uint8_t> cl(U);
-    if (U) {
-        HIP_TRY(hipMemcpy(k.data(), c->ws.ukey, U * 4, hipMemcpyDeviceToHost));
-        HIP_TRY(hipMemcpy(sl.data(), c->ws.uslot, U * 4, hipMemcpyDeviceToHost));
-        HIP_TRY(hipMemcpy(cl.data(), c->ws.ucls, U, hipMemcpyDeviceToHost));
+    const size_t n = c->last_lookup_n;
+    std::vector<uint32_t> k(n);
+    std::vector<int32_t> sl(n);
+    std::vector<uint8_t> cl(n);
+    if (n) {
+        HIP_TRY(hipMemcpy(k.data(), c->ws.skey, n * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(sl.data(), c->ws.head_slot, n * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(cl.data(), c->ws.cls, n, hipMemcpyDeviceToHost));
     }
-    for (size_t u = 0; u < U; ++u) {
-        if (keys) keys[u] = k[u];
-        if (cls) cls[u] = cl[u];
-        if (slots) slots[u] = sl[u];
+    int64_t u = 0;
+    for (size_t j = 0; j < n; ++j) {             // per-key facts sit at the head of each run
+        if (k[j] == c->cv.vocab || (j > 0 && k[j] == k[j - 1])) continue;
+        if (keys) keys[u] = k[j];
+        if (cls) cls[u] = cl[j];
+        if (slots) slots[u] = sl[j];
+        ++u;
     }
-    if (n_unique) *n_unique = (int64_t)U;
+    if (n_unique) *n_unique = u;
     return HET_OK;
 }
 

@@ -1,13 +1,18 @@
 // Dedup of a minibatch's ids: the "unique embedding key set" of Algorithm 1 of the paper.
 //
-// A stable least-significant-digit radix sort of (id, position) pairs, 8 bits per pass, over
-// just the bits the vocabulary needs, followed by head-flag ranking.  The result is:
-//   skey[j], perm[j]   ids ascending, with the original position of each (ties keep the
-//                      original order, so a key's occurrences come in increasing position);
-//   rank[j]            index of position j's key in the sorted unique key list;
-//   ukey[r], seg[r]    the unique keys and where each key's run starts in the sorted order.
-// Ids outside [0, vocab) are given the key `vocab`, which sorts behind every valid id, and are
-// left out of the unique list.
+// A stable least-significant-digit radix sort of (id, position) pairs over just the bits the
+// vocabulary needs, in one to three passes of up to 11 bits.  The result is
+//   skey[j], perm[j]   ids ascending with the original position of each; equal ids keep their
+//                      original order, so a key's occurrences come in increasing position.
+// A run of equal keys in skey is one unique key; its first position is the key's "head".
+// Ids outside [0, vocab) get the key `vocab`, which sorts behind every valid id.
+//
+// Kernel count is what matters at minibatch sizes (a launch costs more than moving 100k
+// keys), so a pass is a single kernel: every workgroup owns a tile of keys and derives its
+// output offsets itself from the per-tile digit histograms ("count at the producer, prefix at
+// the consumer").  The histograms of the first pass are counted from the ids; while a pass
+// scatters a key it already counts it for the next pass, in the tile where it lands.  No
+// workgroup ever waits for another one.
 #pragma once
 #include "common.hpp"
 
@@ -15,108 +20,157 @@ namespace het {
 
 constexpr int SORT_THREADS = 256;
 constexpr int SORT_WAVES = SORT_THREADS / WAVE;
-constexpr int SORT_ITEMS = 8;
-constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;   // 2048 keys per workgroup
-constexpr int RADIX_BITS = 8;
-constexpr int RADIX = 1 << RADIX_BITS;
-
-// Position of item `it` of this thread inside its tile: a wave owns 512 consecutive keys and
-// walks them 64 at a time, so (wave, item, lane) order is position order.
-__device__ __forceinline__ uint32_t sort_pos(uint32_t tile, int it)
-{
-    const uint32_t w = threadIdx.x / WAVE;
-    return tile * SORT_TILE + w * (WAVE * SORT_ITEMS) + it * WAVE + lane_id();
-}
+constexpr int SORT_MAX_BITS = 11;
+constexpr int SORT_MAX_BINS = 1 << SORT_MAX_BITS;
+constexpr int SORT_MAX_PASSES = 3;                       // vocab < 2^32
+constexpr int SORT_BINS_PER_THREAD = SORT_MAX_BINS / SORT_THREADS;
 
 constexpr int CALL_BUMP_ITERATION = 1;   // this call is a Read: advance the iteration counter
 constexpr int CALL_RESET_LAST = 2;       // start the per-call counters from zero
 
-// Per-tile digit histogram.  FIRST: also turns the int64 ids into 32-bit sort keys, flags ids
-// outside the vocabulary and resets the per-call counters (block 0).
-template <bool FIRST>
-__global__ __launch_bounds__(SORT_THREADS) void sort_count_kernel(
-    const int64_t *__restrict__ ids, const uint32_t *__restrict__ keys_in,
-    uint32_t *__restrict__ keys0, uint32_t n, uint32_t vocab, uint32_t shift,
-    uint32_t *__restrict__ tile_hist, uint32_t ntiles, DState *ds, int call_flags)
+struct SortPlan {
+    uint32_t n;            // keys
+    uint32_t vocab;
+    uint32_t tile;         // keys per workgroup = SORT_THREADS * items
+    uint32_t ntiles;
+    int passes;            // 1..3
+    int width;             // bits per digit (<= 11)
+    uint32_t *hist[SORT_MAX_PASSES];   // per pass: [ntiles][1 << width]
+};
+
+__device__ __forceinline__ uint32_t id_to_key(int64_t id, uint32_t vocab)
 {
-    __shared__ uint32_t hist[RADIX];
+    return (id >= 0 && id < (int64_t)vocab) ? (uint32_t)id : vocab;
+}
+
+// Position of item `it` of this thread inside its tile: a wave owns ITEMS*64 consecutive keys
+// and walks them 64 at a time, so (wave, item, lane) order is position order.
+template <int ITEMS>
+__device__ __forceinline__ uint32_t sort_pos(uint32_t tile_index, int it)
+{
+    const uint32_t w = threadIdx.x / WAVE;
+    return tile_index * (SORT_THREADS * ITEMS) + w * (WAVE * ITEMS) + it * WAVE + lane_id();
+}
+
+// First kernel of a call: digit histogram of pass 0 per tile, straight from the ids; flags ids
+// outside the vocabulary; clears the histograms the later passes count into; per-call counters.
+template <int ITEMS>
+__global__ __launch_bounds__(SORT_THREADS) void dedup_hist_kernel(const int64_t *__restrict__ ids, SortPlan sp, DState *ds,
+                                                                  int call_flags)
+{
+    __shared__ uint32_t hist[SORT_MAX_BINS];
     const uint32_t tile = blockIdx.x;
-    for (int b = threadIdx.x; b < RADIX; b += SORT_THREADS) hist[b] = 0;
+    const uint32_t bins = 1u << sp.width, mask = bins - 1u;
+    for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) hist[b] = 0;
+    for (int p = 1; p < sp.passes; ++p)
+        for (uint32_t i = tile * SORT_THREADS + threadIdx.x; i < sp.ntiles * bins; i += gridDim.x * SORT_THREADS) sp.hist[p][i] = 0;
     __syncthreads();
     bool bad = false;
 #pragma unroll
-    for (int it = 0; it < SORT_ITEMS; ++it) {
-        const uint32_t i = sort_pos(tile, it);
-        if (i < n) {
-            uint32_t key;
-            if (FIRST) {
-                const int64_t id = ids[i];
-                const bool ok = id >= 0 && id < (int64_t)vocab;
-                key = ok ? (uint32_t)id : vocab;
-                bad |= !ok;
-                keys0[i] = key;
-            } else {
-                key = keys_in[i];
-            }
-            atomicAdd(&hist[(key >> shift) & (RADIX - 1)], 1u);
+    for (int it = 0; it < ITEMS; ++it) {
+        const uint32_t i = sort_pos<ITEMS>(tile, it);
+        if (i < sp.n) {
+            const uint32_t key = id_to_key(ids[i], sp.vocab);
+            bad |= key == sp.vocab;
+            atomicAdd(&hist[key & mask], 1u);
         }
     }
-    if (FIRST) {
-        if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
-        if (tile == 0 && threadIdx.x == 0) {
-            if (call_flags & CALL_BUMP_ITERATION) ds->t += 1;
-            if (call_flags & CALL_RESET_LAST) { Counters z{}; ds->last = z; }
-            ds->last.n = n;
-            atomicAdd(&ds->total.n, (unsigned long long)n);
-        }
+    if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
+    if (tile == 0 && threadIdx.x == 0) {
+        if (call_flags & CALL_BUMP_ITERATION) ds->t += 1;
+        if (call_flags & CALL_RESET_LAST) { Counters z{}; ds->last = z; }
+        ds->last.n = sp.n;
+        ds->n_valid = 0;
+        atomicAdd(&ds->total.n, (unsigned long long)sp.n);
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < RADIX; b += SORT_THREADS) tile_hist[b * ntiles + tile] = hist[b];
+    for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) sp.hist[0][tile * bins + b] = hist[b];
 }
 
-// Exclusive scan, in place, of the RADIX x ntiles histogram laid out digit-major: entry
-// (digit, tile) becomes the first output position of that digit's keys from that tile.
-constexpr int SCAN_THREADS = 1024;
-__global__ __launch_bounds__(SCAN_THREADS) void sort_scan_kernel(uint32_t *__restrict__ tile_hist, uint32_t total)
+// One stable scatter pass.  FIRST reads the ids (positions are the payload); later passes
+// read the previous pass's keys and payload.
+template <int ITEMS, bool FIRST>
+__global__ __launch_bounds__(SORT_THREADS) void sort_pass_kernel(const int64_t *__restrict__ ids, const uint32_t *__restrict__ keys_in,
+                                                                 const uint32_t *__restrict__ idx_in, uint32_t *__restrict__ keys_out,
+                                                                 uint32_t *__restrict__ idx_out, SortPlan sp, int pass)
 {
-    __shared__ uint32_t lds[SCAN_THREADS / WAVE + 1];
-    const uint32_t per = (total + SCAN_THREADS - 1) / SCAN_THREADS;
-    const uint32_t lo = min(threadIdx.x * per, total), hi = min(lo + per, total);
-    uint32_t s = 0;
-    for (uint32_t i = lo; i < hi; ++i) s += tile_hist[i];
-    uint32_t tot;
-    uint32_t run = block_excl_scan<SCAN_THREADS / WAVE>(s, lds, tot);
-    for (uint32_t i = lo; i < hi; ++i) { const uint32_t c = tile_hist[i]; tile_hist[i] = run; run += c; }
-}
-
-// Stable scatter of one pass.  Ranking inside the tile: each wave ranks 64 keys at a time with
-// eight ballots (lanes holding the same digit find each other), keeps a running per-wave digit
-// count in LDS, and the per-wave counts are then turned into offsets in wave order.
-template <bool FIRST>
-__global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
-    const uint32_t *__restrict__ keys_in, const uint32_t *__restrict__ idx_in,
-    uint32_t *__restrict__ keys_out, uint32_t *__restrict__ idx_out, uint32_t n, uint32_t shift,
-    const uint32_t *__restrict__ tile_off, uint32_t ntiles)
-{
-    __shared__ uint32_t wave_hist[SORT_WAVES][RADIX];
+    __shared__ uint32_t wave_hist[SORT_WAVES][SORT_MAX_BINS];
+    __shared__ uint32_t tile_base[SORT_MAX_BINS];
+    __shared__ uint32_t scan_lds[SORT_WAVES + 1];
     const uint32_t tile = blockIdx.x, w = threadIdx.x / WAVE;
-    for (int b = threadIdx.x; b < SORT_WAVES * RADIX; b += SORT_THREADS) (&wave_hist[0][0])[b] = 0;
+    const int width = sp.width;
+    const uint32_t bins = 1u << width, mask = bins - 1u;
+    const uint32_t shift = (uint32_t)(pass * width);
+    const bool last = pass + 1 == sp.passes;
+
+    for (uint32_t b = threadIdx.x; b < SORT_WAVES * SORT_MAX_BINS; b += SORT_THREADS) (&wave_hist[0][0])[b] = 0;
+
+    // Output offset of each digit for this tile: keys of smaller digits anywhere, plus keys of
+    // the same digit in earlier tiles.  A thread adds up four consecutive digits (one 16-byte
+    // load per tile, many loads in flight) over every TLN-th tile; LDS merges the tile lanes.
+    {
+        uint32_t *tot = &wave_hist[0][0], *bef = &wave_hist[1][0];      // borrowed until the ranking starts
+        for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) { tot[b] = 0; bef[b] = 0; }
+        __syncthreads();
+        const uint4 *h4 = reinterpret_cast<const uint4 *>(sp.hist[pass]);
+        const uint32_t quads = bins / 4;                                 // width >= 2
+        const uint32_t tln = quads >= SORT_THREADS ? 1u : SORT_THREADS / quads;
+        for (uint32_t item = threadIdx.x; item < quads * tln; item += SORT_THREADS) {
+            const uint32_t bq = item % quads, tl = item / quads;
+            uint4 t4 = make_uint4(0, 0, 0, 0), f4 = make_uint4(0, 0, 0, 0);
+#pragma unroll 8
+            for (uint32_t t = tl; t < sp.ntiles; t += tln) {
+                const uint4 v = h4[(size_t)t * quads + bq];
+                t4.x += v.x; t4.y += v.y; t4.z += v.z; t4.w += v.w;
+                if (t < tile) { f4.x += v.x; f4.y += v.y; f4.z += v.z; f4.w += v.w; }
+            }
+            const uint32_t b = bq * 4;
+            if (tln == 1) {
+                tot[b] = t4.x; tot[b + 1] = t4.y; tot[b + 2] = t4.z; tot[b + 3] = t4.w;
+                bef[b] = f4.x; bef[b + 1] = f4.y; bef[b + 2] = f4.z; bef[b + 3] = f4.w;
+            } else {
+                atomicAdd(&tot[b], t4.x); atomicAdd(&tot[b + 1], t4.y); atomicAdd(&tot[b + 2], t4.z); atomicAdd(&tot[b + 3], t4.w);
+                atomicAdd(&bef[b], f4.x); atomicAdd(&bef[b + 1], f4.y); atomicAdd(&bef[b + 2], f4.z); atomicAdd(&bef[b + 3], f4.w);
+            }
+        }
+        __syncthreads();
+        // exclusive scan over the digits; thread t owns SORT_BINS_PER_THREAD consecutive digits
+        const uint32_t b0 = threadIdx.x * SORT_BINS_PER_THREAD;
+        uint32_t t8[SORT_BINS_PER_THREAD], f8[SORT_BINS_PER_THREAD], mine = 0;
+#pragma unroll
+        for (int q = 0; q < SORT_BINS_PER_THREAD; ++q) {
+            t8[q] = b0 + q < bins ? tot[b0 + q] : 0u;
+            f8[q] = b0 + q < bins ? bef[b0 + q] : 0u;
+            mine += t8[q];
+        }
+        uint32_t total;
+        uint32_t run = block_excl_scan<SORT_WAVES>(mine, scan_lds, total);
+#pragma unroll
+        for (int q = 0; q < SORT_BINS_PER_THREAD; ++q) {
+            if (b0 + q < bins) tile_base[b0 + q] = run + f8[q];
+            run += t8[q];
+        }
+        __syncthreads();
+        for (uint32_t b = threadIdx.x; b < 2 * SORT_MAX_BINS; b += SORT_THREADS) (&wave_hist[0][0])[b] = 0;
+    }
     __syncthreads();
 
-    uint32_t key[SORT_ITEMS], lrank[SORT_ITEMS];
+    uint32_t key[ITEMS], lrank[ITEMS];
     volatile uint32_t *my_hist = wave_hist[w];
 #pragma unroll
-    for (int it = 0; it < SORT_ITEMS; ++it) {
-        const uint32_t i = sort_pos(tile, it);
-        const bool valid = i < n;
-        key[it] = valid ? keys_in[i] : 0u;
-        const uint32_t d = (key[it] >> shift) & (RADIX - 1);
+    for (int it = 0; it < ITEMS; ++it) {
+        const uint32_t i = sort_pos<ITEMS>(tile, it);
+        const bool valid = i < sp.n;
+        key[it] = valid ? (FIRST ? id_to_key(ids[i], sp.vocab) : keys_in[i]) : 0u;
+        const uint32_t d = (key[it] >> shift) & mask;
         uint64_t peers = __ballot(valid);
 #pragma unroll
-        for (int b = 0; b < RADIX_BITS; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const uint64_t bal = __ballot(bit);
-            peers &= bit ? bal : ~bal;
+        for (int b = 0; b < SORT_MAX_BITS; ++b) {
+            if (b < width) {
+                const bool bit = (d >> b) & 1u;
+                const uint64_t bal = __ballot(bit);
+                peers &= bit ? bal : ~bal;
+            }
         }
         const uint32_t r = mask_rank(peers);
         const uint32_t before = my_hist[d];
@@ -126,8 +180,8 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
         __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < RADIX; b += SORT_THREADS) {
-        uint32_t run = tile_off[b * ntiles + tile];
+    for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) {
+        uint32_t run = tile_base[b];
 #pragma unroll
         for (int ww = 0; ww < SORT_WAVES; ++ww) {
             const uint32_t c = wave_hist[ww][b];
@@ -136,42 +190,40 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(
         }
     }
     __syncthreads();
+    uint32_t *next = last ? nullptr : sp.hist[pass + 1];
 #pragma unroll
-    for (int it = 0; it < SORT_ITEMS; ++it) {
-        const uint32_t i = sort_pos(tile, it);
-        if (i < n) {
-            const uint32_t d = (key[it] >> shift) & (RADIX - 1);
+    for (int it = 0; it < ITEMS; ++it) {
+        const uint32_t i = sort_pos<ITEMS>(tile, it);
+        if (i < sp.n) {
+            const uint32_t d = (key[it] >> shift) & mask;
             const uint32_t pos = wave_hist[w][d] + lrank[it];
             keys_out[pos] = key[it];
             idx_out[pos] = FIRST ? i : idx_in[i];
+            if (next) atomicAdd(&next[(size_t)(pos / sp.tile) * bins + ((key[it] >> (shift + width)) & mask)], 1u);
         }
     }
 }
 
-// ---- unique: head flags over the sorted keys -------------------------------------------------
-constexpr int UQ_THREADS = 256;
-constexpr int UQ_WAVES = UQ_THREADS / WAVE;
-constexpr int UQ_ITEMS = 4;
-constexpr int UQ_TILE = UQ_THREADS * UQ_ITEMS;   // 1024 sorted positions per workgroup
-
-__device__ __forceinline__ bool is_head(const uint32_t *skey, uint32_t j, uint32_t n, uint32_t vocab)
+// First position of `key` in the sorted keys: lower bound over skey[0 .. hi).
+__device__ __forceinline__ uint32_t run_head(const uint32_t *skey, uint32_t hi, uint32_t key)
 {
-    if (j >= n) return false;
-    const uint32_t k = skey[j];
-    return k != vocab && (j == 0 || skey[j - 1] != k);
+    uint32_t lo = 0;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (skey[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
 }
 
-// tile_heads[tile] = number of distinct valid keys that start inside the tile.
-__global__ __launch_bounds__(UQ_THREADS) void unique_count_kernel(
-    const uint32_t *__restrict__ skey, uint32_t n, uint32_t vocab, uint32_t *__restrict__ tile_heads)
+// One past the last position of `key`: upper bound over skey[lo .. n).
+__device__ __forceinline__ uint32_t run_end(const uint32_t *skey, uint32_t lo, uint32_t n, uint32_t key)
 {
-    __shared__ uint32_t lds[UQ_WAVES];
-    const uint32_t base = blockIdx.x * UQ_TILE + threadIdx.x * UQ_ITEMS;
-    uint32_t c = 0;
-#pragma unroll
-    for (int it = 0; it < UQ_ITEMS; ++it) c += is_head(skey, base + it, n, vocab) ? 1u : 0u;
-    c = block_sum<UQ_WAVES>(c, lds);
-    if (threadIdx.x == 0) tile_heads[blockIdx.x] = c;
+    uint32_t hi = n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (skey[mid] <= key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
 }
 
 } // namespace het

@@ -154,3 +154,34 @@ def test_everything_fits_no_eviction():
     w = wl.WORKLOADS[1].scaled(vocab=2000, capacity=2000, s=1)
     st = run_workload(w, 25, state_every=5, values_every=5)
     assert st["total"]["evicted"] == 0
+
+
+def test_update_reuses_the_lookup_order_only_for_the_same_ids():
+    """An update handed the lookup's own id buffer reuses its sorted order and checks every id
+    against it on the device; a buffer whose contents changed in between is flagged, not
+    silently misapplied; a different buffer with the same ids is sorted afresh."""
+    w = wl.WORKLOADS[1].scaled(capacity=400, s=3)
+    ids_np = wl.IdStream(w).batches(3)
+    g_np = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        ids = torch.from_numpy(ids_np[0]).cuda()
+        out = torch.empty(w.n, w.dim, device="cuda")
+        g = torch.from_numpy(g_np[0]).cuda()
+        # same buffer: fast path
+        p.cache.lookup(ids, out); p.oracle.lookup(ids_np[0])
+        p.cache.update(ids, g, w.lr); p.oracle.update(ids_np[0], g_np[0], w.lr)
+        p.compare_state(values=True); p.compare_counters()
+        # a copy of the buffer: sorted again, same result
+        ids1 = torch.from_numpy(ids_np[1]).cuda()
+        p.cache.lookup(ids1, out); p.oracle.lookup(ids_np[1])
+        p.cache.update(ids1.clone(), g, w.lr); p.oracle.update(ids_np[1], g_np[0], w.lr)
+        p.compare_state(values=True); p.compare_counters()
+        # same buffer, contents overwritten after the lookup: flagged
+        ids2 = torch.from_numpy(ids_np[2]).cuda()
+        p.cache.lookup(ids2, out)
+        ids2[:100] = (ids2[:100] + 1) % w.vocab
+        p.cache.update(ids2, g, w.lr)
+        assert p.cache.stats()["error_bits"] & 2
+    finally:
+        p.close()
