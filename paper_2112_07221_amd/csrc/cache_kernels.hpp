@@ -15,6 +15,20 @@
 
 namespace het {
 
+// Clocks (Section 3.1) and policy counters (Section 4.3) of one cache slot; read and written
+// as one 16-byte word where several fields are needed.
+struct alignas(16) SlotMeta {
+    uint32_t cs;         // start clock c_s
+    uint32_t cc;         // local clock c_c
+    uint32_t last_use;   // iteration of the last Read that had the key
+    uint32_t freq;       // number of Reads that had the key since it was fetched
+};
+__device__ __forceinline__ uint4 load_meta(const SlotMeta *m, uint32_t slot) { return reinterpret_cast<const uint4 *>(m)[slot]; }
+__device__ __forceinline__ void store_meta(SlotMeta *m, uint32_t slot, uint32_t cs, uint32_t cc, uint32_t lu, uint32_t fr)
+{
+    reinterpret_cast<uint4 *>(m)[slot] = make_uint4(cs, cc, lu, fr);
+}
+
 // Everything a kernel needs to know about one cache, passed by value.
 struct CacheView {
     // global table (Section 3.1): rows, optimizer state, global clock c_g
@@ -23,7 +37,8 @@ struct CacheView {
     uint32_t vocab;
     // cache slots
     float *rows, *acc;
-    uint32_t *slot_key, *cs, *cc, *last_use, *freq;
+    uint32_t *slot_key;
+    SlotMeta *meta;       // start clock, local clock, LRU stamp, LFU count: one 16-byte record per slot
     uint32_t n_slots;     // capacity + max_batch_ids
     uint32_t capacity;
     uint32_t max_ids;
@@ -41,7 +56,7 @@ constexpr int32_t SRC_ZERO = -2;      // id outside the vocabulary: the output r
 constexpr int PT_THREADS = 1024;                // probe tiles: 1024 sorted positions per workgroup,
 constexpr int PT_WAVES = PT_THREADS / WAVE;     // one per thread, so every probe's loads are in flight at once
 constexpr int PT_TILE = PT_THREADS;
-constexpr int CHUNK = 16;                       // sorted positions per row group in the apply kernel
+constexpr int CHUNK = 8;                        // sorted positions per row group in the apply kernel
 
 // Per-call workspaces (sized by max_batch_ids unless noted).  Per-key facts are stored at the
 // key's head position in the sorted order.
@@ -51,9 +66,10 @@ struct Workspace {
     int32_t *head_slot;           // at heads: slot of the key (set by fill for a missed key)
     uint8_t *cls;                 // at heads: HIT / STALE / MISS (lookup)
     uint32_t *tile_miss, *tile_stale;     // per probe tile counts
-    uint32_t *miss_stage, *stale_stage;   // per probe tile: head positions of its missed / stale keys
+    uint2 *miss_stage, *stale_stage;      // per probe tile: (head position, key) of its missed / stale keys
     uint32_t *bag_of;             // pooled: bag of each original position
     double *partial;              // apply: [chunks][2][dim] partial gradient sums of runs that cross chunk borders
+    int32_t *cross_slot;          // apply: [chunks] slot of the run that starts in the chunk and crosses its back border
 };
 
 // CheckValid (Section 3.1): c_c <= c_s + s and c_g <= c_c + s, as differences so that an
@@ -73,7 +89,7 @@ __device__ __forceinline__ void count2(unsigned long long *a, unsigned long long
 // per tile for the fill kernel and tells the gather where each position's row comes from.
 // Otherwise (update that sorted its own ids): only resolves slots and flags keys not cached.
 template <bool LOOKUP>
-__global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n)
+__global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
     const uint32_t tile = blockIdx.x;
@@ -90,12 +106,15 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         } else {
             head = j == 0 || ws.skey[j - 1] != key;
             if (j + 1 == n || ws.skey[j + 1] == vocab) ds->n_valid = j + 1;    // one writer: the last valid position
+            const uint32_t cg = LOOKUP ? cv.Cg[key] : 0u;        // in flight together with the probe's loads
             const int32_t slot = ht_find(cv.ht, key);
             int32_t src = slot == SLOT_NONE ? SRC_BACKING : slot;
             bool valid = true;
+            uint4 m = make_uint4(0, 0, 0, 0);
             if (LOOKUP && slot != SLOT_NONE) {
-                const uint32_t cs = cv.cs[slot], cc = cv.cc[slot];
-                valid = check_valid(cs, cc, cv.Cg[key], cv.s);
+                m = load_meta(cv.meta, (uint32_t)slot);
+                const uint32_t cs = m.x, cc = m.y;
+                valid = check_valid(cs, cc, cg, cv.s);
                 // A stale row that holds no updates of its own is refetched: its value is the
                 // global row.  (One with updates is pushed first, so its own value stays current.)
                 if (!valid && !(cc > cs)) src = SRC_BACKING;
@@ -107,8 +126,7 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
                     if (slot == SLOT_NONE) miss = true;
                     else {
                         hit = valid; stale = !valid;
-                        cv.last_use[slot] = ds->t;            // one use per key per Read
-                        cv.freq[slot] += 1;
+                        store_meta(cv.meta, (uint32_t)slot, m.x, m.y, t_now, m.w + 1);   // one use per key per Read
                     }
                     ws.cls[j] = (uint8_t)(miss ? CLS_MISS : (stale ? CLS_STALE : CLS_HIT));
                 } else {
@@ -123,8 +141,8 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         uint32_t tot_miss, tot_stale;
         const uint32_t mo = block_excl_scan<PT_WAVES>(miss ? 1u : 0u, lds, tot_miss);
         const uint32_t so = block_excl_scan<PT_WAVES>(stale ? 1u : 0u, lds, tot_stale);
-        if (miss) ws.miss_stage[tile * PT_TILE + mo] = j;
-        if (stale) ws.stale_stage[tile * PT_TILE + so] = j;
+        if (miss) ws.miss_stage[tile * PT_TILE + mo] = make_uint2(j, ws.skey[j]);
+        if (stale) ws.stale_stage[tile * PT_TILE + so] = make_uint2(j, ws.skey[j]);
         const uint32_t tot_hit = block_sum<PT_WAVES>(hit ? 1u : 0u, lds);
         const uint32_t tot_heads = block_sum<PT_WAVES>(head ? 1u : 0u, lds);
         if (threadIdx.x == 0) {
@@ -152,7 +170,7 @@ __device__ __forceinline__ void push_row(const CacheView &cv, uint32_t key, uint
     row_copy<VEC>(cv.W + (size_t)key * g.dim, cv.rows + (size_t)slot * g.dim, g.chunks, g.lanes, gl);
     if (cv.adagrad)
         row_copy<VEC>(cv.A + (size_t)key * g.dim, cv.acc + (size_t)slot * g.dim, g.chunks, g.lanes, gl);
-    if (gl == 0) { const uint32_t cc = cv.cc[slot]; if (cc > cv.Cg[key]) cv.Cg[key] = cc; }
+    if (gl == 0) { const uint32_t cc = cv.meta[slot].cc; if (cc > cv.Cg[key]) cv.Cg[key] = cc; }
 }
 
 // Fetch's pull for one row: copy the global row (and the accumulator) into the slot.
@@ -192,59 +210,64 @@ __device__ __forceinline__ uint32_t tile_of(const uint32_t *pre, uint32_t ntiles
 
 constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 
-// Fetch of the missed keys, Evict + Fetch of the stale ones (Algorithm 2), and Get.  One row
+// Fetch of the missed keys, Evict + Fetch of the stale ones (Algorithm 2), and Get, one row
 // group per item.  The i-th missed key in ascending key order takes the i-th free slot in
 // ascending slot order.  The gather reads a missed key's row from the global table (the same
-// values the fetch copies), so it does not have to wait for the fetch.
+// values the fetch copies), so it does not wait for the fetch: the first `fill_blocks`
+// workgroups fetch, the others gather, side by side.
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
 template <int VEC, bool POOLED>
-__global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t ptiles, float *__restrict__ out,
-                                                          const int64_t *__restrict__ offsets, uint32_t n_bags,
+__global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t ptiles, uint32_t fill_blocks,
+                                                          float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv)
 {
     using V = typename VecT<VEC>::type;
-    __shared__ uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
-    __shared__ uint32_t scan[4 + 1];
     const RowGeom g = cv.geom;
-    const uint32_t tot_miss = tile_prefix_to_lds<4>(ws.tile_miss, ptiles, pre_miss, scan);
-    const uint32_t tot_stale = tile_prefix_to_lds<4>(ws.tile_stale, ptiles, pre_stale, scan);
-    const uint32_t gid = (blockIdx.x * 256u + threadIdx.x) / g.lanes;
     const int gl = threadIdx.x % g.lanes;
-    const uint32_t ngroups = gridDim.x * 256u / g.lanes;
-    const uint32_t t = cv.ds->t;
+    const uint32_t groups_per_block = 256u / g.lanes;
 
-    for (uint32_t m = gid; m < tot_miss; m += ngroups) {                 // Fetch(k) into a new slot
-        const uint32_t tl = tile_of(pre_miss, ptiles, m);
-        const uint32_t j = ws.miss_stage[tl * PT_TILE + (m - pre_miss[tl])];
-        const uint32_t key = ws.skey[j];
-        const uint32_t slot = cv.free_list[m];
-        pull_row<VEC>(cv, key, slot, gl);
-        if (gl == 0) {
+    if (blockIdx.x < fill_blocks) {
+        __shared__ uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
+        __shared__ uint32_t scan[4 + 1];
+        const uint32_t tot_miss = tile_prefix_to_lds<4>(ws.tile_miss, ptiles, pre_miss, scan);
+        const uint32_t tot_stale = tile_prefix_to_lds<4>(ws.tile_stale, ptiles, pre_stale, scan);
+        const uint32_t gid = blockIdx.x * groups_per_block + threadIdx.x / g.lanes;
+        const uint32_t ngroups = fill_blocks * groups_per_block;
+        const uint32_t t = cv.ds->t;
+        if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.ds->last.unique;   // for an update that reuses this order
+        for (uint32_t m = gid; m < tot_miss; m += ngroups) {                 // Fetch(k) into a new slot
+            const uint32_t tl = tile_of(pre_miss, ptiles, m);
+            const uint2 jk = ws.miss_stage[tl * PT_TILE + (m - pre_miss[tl])];
+            const uint32_t slot = cv.free_list[m];
+            const uint32_t j = jk.x, key = jk.y;
             const uint32_t cg = cv.Cg[key];
-            cv.cs[slot] = cg; cv.cc[slot] = cg;                          // c_s = c_c = c_g
-            cv.slot_key[slot] = key;
-            cv.last_use[slot] = t;
-            cv.freq[slot] = 1;
-            ws.head_slot[j] = (int32_t)slot;
-            if (!ht_insert(cv.ht, key, slot)) atomicOr(&cv.ds->err, ERRBIT_INTERNAL);
+            pull_row<VEC>(cv, key, slot, gl);
+            if (gl == 0) {
+                store_meta(cv.meta, slot, cg, cg, t, 1u);                    // c_s = c_c = c_g; first use
+                cv.slot_key[slot] = key;
+                ws.head_slot[j] = (int32_t)slot;
+                if (!ht_insert(cv.ht, key, slot)) atomicOr(&cv.ds->err, ERRBIT_INTERNAL);
+            }
         }
-    }
-    for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
-        const uint32_t tl = tile_of(pre_stale, ptiles, m);
-        const uint32_t j = ws.stale_stage[tl * PT_TILE + (m - pre_stale[tl])];
-        const uint32_t key = ws.skey[j];
-        const uint32_t slot = (uint32_t)ws.head_slot[j];
-        const bool has_updates = cv.cc[slot] > cv.cs[slot];
-        if (has_updates) push_row<VEC>(cv, key, slot, gl);               // now the global row equals the cached one
-        else pull_row<VEC>(cv, key, slot, gl);
-        if (gl == 0) {
-            const uint32_t cg = cv.Cg[key];
-            cv.cs[slot] = cg; cv.cc[slot] = cg;
-            if (has_updates) count2(&cv.ds->last.stale_dirty, &cv.ds->total.stale_dirty, 1u);
+        for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
+            const uint32_t tl = tile_of(pre_stale, ptiles, m);
+            const uint2 jk = ws.stale_stage[tl * PT_TILE + (m - pre_stale[tl])];
+            const uint32_t key = jk.y;
+            const uint32_t slot = (uint32_t)ws.head_slot[jk.x];
+            const bool has_updates = cv.meta[slot].cc > cv.meta[slot].cs;
+            if (has_updates) push_row<VEC>(cv, key, slot, gl);               // now the global row equals the cached one
+            else pull_row<VEC>(cv, key, slot, gl);
+            if (gl == 0) {
+                const uint32_t cg = cv.Cg[key];
+                cv.meta[slot].cs = cg; cv.meta[slot].cc = cg;
+                if (has_updates) count2(&cv.ds->last.stale_dirty, &cv.ds->total.stale_dirty, 1u);
+            }
         }
+        return;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.ds->last.unique;   // for an update that reuses this order
 
+    const uint32_t gid = (blockIdx.x - fill_blocks) * groups_per_block + threadIdx.x / g.lanes;
+    const uint32_t ngroups = (gridDim.x - fill_blocks) * groups_per_block;
     if (!POOLED) {
         for (uint32_t j = gid; j < n; j += ngroups) {                    // Get
             const int32_t s = ws.src[j];
@@ -287,6 +310,12 @@ __global__ __launch_bounds__(256) void pooled_index_kernel(Workspace ws, uint32_
     }
 }
 
+// Hardware square root and reciprocal (about one unit in the last place each): the Adagrad
+// step lr * G / (sqrt(a) + eps) tolerates that a hundred times over, and the correctly rounded
+// sequences cost more instructions than everything else in the kernel.
+__device__ __forceinline__ float fast_sqrt(float v) { return __builtin_amdgcn_sqrtf(v); }
+__device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
+
 // The optimizer step on one cached row for chunk c of the row, and nothing else.
 template <int VEC>
 __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, int c, const double *g64, float lr, float eps)
@@ -303,7 +332,7 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
         V av = *ap;
         float *a = reinterpret_cast<float *>(&av);
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) { a[k] += G[k] * G[k]; x[k] -= lr * G[k] / (sqrtf(a[k]) + eps); }
+        for (int k = 0; k < VEC; ++k) { a[k] += G[k] * G[k]; x[k] -= lr * G[k] * fast_rcp(fast_sqrt(a[k]) + eps); }
         *ap = av;
     } else {
 #pragma unroll
@@ -313,12 +342,13 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 }
 
 // Update + Clock (Algorithm 3), first of two kernels.  Each row group takes CHUNK consecutive
-// sorted positions: it loads their keys, original positions and gradient rows up front (all
-// loads in flight together), then sums the gradients of each run of equal keys in fp64 (the
-// kernel is bound by reading the gradients; summing wide makes a long run of a popular key
-// lose no digits) and rounds once to fp32.  A run that lies inside the chunk is applied at
-// once.  A run that crosses a chunk border leaves one partial sum per chunk for the second
-// kernel.
+// sorted positions.  It loads their keys, original positions and slots, then - all in flight
+// together - their gradient rows and the cached rows (and accumulators) of the runs of equal
+// keys that lie inside the chunk.  The gradients of a run are summed in fp64 (the kernel is
+// bound by reading the gradients; summing wide makes a long run of a popular key lose no
+// digits) and rounded once to fp32.  A run inside the chunk is applied at once.  A run that
+// crosses a chunk border leaves one partial sum per chunk for the second kernel; the chunk in
+// which it starts also leaves the run's slot in cross_slot.
 // VERIFY: the ids must be the ones the sorted order was built from (an update that reuses the
 // preceding lookup's order); a position whose id differs is skipped and flagged.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
@@ -333,7 +363,6 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
     const int gl = threadIdx.x % g.lanes;
     const uint32_t ngroups = gridDim.x * 256u / g.lanes;
     const uint32_t nv = cv.ds->n_valid;
-    const uint32_t nchunks_total = (nv + CHUNK - 1) / CHUNK;
     const uint32_t *skey = ws.skey;
     if (VERIFY && blockIdx.x == 0 && threadIdx.x == 0) {
         // this call did not sort: its per-call counters start here, with the lookup's key count
@@ -346,52 +375,90 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         if (nv < n_ids) atomicOr(&ds->err, ERRBIT_RANGE);      // the order holds ids outside the vocabulary
     }
 
-    for (uint32_t c = gid; c < nchunks_total; c += ngroups) {
+    const uint32_t nchunks_max = (n_ids + CHUNK - 1) / CHUNK;      // known to the host; nv <= n_ids
+    for (uint32_t c = gid; c < nchunks_max; c += ngroups) {
         const uint32_t j0 = c * CHUNK;
-        const uint32_t cnt = min((uint32_t)CHUNK, nv - j0);
+        // loaded for every position the call has, then masked by the valid count (read meanwhile)
         uint32_t k[CHUNK], p[CHUNK];
         int32_t hs[CHUNK];
 #pragma unroll
         for (int i = 0; i < CHUNK; ++i) {
-            const bool in = (uint32_t)i < cnt;
+            const bool in = j0 + i < n_ids;
             k[i] = in ? skey[j0 + i] : KEY_NONE;
             p[i] = in ? ws.perm[j0 + i] : 0u;
             hs[i] = in ? ws.head_slot[j0 + i] : SLOT_NONE;
         }
-        const uint32_t prev_key = j0 > 0 ? skey[j0 - 1] : KEY_NONE;
-        const uint32_t next_key = j0 + cnt < nv ? skey[j0 + cnt] : KEY_NONE;
-        uint32_t use = 0;                                   // positions whose gradient counts
+        const uint32_t before_key = j0 > 0 ? skey[j0 - 1] : KEY_NONE;
+        const uint32_t after_key = j0 + CHUNK < n_ids ? skey[j0 + CHUNK] : KEY_NONE;
+        if (j0 >= nv) break;
+        const uint32_t cnt = min((uint32_t)CHUNK, nv - j0);
+#pragma unroll
+        for (int i = 0; i < CHUNK; ++i) if ((uint32_t)i >= cnt) { k[i] = KEY_NONE; hs[i] = SLOT_NONE; }
+        const uint32_t prev_key = before_key;
+        const uint32_t next_key = cnt == CHUNK && j0 + CHUNK < nv ? after_key : KEY_NONE;
+        uint32_t last_key = KEY_NONE;
+#pragma unroll
+        for (int i = 0; i < CHUNK; ++i) last_key = (uint32_t)i < cnt ? k[i] : last_key;
+        const bool open_front = prev_key == k[0];           // the first run began in an earlier chunk
+        const bool open_back = next_key == last_key;        // the last run goes on in a later chunk
+
+        uint32_t use = 0, heads = 0, whole = 0;             // bit i: gradient counts / run head / head of a run inside the chunk
 #pragma unroll
         for (int i = 0; i < CHUNK; ++i) {
-            bool ok = (uint32_t)i < cnt;
-            if (VERIFY && ok) ok = ids[p[i]] == (int64_t)k[i];
+            const bool in = (uint32_t)i < cnt;
+            bool ok = in;
+            if (VERIFY && in) ok = ids[p[i]] == (int64_t)k[i];
             use |= ok ? (1u << i) : 0u;
+            const bool head = in && (i == 0 || k[i] != k[i - 1]);
+            heads |= head ? (1u << i) : 0u;
+            const bool inside = head && !(i == 0 && open_front) && !(k[i] == last_key && open_back);
+            whole |= (inside && hs[i] != SLOT_NONE) ? (1u << i) : 0u;
         }
-        if (VERIFY && gl == 0 && use != (cnt >= 32 ? ~0u : ((1u << cnt) - 1u))) atomicOr(&cv.ds->err, ERRBIT_STATE);
+        if (VERIFY && gl == 0 && use != ((1u << cnt) - 1u)) atomicOr(&cv.ds->err, ERRBIT_STATE);
         if (grad_row) {
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) if ((uint32_t)i < cnt) p[i] = grad_row[p[i]];
+        }
+        if (gl == 0) {
+            // the run that starts here and leaves through the back border is finished by the second kernel
+            int32_t cross = SLOT_NONE;
+            if (open_back) {
+#pragma unroll
+                for (int i = 0; i < CHUNK; ++i)
+                    if (((heads >> i) & 1u) && k[i] == last_key && !(i == 0 && open_front)) cross = hs[i];
+            }
+            ws.cross_slot[c] = cross;
         }
 #pragma unroll
         for (int q = 0; q < MAXC; ++q) {
             const int cidx = gl + q * g.lanes;
             const bool act = cidx < g.chunks;
-            V v[CHUNK];
+            V v[CHUNK], xr[CHUNK], ar[CHUNK];
+            uint32_t ccv[CHUNK];
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) {
+                v[i] = V{}; xr[i] = V{}; ar[i] = V{}; ccv[i] = 0;
+                if (q == 0 && gl == 0 && ((whole >> i) & 1u)) ccv[i] = cv.meta[hs[i]].cc;
                 if (act && ((use >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
-                else v[i] = V{};
+                if (act && ((whole >> i) & 1u)) {
+                    xr[i] = reinterpret_cast<const V *>(cv.rows + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
+                    if (cv.adagrad) ar[i] = reinterpret_cast<const V *>(cv.acc + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
+                }
             }
             double acc64[VEC];
-            int run_start = 0;
+            V cur_x{}, cur_a{};
+            int32_t cur_slot = SLOT_NONE;
+            uint32_t cur_cc = 0;
+            bool cur_whole = false, cur_front = false;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) {
                 const bool in = (uint32_t)i < cnt;
-                const bool begins = in && (i == 0 || k[i] != k[i - 1]);
-                if (begins) {
-                    run_start = i;
+                if ((heads >> i) & 1u) {
+                    cur_x = xr[i]; cur_a = ar[i]; cur_slot = hs[i]; cur_cc = ccv[i];
+                    cur_whole = (whole >> i) & 1u;
+                    cur_front = i == 0 && open_front;
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
                 }
@@ -400,22 +467,27 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
                 for (int e = 0; e < VEC; ++e) acc64[e] += (double)vf[e];       // v[i] is zero where it does not count
                 bool run_ends = in && (uint32_t)(i + 1) == cnt;
                 if (i + 1 < CHUNK) run_ends = run_ends || (in && (uint32_t)(i + 1) < cnt && k[i + 1] != k[i]);
-                if (run_ends) {
-                    const bool starts_here = run_start > 0 || prev_key != k[i];
-                    const bool ends_here = (uint32_t)(i + 1) < cnt || next_key != k[i];
-                    if (starts_here && ends_here) {
-                        int32_t slot = SLOT_NONE;          // hs[run_start], read with compile-time indices
+                if (!run_ends) continue;
+                if (cur_whole) {
+                    if (act) {
+                        float G[VEC];
+                        float *x = reinterpret_cast<float *>(&cur_x), *a = reinterpret_cast<float *>(&cur_a);
 #pragma unroll
-                        for (int h = 0; h < CHUNK; ++h) slot = (h == run_start) ? hs[h] : slot;
-                        if (slot != SLOT_NONE) {
-                            if (act) apply_step<VEC>(cv, (uint32_t)slot, cidx, acc64, lr, eps);
-                            if (q == 0 && gl == 0) cv.cc[slot] += 1;          // Clock(k)
+                        for (int e = 0; e < VEC; ++e) {
+                            G[e] = (float)acc64[e];                            // the fp64 sum is rounded once
+                            if (cv.adagrad) { a[e] += G[e] * G[e]; x[e] -= lr * G[e] * fast_rcp(fast_sqrt(a[e]) + eps); }
+                            else x[e] -= lr * G[e];
                         }
-                    } else if (act) {
-                        double *mine = ws.partial + ((size_t)c * 2 + (starts_here ? 1 : 0)) * (size_t)g.dim + (size_t)cidx * VEC;
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) mine[e] = acc64[e];
+                        reinterpret_cast<V *>(cv.rows + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_x;
+                        if (cv.adagrad) reinterpret_cast<V *>(cv.acc + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_a;
                     }
+                    if (q == 0 && gl == 0) cv.meta[cur_slot].cc = cur_cc + 1;       // Clock(k)
+                } else if (act && (cur_front || (k[i] == last_key && open_back))) {
+                    // slot 0 of the chunk: a run that came in through the front border;
+                    // slot 1: a run that starts here and leaves through the back border
+                    double *mine = ws.partial + ((size_t)c * 2 + (cur_front ? 0 : 1)) * (size_t)g.dim + (size_t)cidx * VEC;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) mine[e] = acc64[e];
                 }
             }
         }
@@ -423,51 +495,129 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 }
 
 // Second kernel of Write: finishes the runs that cross chunk borders.  The group of the chunk
-// in which such a run starts adds the run's partial sums in chunk order and applies the step,
-// so the result does not depend on scheduling.  The kernel also prepares the trim that
-// follows (clears the select histograms and the evicted-id count).
-struct TrimPlan;
+// in which such a run starts adds the run's partial sums in chunk order and applies the step.
+// A run spread over more than FIN_NEAR + 1 chunks (a very popular key) is summed by the whole
+// workgroup instead: every group adds a contiguous share of the partial sums in order, and the
+// shares are added in group order.  Either way the order of additions is fixed by the sorted
+// order alone.  The kernel also prepares the trim that follows (clears the select histograms
+// and the evicted-id count).
+constexpr int FIN_NEAR = 4;
 template <int VEC, int MAXC>
-__global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t *trim_hist,
-                                                           uint32_t trim_hist_words)
+__global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
+                                                           uint32_t *trim_hist, uint32_t trim_hist_words)
 {
+    __shared__ uint32_t long_c[256], long_c1[256];
+    __shared__ int32_t long_slot[256];
+    __shared__ uint32_t n_long;
+    __shared__ double share[256 * VEC];
     const RowGeom g = cv.geom;
-    const uint32_t gid = (blockIdx.x * 256u + threadIdx.x) / g.lanes;
+    const uint32_t groups_per_block = 256u / g.lanes;
+    const uint32_t group = threadIdx.x / g.lanes;
     const int gl = threadIdx.x % g.lanes;
-    const uint32_t ngroups = gridDim.x * 256u / g.lanes;
     const uint32_t nv = cv.ds->n_valid;
-    const uint32_t nchunks_total = (nv + CHUNK - 1) / CHUNK;
+    const uint32_t nchunks_max = (n_ids + CHUNK - 1) / CHUNK;
     const uint32_t *skey = ws.skey;
+    const size_t pstride = (size_t)g.dim;
     for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < trim_hist_words; i += gridDim.x * 256u) trim_hist[i] = 0;
     if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->ev_n = 0;
+    if (threadIdx.x == 0) n_long = 0;
+    __syncthreads();
 
-    for (uint32_t c = gid; c + 1 < nchunks_total; c += ngroups) {
-        const uint32_t j0 = c * CHUNK, jb = j0 + CHUNK;        // jb < nv: the border after chunk c
-        const uint32_t key = skey[jb - 1];
-        if (skey[jb] != key) continue;                         // no run crosses this border
-        if (skey[j0] == key && j0 > 0 && skey[j0 - 1] == key) continue;   // the run started in an earlier chunk
-        uint32_t head = jb - 1;
-        while (head > j0 && skey[head - 1] == key) --head;
-        const uint32_t tail = run_end(skey, jb, nv, key);
-        const uint32_t c1 = (tail - 1) / CHUNK;
-        const int32_t slot = ws.head_slot[head];
-        if (slot == SLOT_NONE) continue;
+    for (uint32_t base = blockIdx.x * groups_per_block; base < nchunks_max; base += gridDim.x * groups_per_block) {
+        const uint32_t c = base + group;
+        const uint32_t jb = (c + 1) * CHUNK;                       // first position of the next chunk
+        int32_t slot = SLOT_NONE;
+        uint32_t key = KEY_NONE, nxt[FIN_NEAR];
+        if (c < nchunks_max) {
+            slot = ws.cross_slot[c];
+            key = jb < n_ids ? skey[jb] : KEY_NONE;
 #pragma unroll
-        for (int q = 0; q < MAXC; ++q) {
-            const int cidx = gl + q * g.lanes;
-            if (cidx >= g.chunks) continue;
-            double sum[VEC];
-            const double *first = ws.partial + ((size_t)c * 2 + 1) * (size_t)g.dim + (size_t)cidx * VEC;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) sum[e] = first[e];
-            for (uint32_t cc_ = c + 1; cc_ <= c1; ++cc_) {
-                const double *pp = ws.partial + ((size_t)cc_ * 2) * (size_t)g.dim + (size_t)cidx * VEC;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) sum[e] += pp[e];
-            }
-            apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps);
+            for (int d = 0; d < FIN_NEAR; ++d) { const uint32_t jj = jb + (d + 1) * CHUNK; nxt[d] = jj < n_ids ? skey[jj] : KEY_NONE; }
         }
-        if (gl == 0) cv.cc[slot] += 1;                         // Clock(k)
+        const bool mine = c < nchunks_max && jb < nv && slot != SLOT_NONE;
+        uint32_t c1 = c + 1;                                       // last chunk that holds part of the run
+        bool open = mine;
+#pragma unroll
+        for (int d = 0; d < FIN_NEAR; ++d) {
+            open = open && (jb + (d + 1) * CHUNK < nv) && nxt[d] == key;
+            if (open) c1 = c + 2 + d;
+        }
+        if (open) {                                                // reaches past the near chunks: a long run
+            c1 = (run_end(skey, jb + FIN_NEAR * CHUNK, nv, key) - 1) / CHUNK;
+            if (gl == 0) { const uint32_t at = atomicAdd(&n_long, 1u); long_c[at] = c; long_c1[at] = c1; long_slot[at] = slot; }
+        } else if (mine) {
+#pragma unroll
+            for (int q = 0; q < MAXC; ++q) {
+                const int cidx = gl + q * g.lanes;
+                if (cidx >= g.chunks) continue;
+                // the run's partial sums (at most FIN_NEAR + 1) and its row, all requested at once
+                double part[FIN_NEAR + 1][VEC];
+#pragma unroll
+                for (int d = 0; d <= FIN_NEAR; ++d) {
+                    const uint32_t cc_ = c + d;
+                    const double *pp = ws.partial + ((size_t)cc_ * 2 + (d == 0 ? 1 : 0)) * pstride + (size_t)cidx * VEC;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) part[d][e] = cc_ <= c1 ? pp[e] : 0.0;
+                }
+                double sum[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sum[e] = part[0][e];
+#pragma unroll
+                for (int d = 1; d <= FIN_NEAR; ++d)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) sum[e] += part[d][e];
+                apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps);
+            }
+            if (gl == 0) cv.meta[slot].cc += 1;                    // Clock(k)
+        }
+        __syncthreads();
+        const uint32_t nl = n_long;
+        for (uint32_t li = 0; li < nl; ++li) {                     // long runs, one at a time, whole workgroup
+            const uint32_t lc = long_c[li], lc1 = long_c1[li];
+            const int32_t lslot = long_slot[li];
+            const uint32_t m = lc1 - lc + 1;                       // partial sums of the run
+            const uint32_t per = (m + groups_per_block - 1) / groups_per_block;
+            const uint32_t lo = min(group * per, m), hi = min(lo + per, m);
+#pragma unroll
+            for (int q = 0; q < MAXC; ++q) {
+                const int cidx = gl + q * g.lanes;
+                const bool act = cidx < g.chunks;
+                double sum[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
+                for (uint32_t i0 = lo; i0 < hi; i0 += 8) {
+                    double part[8][VEC];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const uint32_t i = i0 + u;
+                        const double *pp = ws.partial + ((size_t)(lc + i) * 2 + (i == 0 ? 1 : 0)) * pstride + (size_t)cidx * VEC;
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) part[u][e] = (act && i < hi) ? pp[e] : 0.0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) share[threadIdx.x * VEC + e] = sum[e];
+                __syncthreads();
+                if (group == 0 && act) {
+                    double tot[VEC];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) tot[e] = 0.0;
+                    for (uint32_t gi = 0; gi < groups_per_block; ++gi)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) tot[e] += share[(gi * g.lanes + gl) * VEC + e];
+                    apply_step<VEC>(cv, (uint32_t)lslot, cidx, tot, lr, eps);
+                }
+            }
+            if (threadIdx.x == 0) cv.meta[lslot].cc += 1;          // Clock(k)
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) n_long = 0;
+        __syncthreads();
     }
 }
 
@@ -489,15 +639,17 @@ struct TrimPlan {
     int bits;         // bits per policy field
     int key_bits;     // bits of the packed policy key
     int passes;       // select passes
-    uint32_t *hist;   // [SEL_MAX_PASSES][SEL_BINS], zeroed before the first pass
-    uint32_t *tile_eq, *tile_free;     // per slot-tile counts
+    uint32_t *hist;   // [SEL_MAX_PASSES][SEL_BINS] followed by sup_eq: zeroed together before the first pass
+    uint32_t zero_words;
+    uint32_t *blk_eq, *sup_eq;         // rows tied at the threshold: per 256 slots, and per EV_SUPER such blocks
+    uint32_t *tile_free;               // free slots per 1024-slot tile
     uint32_t *ev_ids;                  // ids dropped by this trim
 };
 
-__device__ __forceinline__ uint64_t policy_key(const CacheView &cv, const TrimPlan &tp, uint32_t slot)
+__device__ __forceinline__ uint64_t policy_key(const TrimPlan &tp, const uint4 &meta)
 {
-    const uint64_t lu = cv.last_use[slot];
-    return tp.lfu ? (((uint64_t)cv.freq[slot] << tp.bits) | lu) : lu;
+    const uint64_t lu = meta.z;
+    return tp.lfu ? (((uint64_t)meta.w << tp.bits) | lu) : lu;
 }
 
 __device__ __forceinline__ int sel_shift(const TrimPlan &tp, int pass)
@@ -548,7 +700,7 @@ __device__ __forceinline__ void sel_replay(const TrimPlan &tp, int upto, uint32_
 
 __global__ __launch_bounds__(TRIM_THREADS) void trim_begin_kernel(CacheView cv, TrimPlan tp)
 {
-    for (uint32_t i = blockIdx.x * TRIM_THREADS + threadIdx.x; i < SEL_MAX_PASSES * SEL_BINS; i += gridDim.x * TRIM_THREADS) tp.hist[i] = 0;
+    for (uint32_t i = blockIdx.x * TRIM_THREADS + threadIdx.x; i < tp.zero_words; i += gridDim.x * TRIM_THREADS) tp.hist[i] = 0;
     if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->ev_n = 0;
 }
 
@@ -567,8 +719,10 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_hist_kernel(CacheView cv, T
     const int shift = sel_shift(tp, pass), width = sel_width(tp, pass);
     const int decided = shift + width;                 // bits above are fixed by the prefix
     for (uint32_t slot = blockIdx.x * TRIM_THREADS + threadIdx.x; slot < cv.n_slots; slot += gridDim.x * TRIM_THREADS) {
-        if (cv.slot_key[slot] == KEY_NONE) continue;
-        const uint64_t k = policy_key(cv, tp, slot);
+        const uint32_t sk = cv.slot_key[slot];
+        const uint4 m = load_meta(cv.meta, slot);
+        if (sk == KEY_NONE) continue;
+        const uint64_t k = policy_key(tp, m);
         if (decided < 64 && (k >> decided) != (prefix >> decided)) continue;
         atomicAdd(&bins[(uint32_t)(k >> shift) & ((1u << width) - 1u)], 1u);
     }
@@ -577,87 +731,97 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_hist_kernel(CacheView cv, T
         if (bins[b]) atomicAdd(&tp.hist[pass * SEL_BINS + b], bins[b]);
 }
 
-// Per slot tile: how many cached rows have a policy key equal to tau.
+// Finds tau (replaying the select) and counts, per block of 256 slots, the cached rows whose
+// policy key equals tau; sup_eq adds these up per EV_SUPER blocks (zero when the trim starts).
+constexpr int EV_SLOTS = 256;
+constexpr int EV_SUPER = 32;
 __global__ __launch_bounds__(TRIM_THREADS) void trim_count_kernel(CacheView cv, TrimPlan tp)
 {
     __shared__ uint32_t pick[2];
     __shared__ uint32_t scan[TRIM_WAVES + 1];
     const int32_t over = cv.ds->size - (int32_t)cv.capacity;
     if (over <= 0) return;
+    const uint32_t slot = blockIdx.x * EV_SLOTS + threadIdx.x;       // loads first: they overlap the replay
+    const bool cached = slot < cv.n_slots && cv.slot_key[slot] != KEY_NONE;
+    const uint64_t key = slot < cv.n_slots ? policy_key(tp, load_meta(cv.meta, slot)) : 0;
     uint64_t tau; uint32_t take_eq;
     sel_replay(tp, tp.passes, (uint32_t)over, tau, take_eq, pick, scan);
-    uint32_t eq = 0;
-#pragma unroll
-    for (int it = 0; it < TRIM_ITEMS; ++it) {
-        const uint32_t slot = blockIdx.x * TRIM_TILE + threadIdx.x * TRIM_ITEMS + it;
-        if (slot < cv.n_slots && cv.slot_key[slot] != KEY_NONE && policy_key(cv, tp, slot) == tau) ++eq;
+    const uint32_t eq = block_sum<TRIM_WAVES>((cached && key == tau) ? 1u : 0u, scan);
+    if (threadIdx.x == 0) {
+        tp.blk_eq[blockIdx.x] = eq;
+        if (eq) atomicAdd(&tp.sup_eq[blockIdx.x / EV_SUPER], eq);
+        if (blockIdx.x == 0) { cv.ds->sel_tau = tau; cv.ds->sel_take = take_eq; }
     }
-    eq = block_sum<TRIM_WAVES>(eq, scan);
-    if (threadIdx.x == 0) tp.tile_eq[blockIdx.x] = eq;
 }
 
-// Drops the victims among 256 consecutive slots: push if the row holds updates, erase the key,
-// free the slot.  Four workgroups share a counting tile; each adds its free slots to the
-// tile's count for the free-list kernel (tile_free is zero when the trim starts).
-constexpr int EV_SLOTS = 256;
+// Drops the victims among 256 consecutive slots, one thread per slot: erase the key, free the
+// slot, raise c_g; then one row group per victim that holds updates copies its row (and
+// accumulator) to the global table: Evict's push (Section 3.1).  Four workgroups share a
+// 1024-slot tile of the free-list kernel; each adds its free slots to the tile's count
+// (tile_free is zero when the trim starts).
 template <int VEC>
 __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, TrimPlan tp)
 {
-    __shared__ uint32_t pick[2];
     __shared__ uint32_t scan[TRIM_WAVES + 1];
-    __shared__ uint32_t victims[EV_SLOTS];
-    __shared__ uint32_t n_victims;
-    const uint32_t first = blockIdx.x * EV_SLOTS;
-    const uint32_t tile = first / TRIM_TILE;
+    __shared__ uint32_t v_slot[EV_SLOTS], v_key[EV_SLOTS];
+    __shared__ uint32_t n_push, ev_base;
+    const uint32_t blk = blockIdx.x;
+    const uint32_t slot = blk * EV_SLOTS + threadIdx.x;
+    const bool in = slot < cv.n_slots;
+    // everything this thread may need, requested at once
     const int32_t over = cv.ds->size - (int32_t)cv.capacity;
-    uint64_t tau = 0; uint32_t take_eq = 0, eq_before = 0;
+    const uint64_t tau = cv.ds->sel_tau;
+    const uint32_t take_eq = cv.ds->sel_take;
+    const uint32_t my_key = in ? cv.slot_key[slot] : KEY_NONE;
+    const uint4 my_meta = in ? load_meta(cv.meta, slot) : make_uint4(0, 0, 0, 0);
+    const uint64_t pk = policy_key(tp, my_meta);
+    const uint32_t my_cs = my_meta.x, my_cc = my_meta.y;
+    uint32_t e = 0;
     if (over > 0) {
-        sel_replay(tp, tp.passes, (uint32_t)over, tau, take_eq, pick, scan);
-        eq_before = block_sum_array<TRIM_WAVES>(tp.tile_eq, tile, scan);
-        // rows equal to tau in the same counting tile but in earlier slots
-        uint32_t e = 0;
-        for (uint32_t slot = tile * TRIM_TILE + threadIdx.x; slot < first; slot += TRIM_THREADS)
-            if (cv.slot_key[slot] != KEY_NONE && policy_key(cv, tp, slot) == tau) ++e;
-        eq_before += block_sum<TRIM_WAVES>(e, scan);
+        // rows equal to tau in earlier slots: whole supers, then the blocks of this super before this one
+        const uint32_t sup = blk / EV_SUPER;
+        for (uint32_t i = threadIdx.x; i < sup; i += TRIM_THREADS) e += tp.sup_eq[i];
+        const uint32_t b = sup * EV_SUPER + threadIdx.x;
+        if (threadIdx.x < EV_SUPER && b < blk) e += tp.blk_eq[b];
     }
-    if (threadIdx.x == 0) n_victims = 0;
-    const uint32_t slot = first + threadIdx.x;
-    bool is_free = false, lt = false, eq = false;
-    if (slot < cv.n_slots) {
-        if (cv.slot_key[slot] == KEY_NONE) is_free = true;
-        else if (over > 0) { const uint64_t k = policy_key(cv, tp, slot); lt = k < tau; eq = k == tau; }
-    }
+    const uint32_t eq_before = block_sum<TRIM_WAVES>(e, scan);
+    if (threadIdx.x == 0) n_push = 0;
+    const bool is_free = in && my_key == KEY_NONE;
+    const bool cached = in && my_key != KEY_NONE && over > 0;
+    const bool lt = cached && pk < tau, eq = cached && pk == tau;
     uint32_t tot_eq;
-    const uint32_t eq_rank = eq_before + block_excl_scan<TRIM_WAVES>(eq ? 1u : 0u, scan, tot_eq);
-    __syncthreads();
-    if (lt || (eq && eq_rank < take_eq)) victims[atomicAdd(&n_victims, 1u)] = slot;
-    __syncthreads();
-    const uint32_t nv = n_victims;
-    const int lanes = cv.geom.lanes;
-    const int group = threadIdx.x / lanes, gl = threadIdx.x % lanes, ngroups = TRIM_THREADS / lanes;
-    __shared__ uint32_t ev_base;
-    if (threadIdx.x == 0 && nv) ev_base = atomicAdd(&cv.ds->ev_n, nv);      // one append per workgroup
-    __syncthreads();
-    uint32_t dirty = 0;
-    for (uint32_t v = group; v < nv; v += ngroups) {
-        const uint32_t vs = victims[v];
-        const uint32_t key = cv.slot_key[vs];
-        const bool has_updates = cv.cc[vs] > cv.cs[vs];
-        if (has_updates) push_row<VEC>(cv, key, vs, gl);
-        if (gl == 0) {
-            dirty += has_updates ? 1u : 0u;
-            ht_erase(cv.ht, key);
-            tp.ev_ids[ev_base + v] = key;
+    const uint32_t eq_rank = eq_before + block_excl_scan<TRIM_WAVES>(eq ? 1u : 0u, scan, tot_eq);   // slot order
+    const bool victim = lt || (eq && eq_rank < take_eq);
+    const bool has_updates = victim && my_cc > my_cs;
+    if (victim) {
+        const uint32_t cg = has_updates ? cv.Cg[my_key] : 0u;                  // in flight together with the erase's loads
+        ht_erase(cv.ht, my_key);
+        cv.slot_key[slot] = KEY_NONE;
+        if (has_updates) {
+            if (my_cc > cg) cv.Cg[my_key] = my_cc;                             // c_g = max(c_g, c_c)
+            const uint32_t at = atomicAdd(&n_push, 1u);
+            v_slot[at] = slot; v_key[at] = my_key;
         }
     }
-    __syncthreads();
-    for (uint32_t v = threadIdx.x; v < nv; v += TRIM_THREADS) cv.slot_key[victims[v]] = KEY_NONE;
-    dirty = block_sum<TRIM_WAVES>(dirty, scan);
+    const uint32_t nv = block_sum<TRIM_WAVES>(victim ? 1u : 0u, scan);
     const uint32_t free_here = block_sum<TRIM_WAVES>(is_free ? 1u : 0u, scan);
+    if (threadIdx.x == 0 && nv) ev_base = atomicAdd(&cv.ds->ev_n, nv);          // one append per workgroup
+    uint32_t dummy;
+    const uint32_t ev_at = block_excl_scan<TRIM_WAVES>(victim ? 1u : 0u, scan, dummy);
+    if (victim) tp.ev_ids[ev_base + ev_at] = my_key;
+    const uint32_t np = n_push;
+    const int lanes = cv.geom.lanes;
+    const int group = threadIdx.x / lanes, gl = threadIdx.x % lanes, ngroups = TRIM_THREADS / lanes;
+    const RowGeom g = cv.geom;
+    for (uint32_t v = group; v < np; v += ngroups) {
+        const uint32_t vs = v_slot[v], vk = v_key[v];
+        row_copy<VEC>(cv.W + (size_t)vk * g.dim, cv.rows + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
+        if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)vk * g.dim, cv.acc + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
+    }
     if (threadIdx.x == 0) {
-        if (free_here + nv) atomicAdd(&tp.tile_free[tile], free_here + nv);
+        if (free_here + nv) atomicAdd(&tp.tile_free[blk * EV_SLOTS / TRIM_TILE], free_here + nv);
         count2(&cv.ds->last.evicted, &cv.ds->total.evicted, nv);
-        count2(&cv.ds->last.evicted_dirty, &cv.ds->total.evicted_dirty, dirty);
+        count2(&cv.ds->last.evicted_dirty, &cv.ds->total.evicted_dirty, np);
     }
 }
 
@@ -700,9 +864,9 @@ __global__ __launch_bounds__(256) void flush_kernel(CacheView cv)
     uint32_t pushed = 0;
     for (uint32_t slot = gid; slot < cv.n_slots; slot += ngroups) {
         const uint32_t key = cv.slot_key[slot];
-        if (key == KEY_NONE || cv.cc[slot] <= cv.cs[slot]) continue;
+        if (key == KEY_NONE || cv.meta[slot].cc <= cv.meta[slot].cs) continue;
         push_row<VEC>(cv, key, slot, gl);
-        if (gl == 0) { const uint32_t cg = cv.Cg[key]; cv.cs[slot] = cg; cv.cc[slot] = cg; ++pushed; }
+        if (gl == 0) { const uint32_t cg = cv.Cg[key]; cv.meta[slot].cs = cg; cv.meta[slot].cc = cg; ++pushed; }
     }
     pushed = block_sum<4>(pushed, lds);
     if (threadIdx.x == 0) count2(&cv.ds->last.flushed, &cv.ds->total.flushed, pushed);
@@ -718,7 +882,7 @@ __global__ __launch_bounds__(256) void init_cache_kernel(CacheView cv, uint32_t 
 {
     const uint32_t i0 = blockIdx.x * 256u + threadIdx.x, stride = gridDim.x * 256u;
     for (uint32_t i = i0; i < cv.n_slots; i += stride) {
-        cv.slot_key[i] = KEY_NONE; cv.cs[i] = 0; cv.cc[i] = 0; cv.last_use[i] = 0; cv.freq[i] = 0;
+        cv.slot_key[i] = KEY_NONE; store_meta(cv.meta, i, 0, 0, 0, 0);
     }
     for (uint32_t i = i0; i < cv.max_ids; i += stride) cv.free_list[i] = i;
     for (uint32_t i = i0; i < n_entries; i += stride) cv.ht.entries[i] = ENTRY_EMPTY;

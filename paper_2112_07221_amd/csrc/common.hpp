@@ -29,7 +29,9 @@ struct DState {
     uint32_t n_valid;    // ids of the current call that lie in [0, vocab)
     uint32_t err;        // sticky ERRBIT_*
     uint32_t ev_n;       // ids recorded by the current trim
-    uint32_t pad0, pad1;
+    uint32_t sel_take;   // trim: how many of the rows whose policy key equals sel_tau are evicted (in slot order)
+    uint32_t pad0;
+    unsigned long long sel_tau;   // trim: policy key of the last row to evict
     Counters last, total;
 };
 
@@ -97,12 +99,19 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *lds)
     return s;
 }
 
-// Sum of a[0 .. count) computed by the whole block (every thread gets it).
+// Sum of a[0 .. count) computed by the whole block (every thread gets it).  Loads go out eight
+// at a time per thread before anything is added.
 template <int NW>
 __device__ __forceinline__ uint32_t block_sum_array(const uint32_t *a, uint32_t count, uint32_t *lds)
 {
     uint32_t v = 0;
-    for (uint32_t i = threadIdx.x; i < count; i += NW * WAVE) v += a[i];
+    for (uint32_t i0 = threadIdx.x; i0 < count; i0 += 8 * NW * WAVE) {
+        uint32_t x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const uint32_t i = i0 + u * NW * WAVE; x[u] = i < count ? a[i] : 0u; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v += x[u];
+    }
     return block_sum<NW>(v, lds);
 }
 

@@ -72,8 +72,20 @@ __device__ __forceinline__ bool ht_insert(const HashTable &ht, uint32_t key, uin
     for (uint32_t d = 0; d <= ht.bucket_mask; ++d) {
         const uint32_t b = (h + d) & ht.bucket_mask;
         unsigned long long *line = reinterpret_cast<unsigned long long *>(ht.entries + (size_t)b * BUCKET_ENTRIES);
-        for (int q = 0; q < BUCKET_ENTRIES; ++q) {
-            if (line[q] != ENTRY_EMPTY) continue;
+        // one look at the whole bucket, then claim empty entries in order until one claim holds
+        const uint4 *line4 = reinterpret_cast<const uint4 *>(line);
+        uint4 v[BUCKET_ENTRIES / 2];
+#pragma unroll
+        for (int q = 0; q < BUCKET_ENTRIES / 2; ++q) v[q] = line4[q];
+        uint32_t empties = 0;
+#pragma unroll
+        for (int q = 0; q < BUCKET_ENTRIES / 2; ++q) {
+            if ((v[q].x & v[q].y) == 0xFFFFFFFFu) empties |= 1u << (2 * q);
+            if ((v[q].z & v[q].w) == 0xFFFFFFFFu) empties |= 1u << (2 * q + 1);
+        }
+        while (empties) {
+            const int q = __ffs(empties) - 1;
+            empties &= empties - 1;
             if (atomicCAS(&line[q], (unsigned long long)ENTRY_EMPTY, (unsigned long long)e) == ENTRY_EMPTY) {
                 if (d) atomicMax(&ht.reach[h], d);
                 return true;

@@ -160,7 +160,7 @@ SortPlan make_sort_plan(const het_cache *c, uint32_t n)
     const int bits = bit_width(sp.vocab);               // the key `vocab` itself marks a bad id
     sp.passes = std::max(1, (bits + SORT_MAX_BITS - 1) / SORT_MAX_BITS);
     sp.width = std::max(2, (bits + sp.passes - 1) / sp.passes);      // the pass kernel reads four digits' counts at a time
-    const int items = n <= 64u * 2048u ? 8 : (n <= 64u * 4096u ? 16 : 32);   // keep the tile count small
+    const int items = n <= 32u * 4096u ? 8 : (n <= 32u * 8192u ? 16 : 32);   // keep the tile count small
     sp.tile = SORT_THREADS * items;
     sp.ntiles = cdiv(n, sp.tile);
     for (int p = 0; p < SORT_MAX_PASSES; ++p) sp.hist[p] = c->sort_hist[p];
@@ -196,7 +196,7 @@ int dedup_and_probe(het_cache *c, const int64_t *ids, uint32_t n, bool reset_las
     if (sp.tile == SORT_THREADS * 8) launch_sort<8>(c, ids, sp, flags);
     else if (sp.tile == SORT_THREADS * 16) launch_sort<16>(c, ids, sp, flags);
     else launch_sort<32>(c, ids, sp, flags);
-    LAUNCH(c, K_PROBE, probe_kernel<LOOKUP><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n));
+    LAUNCH(c, K_PROBE, probe_kernel<LOOKUP><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
     return launch_ok();
 }
 
@@ -209,6 +209,7 @@ int run_trim(het_cache *c, bool prepared = false)
     tp.key_bits = tp.lfu ? 2 * tp.bits : tp.bits;
     tp.passes = (tp.key_bits + SEL_BITS - 1) / SEL_BITS;
     tp.tile_free = c->tile_free[c->tile_free_cur];
+    tp.sup_eq = tp.hist + SEL_MAX_PASSES * SEL_BINS;
     uint32_t *tile_free_next = c->tile_free[1 - c->tile_free_cur];
     c->tile_free_cur = 1 - c->tile_free_cur;
     const uint32_t stiles = cdiv(c->cv.n_slots, TRIM_TILE);
@@ -216,7 +217,7 @@ int run_trim(het_cache *c, bool prepared = false)
     if (!prepared) LAUNCH(c, K_TRIM_BEGIN, trim_begin_kernel<<<4, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
     for (int p = 0; p < tp.passes; ++p)
         LAUNCH(c, K_TRIM_HIST, trim_hist_kernel<<<hist_blocks, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, p));
-    LAUNCH(c, K_TRIM_COUNT, trim_count_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    LAUNCH(c, K_TRIM_COUNT, trim_count_kernel<<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
     LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC><<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
     LAUNCH(c, K_TRIM_FREE, trim_free_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, tile_free_next));
     c->overflow_pending = false;
@@ -236,13 +237,14 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     }
     if ((rc = dedup_and_probe<true>(c, ids, n, !pre_trim)) != HET_OK) return rc;
     const uint32_t ptiles = cdiv(n, PT_TILE);
+    const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 1024u);     // they come first: theirs is the longer chain
     if (!offsets) {
-        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, ptiles, out, nullptr, 0, nullptr));
+        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<fill_blocks + row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
+                                     c->cv, c->ws, n, ptiles, fill_blocks, out, nullptr, 0, nullptr));
     } else {
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
-        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<row_grid(c->cv.geom, std::max(n_bags, n / 8)), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, ptiles, out, offsets, n_bags, c->inv));
+        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<fill_blocks + row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(
+                                     c->cv, c->ws, n, ptiles, fill_blocks, out, offsets, n_bags, c->inv));
     }
     c->overflow_pending = true;
     c->last_lookup_n = n;
@@ -258,8 +260,7 @@ void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, con
         LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
     else
         LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, c->tp.hist,
-                                                                                          (uint32_t)(SEL_MAX_PASSES * SEL_BINS)));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n, c->tp.hist, c->tp.zero_words));
 }
 
 template <int VEC>
@@ -345,9 +346,7 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     const size_t row_elems = (size_t)P * (size_t)c->dim;
     if ((rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
     if (cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
-    if ((rc = dev_alloc(c, &cv.slot_key, P)) || (rc = dev_alloc(c, &cv.cs, P)) || (rc = dev_alloc(c, &cv.cc, P)) ||
-        (rc = dev_alloc(c, &cv.last_use, P)) || (rc = dev_alloc(c, &cv.freq, P)))
-        return rc;
+    if ((rc = dev_alloc(c, &cv.slot_key, P)) || (rc = dev_alloc(c, &cv.meta, P))) return rc;
     if ((rc = dev_alloc(c, &cv.free_list, (size_t)max_batch_ids))) return rc;
     if ((rc = dev_alloc(c, &cv.ds, 1))) return rc;
     // hash table: at most a quarter of the entries are ever used
@@ -362,7 +361,7 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     Workspace &ws = c->ws;
     const size_t N = (size_t)max_batch_ids;
     const size_t ptiles = cdiv(N, PT_TILE);
-    const size_t sort_tiles = std::max<size_t>(64, cdiv(N, SORT_THREADS * 32));
+    const size_t sort_tiles = std::max<size_t>(32, cdiv(N, SORT_THREADS * 32));
     const size_t chunks = cdiv(N, CHUNK);
     for (int i = 0; i < 2; ++i)
         if ((rc = dev_alloc(c, &c->keys[i], N)) || (rc = dev_alloc(c, &c->idx[i], N))) return rc;
@@ -372,11 +371,12 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
         (rc = dev_alloc(c, &ws.tile_miss, ptiles)) || (rc = dev_alloc(c, &ws.tile_stale, ptiles)) ||
         (rc = dev_alloc(c, &ws.miss_stage, ptiles * PT_TILE)) || (rc = dev_alloc(c, &ws.stale_stage, ptiles * PT_TILE)) ||
         (rc = dev_alloc(c, &c->inv, N)) || (rc = dev_alloc(c, &ws.bag_of, N)) ||
-        (rc = dev_alloc(c, &ws.partial, chunks * 2 * (size_t)c->dim)))
+        (rc = dev_alloc(c, &ws.partial, chunks * 2 * (size_t)c->dim)) || (rc = dev_alloc(c, &ws.cross_slot, chunks)))
         return rc;
-    const size_t slot_tiles = cdiv(P, TRIM_TILE);
-    if ((rc = dev_alloc(c, &c->tp.hist, (size_t)SEL_MAX_PASSES * SEL_BINS)) ||
-        (rc = dev_alloc(c, &c->tp.tile_eq, slot_tiles)) || (rc = dev_alloc(c, &c->tile_free[0], slot_tiles)) ||
+    const size_t slot_tiles = cdiv(P, TRIM_TILE), ev_blocks = cdiv(P, EV_SLOTS), ev_supers = cdiv(ev_blocks, EV_SUPER);
+    c->tp.zero_words = (uint32_t)(SEL_MAX_PASSES * SEL_BINS + ev_supers);
+    if ((rc = dev_alloc(c, &c->tp.hist, (size_t)c->tp.zero_words)) || (rc = dev_alloc(c, &c->tp.blk_eq, ev_blocks)) ||
+        (rc = dev_alloc(c, &c->tile_free[0], slot_tiles)) ||
         (rc = dev_alloc(c, &c->tile_free[1], slot_tiles)) || (rc = dev_alloc(c, &c->tp.ev_ids, P)))
         return rc;
     HIP_TRY(hipMemsetAsync(c->tile_free[0], 0, slot_tiles * sizeof(uint32_t), c->stream));
@@ -487,21 +487,19 @@ int het_export_state(het_cache *c, int64_t *keys, int32_t *slots, uint32_t *cs, 
     if (!c || !c->configured) return HET_EINVAL;
     HIP_TRY(hipStreamSynchronize(c->stream));
     const size_t P = c->cv.n_slots;
-    std::vector<uint32_t> k(P), a(P), b(P), l(P), f(P);
+    std::vector<uint32_t> k(P);
+    std::vector<SlotMeta> m(P);
     HIP_TRY(hipMemcpy(k.data(), c->cv.slot_key, P * 4, hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(a.data(), c->cv.cs, P * 4, hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(b.data(), c->cv.cc, P * 4, hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(l.data(), c->cv.last_use, P * 4, hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(f.data(), c->cv.freq, P * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(m.data(), c->cv.meta, P * sizeof(SlotMeta), hipMemcpyDeviceToHost));
     int64_t r = 0;
     for (size_t slot = 0; slot < P; ++slot) {
         if (k[slot] == KEY_NONE) continue;
         if (keys) keys[r] = k[slot];
         if (slots) slots[r] = (int32_t)slot;
-        if (cs) cs[r] = a[slot];
-        if (cc) cc[r] = b[slot];
-        if (last_use) last_use[r] = l[slot];
-        if (freq) freq[r] = f[slot];
+        if (cs) cs[r] = m[slot].cs;
+        if (cc) cc[r] = m[slot].cc;
+        if (last_use) last_use[r] = m[slot].last_use;
+        if (freq) freq[r] = m[slot].freq;
         ++r;
     }
     if (n_resident) *n_resident = r;

@@ -18,7 +18,7 @@
 
 namespace het {
 
-constexpr int SORT_THREADS = 256;
+constexpr int SORT_THREADS = 512;
 constexpr int SORT_WAVES = SORT_THREADS / WAVE;
 constexpr int SORT_MAX_BITS = 11;
 constexpr int SORT_MAX_BINS = 1 << SORT_MAX_BITS;
@@ -103,6 +103,15 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_pass_kernel(const int64_t *
     const uint32_t shift = (uint32_t)(pass * width);
     const bool last = pass + 1 == sp.passes;
 
+    // the keys (and payload) of this tile: issued first, they arrive while the offsets are computed
+    uint32_t key[ITEMS], pay[ITEMS], lrank[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const uint32_t i = sort_pos<ITEMS>(tile, it);
+        const bool valid = i < sp.n;
+        key[it] = valid ? (FIRST ? id_to_key(ids[i], sp.vocab) : keys_in[i]) : 0u;
+        pay[it] = FIRST ? i : (valid ? idx_in[i] : 0u);
+    }
     for (uint32_t b = threadIdx.x; b < SORT_WAVES * SORT_MAX_BINS; b += SORT_THREADS) (&wave_hist[0][0])[b] = 0;
 
     // Output offset of each digit for this tile: keys of smaller digits anywhere, plus keys of
@@ -118,11 +127,20 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_pass_kernel(const int64_t *
         for (uint32_t item = threadIdx.x; item < quads * tln; item += SORT_THREADS) {
             const uint32_t bq = item % quads, tl = item / quads;
             uint4 t4 = make_uint4(0, 0, 0, 0), f4 = make_uint4(0, 0, 0, 0);
-#pragma unroll 8
-            for (uint32_t t = tl; t < sp.ntiles; t += tln) {
-                const uint4 v = h4[(size_t)t * quads + bq];
-                t4.x += v.x; t4.y += v.y; t4.z += v.z; t4.w += v.w;
-                if (t < tile) { f4.x += v.x; f4.y += v.y; f4.z += v.z; f4.w += v.w; }
+            // sixteen tiles at a time, every load issued before the first add
+            for (uint32_t t0 = tl; t0 < sp.ntiles; t0 += 16 * tln) {
+                uint4 v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const uint32_t t = t0 + u * tln;
+                    v[u] = t < sp.ntiles ? h4[(size_t)t * quads + bq] : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const uint32_t t = t0 + u * tln;
+                    t4.x += v[u].x; t4.y += v[u].y; t4.z += v[u].z; t4.w += v[u].w;
+                    if (t < tile) { f4.x += v[u].x; f4.y += v[u].y; f4.z += v[u].z; f4.w += v[u].w; }
+                }
             }
             const uint32_t b = bq * 4;
             if (tln == 1) {
@@ -155,13 +173,11 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_pass_kernel(const int64_t *
     }
     __syncthreads();
 
-    uint32_t key[ITEMS], lrank[ITEMS];
     volatile uint32_t *my_hist = wave_hist[w];
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         const uint32_t i = sort_pos<ITEMS>(tile, it);
         const bool valid = i < sp.n;
-        key[it] = valid ? (FIRST ? id_to_key(ids[i], sp.vocab) : keys_in[i]) : 0u;
         const uint32_t d = (key[it] >> shift) & mask;
         uint64_t peers = __ballot(valid);
 #pragma unroll
@@ -198,7 +214,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_pass_kernel(const int64_t *
             const uint32_t d = (key[it] >> shift) & mask;
             const uint32_t pos = wave_hist[w][d] + lrank[it];
             keys_out[pos] = key[it];
-            idx_out[pos] = FIRST ? i : idx_in[i];
+            idx_out[pos] = pay[it];
             if (next) atomicAdd(&next[(size_t)(pos / sp.tile) * bins + ((key[it] >> (shift + width)) & mask)], 1u);
         }
     }
