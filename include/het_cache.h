@@ -13,8 +13,9 @@
  *   - Every function returns an int status: HET_OK (0) or a negative het_status.
  *   - "device" pointers are HIP device allocations of the current device, owned by the caller
  *     and only borrowed for the duration stated; "host" pointers are ordinary host memory.
- *   - het_lookup* / het_update* only enqueue work on the configured stream and return; their
- *     results are valid in stream order.  het_flush, het_stats, het_export_*, het_last_* and
+ *   - het_lookup* / het_update* only enqueue work and return; their results are valid in the
+ *     order of the configured stream.  (Internally a second stream carries work that does not
+ *     depend on the caller's data order; it is joined to the configured stream by events.)  het_flush, het_stats, het_export_*, het_last_* and
  *     het_cache_destroy wait for the stream.
  *   - Errors the host can see (NULL, sizes out of range, wrong call order) are returned at
  *     once and change nothing.  Errors only the device can see (an id outside [0, vocab), an
@@ -114,6 +115,16 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
  * overflow it left is trimmed first.
  */
 int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out);
+
+/*
+ * Optional: announces the ids of the NEXT lookup so that their sort (the dedup of Algorithm 1)
+ * runs on an internal side stream next to the calls in between, typically the current update
+ * (Section 4.2: the indices of the next minibatch are fetched in advance).  ids[n] must be
+ * complete in stream order at the time of this call and must stay unchanged until the lookup
+ * that passes the same pointer and n; that lookup then skips its sort.  Results are identical
+ * with and without the announcement; a lookup with other ids simply ignores it.
+ */
+int het_prefetch(het_cache *c, const int64_t *ids, int64_t n);
 
 /*
  * Pooled Read for multi-hot inputs: bag b holds ids[offsets[b] .. offsets[b+1]) and

@@ -46,6 +46,8 @@ struct CacheView {
     HashTable ht;
     uint32_t *free_list;  // free slots in ascending order (first max_ids of them)
     DState *ds;
+    Counters *last;       // this call's counters (one of ds->call)
+    Counters *next_call;  // the other one: cleared by this call for the next
     RowGeom geom;
     int adagrad;
 };
@@ -97,12 +99,20 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
     const uint32_t j = tile * PT_TILE + threadIdx.x;
     DState *ds = cv.ds;
 
+    if (tile == 0 && threadIdx.x == 0) {                      // this call's bookkeeping
+        Counters z{};
+        *cv.next_call = z;
+        cv.last->n = n;
+        atomicAdd(&ds->total.n, (unsigned long long)n);
+        if (LOOKUP) ds->t = t_now;
+    }
     bool head = false, miss = false, stale = false, hit = false, absent = false;
     if (j < n) {
         const uint32_t key = ws.skey[j];
         if (key == vocab) {                                   // id outside the vocabulary
             if (LOOKUP) ws.src[j] = SRC_ZERO;
             ws.head_slot[j] = SLOT_NONE;
+            if (j == 0) ds->n_valid = 0;                      // not one valid id in the call
         } else {
             head = j == 0 || ws.skey[j - 1] != key;
             if (j + 1 == n || ws.skey[j + 1] == vocab) ds->n_valid = j + 1;    // one writer: the last valid position
@@ -148,16 +158,16 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         if (threadIdx.x == 0) {
             ws.tile_miss[tile] = tot_miss;
             ws.tile_stale[tile] = tot_stale;
-            count2(&ds->last.hit, &ds->total.hit, tot_hit);
-            count2(&ds->last.stale, &ds->total.stale, tot_stale);
-            count2(&ds->last.miss, &ds->total.miss, tot_miss);
-            count2(&ds->last.unique, &ds->total.unique, tot_heads);
+            count2(&cv.last->hit, &ds->total.hit, tot_hit);
+            count2(&cv.last->stale, &ds->total.stale, tot_stale);
+            count2(&cv.last->miss, &ds->total.miss, tot_miss);
+            count2(&cv.last->unique, &ds->total.unique, tot_heads);
             if (tot_miss) atomicAdd(&ds->size, (int32_t)tot_miss);
         }
     } else {
         if (__any(absent) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_STATE);
         const uint32_t tot_heads = block_sum<PT_WAVES>(head ? 1u : 0u, lds);
-        if (threadIdx.x == 0) count2(&ds->last.unique, &ds->total.unique, tot_heads);
+        if (threadIdx.x == 0) count2(&cv.last->unique, &ds->total.unique, tot_heads);
     }
 }
 
@@ -217,7 +227,7 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // workgroups fetch, the others gather, side by side.
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
 template <int VEC, bool POOLED>
-__global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t ptiles, uint32_t fill_blocks,
+__global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv)
 {
@@ -233,8 +243,8 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         const uint32_t tot_stale = tile_prefix_to_lds<4>(ws.tile_stale, ptiles, pre_stale, scan);
         const uint32_t gid = blockIdx.x * groups_per_block + threadIdx.x / g.lanes;
         const uint32_t ngroups = fill_blocks * groups_per_block;
-        const uint32_t t = cv.ds->t;
-        if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.ds->last.unique;   // for an update that reuses this order
+        const uint32_t t = t_now;
+        if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // for an update that reuses this order
         for (uint32_t m = gid; m < tot_miss; m += ngroups) {                 // Fetch(k) into a new slot
             const uint32_t tl = tile_of(pre_miss, ptiles, m);
             const uint2 jk = ws.miss_stage[tl * PT_TILE + (m - pre_miss[tl])];
@@ -260,7 +270,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             if (gl == 0) {
                 const uint32_t cg = cv.Cg[key];
                 cv.meta[slot].cs = cg; cv.meta[slot].cc = cg;
-                if (has_updates) count2(&cv.ds->last.stale_dirty, &cv.ds->total.stale_dirty, 1u);
+                if (has_updates) count2(&cv.last->stale_dirty, &cv.ds->total.stale_dirty, 1u);
             }
         }
         return;
@@ -368,8 +378,8 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         // this call did not sort: its per-call counters start here, with the lookup's key count
         DState *ds = cv.ds;
         Counters z{};
-        z.n = n_ids; z.unique = ds->n_unique;
-        ds->last = z;
+        *cv.next_call = z;
+        cv.last->n = n_ids; cv.last->unique = ds->n_unique;
         atomicAdd(&ds->total.n, (unsigned long long)n_ids);
         atomicAdd(&ds->total.unique, (unsigned long long)ds->n_unique);
         if (nv < n_ids) atomicOr(&ds->err, ERRBIT_RANGE);      // the order holds ids outside the vocabulary
@@ -499,12 +509,10 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 // A run spread over more than FIN_NEAR + 1 chunks (a very popular key) is summed by the whole
 // workgroup instead: every group adds a contiguous share of the partial sums in order, and the
 // shares are added in group order.  Either way the order of additions is fixed by the sorted
-// order alone.  The kernel also prepares the trim that follows (clears the select histograms
-// and the evicted-id count).
+// order alone.
 constexpr int FIN_NEAR = 4;
 template <int VEC, int MAXC>
-__global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
-                                                           uint32_t *trim_hist, uint32_t trim_hist_words)
+__global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids)
 {
     __shared__ uint32_t long_c[256], long_c1[256];
     __shared__ int32_t long_slot[256];
@@ -518,8 +526,6 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
     const uint32_t nchunks_max = (n_ids + CHUNK - 1) / CHUNK;
     const uint32_t *skey = ws.skey;
     const size_t pstride = (size_t)g.dim;
-    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < trim_hist_words; i += gridDim.x * 256u) trim_hist[i] = 0;
-    if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->ev_n = 0;
     if (threadIdx.x == 0) n_long = 0;
     __syncthreads();
 
@@ -644,6 +650,7 @@ struct TrimPlan {
     uint32_t *blk_eq, *sup_eq;         // rows tied at the threshold: per 256 slots, and per EV_SUPER such blocks
     uint32_t *tile_free;               // free slots per 1024-slot tile
     uint32_t *ev_ids;                  // ids dropped by this trim
+    int ev_slot;                       // which of the two evicted-id counts this trim appends to
 };
 
 __device__ __forceinline__ uint64_t policy_key(const TrimPlan &tp, const uint4 &meta)
@@ -701,7 +708,6 @@ __device__ __forceinline__ void sel_replay(const TrimPlan &tp, int upto, uint32_
 __global__ __launch_bounds__(TRIM_THREADS) void trim_begin_kernel(CacheView cv, TrimPlan tp)
 {
     for (uint32_t i = blockIdx.x * TRIM_THREADS + threadIdx.x; i < tp.zero_words; i += gridDim.x * TRIM_THREADS) tp.hist[i] = 0;
-    if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->ev_n = 0;
 }
 
 // One histogram pass of the select over the rows whose key matches the prefix chosen so far.
@@ -805,7 +811,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     }
     const uint32_t nv = block_sum<TRIM_WAVES>(victim ? 1u : 0u, scan);
     const uint32_t free_here = block_sum<TRIM_WAVES>(is_free ? 1u : 0u, scan);
-    if (threadIdx.x == 0 && nv) ev_base = atomicAdd(&cv.ds->ev_n, nv);          // one append per workgroup
+    if (threadIdx.x == 0 && nv) ev_base = atomicAdd(&cv.ds->ev_n[tp.ev_slot], nv);          // one append per workgroup
     uint32_t dummy;
     const uint32_t ev_at = block_excl_scan<TRIM_WAVES>(victim ? 1u : 0u, scan, dummy);
     if (victim) tp.ev_ids[ev_base + ev_at] = my_key;
@@ -820,8 +826,8 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     }
     if (threadIdx.x == 0) {
         if (free_here + nv) atomicAdd(&tp.tile_free[blk * EV_SLOTS / TRIM_TILE], free_here + nv);
-        count2(&cv.ds->last.evicted, &cv.ds->total.evicted, nv);
-        count2(&cv.ds->last.evicted_dirty, &cv.ds->total.evicted_dirty, np);
+        count2(&cv.last->evicted, &cv.ds->total.evicted, nv);
+        count2(&cv.last->evicted_dirty, &cv.ds->total.evicted_dirty, np);
     }
 }
 
@@ -833,6 +839,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_free_kernel(CacheView cv, T
     const uint32_t tile = blockIdx.x;
     if (tile == 0 && threadIdx.x == 0 && cv.ds->size > (int32_t)cv.capacity) cv.ds->size = (int32_t)cv.capacity;
     if (threadIdx.x == 0) tile_free_next[tile] = 0;
+    if (tile == 0 && threadIdx.x == 0) cv.ds->ev_n[1 - tp.ev_slot] = 0;
     const uint32_t before = block_sum_array<TRIM_WAVES>(tp.tile_free, tile, scan);
     if (before >= cv.max_ids) return;
     uint32_t mine = 0;
@@ -869,12 +876,8 @@ __global__ __launch_bounds__(256) void flush_kernel(CacheView cv)
         if (gl == 0) { const uint32_t cg = cv.Cg[key]; cv.meta[slot].cs = cg; cv.meta[slot].cc = cg; ++pushed; }
     }
     pushed = block_sum<4>(pushed, lds);
-    if (threadIdx.x == 0) count2(&cv.ds->last.flushed, &cv.ds->total.flushed, pushed);
-}
-
-__global__ void reset_last_kernel(DState *ds)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) { Counters z{}; ds->last = z; }
+    if (blockIdx.x == 0 && threadIdx.x == 0) { Counters z{}; *cv.next_call = z; }
+    if (threadIdx.x == 0) count2(&cv.last->flushed, &cv.ds->total.flushed, pushed);
 }
 
 // Initial free list (every slot free) and empty slots / hash table.

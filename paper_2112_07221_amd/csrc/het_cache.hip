@@ -44,11 +44,26 @@ struct het_cache {
     CacheView cv{};
     Workspace ws{};
     TrimPlan tp{};
-    uint32_t *keys[2] = {nullptr, nullptr}, *idx[2] = {nullptr, nullptr};
-    uint32_t *sort_hist[SORT_MAX_PASSES] = {nullptr, nullptr, nullptr};
+    // two complete sets of sort buffers: the order of the current batch stays intact for the
+    // update while the next batch is sorted into the other set
+    uint32_t *keys[2][2] = {}, *idx[2][2] = {};
+    uint32_t *sort_hist[2][SORT_MAX_PASSES] = {};
+    int sort_set = 0;                // the set that holds the current batch's order
+    // side stream: the next batch's sort and the trim's select run beside the main stream
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_sort = nullptr, ev_lookup = nullptr, ev_select = nullptr;
+    const int64_t *prefetch_ids = nullptr;   // ids sorted ahead of their lookup by het_prefetch
+    uint32_t prefetch_n = 0;
+    bool prefetched = false;
+    int prefetch_buf = 0;
+    bool select_pending = false;     // the victims' threshold for the rows now cached has been computed
+    bool select_on_side = false;
+    TrimPlan sel_tp{};               // the plan that select used; the eviction must use the same
+    int cslot = 0;                   // which of the two per-call counter blocks the current call uses
     uint32_t *inv = nullptr;
     uint32_t *tile_free[2] = {nullptr, nullptr};   // alternate between trims: one in use, one being cleared
     int tile_free_cur = 0;
+    uint32_t *ev_ids[2] = {nullptr, nullptr};      // evicted ids of the last two trims, alternating like tile_free
     uint32_t n_buckets = 0;
     int max_chunks_per_lane = 1;     // row chunks one lane handles in the apply kernel
     std::vector<void *> owned;       // every device allocation, for destroy
@@ -118,25 +133,27 @@ struct LaunchScope {
     het_cache *c;
     ProfSpan sp{};
     bool on;
-    LaunchScope(het_cache *cache, int id) : c(cache), on(cache->profiling)
+    hipStream_t st;
+    LaunchScope(het_cache *cache, int id, hipStream_t stream) : c(cache), on(cache->profiling), st(stream)
     {
         if (!on) return;
         sp.id = id;
         if (hipEventCreate(&sp.start) != hipSuccess || hipEventCreate(&sp.stop) != hipSuccess) { on = false; return; }
-        (void)hipEventRecord(sp.start, c->stream);
+        (void)hipEventRecord(sp.start, st);
     }
     ~LaunchScope()
     {
         if (!on) return;
-        (void)hipEventRecord(sp.stop, c->stream);
+        (void)hipEventRecord(sp.stop, st);
         c->spans.push_back(sp);
     }
 };
-#define LAUNCH(cache, id, ...)            \
-    do {                                  \
-        LaunchScope scope_(cache, id);    \
-        __VA_ARGS__;                      \
+#define LAUNCH_ON(cache, stream_, id, ...)         \
+    do {                                           \
+        LaunchScope scope_(cache, id, stream_);    \
+        __VA_ARGS__;                               \
     } while (0)
+#define LAUNCH(cache, id, ...) LAUNCH_ON(cache, (cache)->stream, id, __VA_ARGS__)
 
 int launch_ok()
 {
@@ -152,7 +169,7 @@ uint32_t row_grid(const RowGeom &g, uint64_t items)
     return std::max(1u, std::min(cdiv(items, per_block), 256u * 8u));      // at most 8 workgroups per CU
 }
 
-SortPlan make_sort_plan(const het_cache *c, uint32_t n)
+SortPlan make_sort_plan(const het_cache *c, uint32_t n, int set)
 {
     SortPlan sp{};
     sp.n = n;
@@ -163,63 +180,94 @@ SortPlan make_sort_plan(const het_cache *c, uint32_t n)
     const int items = n <= 32u * 4096u ? 8 : (n <= 32u * 8192u ? 16 : 32);   // keep the tile count small
     sp.tile = SORT_THREADS * items;
     sp.ntiles = cdiv(n, sp.tile);
-    for (int p = 0; p < SORT_MAX_PASSES; ++p) sp.hist[p] = c->sort_hist[p];
+    for (int p = 0; p < SORT_MAX_PASSES; ++p) sp.hist[p] = c->sort_hist[set][p];
     return sp;
 }
 
-template <int ITEMS>
-void launch_sort(het_cache *c, const int64_t *ids, const SortPlan &sp, int call_flags)
+// Begins a call that touches the cache: per-call counters go to the other counter block.
+void begin_call(het_cache *c)
 {
-    LAUNCH(c, K_DEDUP_HIST, dedup_hist_kernel<ITEMS><<<sp.ntiles, SORT_THREADS, 0, c->stream>>>(ids, sp, c->cv.ds, call_flags));
+    c->cslot = 1 - c->cslot;
+    c->cv.last = &c->cv.ds->call[c->cslot];
+    c->cv.next_call = &c->cv.ds->call[1 - c->cslot];
+}
+
+template <int ITEMS>
+void launch_sort(het_cache *c, hipStream_t st, const int64_t *ids, const SortPlan &sp, int set, int *result_buffer)
+{
+    LAUNCH_ON(c, st, K_DEDUP_HIST, dedup_hist_kernel<ITEMS><<<sp.ntiles, SORT_THREADS, 0, st>>>(ids, sp, c->cv.ds));
     int in = 0;
     for (int p = 0; p < sp.passes; ++p) {
         const int out = p == 0 ? 0 : 1 - in;
         if (p == 0)
-            LAUNCH(c, K_SORT_PASS, sort_pass_kernel<ITEMS, true><<<sp.ntiles, SORT_THREADS, 0, c->stream>>>(
-                                       ids, nullptr, nullptr, c->keys[out], c->idx[out], sp, p));
+            LAUNCH_ON(c, st, K_SORT_PASS, sort_pass_kernel<ITEMS, true><<<sp.ntiles, SORT_THREADS, 0, st>>>(
+                                              ids, nullptr, nullptr, c->keys[set][out], c->idx[set][out], sp, p));
         else
-            LAUNCH(c, K_SORT_PASS, sort_pass_kernel<ITEMS, false><<<sp.ntiles, SORT_THREADS, 0, c->stream>>>(
-                                       nullptr, c->keys[in], c->idx[in], c->keys[out], c->idx[out], sp, p));
+            LAUNCH_ON(c, st, K_SORT_PASS, sort_pass_kernel<ITEMS, false><<<sp.ntiles, SORT_THREADS, 0, st>>>(
+                                              nullptr, c->keys[set][in], c->idx[set][in], c->keys[set][out], c->idx[set][out], sp, p));
         in = out;
     }
-    c->ws.skey = c->keys[in];
-    c->ws.perm = c->idx[in];
+    *result_buffer = in;
 }
 
-// Sort of ids[n] and Find of every position; for a lookup also the classes and the staged miss
-// and stale lists.
-template <bool LOOKUP>
-int dedup_and_probe(het_cache *c, const int64_t *ids, uint32_t n, bool reset_last = true)
+// Sorts ids[n] into buffer set `set` on stream `st`; returns which buffer of the set holds the result.
+int sort_ids(het_cache *c, hipStream_t st, const int64_t *ids, uint32_t n, int set)
 {
-    const SortPlan sp = make_sort_plan(c, n);
-    const int flags = (LOOKUP ? CALL_BUMP_ITERATION : 0) | (reset_last ? CALL_RESET_LAST : 0);
-    if (sp.tile == SORT_THREADS * 8) launch_sort<8>(c, ids, sp, flags);
-    else if (sp.tile == SORT_THREADS * 16) launch_sort<16>(c, ids, sp, flags);
-    else launch_sort<32>(c, ids, sp, flags);
-    LAUNCH(c, K_PROBE, probe_kernel<LOOKUP><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
-    return launch_ok();
+    const SortPlan sp = make_sort_plan(c, n, set);
+    int buf = 0;
+    if (sp.tile == SORT_THREADS * 8) launch_sort<8>(c, st, ids, sp, set, &buf);
+    else if (sp.tile == SORT_THREADS * 16) launch_sort<16>(c, st, ids, sp, set, &buf);
+    else launch_sort<32>(c, st, ids, sp, set, &buf);
+    return buf;
 }
 
-template <int VEC>
-int run_trim(het_cache *c, bool prepared = false)
+void use_order(het_cache *c, int set, int buf)
+{
+    c->sort_set = set;
+    c->ws.skey = c->keys[set][buf];
+    c->ws.perm = c->idx[set][buf];
+}
+
+// The select of the trim (histogram passes and the tie count) for the rows cached right now.
+// It reads only policy counters and the row count, which an update does not change, so it can
+// run on the side stream as soon as the lookup is through.
+int run_select(het_cache *c, hipStream_t st)
 {
     TrimPlan tp = c->tp;
     tp.lfu = c->policy == HET_POLICY_LFU;
     tp.bits = std::max(1, bit_width(c->t_host));
     tp.key_bits = tp.lfu ? 2 * tp.bits : tp.bits;
     tp.passes = (tp.key_bits + SEL_BITS - 1) / SEL_BITS;
-    tp.tile_free = c->tile_free[c->tile_free_cur];
     tp.sup_eq = tp.hist + SEL_MAX_PASSES * SEL_BINS;
+    const uint32_t stiles = cdiv(c->cv.n_slots, TRIM_TILE);
+    const uint32_t hist_blocks = std::min(stiles, 1024u);
+    LAUNCH_ON(c, st, K_TRIM_BEGIN, trim_begin_kernel<<<4, TRIM_THREADS, 0, st>>>(c->cv, tp));
+    for (int p = 0; p < tp.passes; ++p)
+        LAUNCH_ON(c, st, K_TRIM_HIST, trim_hist_kernel<<<hist_blocks, TRIM_THREADS, 0, st>>>(c->cv, tp, p));
+    LAUNCH_ON(c, st, K_TRIM_COUNT, trim_count_kernel<<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, st>>>(c->cv, tp));
+    c->sel_tp = tp;
+    c->select_pending = true;
+    c->select_on_side = st != c->stream;
+    return launch_ok();
+}
+
+// Evict(): drops the overflow on the main stream, using the select computed before.
+template <int VEC>
+int run_trim(het_cache *c)
+{
+    int rc;
+    if (!c->select_pending && (rc = run_select(c, c->stream)) != HET_OK) return rc;
+    if (c->select_on_side) HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_select, 0));
+    TrimPlan tp = c->sel_tp;
+    tp.tile_free = c->tile_free[c->tile_free_cur];
+    tp.ev_slot = c->tile_free_cur;
+    tp.ev_ids = c->ev_ids[c->tile_free_cur];
     uint32_t *tile_free_next = c->tile_free[1 - c->tile_free_cur];
     c->tile_free_cur = 1 - c->tile_free_cur;
     const uint32_t stiles = cdiv(c->cv.n_slots, TRIM_TILE);
-    const uint32_t hist_blocks = std::min(stiles, 1024u);
-    if (!prepared) LAUNCH(c, K_TRIM_BEGIN, trim_begin_kernel<<<4, TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
-    for (int p = 0; p < tp.passes; ++p)
-        LAUNCH(c, K_TRIM_HIST, trim_hist_kernel<<<hist_blocks, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, p));
-    LAUNCH(c, K_TRIM_COUNT, trim_count_kernel<<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
     LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC><<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
     LAUNCH(c, K_TRIM_FREE, trim_free_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, tile_free_next));
+    c->select_pending = false;
     c->overflow_pending = false;
     c->order_valid = false;          // slots recorded for the sorted order may be gone now
     return launch_ok();
@@ -228,28 +276,43 @@ int run_trim(het_cache *c, bool prepared = false)
 template <int VEC>
 int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offsets, uint32_t n_bags, float *out)
 {
+    begin_call(c);
     c->t_host += 1;
     int rc;
-    const bool pre_trim = c->overflow_pending;                  // a Read that follows a Read
-    if (pre_trim) {
-        LAUNCH(c, K_MISC, reset_last_kernel<<<1, 64, 0, c->stream>>>(c->cv.ds));
-        if ((rc = run_trim<VEC>(c)) != HET_OK) return rc;
+    if (c->overflow_pending && (rc = run_trim<VEC>(c)) != HET_OK) return rc;   // a Read that follows a Read
+    // the sorted order: already made by het_prefetch on the side stream, or made here
+    const int set = 1 - c->sort_set;
+    if (c->prefetched && ids == c->prefetch_ids && n == c->prefetch_n) {
+        HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_sort, 0));
+        use_order(c, set, c->prefetch_buf);
+    } else {
+        if (c->prefetched) HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_sort, 0));   // an unused prefetch still owns the set
+        const int buf = sort_ids(c, c->stream, ids, n, set);
+        use_order(c, set, buf);
     }
-    if ((rc = dedup_and_probe<true>(c, ids, n, !pre_trim)) != HET_OK) return rc;
+    c->prefetched = false;
+    const uint32_t t_now = (uint32_t)c->t_host;
+    LAUNCH(c, K_PROBE, probe_kernel<true><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now));
     const uint32_t ptiles = cdiv(n, PT_TILE);
     const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 1024u);     // they come first: theirs is the longer chain
     if (!offsets) {
         LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<fill_blocks + row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, ptiles, fill_blocks, out, nullptr, 0, nullptr));
+                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, out, nullptr, 0, nullptr));
     } else {
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
         LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<fill_blocks + row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, ptiles, fill_blocks, out, offsets, n_bags, c->inv));
+                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, out, offsets, n_bags, c->inv));
     }
+    if ((rc = launch_ok()) != HET_OK) return rc;
+    // from here on the side stream may work out which rows the coming trim evicts
+    HIP_TRY(hipEventRecord(c->ev_lookup, c->stream));
+    HIP_TRY(hipStreamWaitEvent(c->side, c->ev_lookup, 0));
+    if ((rc = run_select(c, c->side)) != HET_OK) return rc;
+    HIP_TRY(hipEventRecord(c->ev_select, c->side));
     c->overflow_pending = true;
     c->last_lookup_n = n;
     c->order_ids = ids; c->order_n = n; c->order_valid = true;
-    return launch_ok();
+    return HET_OK;
 }
 
 template <int VEC, int MAXC>
@@ -260,18 +323,24 @@ void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, con
         LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
     else
         LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n, c->tp.hist, c->tp.zero_words));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n));
 }
 
 template <int VEC>
 int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offsets, uint32_t n_bags,
                const float *grads, float lr)
 {
+    begin_call(c);
     int rc;
     // The ids of the preceding lookup, passed again: reuse its sorted order (the apply kernel
-    // checks every id against it).  Anything else is sorted and probed afresh.
+    // checks every id against it).  Anything else is sorted and probed afresh, into the current
+    // set of sort buffers (a prefetch under way uses the other set).
     const bool reuse = c->order_valid && ids == c->order_ids && n == c->order_n;
-    if (!reuse && (rc = dedup_and_probe<false>(c, ids, n)) != HET_OK) return rc;
+    if (!reuse) {
+        const int buf = sort_ids(c, c->stream, ids, n, c->sort_set);
+        use_order(c, c->sort_set, buf);
+        LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
+    }
     const uint32_t *grad_row = nullptr;
     if (offsets) {
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
@@ -284,12 +353,20 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     default: launch_apply<VEC, 16>(c, reuse, ids, n, grads, grad_row, lr); break;
     }
     if ((rc = launch_ok()) != HET_OK) return rc;
-    return run_trim<VEC>(c, true);        // apply_finish_kernel has cleared the select histograms
+    return run_trim<VEC>(c);
+}
+
+int sync_all(het_cache *c)
+{
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    if (c->side) HIP_TRY(hipStreamSynchronize(c->side));
+    return HET_OK;
 }
 
 int sync_and_status(het_cache *c, DState *host_copy)
 {
-    HIP_TRY(hipStreamSynchronize(c->stream));
+    int rc0 = sync_all(c);
+    if (rc0) return rc0;
     DState h;
     HIP_TRY(hipMemcpy(&h, c->cv.ds, sizeof(DState), hipMemcpyDeviceToHost));
     if (host_copy) *host_copy = h;
@@ -363,10 +440,17 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     const size_t ptiles = cdiv(N, PT_TILE);
     const size_t sort_tiles = std::max<size_t>(32, cdiv(N, SORT_THREADS * 32));
     const size_t chunks = cdiv(N, CHUNK);
-    for (int i = 0; i < 2; ++i)
-        if ((rc = dev_alloc(c, &c->keys[i], N)) || (rc = dev_alloc(c, &c->idx[i], N))) return rc;
-    for (int p = 0; p < SORT_MAX_PASSES; ++p)
-        if ((rc = dev_alloc(c, &c->sort_hist[p], sort_tiles * SORT_MAX_BINS))) return rc;
+    for (int set = 0; set < 2; ++set) {
+        for (int i = 0; i < 2; ++i)
+            if ((rc = dev_alloc(c, &c->keys[set][i], N)) || (rc = dev_alloc(c, &c->idx[set][i], N))) return rc;
+        for (int p = 0; p < SORT_MAX_PASSES; ++p)
+            if ((rc = dev_alloc(c, &c->sort_hist[set][p], sort_tiles * SORT_MAX_BINS))) return rc;
+    }
+    HIP_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));       // default priority
+    for (hipEvent_t *e : {&c->ev_fork, &c->ev_sort, &c->ev_lookup, &c->ev_select})
+        HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    c->cv.last = &cv.ds->call[0];
+    c->cv.next_call = &cv.ds->call[1];
     if ((rc = dev_alloc(c, &ws.src, N)) || (rc = dev_alloc(c, &ws.head_slot, N)) || (rc = dev_alloc(c, &ws.cls, N)) ||
         (rc = dev_alloc(c, &ws.tile_miss, ptiles)) || (rc = dev_alloc(c, &ws.tile_stale, ptiles)) ||
         (rc = dev_alloc(c, &ws.miss_stage, ptiles * PT_TILE)) || (rc = dev_alloc(c, &ws.stale_stage, ptiles * PT_TILE)) ||
@@ -377,7 +461,7 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     c->tp.zero_words = (uint32_t)(SEL_MAX_PASSES * SEL_BINS + ev_supers);
     if ((rc = dev_alloc(c, &c->tp.hist, (size_t)c->tp.zero_words)) || (rc = dev_alloc(c, &c->tp.blk_eq, ev_blocks)) ||
         (rc = dev_alloc(c, &c->tile_free[0], slot_tiles)) ||
-        (rc = dev_alloc(c, &c->tile_free[1], slot_tiles)) || (rc = dev_alloc(c, &c->tp.ev_ids, P)))
+        (rc = dev_alloc(c, &c->tile_free[1], slot_tiles)) || (rc = dev_alloc(c, &c->ev_ids[0], P)) || (rc = dev_alloc(c, &c->ev_ids[1], P)))
         return rc;
     HIP_TRY(hipMemsetAsync(c->tile_free[0], 0, slot_tiles * sizeof(uint32_t), c->stream));
     HIP_TRY(hipMemsetAsync(c->tile_free[1], 0, slot_tiles * sizeof(uint32_t), c->stream));
@@ -407,6 +491,26 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
     c->cv.W = table; c->cv.A = state; c->cv.Cg = cg; c->cv.vocab = (uint32_t)vocab;
     c->location = location;
     c->attached = true;
+    return HET_OK;
+}
+
+int het_prefetch(het_cache *c, const int64_t *ids, int64_t n)
+{
+    if (!ready(c) || n < 0 || n > c->max_ids) return HET_EINVAL;
+    if (n == 0) return HET_OK;
+    if (!ids) return HET_EINVAL;
+    // The side stream starts after everything enqueued on the main stream so far: the ids are
+    // there, and the last readers of the buffer set it sorts into (the calls before the current
+    // batch's lookup) are among that work.
+    const int set = 1 - c->sort_set;
+    HIP_TRY(hipEventRecord(c->ev_fork, c->stream));
+    HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+    const int buf = sort_ids(c, c->side, ids, (uint32_t)n, set);
+    int rc = launch_ok();
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(c->ev_sort, c->side));
+    c->prefetch_ids = ids; c->prefetch_n = (uint32_t)n; c->prefetched = true;
+    c->prefetch_buf = buf;
     return HET_OK;
 }
 
@@ -450,7 +554,7 @@ int het_update_pooled(het_cache *c, const int64_t *ids, int64_t n, const int64_t
 int het_flush(het_cache *c)
 {
     if (!ready(c)) return HET_EINVAL;
-    LAUNCH(c, K_MISC, reset_last_kernel<<<1, 64, 0, c->stream>>>(c->cv.ds));
+    begin_call(c);
     const uint32_t grid = row_grid(c->cv.geom, c->cv.n_slots);
     if (c->cv.geom.vec == 4) LAUNCH(c, K_FLUSH, flush_kernel<4><<<grid, 256, 0, c->stream>>>(c->cv));
     else LAUNCH(c, K_FLUSH, flush_kernel<1><<<grid, 256, 0, c->stream>>>(c->cv));
@@ -465,9 +569,10 @@ int het_stats(het_cache *c, het_stats_t *out)
     DState h;
     int rc = sync_and_status(c, &h);
     if (rc == HET_EHIP) return rc;
-    to_public(h.last, &out->last);
+    to_public(h.call[c->cslot], &out->last);
     to_public(h.total, &out->total);
-    out->resident = h.size;
+    // between a lookup and its update the overflow is still cached; after a trim the count is the capacity at most
+    out->resident = c->overflow_pending ? h.size : std::min<int64_t>(h.size, c->capacity);
     out->iteration = h.t;
     out->error_bits = (int32_t)h.err;
     return HET_OK;
@@ -476,7 +581,7 @@ int het_stats(het_cache *c, het_stats_t *out)
 int het_clear_error(het_cache *c)
 {
     if (!c || !c->configured) return HET_EINVAL;
-    HIP_TRY(hipStreamSynchronize(c->stream));
+    { int rc0 = sync_all(c); if (rc0) return rc0; }
     HIP_TRY(hipMemset(&c->cv.ds->err, 0, sizeof(uint32_t)));
     return HET_OK;
 }
@@ -485,7 +590,7 @@ int het_export_state(het_cache *c, int64_t *keys, int32_t *slots, uint32_t *cs, 
                      uint32_t *freq, int64_t *n_resident)
 {
     if (!c || !c->configured) return HET_EINVAL;
-    HIP_TRY(hipStreamSynchronize(c->stream));
+    { int rc0 = sync_all(c); if (rc0) return rc0; }
     const size_t P = c->cv.n_slots;
     std::vector<uint32_t> k(P);
     std::vector<SlotMeta> m(P);
@@ -509,7 +614,7 @@ int het_export_state(het_cache *c, int64_t *keys, int32_t *slots, uint32_t *cs, 
 int het_export_rows(het_cache *c, float *rows, float *acc)
 {
     if (!c || !c->configured) return HET_EINVAL;
-    HIP_TRY(hipStreamSynchronize(c->stream));
+    { int rc0 = sync_all(c); if (rc0) return rc0; }
     const size_t P = c->cv.n_slots, D = (size_t)c->dim;
     std::vector<uint32_t> k(P);
     HIP_TRY(hipMemcpy(k.data(), c->cv.slot_key, P * 4, hipMemcpyDeviceToHost));
@@ -526,7 +631,7 @@ int het_export_rows(het_cache *c, float *rows, float *acc)
 int het_last_lookup(het_cache *c, int64_t *keys, int32_t *cls, int32_t *slots, int64_t *n_unique)
 {
     if (!c || !c->configured) return HET_EINVAL;
-    HIP_TRY(hipStreamSynchronize(c->stream));
+    { int rc0 = sync_all(c); if (rc0) return rc0; }
     const size_t n = c->last_lookup_n;
     std::vector<uint32_t> k(n);
     std::vector<int32_t> sl(n);
@@ -551,14 +656,16 @@ int het_last_lookup(het_cache *c, int64_t *keys, int32_t *cls, int32_t *slots, i
 int het_last_evicted(het_cache *c, int64_t *ids, int64_t *n)
 {
     if (!c || !c->configured) return HET_EINVAL;
-    HIP_TRY(hipStreamSynchronize(c->stream));
+    { int rc0 = sync_all(c); if (rc0) return rc0; }
     DState h;
     HIP_TRY(hipMemcpy(&h, c->cv.ds, sizeof(DState), hipMemcpyDeviceToHost));
-    std::vector<uint32_t> e(h.ev_n);
-    if (h.ev_n) HIP_TRY(hipMemcpy(e.data(), c->tp.ev_ids, (size_t)h.ev_n * 4, hipMemcpyDeviceToHost));
+    const int last = 1 - c->tile_free_cur;               // the trim before the upcoming one
+    const uint32_t ev_n = h.ev_n[last];
+    std::vector<uint32_t> e(ev_n);
+    if (ev_n) HIP_TRY(hipMemcpy(e.data(), c->ev_ids[last], (size_t)ev_n * 4, hipMemcpyDeviceToHost));
     for (size_t i = 0; i < e.size(); ++i)
         if (ids) ids[i] = e[i];
-    if (n) *n = (int64_t)h.ev_n;
+    if (n) *n = (int64_t)ev_n;
     return HET_OK;
 }
 
@@ -574,7 +681,7 @@ int het_profile_end(het_cache *c, double *total_ms, int64_t *launches, int32_t n
     if (!c || !c->profiling) return HET_EINVAL;
     c->profiling = false;
     int rc = HET_OK;
-    if (hipStreamSynchronize(c->stream) != hipSuccess) rc = HET_EHIP;
+    if (sync_all(c) != HET_OK) rc = HET_EHIP;
     for (int i = 0; i < n_kernels; ++i) {
         if (total_ms) total_ms[i] = 0.0;
         if (launches) launches[i] = 0;
@@ -600,7 +707,10 @@ int het_cache_destroy(het_cache *c)
 {
     if (!c) return HET_OK;
     int rc = HET_OK;
-    if (c->configured && hipStreamSynchronize(c->stream) != hipSuccess) rc = HET_EHIP;
+    if (c->configured && sync_all(c) != HET_OK) rc = HET_EHIP;
+    for (hipEvent_t e : {c->ev_fork, c->ev_sort, c->ev_lookup, c->ev_select})
+        if (e && hipEventDestroy(e) != hipSuccess) rc = HET_EHIP;
+    if (c->side && hipStreamDestroy(c->side) != hipSuccess) rc = HET_EHIP;
     for (void *p : c->owned)
         if (hipFree(p) != hipSuccess) rc = HET_EHIP;
     delete c;

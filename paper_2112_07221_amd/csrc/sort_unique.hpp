@@ -25,9 +25,6 @@ constexpr int SORT_MAX_BINS = 1 << SORT_MAX_BITS;
 constexpr int SORT_MAX_PASSES = 3;                       // vocab < 2^32
 constexpr int SORT_BINS_PER_THREAD = SORT_MAX_BINS / SORT_THREADS;
 
-constexpr int CALL_BUMP_ITERATION = 1;   // this call is a Read: advance the iteration counter
-constexpr int CALL_RESET_LAST = 2;       // start the per-call counters from zero
-
 struct SortPlan {
     uint32_t n;            // keys
     uint32_t vocab;
@@ -52,11 +49,11 @@ __device__ __forceinline__ uint32_t sort_pos(uint32_t tile_index, int it)
     return tile_index * (SORT_THREADS * ITEMS) + w * (WAVE * ITEMS) + it * WAVE + lane_id();
 }
 
-// First kernel of a call: digit histogram of pass 0 per tile, straight from the ids; flags ids
-// outside the vocabulary; clears the histograms the later passes count into; per-call counters.
+// First kernel of a sort: digit histogram of pass 0 per tile, straight from the ids; flags ids
+// outside the vocabulary; clears the histograms the later passes count into.  It touches no
+// cache state, so the sort of the next minibatch may run beside the current update.
 template <int ITEMS>
-__global__ __launch_bounds__(SORT_THREADS) void dedup_hist_kernel(const int64_t *__restrict__ ids, SortPlan sp, DState *ds,
-                                                                  int call_flags)
+__global__ __launch_bounds__(SORT_THREADS) void dedup_hist_kernel(const int64_t *__restrict__ ids, SortPlan sp, DState *ds)
 {
     __shared__ uint32_t hist[SORT_MAX_BINS];
     const uint32_t tile = blockIdx.x;
@@ -76,13 +73,6 @@ __global__ __launch_bounds__(SORT_THREADS) void dedup_hist_kernel(const int64_t 
         }
     }
     if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
-    if (tile == 0 && threadIdx.x == 0) {
-        if (call_flags & CALL_BUMP_ITERATION) ds->t += 1;
-        if (call_flags & CALL_RESET_LAST) { Counters z{}; ds->last = z; }
-        ds->last.n = sp.n;
-        ds->n_valid = 0;
-        atomicAdd(&ds->total.n, (unsigned long long)sp.n);
-    }
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) sp.hist[0][tile * bins + b] = hist[b];
 }

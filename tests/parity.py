@@ -53,8 +53,8 @@ class Pair:
             self.offsets = torch.from_numpy(self.offsets_np).to(dev)
 
     # -- one Read on both sides, compared
-    def lookup(self, ids_np, check_values=True, expect_rc=0):
-        ids = torch.from_numpy(ids_np).to(self.dev)
+    def lookup(self, ids_np, check_values=True, expect_rc=0, ids_dev=None):
+        ids = torch.from_numpy(ids_np).to(self.dev) if ids_dev is None else ids_dev
         if self.w.pooled:
             out = torch.full((self.w.batch, self.w.dim), float("nan"), device=self.dev)
             self.cache.lookup_pooled(ids, self.offsets, out)
@@ -73,9 +73,9 @@ class Pair:
             close(out.cpu().numpy(), want, "lookup output")
         return out
 
-    def update(self, ids_np, grads_np, lr=None):
+    def update(self, ids_np, grads_np, lr=None, ids_dev=None):
         lr = self.w.lr if lr is None else lr
-        ids = torch.from_numpy(ids_np).to(self.dev)
+        ids = torch.from_numpy(ids_np).to(self.dev) if ids_dev is None else ids_dev
         g = torch.from_numpy(grads_np).to(self.dev)
         if self.w.pooled:
             self.cache.update_pooled(ids, self.offsets, g, lr)
@@ -125,16 +125,20 @@ class Pair:
 
 
 def run_workload(w: wl.Workload, iters: int, state_every: int = 1, table=None, ids=None, grads=None,
-                 values_every: int = 0):
-    """Runs `iters` lookup+update iterations of workload `w` on both sides."""
+                 values_every: int = 0, prefetch: bool = False):
+    """Runs `iters` lookup+update iterations of workload `w` on both sides.  With `prefetch` the
+    ids of iteration t+1 are announced between lookup t and update t, as the benchmark does."""
     table = wl.table_init(w) if table is None else table
     ids = wl.IdStream(w).batches(iters) if ids is None else ids
     grads = wl.grad_pool(w) if grads is None else grads
     p = Pair(w, table)
     try:
+        ids_dev = torch.from_numpy(ids).to(p.dev) if prefetch else None
         for t in range(iters):
-            p.lookup(ids[t])
-            p.update(ids[t], grads[t % len(grads)])
+            p.lookup(ids[t], ids_dev=ids_dev[t] if prefetch else None)
+            if prefetch and t + 1 < iters:
+                p.cache.prefetch(ids_dev[t + 1])
+            p.update(ids[t], grads[t % len(grads)], ids_dev=ids_dev[t] if prefetch else None)
             if state_every and (t % state_every == 0 or t == iters - 1):
                 p.compare_state(values=bool(values_every) and t % values_every == 0)
                 p.compare_counters()

@@ -10,6 +10,31 @@ from parity import Pair, close, run_workload
 pytestmark = pytest.mark.gpu
 
 
+def test_prefetch_changes_nothing_and_an_unused_prefetch_is_harmless():
+    """Announcing the next ids only moves their sort to the side stream; a lookup with other ids
+    than the announced ones sorts for itself."""
+    w = wl.WORKLOADS[1].scaled(policy=wl.LFU, s=2)
+    run_workload(w, 25, state_every=1, values_every=5, prefetch=True)
+    ids_np = wl.IdStream(w).batches(4)
+    g = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        d = torch.from_numpy(ids_np).cuda()
+        p.lookup(ids_np[0], ids_dev=d[0])
+        p.cache.prefetch(d[3])                     # announced, never looked up next
+        p.update(ids_np[0], g[0], ids_dev=d[0])
+        p.lookup(ids_np[1], ids_dev=d[1])
+        p.update(ids_np[1], g[1], ids_dev=d[1])
+        p.cache.prefetch(d[2])
+        p.cache.prefetch(d[2])                     # twice is allowed
+        p.lookup(ids_np[2], ids_dev=d[2])
+        p.update(ids_np[2], g[2])                  # other buffer: sorted afresh
+        p.compare_state(values=True); p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_tiny_config_full_length():
     """Config 1 as stated: 10k ids, dim 16, 128 x 26 lookups, LRU cache of 1000, s = 10, SGD,
     100 iterations, every integer of the state compared after every iteration."""
@@ -42,9 +67,9 @@ def test_config2_shape_reduced():
 
 def test_config2_full_size():
     """Config 2 at full size in the launch configuration the benchmark times: 1M ids, dim 64,
-    4096 x 26 lookups, LFU cache of 100k, Adagrad."""
+    4096 x 26 lookups, LFU cache of 100k, Adagrad, the next batch's ids announced ahead."""
     w = wl.WORKLOADS[2].scaled(s=5)
-    st = run_workload(w, 24, state_every=6, values_every=12)
+    st = run_workload(w, 24, state_every=6, values_every=12, prefetch=True)
     assert st["total"]["stale"] > 0 and st["total"]["evicted"] > 0
 
 
