@@ -28,6 +28,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch (fetch + write) read from rocprofv3 FETCH_SIZE / WRITE_SIZE counters and
+# scaled by a 256 MiB device copy of the same run (profiles/config2_hbm_traffic.md).  Keyed by
+# (kernel, workload); a workload that was not measured reports null.
+MEASURED_TRAFFIC = {("apply_kernel", 2): 86.0e6}
+
 
 def algorithmic_bytes(w, c):
     """HBM bytes one step must move, from device counters `c` (per-step averages):
@@ -66,6 +71,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefetch", action="store_true", help="do not announce the next batch's ids")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy five times (a known-size reference for HBM counters)")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -116,6 +123,14 @@ def main():
         else:
             cache.update(ids[t], grads[t % w.grad_pool], w.lr)
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- warm-up (cold cache), then the timed region
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -144,17 +159,23 @@ def main():
     per_step["unique_lookup"] = per_step["unique"] / 2.0      # counted by lookup and by update
 
     # ---- per-kernel durations, HIP events around every launch (outside the timed region)
-    cache.profile_begin()
-    for t in range(W + K, total):
-        step(t)
-    prof = cache.profile_end()
-    kern = {k: {"avg_us": ms * 1e3 / cnt, "launches_per_step": cnt / args.profile_steps}
-            for k, (ms, cnt) in prof.items()}
-    per_step_us = {k: v["avg_us"] * v["launches_per_step"] for k, v in kern.items()}
-    candidates = [k for k in per_step_us if kernel_bytes(w, per_step, k) is not None]
-    dominant = max(candidates, key=lambda k: per_step_us[k])
-    dom_bytes = kernel_bytes(w, per_step, dominant)
-    achieved = dom_bytes / (kern[dominant]["avg_us"] * 1e-6) / 1e9
+    roofline, per_step_us = None, {}
+    if args.profile_steps > 0:
+        cache.profile_begin()
+        for t in range(W + K, total):
+            step(t)
+        prof = cache.profile_end()
+        kern = {k: {"avg_us": ms * 1e3 / cnt, "launches_per_step": cnt / args.profile_steps}
+                for k, (ms, cnt) in prof.items()}
+        per_step_us = {k: v["avg_us"] * v["launches_per_step"] for k, v in kern.items()}
+        candidates = [k for k in per_step_us if kernel_bytes(w, per_step, k) is not None]
+        dominant = max(candidates, key=lambda k: per_step_us[k])
+        dom_bytes = kernel_bytes(w, per_step, dominant)
+        achieved = dom_bytes / (kern[dominant]["avg_us"] * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                    "traffic": MEASURED_TRAFFIC.get((dominant, w.index)),
+                    "bytes_per_launch": dom_bytes, "avg_us": kern[dominant]["avg_us"]}
     step_bytes = algorithmic_bytes(w, per_step)
 
     result = {
@@ -175,9 +196,7 @@ def main():
         "step_hbm": {"algorithmic_bytes": step_bytes,
                      "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
-        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "bytes_per_launch": dom_bytes, "avg_us": kern[dominant]["avg_us"]},
+        "roofline": roofline,
         "kernels_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda x: -x[1])},
     }
     if host:
