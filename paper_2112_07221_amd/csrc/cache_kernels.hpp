@@ -86,14 +86,185 @@ __device__ __forceinline__ void count2(unsigned long long *a, unsigned long long
     if (v) { atomicAdd(a, (unsigned long long)v); atomicAdd(b, (unsigned long long)v); }
 }
 
+// ---- Evict(): policy trim ---------------------------------------------------------------------
+// The victims are the m = size - capacity cached rows smallest in (last_use, slot) [LRU] or
+// (freq, last_use, slot) [LFU].  A most-significant-digit radix select finds the policy key
+// tau of the m-th smallest row; rows below tau go, and of the rows equal to tau the first few in
+// slot order.  `bits` is the width of last_use / freq values (both are at most t).
+constexpr int SEL_BITS = 11;
+constexpr int SEL_BINS = 1 << SEL_BITS;
+constexpr int SEL_MAX_PASSES = 6;
+constexpr int TRIM_THREADS = 256;
+constexpr int TRIM_WAVES = TRIM_THREADS / WAVE;
+constexpr int TRIM_ITEMS = 4;
+constexpr int TRIM_TILE = TRIM_THREADS * TRIM_ITEMS;   // 1024 slots per counting tile
+
+struct TrimPlan {
+    int lfu;          // policy
+    int bits;         // bits per policy field
+    int key_bits;     // bits of the packed policy key
+    int passes;       // select passes
+    uint32_t *hist;   // [SEL_MAX_PASSES][SEL_BINS] followed by sup_eq: zeroed together before the first pass
+    uint32_t zero_words;
+    uint32_t *blk_eq, *sup_eq;         // rows tied at the threshold: per 256 slots, and per EV_SUPER such blocks
+    uint32_t *tile_free;               // free slots per 1024-slot tile
+    uint32_t *ev_ids;                  // ids dropped by this trim
+    int ev_slot;                       // which of the two evicted-id counts this trim appends to
+};
+
+__device__ __forceinline__ uint64_t policy_key(const TrimPlan &tp, const uint4 &meta)
+{
+    const uint64_t lu = meta.z;
+    return tp.lfu ? (((uint64_t)meta.w << tp.bits) | lu) : lu;
+}
+
+__device__ __forceinline__ int sel_shift(const TrimPlan &tp, int pass)
+{
+    const int sh = tp.key_bits - SEL_BITS * (pass + 1);
+    return sh < 0 ? 0 : sh;
+}
+__device__ __forceinline__ int sel_width(const TrimPlan &tp, int pass)
+{
+    const int hi = tp.key_bits - SEL_BITS * pass;       // bits not yet decided
+    return hi < SEL_BITS ? hi : SEL_BITS;
+}
+
+// Replays the select decisions of passes [0, upto): returns the key prefix chosen so far
+// (in the high bits of `prefix`) and how many victims remain to be found inside it.
+// Every thread of the block gets the same answer.
+__device__ __forceinline__ void sel_replay(const TrimPlan &tp, int upto, uint32_t m, uint64_t &prefix,
+                                           uint32_t &remaining, uint32_t *lds_pick, uint32_t *lds_scan)
+{
+    prefix = 0; remaining = m;
+    for (int p = 0; p < upto; ++p) {
+        const int width = sel_width(tp, p), bins = 1 << width;
+        uint32_t local[SEL_BINS / TRIM_THREADS];
+        uint32_t s = 0;
+#pragma unroll
+        for (int q = 0; q < SEL_BINS / TRIM_THREADS; ++q) {
+            const int b = threadIdx.x * (SEL_BINS / TRIM_THREADS) + q;
+            local[q] = b < bins ? tp.hist[p * SEL_BINS + b] : 0u;
+            s += local[q];
+        }
+        uint32_t tot;
+        uint32_t run = block_excl_scan<TRIM_WAVES>(s, lds_scan, tot);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < SEL_BINS / TRIM_THREADS; ++q) {
+            const int b = threadIdx.x * (SEL_BINS / TRIM_THREADS) + q;
+            // the digit whose cumulative count first reaches `remaining`
+            if (local[q] && run < remaining && remaining <= run + local[q]) { lds_pick[0] = (uint32_t)b; lds_pick[1] = run; }
+            run += local[q];
+        }
+        __syncthreads();
+        const uint32_t digit = lds_pick[0], below = lds_pick[1];
+        __syncthreads();
+        prefix |= (uint64_t)digit << sel_shift(tp, p);
+        remaining -= below;
+    }
+}
+
+// LDS of one select stage (a workgroup of TRIM_THREADS threads).
+struct TrimLds {
+    uint32_t bins[SEL_BINS];
+    uint32_t pick[2];
+    uint32_t scan[TRIM_WAVES + 1];
+};
+
+// One histogram pass of the select over the rows whose key matches the prefix chosen so far.
+// Runs in `nblocks` workgroups of TRIM_THREADS threads; `vblock` is this one's index.
+__device__ __forceinline__ void trim_hist_body(const CacheView &cv, const TrimPlan &tp, int pass, uint32_t vblock, uint32_t nblocks, TrimLds &l)
+{
+    const int32_t over = cv.ds->size - (int32_t)cv.capacity;
+    if (over <= 0) return;
+    uint64_t prefix; uint32_t remaining;
+    sel_replay(tp, pass, (uint32_t)over, prefix, remaining, l.pick, l.scan);
+    for (int b = threadIdx.x; b < SEL_BINS; b += TRIM_THREADS) l.bins[b] = 0;
+    __syncthreads();
+    const int shift = sel_shift(tp, pass), width = sel_width(tp, pass);
+    const int decided = shift + width;                 // bits above are fixed by the prefix
+    for (uint32_t slot = vblock * TRIM_THREADS + threadIdx.x; slot < cv.n_slots; slot += nblocks * TRIM_THREADS) {
+        const uint32_t sk = cv.slot_key[slot];
+        const uint4 m = load_meta(cv.meta, slot);
+        if (sk == KEY_NONE) continue;
+        const uint64_t k = policy_key(tp, m);
+        if (decided < 64 && (k >> decided) != (prefix >> decided)) continue;
+        atomicAdd(&l.bins[(uint32_t)(k >> shift) & ((1u << width) - 1u)], 1u);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < SEL_BINS; b += TRIM_THREADS)
+        if (l.bins[b]) atomicAdd(&tp.hist[pass * SEL_BINS + b], l.bins[b]);
+}
+
+// Last stage of the select: finds tau (replaying the passes) and counts, per block of 256
+// slots, the cached rows whose policy key equals tau; sup_eq adds these up per EV_SUPER blocks
+// (zero when the select starts).  One workgroup per 256 slots.
+constexpr int EV_SLOTS = 256;
+constexpr int EV_SUPER = 32;
+__device__ __forceinline__ void trim_count_body(const CacheView &cv, const TrimPlan &tp, uint32_t vblock, TrimLds &l)
+{
+    const int32_t over = cv.ds->size - (int32_t)cv.capacity;
+    if (vblock == 0 && threadIdx.x == 0) cv.ds->over = over;
+    if (over <= 0) return;
+    const uint32_t slot = vblock * EV_SLOTS + threadIdx.x;       // loads first: they overlap the replay
+    const bool cached = slot < cv.n_slots && cv.slot_key[slot] != KEY_NONE;
+    const uint64_t key = slot < cv.n_slots ? policy_key(tp, load_meta(cv.meta, slot)) : 0;
+    uint64_t tau; uint32_t take_eq;
+    sel_replay(tp, tp.passes, (uint32_t)over, tau, take_eq, l.pick, l.scan);
+    const uint32_t eq = block_sum<TRIM_WAVES>((cached && key == tau) ? 1u : 0u, l.scan);
+    if (threadIdx.x == 0) {
+        tp.blk_eq[vblock] = eq;
+        if (eq) atomicAdd(&tp.sup_eq[vblock / EV_SUPER], eq);
+        if (vblock == 0) { cv.ds->sel_tau = tau; cv.ds->sel_take = take_eq; }
+    }
+}
+
+// Stage `stage` of the select: the histogram passes first, then the count.  Kernels that have
+// nothing to do with the trim (the optimizer step) carry a stage in extra workgroups, because
+// at minibatch size a kernel boundary costs more than the stage's work.
+__device__ __forceinline__ void trim_stage_body(const CacheView &cv, const TrimPlan &tp, int stage, uint32_t vblock, uint32_t nblocks, TrimLds &l)
+{
+    if (stage < tp.passes) trim_hist_body(cv, tp, stage, vblock, nblocks, l);
+    else trim_count_body(cv, tp, vblock, l);
+}
+
+__global__ __launch_bounds__(TRIM_THREADS) void trim_stage_kernel(CacheView cv, TrimPlan tp, int stage)
+{
+    __shared__ TrimLds l;
+    trim_stage_body(cv, tp, stage, blockIdx.x, gridDim.x, l);
+}
+
+// Lists the free slots of one 1024-slot tile in ascending order behind those of the earlier
+// tiles (only the first max_ids are ever needed).  tile_free holds the free count of every
+// tile, left by the last trim; the idle twin of that array is cleared for the next trim.
+// Workgroup of PT_THREADS threads, one slot each.
+__device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle,
+                                               uint32_t tile, uint32_t *lds)
+{
+    if (threadIdx.x == 0) tile_free_idle[tile] = 0;
+    if (tile == 0 && threadIdx.x == 0) cv.ds->ev_n[ev_idle] = 0;
+    const uint32_t slot = tile * PT_TILE + threadIdx.x;
+    const bool fr = slot < cv.n_slots && cv.slot_key[slot] == KEY_NONE;
+    const uint32_t before = block_sum_array<PT_WAVES>(tile_free, tile, lds);
+    if (before >= cv.max_ids) return;
+    uint32_t tot;
+    const uint32_t pos = before + block_excl_scan<PT_WAVES>(fr ? 1u : 0u, lds, tot);
+    if (fr && pos < cv.max_ids) cv.free_list[pos] = slot;
+}
+
 // Find for every sorted position; at the head of every run of equal keys also CheckValid and
 // the policy's use count.  LOOKUP: classifies HIT / STALE / MISS, stages missed and stale keys
 // per tile for the fill kernel and tells the gather where each position's row comes from.
 // Otherwise (update that sorted its own ids): only resolves slots and flags keys not cached.
 template <bool LOOKUP>
-__global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now)
+__global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
+                                                           const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
+    if (blockIdx.x >= ptiles) {          // extra workgroups of a lookup: the free list for the fill kernel
+        free_list_body(cv, tile_free, tile_free_idle, ev_idle, blockIdx.x - ptiles, lds);
+        return;
+    }
     const uint32_t tile = blockIdx.x;
     const uint32_t vocab = cv.vocab;
     const uint32_t j = tile * PT_TILE + threadIdx.x;
@@ -228,13 +399,15 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
 template <int VEC, bool POOLED>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
-                                                          float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
+                                                          uint32_t *zero_from, uint32_t zero_words, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv)
 {
     using V = typename VecT<VEC>::type;
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
+    // the select of the coming trim counts into these
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < zero_words; i += gridDim.x * 256u) zero_from[i] = 0;
 
     if (blockIdx.x < fill_blocks) {
         __shared__ uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
@@ -365,13 +538,18 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 template <int VEC, int MAXC, bool VERIFY>
 __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, const int64_t *__restrict__ ids,
                                                     const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
-                                                    float lr, float eps, uint32_t n_ids)
+                                                    float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage)
 {
     using V = typename VecT<VEC>::type;
+    if (blockIdx.x >= work_blocks) {     // extra workgroups: a stage of the coming trim's select
+        __shared__ TrimLds tl;
+        trim_stage_body(cv, tp, stage, blockIdx.x - work_blocks, gridDim.x - work_blocks, tl);
+        return;
+    }
     const RowGeom g = cv.geom;
     const uint32_t gid = (blockIdx.x * 256u + threadIdx.x) / g.lanes;
     const int gl = threadIdx.x % g.lanes;
-    const uint32_t ngroups = gridDim.x * 256u / g.lanes;
+    const uint32_t ngroups = work_blocks * 256u / g.lanes;
     const uint32_t nv = cv.ds->n_valid;
     const uint32_t *skey = ws.skey;
     if (VERIFY && blockIdx.x == 0 && threadIdx.x == 0) {
@@ -512,8 +690,14 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 // order alone.
 constexpr int FIN_NEAR = 4;
 template <int VEC, int MAXC>
-__global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids)
+__global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
+                                                           uint32_t work_blocks, TrimPlan tp, int stage)
 {
+    if (blockIdx.x >= work_blocks) {     // extra workgroups: the next stage of the trim's select
+        __shared__ TrimLds tl;
+        trim_stage_body(cv, tp, stage, blockIdx.x - work_blocks, gridDim.x - work_blocks, tl);
+        return;
+    }
     __shared__ uint32_t long_c[256], long_c1[256];
     __shared__ int32_t long_slot[256];
     __shared__ uint32_t n_long;
@@ -529,7 +713,7 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
     if (threadIdx.x == 0) n_long = 0;
     __syncthreads();
 
-    for (uint32_t base = blockIdx.x * groups_per_block; base < nchunks_max; base += gridDim.x * groups_per_block) {
+    for (uint32_t base = blockIdx.x * groups_per_block; base < nchunks_max; base += work_blocks * groups_per_block) {
         const uint32_t c = base + group;
         const uint32_t jb = (c + 1) * CHUNK;                       // first position of the next chunk
         int32_t slot = SLOT_NONE;
@@ -627,139 +811,6 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
     }
 }
 
-// ---- Evict(): policy trim ---------------------------------------------------------------------
-// The victims are the m = size - capacity cached rows smallest in (last_use, slot) [LRU] or
-// (freq, last_use, slot) [LFU].  A most-significant-digit radix select finds the policy key
-// tau of the m-th smallest row; rows below tau go, and of the rows equal to tau the first few in
-// slot order.  `bits` is the width of last_use / freq values (both are at most t).
-constexpr int SEL_BITS = 11;
-constexpr int SEL_BINS = 1 << SEL_BITS;
-constexpr int SEL_MAX_PASSES = 6;
-constexpr int TRIM_THREADS = 256;
-constexpr int TRIM_WAVES = TRIM_THREADS / WAVE;
-constexpr int TRIM_ITEMS = 4;
-constexpr int TRIM_TILE = TRIM_THREADS * TRIM_ITEMS;   // 1024 slots per counting tile
-
-struct TrimPlan {
-    int lfu;          // policy
-    int bits;         // bits per policy field
-    int key_bits;     // bits of the packed policy key
-    int passes;       // select passes
-    uint32_t *hist;   // [SEL_MAX_PASSES][SEL_BINS] followed by sup_eq: zeroed together before the first pass
-    uint32_t zero_words;
-    uint32_t *blk_eq, *sup_eq;         // rows tied at the threshold: per 256 slots, and per EV_SUPER such blocks
-    uint32_t *tile_free;               // free slots per 1024-slot tile
-    uint32_t *ev_ids;                  // ids dropped by this trim
-    int ev_slot;                       // which of the two evicted-id counts this trim appends to
-};
-
-__device__ __forceinline__ uint64_t policy_key(const TrimPlan &tp, const uint4 &meta)
-{
-    const uint64_t lu = meta.z;
-    return tp.lfu ? (((uint64_t)meta.w << tp.bits) | lu) : lu;
-}
-
-__device__ __forceinline__ int sel_shift(const TrimPlan &tp, int pass)
-{
-    const int sh = tp.key_bits - SEL_BITS * (pass + 1);
-    return sh < 0 ? 0 : sh;
-}
-__device__ __forceinline__ int sel_width(const TrimPlan &tp, int pass)
-{
-    const int hi = tp.key_bits - SEL_BITS * pass;       // bits not yet decided
-    return hi < SEL_BITS ? hi : SEL_BITS;
-}
-
-// Replays the select decisions of passes [0, upto): returns the key prefix chosen so far
-// (in the high bits of `prefix`) and how many victims remain to be found inside it.
-// Every thread of the block gets the same answer.
-__device__ __forceinline__ void sel_replay(const TrimPlan &tp, int upto, uint32_t m, uint64_t &prefix,
-                                           uint32_t &remaining, uint32_t *lds_pick, uint32_t *lds_scan)
-{
-    prefix = 0; remaining = m;
-    for (int p = 0; p < upto; ++p) {
-        const int width = sel_width(tp, p), bins = 1 << width;
-        uint32_t local[SEL_BINS / TRIM_THREADS];
-        uint32_t s = 0;
-#pragma unroll
-        for (int q = 0; q < SEL_BINS / TRIM_THREADS; ++q) {
-            const int b = threadIdx.x * (SEL_BINS / TRIM_THREADS) + q;
-            local[q] = b < bins ? tp.hist[p * SEL_BINS + b] : 0u;
-            s += local[q];
-        }
-        uint32_t tot;
-        uint32_t run = block_excl_scan<TRIM_WAVES>(s, lds_scan, tot);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < SEL_BINS / TRIM_THREADS; ++q) {
-            const int b = threadIdx.x * (SEL_BINS / TRIM_THREADS) + q;
-            // the digit whose cumulative count first reaches `remaining`
-            if (local[q] && run < remaining && remaining <= run + local[q]) { lds_pick[0] = (uint32_t)b; lds_pick[1] = run; }
-            run += local[q];
-        }
-        __syncthreads();
-        const uint32_t digit = lds_pick[0], below = lds_pick[1];
-        __syncthreads();
-        prefix |= (uint64_t)digit << sel_shift(tp, p);
-        remaining -= below;
-    }
-}
-
-__global__ __launch_bounds__(TRIM_THREADS) void trim_begin_kernel(CacheView cv, TrimPlan tp)
-{
-    for (uint32_t i = blockIdx.x * TRIM_THREADS + threadIdx.x; i < tp.zero_words; i += gridDim.x * TRIM_THREADS) tp.hist[i] = 0;
-}
-
-// One histogram pass of the select over the rows whose key matches the prefix chosen so far.
-__global__ __launch_bounds__(TRIM_THREADS) void trim_hist_kernel(CacheView cv, TrimPlan tp, int pass)
-{
-    __shared__ uint32_t bins[SEL_BINS];
-    __shared__ uint32_t pick[2];
-    __shared__ uint32_t scan[TRIM_WAVES + 1];
-    const int32_t over = cv.ds->size - (int32_t)cv.capacity;
-    if (over <= 0) return;
-    uint64_t prefix; uint32_t remaining;
-    sel_replay(tp, pass, (uint32_t)over, prefix, remaining, pick, scan);
-    for (int b = threadIdx.x; b < SEL_BINS; b += TRIM_THREADS) bins[b] = 0;
-    __syncthreads();
-    const int shift = sel_shift(tp, pass), width = sel_width(tp, pass);
-    const int decided = shift + width;                 // bits above are fixed by the prefix
-    for (uint32_t slot = blockIdx.x * TRIM_THREADS + threadIdx.x; slot < cv.n_slots; slot += gridDim.x * TRIM_THREADS) {
-        const uint32_t sk = cv.slot_key[slot];
-        const uint4 m = load_meta(cv.meta, slot);
-        if (sk == KEY_NONE) continue;
-        const uint64_t k = policy_key(tp, m);
-        if (decided < 64 && (k >> decided) != (prefix >> decided)) continue;
-        atomicAdd(&bins[(uint32_t)(k >> shift) & ((1u << width) - 1u)], 1u);
-    }
-    __syncthreads();
-    for (int b = threadIdx.x; b < SEL_BINS; b += TRIM_THREADS)
-        if (bins[b]) atomicAdd(&tp.hist[pass * SEL_BINS + b], bins[b]);
-}
-
-// Finds tau (replaying the select) and counts, per block of 256 slots, the cached rows whose
-// policy key equals tau; sup_eq adds these up per EV_SUPER blocks (zero when the trim starts).
-constexpr int EV_SLOTS = 256;
-constexpr int EV_SUPER = 32;
-__global__ __launch_bounds__(TRIM_THREADS) void trim_count_kernel(CacheView cv, TrimPlan tp)
-{
-    __shared__ uint32_t pick[2];
-    __shared__ uint32_t scan[TRIM_WAVES + 1];
-    const int32_t over = cv.ds->size - (int32_t)cv.capacity;
-    if (over <= 0) return;
-    const uint32_t slot = blockIdx.x * EV_SLOTS + threadIdx.x;       // loads first: they overlap the replay
-    const bool cached = slot < cv.n_slots && cv.slot_key[slot] != KEY_NONE;
-    const uint64_t key = slot < cv.n_slots ? policy_key(tp, load_meta(cv.meta, slot)) : 0;
-    uint64_t tau; uint32_t take_eq;
-    sel_replay(tp, tp.passes, (uint32_t)over, tau, take_eq, pick, scan);
-    const uint32_t eq = block_sum<TRIM_WAVES>((cached && key == tau) ? 1u : 0u, scan);
-    if (threadIdx.x == 0) {
-        tp.blk_eq[blockIdx.x] = eq;
-        if (eq) atomicAdd(&tp.sup_eq[blockIdx.x / EV_SUPER], eq);
-        if (blockIdx.x == 0) { cv.ds->sel_tau = tau; cv.ds->sel_take = take_eq; }
-    }
-}
-
 // Drops the victims among 256 consecutive slots, one thread per slot: erase the key, free the
 // slot, raise c_g; then one row group per victim that holds updates copies its row (and
 // accumulator) to the global table: Evict's push (Section 3.1).  Four workgroups share a
@@ -775,7 +826,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     const uint32_t slot = blk * EV_SLOTS + threadIdx.x;
     const bool in = slot < cv.n_slots;
     // everything this thread may need, requested at once
-    const int32_t over = cv.ds->size - (int32_t)cv.capacity;
+    const int32_t over = cv.ds->over;                  // snapshot taken by the select: size changes below
     const uint64_t tau = cv.ds->sel_tau;
     const uint32_t take_eq = cv.ds->sel_take;
     const uint32_t my_key = in ? cv.slot_key[slot] : KEY_NONE;
@@ -826,36 +877,9 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     }
     if (threadIdx.x == 0) {
         if (free_here + nv) atomicAdd(&tp.tile_free[blk * EV_SLOTS / TRIM_TILE], free_here + nv);
+        if (nv) atomicSub(&cv.ds->size, (int32_t)nv);
         count2(&cv.last->evicted, &cv.ds->total.evicted, nv);
         count2(&cv.last->evicted_dirty, &cv.ds->total.evicted_dirty, np);
-    }
-}
-
-// Lists the free slots in ascending order (only the first max_ids are ever needed), settles
-// the row count after the trim and clears the per-tile counts for the next trim.
-__global__ __launch_bounds__(TRIM_THREADS) void trim_free_kernel(CacheView cv, TrimPlan tp, uint32_t *tile_free_next)
-{
-    __shared__ uint32_t scan[TRIM_WAVES + 1];
-    const uint32_t tile = blockIdx.x;
-    if (tile == 0 && threadIdx.x == 0 && cv.ds->size > (int32_t)cv.capacity) cv.ds->size = (int32_t)cv.capacity;
-    if (threadIdx.x == 0) tile_free_next[tile] = 0;
-    if (tile == 0 && threadIdx.x == 0) cv.ds->ev_n[1 - tp.ev_slot] = 0;
-    const uint32_t before = block_sum_array<TRIM_WAVES>(tp.tile_free, tile, scan);
-    if (before >= cv.max_ids) return;
-    uint32_t mine = 0;
-    bool fr[TRIM_ITEMS];
-#pragma unroll
-    for (int it = 0; it < TRIM_ITEMS; ++it) {
-        const uint32_t slot = tile * TRIM_TILE + threadIdx.x * TRIM_ITEMS + it;
-        fr[it] = slot < cv.n_slots && cv.slot_key[slot] == KEY_NONE;
-        mine += fr[it] ? 1u : 0u;
-    }
-    uint32_t tot;
-    uint32_t pos = before + block_excl_scan<TRIM_WAVES>(mine, scan, tot);
-#pragma unroll
-    for (int it = 0; it < TRIM_ITEMS; ++it) {
-        const uint32_t slot = tile * TRIM_TILE + threadIdx.x * TRIM_ITEMS + it;
-        if (fr[it]) { if (pos < cv.max_ids) cv.free_list[pos] = slot; ++pos; }
     }
 }
 

@@ -28,9 +28,11 @@ struct DState {
     uint32_t n_unique;   // distinct valid ids of the current call
     uint32_t n_valid;    // ids of the current call that lie in [0, vocab)
     uint32_t err;        // sticky ERRBIT_*
-    uint32_t ev_n[2];    // ids recorded by a trim; trims alternate, each clears the other's count
+    uint32_t ev_n[2];    // ids recorded by a trim; trims alternate, the lookup in between clears the idle count
     uint32_t sel_take;   // trim: how many of the rows whose policy key equals sel_tau are evicted (in slot order)
     unsigned long long sel_tau;   // trim: policy key of the last row to evict
+    int32_t over;        // trim: rows above capacity when the select ran (what the eviction removes)
+    int32_t pad1;
     Counters call[2];    // per-call counters: calls alternate between the two, the idle one is cleared meanwhile
     Counters total;
 };

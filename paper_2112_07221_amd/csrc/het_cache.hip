@@ -19,13 +19,12 @@ using namespace het;
 
 // Kernels of the path, as named in profiles and by het_profile_kernel_name.
 enum KernelId {
-    K_DEDUP_HIST, K_SORT_PASS, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_APPLY_FINISH, K_TRIM_BEGIN, K_TRIM_HIST,
-    K_TRIM_COUNT, K_TRIM_EVICT, K_TRIM_FREE, K_FLUSH, K_MISC, K_NUM
+    K_DEDUP_HIST, K_SORT_PASS, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_APPLY_FINISH, K_TRIM_STAGE,
+    K_TRIM_EVICT, K_FLUSH, K_MISC, K_NUM
 };
 static const char *const kKernelNames[K_NUM] = {
     "dedup_hist_kernel", "sort_pass_kernel", "probe_kernel", "pooled_index_kernel", "fill_gather_kernel",
-    "apply_kernel", "apply_finish_kernel", "trim_begin_kernel", "trim_hist_kernel", "trim_count_kernel", "trim_evict_kernel",
-    "trim_free_kernel", "flush_kernel", "misc"};
+    "apply_kernel", "apply_finish_kernel", "trim_stage_kernel", "trim_evict_kernel", "flush_kernel", "misc"};
 
 struct ProfSpan { int id; hipEvent_t start, stop; };
 
@@ -51,18 +50,17 @@ struct het_cache {
     int sort_set = 0;                // the set that holds the current batch's order
     // side stream: the next batch's sort and the trim's select run beside the main stream
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_sort = nullptr, ev_lookup = nullptr, ev_select = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_sort = nullptr;
     const int64_t *prefetch_ids = nullptr;   // ids sorted ahead of their lookup by het_prefetch
     uint32_t prefetch_n = 0;
     bool prefetched = false;
     int prefetch_buf = 0;
-    bool select_pending = false;     // the victims' threshold for the rows now cached has been computed
-    bool select_on_side = false;
-    TrimPlan sel_tp{};               // the plan that select used; the eviction must use the same
+    TrimPlan sel_tp{};               // the select plan of the rows now cached (fixed at the lookup)
+    bool last_trim_skipped = false;  // the last update had nothing to trim: its evicted-id list is empty
     int cslot = 0;                   // which of the two per-call counter blocks the current call uses
     uint32_t *inv = nullptr;
-    uint32_t *tile_free[2] = {nullptr, nullptr};   // alternate between trims: one in use, one being cleared
-    int tile_free_cur = 0;
+    uint32_t *tile_free[2] = {nullptr, nullptr};   // free slots per tile, left by a trim; trims alternate between the two
+    int tf_last = 0;                 // the one the last trim filled (initially: every slot free)
     uint32_t *ev_ids[2] = {nullptr, nullptr};      // evicted ids of the last two trims, alternating like tile_free
     uint32_t n_buckets = 0;
     int max_chunks_per_lane = 1;     // row chunks one lane handles in the apply kernel
@@ -228,10 +226,9 @@ void use_order(het_cache *c, int set, int buf)
     c->ws.perm = c->idx[set][buf];
 }
 
-// The select of the trim (histogram passes and the tie count) for the rows cached right now.
-// It reads only policy counters and the row count, which an update does not change, so it can
-// run on the side stream as soon as the lookup is through.
-int run_select(het_cache *c, hipStream_t st)
+// The trim's select plan for the rows cached after the lookup that just ran: stages 0..passes-1
+// are histogram passes, stage `passes` is the tie count.
+TrimPlan make_trim_plan(const het_cache *c)
 {
     TrimPlan tp = c->tp;
     tp.lfu = c->policy == HET_POLICY_LFU;
@@ -239,36 +236,31 @@ int run_select(het_cache *c, hipStream_t st)
     tp.key_bits = tp.lfu ? 2 * tp.bits : tp.bits;
     tp.passes = (tp.key_bits + SEL_BITS - 1) / SEL_BITS;
     tp.sup_eq = tp.hist + SEL_MAX_PASSES * SEL_BINS;
-    const uint32_t stiles = cdiv(c->cv.n_slots, TRIM_TILE);
-    const uint32_t hist_blocks = std::min(stiles, 1024u);
-    LAUNCH_ON(c, st, K_TRIM_BEGIN, trim_begin_kernel<<<4, TRIM_THREADS, 0, st>>>(c->cv, tp));
-    for (int p = 0; p < tp.passes; ++p)
-        LAUNCH_ON(c, st, K_TRIM_HIST, trim_hist_kernel<<<hist_blocks, TRIM_THREADS, 0, st>>>(c->cv, tp, p));
-    LAUNCH_ON(c, st, K_TRIM_COUNT, trim_count_kernel<<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, st>>>(c->cv, tp));
-    c->sel_tp = tp;
-    c->select_pending = true;
-    c->select_on_side = st != c->stream;
-    return launch_ok();
+    return tp;
 }
 
-// Evict(): drops the overflow on the main stream, using the select computed before.
-template <int VEC>
-int run_trim(het_cache *c)
+uint32_t stage_blocks(const het_cache *c, const TrimPlan &tp, int stage)
 {
-    int rc;
-    if (!c->select_pending && (rc = run_select(c, c->stream)) != HET_OK) return rc;
-    if (c->select_on_side) HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_select, 0));
+    if (stage < tp.passes) return std::min(cdiv(c->cv.n_slots, TRIM_TILE), 1024u);
+    return cdiv(c->cv.n_slots, EV_SLOTS);
+}
+
+// Evict(): the select stages from `first_stage` on (earlier ones rode along with the update's
+// kernels), then the eviction itself.
+template <int VEC>
+int run_trim(het_cache *c, int first_stage)
+{
     TrimPlan tp = c->sel_tp;
-    tp.tile_free = c->tile_free[c->tile_free_cur];
-    tp.ev_slot = c->tile_free_cur;
-    tp.ev_ids = c->ev_ids[c->tile_free_cur];
-    uint32_t *tile_free_next = c->tile_free[1 - c->tile_free_cur];
-    c->tile_free_cur = 1 - c->tile_free_cur;
-    const uint32_t stiles = cdiv(c->cv.n_slots, TRIM_TILE);
+    for (int st = first_stage; st <= tp.passes; ++st)
+        LAUNCH(c, K_TRIM_STAGE, trim_stage_kernel<<<stage_blocks(c, tp, st), TRIM_THREADS, 0, c->stream>>>(c->cv, tp, st));
+    const int fill = 1 - c->tf_last;                 // the idle array: cleared by the lookup in between
+    tp.tile_free = c->tile_free[fill];
+    tp.ev_slot = fill;
+    tp.ev_ids = c->ev_ids[fill];
     LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC><<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
-    LAUNCH(c, K_TRIM_FREE, trim_free_kernel<<<stiles, TRIM_THREADS, 0, c->stream>>>(c->cv, tp, tile_free_next));
-    c->select_pending = false;
+    c->tf_last = fill;
     c->overflow_pending = false;
+    c->last_trim_skipped = false;
     c->order_valid = false;          // slots recorded for the sorted order may be gone now
     return launch_ok();
 }
@@ -279,7 +271,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     begin_call(c);
     c->t_host += 1;
     int rc;
-    if (c->overflow_pending && (rc = run_trim<VEC>(c)) != HET_OK) return rc;   // a Read that follows a Read
+    if (c->overflow_pending && (rc = run_trim<VEC>(c, 0)) != HET_OK) return rc;   // a Read that follows a Read
     // the sorted order: already made by het_prefetch on the side stream, or made here
     const int set = 1 - c->sort_set;
     if (c->prefetched && ids == c->prefetch_ids && n == c->prefetch_n) {
@@ -292,38 +284,40 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     }
     c->prefetched = false;
     const uint32_t t_now = (uint32_t)c->t_host;
-    LAUNCH(c, K_PROBE, probe_kernel<true><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now));
-    const uint32_t ptiles = cdiv(n, PT_TILE);
+    const uint32_t ptiles = cdiv(n, PT_TILE), stiles = cdiv(c->cv.n_slots, PT_TILE);
+    LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + stiles, PT_THREADS, 0, c->stream>>>(
+                           c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last)));
     const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 1024u);     // they come first: theirs is the longer chain
     if (!offsets) {
         LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<fill_blocks + row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, out, nullptr, 0, nullptr));
+                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, c->tp.hist, c->tp.zero_words, out, nullptr, 0, nullptr));
     } else {
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
         LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<fill_blocks + row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, out, offsets, n_bags, c->inv));
+                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, c->tp.hist, c->tp.zero_words, out, offsets, n_bags, c->inv));
     }
     if ((rc = launch_ok()) != HET_OK) return rc;
-    // from here on the side stream may work out which rows the coming trim evicts
-    HIP_TRY(hipEventRecord(c->ev_lookup, c->stream));
-    HIP_TRY(hipStreamWaitEvent(c->side, c->ev_lookup, 0));
-    if ((rc = run_select(c, c->side)) != HET_OK) return rc;
-    HIP_TRY(hipEventRecord(c->ev_select, c->side));
+    c->sel_tp = make_trim_plan(c);
     c->overflow_pending = true;
     c->last_lookup_n = n;
     c->order_ids = ids; c->order_n = n; c->order_valid = true;
     return HET_OK;
 }
 
+// The two kernels of Write; each carries one stage of the coming trim's select in extra workgroups.
 template <int VEC, int MAXC>
-void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr)
+void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
+                  int stages_carried)
 {
     const uint32_t grid = row_grid(c->cv.geom, cdiv(n, CHUNK));
+    const TrimPlan &tp = c->sel_tp;
+    const uint32_t extra0 = stages_carried > 0 ? stage_blocks(c, tp, 0) : 0u;
+    const uint32_t extra1 = stages_carried > 1 ? stage_blocks(c, tp, 1) : 0u;
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 0));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n));
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 0));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid + extra1, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, 1));
 }
 
 template <int VEC>
@@ -339,21 +333,26 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     if (!reuse) {
         const int buf = sort_ids(c, c->stream, ids, n, c->sort_set);
         use_order(c, c->sort_set, buf);
-        LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
+        LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
+                               c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u));
     }
     const uint32_t *grad_row = nullptr;
     if (offsets) {
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
         grad_row = c->ws.bag_of;
     }
+    // Only a lookup leaves rows above capacity; an update that follows no lookup has nothing to trim.
+    const bool trim = c->overflow_pending;
+    const int carried = trim ? std::min(2, c->sel_tp.passes + 1) : 0;
     switch (c->max_chunks_per_lane) {
-    case 1: launch_apply<VEC, 1>(c, reuse, ids, n, grads, grad_row, lr); break;
-    case 2: launch_apply<VEC, 2>(c, reuse, ids, n, grads, grad_row, lr); break;
-    case 4: launch_apply<VEC, 4>(c, reuse, ids, n, grads, grad_row, lr); break;
-    default: launch_apply<VEC, 16>(c, reuse, ids, n, grads, grad_row, lr); break;
+    case 1: launch_apply<VEC, 1>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
+    case 2: launch_apply<VEC, 2>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
+    case 4: launch_apply<VEC, 4>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
+    default: launch_apply<VEC, 16>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
     }
     if ((rc = launch_ok()) != HET_OK) return rc;
-    return run_trim<VEC>(c);
+    if (!trim) { c->last_trim_skipped = true; c->order_valid = false; return HET_OK; }
+    return run_trim<VEC>(c, carried);
 }
 
 int sync_all(het_cache *c)
@@ -447,7 +446,7 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
             if ((rc = dev_alloc(c, &c->sort_hist[set][p], sort_tiles * SORT_MAX_BINS))) return rc;
     }
     HIP_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));       // default priority
-    for (hipEvent_t *e : {&c->ev_fork, &c->ev_sort, &c->ev_lookup, &c->ev_select})
+    for (hipEvent_t *e : {&c->ev_fork, &c->ev_sort})
         HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     c->cv.last = &cv.ds->call[0];
     c->cv.next_call = &cv.ds->call[1];
@@ -463,7 +462,11 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
         (rc = dev_alloc(c, &c->tile_free[0], slot_tiles)) ||
         (rc = dev_alloc(c, &c->tile_free[1], slot_tiles)) || (rc = dev_alloc(c, &c->ev_ids[0], P)) || (rc = dev_alloc(c, &c->ev_ids[1], P)))
         return rc;
-    HIP_TRY(hipMemsetAsync(c->tile_free[0], 0, slot_tiles * sizeof(uint32_t), c->stream));
+    {   // before the first trim every slot is free
+        std::vector<uint32_t> full(slot_tiles);
+        for (size_t t = 0; t < slot_tiles; ++t) full[t] = (uint32_t)std::min<uint64_t>(TRIM_TILE, P - t * TRIM_TILE);
+        HIP_TRY(hipMemcpy(c->tile_free[0], full.data(), slot_tiles * sizeof(uint32_t), hipMemcpyHostToDevice));
+    }
     HIP_TRY(hipMemsetAsync(c->tile_free[1], 0, slot_tiles * sizeof(uint32_t), c->stream));
 
     HIP_TRY(hipMemsetAsync(cv.ds, 0, sizeof(DState), c->stream));
@@ -659,8 +662,8 @@ int het_last_evicted(het_cache *c, int64_t *ids, int64_t *n)
     { int rc0 = sync_all(c); if (rc0) return rc0; }
     DState h;
     HIP_TRY(hipMemcpy(&h, c->cv.ds, sizeof(DState), hipMemcpyDeviceToHost));
-    const int last = 1 - c->tile_free_cur;               // the trim before the upcoming one
-    const uint32_t ev_n = h.ev_n[last];
+    const int last = c->tf_last;                         // the list the last trim filled
+    const uint32_t ev_n = c->last_trim_skipped ? 0u : h.ev_n[last];
     std::vector<uint32_t> e(ev_n);
     if (ev_n) HIP_TRY(hipMemcpy(e.data(), c->ev_ids[last], (size_t)ev_n * 4, hipMemcpyDeviceToHost));
     for (size_t i = 0; i < e.size(); ++i)
@@ -708,7 +711,7 @@ int het_cache_destroy(het_cache *c)
     if (!c) return HET_OK;
     int rc = HET_OK;
     if (c->configured && sync_all(c) != HET_OK) rc = HET_EHIP;
-    for (hipEvent_t e : {c->ev_fork, c->ev_sort, c->ev_lookup, c->ev_select})
+    for (hipEvent_t e : {c->ev_fork, c->ev_sort})
         if (e && hipEventDestroy(e) != hipSuccess) rc = HET_EHIP;
     if (c->side && hipStreamDestroy(c->side) != hipSuccess) rc = HET_EHIP;
     for (void *p : c->owned)
