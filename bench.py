@@ -111,17 +111,16 @@ def main():
     cache.attach_backing(Wt, At, Cg, hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
 
     def step(t):
-        # lookup t, then the ids of batch t+1 are announced (their sort runs beside update t), then update t
+        # lookup t, update t, then the ids of batch t+1 are announced: their sort starts where
+        # lookup t ended and runs beside update t on the library's side stream
         if w.pooled:
             cache.lookup_pooled(ids[t], offsets, out)
-        else:
-            cache.lookup(ids[t], out)
-        if not args.no_prefetch and t + 1 < total:
-            cache.prefetch(ids[t + 1])
-        if w.pooled:
             cache.update_pooled(ids[t], offsets, grads[t % w.grad_pool], w.lr)
         else:
+            cache.lookup(ids[t], out)
             cache.update(ids[t], grads[t % w.grad_pool], w.lr)
+        if not args.no_prefetch and t + 1 < total:
+            cache.prefetch(ids[t + 1])
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

@@ -119,10 +119,12 @@ int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out);
 /*
  * Optional: announces the ids of the NEXT lookup so that their sort (the dedup of Algorithm 1)
  * runs on an internal side stream next to the calls in between, typically the current update
- * (Section 4.2: the indices of the next minibatch are fetched in advance).  ids[n] must be
- * complete in stream order at the time of this call and must stay unchanged until the lookup
- * that passes the same pointer and n; that lookup then skips its sort.  Results are identical
- * with and without the announcement; a lookup with other ids simply ignores it.
+ * (Section 4.2: the indices of the next minibatch are fetched in advance).  The sort starts
+ * where the most recent het_lookup ended in stream order (or at this call, if there was none),
+ * whether this call comes before or after the het_update of that lookup: ids[n] must be
+ * complete in stream order before that het_lookup was called, and must stay unchanged until
+ * the lookup that passes the same pointer and n; that lookup then skips its sort.  Results are
+ * identical with and without the announcement; a lookup with other ids simply ignores it.
  */
 int het_prefetch(het_cache *c, const int64_t *ids, int64_t n);
 

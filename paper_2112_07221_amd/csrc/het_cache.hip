@@ -54,6 +54,7 @@ struct het_cache {
     const int64_t *prefetch_ids = nullptr;   // ids sorted ahead of their lookup by het_prefetch
     uint32_t prefetch_n = 0;
     bool prefetched = false;
+    bool fork_recorded = false;      // ev_fork marks the end of the last lookup
     int prefetch_buf = 0;
     TrimPlan sel_tp{};               // the select plan of the rows now cached (fixed at the lookup)
     bool last_trim_skipped = false;  // the last update had nothing to trim: its evicted-id list is empty
@@ -297,6 +298,8 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
                                      c->cv, c->ws, n, t_now, ptiles, fill_blocks, c->tp.hist, c->tp.zero_words, out, offsets, n_bags, c->inv));
     }
     if ((rc = launch_ok()) != HET_OK) return rc;
+    HIP_TRY(hipEventRecord(c->ev_fork, c->stream));      // a prefetch may start from here
+    c->fork_recorded = true;
     c->sel_tp = make_trim_plan(c);
     c->overflow_pending = true;
     c->last_lookup_n = n;
@@ -502,11 +505,13 @@ int het_prefetch(het_cache *c, const int64_t *ids, int64_t n)
     if (!ready(c) || n < 0 || n > c->max_ids) return HET_EINVAL;
     if (n == 0) return HET_OK;
     if (!ids) return HET_EINVAL;
-    // The side stream starts after everything enqueued on the main stream so far: the ids are
-    // there, and the last readers of the buffer set it sorts into (the calls before the current
-    // batch's lookup) are among that work.
+    // The side stream starts where the last lookup ended on the main stream (or here, if there
+    // was none): the last readers of the buffer set it sorts into, the calls before that lookup,
+    // are done by then, and the caller guarantees the ids are.  An update enqueued in between does
+    // not hold the sort back.
     const int set = 1 - c->sort_set;
-    HIP_TRY(hipEventRecord(c->ev_fork, c->stream));
+    if (!c->fork_recorded) HIP_TRY(hipEventRecord(c->ev_fork, c->stream));
+    c->fork_recorded = true;
     HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
     const int buf = sort_ids(c, c->side, ids, (uint32_t)n, set);
     int rc = launch_ok();

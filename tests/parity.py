@@ -125,9 +125,10 @@ class Pair:
 
 
 def run_workload(w: wl.Workload, iters: int, state_every: int = 1, table=None, ids=None, grads=None,
-                 values_every: int = 0, prefetch: bool = False):
+                 values_every: int = 0, prefetch=False):
     """Runs `iters` lookup+update iterations of workload `w` on both sides.  With `prefetch` the
-    ids of iteration t+1 are announced between lookup t and update t, as the benchmark does."""
+    ids of iteration t+1 are announced between lookup t and update t (prefetch=True or "between")
+    or after update t (prefetch="after", as the benchmark does)."""
     table = wl.table_init(w) if table is None else table
     ids = wl.IdStream(w).batches(iters) if ids is None else ids
     grads = wl.grad_pool(w) if grads is None else grads
@@ -136,9 +137,11 @@ def run_workload(w: wl.Workload, iters: int, state_every: int = 1, table=None, i
         ids_dev = torch.from_numpy(ids).to(p.dev) if prefetch else None
         for t in range(iters):
             p.lookup(ids[t], ids_dev=ids_dev[t] if prefetch else None)
-            if prefetch and t + 1 < iters:
+            if prefetch and prefetch != "after" and t + 1 < iters:
                 p.cache.prefetch(ids_dev[t + 1])
             p.update(ids[t], grads[t % len(grads)], ids_dev=ids_dev[t] if prefetch else None)
+            if prefetch == "after" and t + 1 < iters:
+                p.cache.prefetch(ids_dev[t + 1])
             if state_every and (t % state_every == 0 or t == iters - 1):
                 p.compare_state(values=bool(values_every) and t % values_every == 0)
                 p.compare_counters()
