@@ -45,6 +45,7 @@ struct CacheView {
     int64_t s;            // staleness bound
     HashTable ht;
     uint32_t *free_list;  // free slots in ascending order (first max_ids of them)
+    uint8_t *was_free;    // per slot: free when the current lookup began (its fetches may be filling it now)
     DState *ds;
     Counters *last;       // this call's counters (one of ds->call)
     Counters *next_call;  // the other one: cleared by this call for the next
@@ -173,10 +174,18 @@ struct TrimLds {
 
 // One histogram pass of the select over the rows whose key matches the prefix chosen so far.
 // Runs in `nblocks` workgroups of TRIM_THREADS threads; `vblock` is this one's index.
-__device__ __forceinline__ void trim_hist_body(const CacheView &cv, const TrimPlan &tp, int pass, uint32_t vblock, uint32_t nblocks, TrimLds &l)
+// `new_rows` > 0 (first pass, running beside the lookup's fetches): slots that were free when
+// the lookup began are skipped - they are being filled right now - and the rows fetched into
+// them, which all carry the policy key (freq 1, last_use t_now), are counted from their number.
+__device__ __forceinline__ void trim_hist_body(const CacheView &cv, const TrimPlan &tp, int pass, uint32_t vblock, uint32_t nblocks, TrimLds &l,
+                                               bool beside_fill = false, uint32_t new_rows = 0, uint32_t t_now = 0)
 {
     const int32_t over = cv.ds->size - (int32_t)cv.capacity;
     if (over <= 0) return;
+    if (beside_fill && vblock == 0 && threadIdx.x == 0 && new_rows) {
+        const uint64_t k = policy_key(tp, make_uint4(0, 0, t_now, 1));
+        atomicAdd(&tp.hist[pass * SEL_BINS + ((uint32_t)(k >> sel_shift(tp, pass)) & ((1u << sel_width(tp, pass)) - 1u))], new_rows);
+    }
     uint64_t prefix; uint32_t remaining;
     sel_replay(tp, pass, (uint32_t)over, prefix, remaining, l.pick, l.scan);
     for (int b = threadIdx.x; b < SEL_BINS; b += TRIM_THREADS) l.bins[b] = 0;
@@ -186,7 +195,8 @@ __device__ __forceinline__ void trim_hist_body(const CacheView &cv, const TrimPl
     for (uint32_t slot = vblock * TRIM_THREADS + threadIdx.x; slot < cv.n_slots; slot += nblocks * TRIM_THREADS) {
         const uint32_t sk = cv.slot_key[slot];
         const uint4 m = load_meta(cv.meta, slot);
-        if (sk == KEY_NONE) continue;
+        const bool skip = beside_fill ? cv.was_free[slot] != 0 : sk == KEY_NONE;
+        if (skip) continue;
         const uint64_t k = policy_key(tp, m);
         if (decided < 64 && (k >> decided) != (prefix >> decided)) continue;
         atomicAdd(&l.bins[(uint32_t)(k >> shift) & ((1u << width) - 1u)], 1u);
@@ -245,6 +255,7 @@ __device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32
     if (tile == 0 && threadIdx.x == 0) cv.ds->ev_n[ev_idle] = 0;
     const uint32_t slot = tile * PT_TILE + threadIdx.x;
     const bool fr = slot < cv.n_slots && cv.slot_key[slot] == KEY_NONE;
+    if (slot < cv.n_slots) cv.was_free[slot] = fr ? 1 : 0;
     const uint32_t before = block_sum_array<PT_WAVES>(tile_free, tile, lds);
     if (before >= cv.max_ids) return;
     uint32_t tot;
@@ -258,10 +269,13 @@ __device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32
 // Otherwise (update that sorted its own ids): only resolves slots and flags keys not cached.
 template <bool LOOKUP>
 __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
-                                                           const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle)
+                                                           const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle,
+                                                           uint32_t *zero_from, uint32_t zero_words)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
     if (blockIdx.x >= ptiles) {          // extra workgroups of a lookup: the free list for the fill kernel
+        // ... and clean select histograms for the trim that follows this lookup
+        for (uint32_t i = (blockIdx.x - ptiles) * PT_THREADS + threadIdx.x; i < zero_words; i += (gridDim.x - ptiles) * PT_THREADS) zero_from[i] = 0;
         free_list_body(cv, tile_free, tile_free_idle, ev_idle, blockIdx.x - ptiles, lds);
         return;
     }
@@ -399,16 +413,13 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
 template <int VEC, bool POOLED>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
-                                                          uint32_t *zero_from, uint32_t zero_words, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
+                                                          TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv)
 {
     using V = typename VecT<VEC>::type;
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
-    // the select of the coming trim counts into these
-    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < zero_words; i += gridDim.x * 256u) zero_from[i] = 0;
-
     if (blockIdx.x < fill_blocks) {
         __shared__ uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
         __shared__ uint32_t scan[4 + 1];
@@ -449,8 +460,17 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         return;
     }
 
-    const uint32_t gid = (blockIdx.x - fill_blocks) * groups_per_block + threadIdx.x / g.lanes;
-    const uint32_t ngroups = (gridDim.x - fill_blocks) * groups_per_block;
+    if (blockIdx.x < fill_blocks + hist_blocks) {
+        // first pass of the coming trim's select, over the rows cached before this lookup plus the
+        // rows being fetched right now (counted, not read)
+        __shared__ TrimLds tl;
+        const uint32_t new_rows = block_sum_array<TRIM_WAVES>(ws.tile_miss, ptiles, tl.scan);
+        trim_hist_body(cv, tp, 0, blockIdx.x - fill_blocks, hist_blocks, tl, true, new_rows, t_now);
+        return;
+    }
+    const uint32_t first_gather = fill_blocks + hist_blocks;
+    const uint32_t gid = (blockIdx.x - first_gather) * groups_per_block + threadIdx.x / g.lanes;
+    const uint32_t ngroups = (gridDim.x - first_gather) * groups_per_block;
     if (!POOLED) {
         for (uint32_t j = gid; j < n; j += ngroups) {                    // Get
             const int32_t s = ws.src[j];

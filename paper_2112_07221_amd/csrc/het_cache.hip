@@ -272,7 +272,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     begin_call(c);
     c->t_host += 1;
     int rc;
-    if (c->overflow_pending && (rc = run_trim<VEC>(c, 0)) != HET_OK) return rc;   // a Read that follows a Read
+    if (c->overflow_pending && (rc = run_trim<VEC>(c, 1)) != HET_OK) return rc;   // a Read that follows a Read (stage 0 rode with its fetches)
     // the sorted order: already made by het_prefetch on the side stream, or made here
     const int set = 1 - c->sort_set;
     if (c->prefetched && ids == c->prefetch_ids && n == c->prefetch_n) {
@@ -287,20 +287,23 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const uint32_t t_now = (uint32_t)c->t_host;
     const uint32_t ptiles = cdiv(n, PT_TILE), stiles = cdiv(c->cv.n_slots, PT_TILE);
     LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + stiles, PT_THREADS, 0, c->stream>>>(
-                           c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last)));
+                           c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last),
+                           c->tp.hist, c->tp.zero_words));
+    c->sel_tp = make_trim_plan(c);
+    const TrimPlan &tp = c->sel_tp;
+    const uint32_t hist_blocks = stage_blocks(c, tp, 0);       // stage 0 of the select rides with the fetches
     const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 1024u);     // they come first: theirs is the longer chain
     if (!offsets) {
-        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<fill_blocks + row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, c->tp.hist, c->tp.zero_words, out, nullptr, 0, nullptr));
+        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<fill_blocks + hist_blocks + row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
+                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, tp, hist_blocks, out, nullptr, 0, nullptr));
     } else {
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
-        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<fill_blocks + row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, c->tp.hist, c->tp.zero_words, out, offsets, n_bags, c->inv));
+        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<fill_blocks + hist_blocks + row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(
+                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, tp, hist_blocks, out, offsets, n_bags, c->inv));
     }
     if ((rc = launch_ok()) != HET_OK) return rc;
     HIP_TRY(hipEventRecord(c->ev_fork, c->stream));      // a prefetch may start from here
     c->fork_recorded = true;
-    c->sel_tp = make_trim_plan(c);
     c->overflow_pending = true;
     c->last_lookup_n = n;
     c->order_ids = ids; c->order_n = n; c->order_valid = true;
@@ -314,13 +317,14 @@ void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, con
 {
     const uint32_t grid = row_grid(c->cv.geom, cdiv(n, CHUNK));
     const TrimPlan &tp = c->sel_tp;
-    const uint32_t extra0 = stages_carried > 0 ? stage_blocks(c, tp, 0) : 0u;
-    const uint32_t extra1 = stages_carried > 1 ? stage_blocks(c, tp, 1) : 0u;
+    // stage 0 rode with the lookup's fetches; this call's two kernels carry stages 1 and 2
+    const uint32_t extra0 = stages_carried > 0 ? stage_blocks(c, tp, 1) : 0u;
+    const uint32_t extra1 = stages_carried > 1 ? stage_blocks(c, tp, 2) : 0u;
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 0));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 0));
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid + extra1, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, 1));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid + extra1, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, 2));
 }
 
 template <int VEC>
@@ -337,7 +341,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         const int buf = sort_ids(c, c->stream, ids, n, c->sort_set);
         use_order(c, c->sort_set, buf);
         LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
-                               c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u));
+                               c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u));
     }
     const uint32_t *grad_row = nullptr;
     if (offsets) {
@@ -346,7 +350,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     }
     // Only a lookup leaves rows above capacity; an update that follows no lookup has nothing to trim.
     const bool trim = c->overflow_pending;
-    const int carried = trim ? std::min(2, c->sel_tp.passes + 1) : 0;
+    const int carried = trim ? std::min(2, c->sel_tp.passes) : 0;     // of the stages 1 .. passes still to run
     switch (c->max_chunks_per_lane) {
     case 1: launch_apply<VEC, 1>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
     case 2: launch_apply<VEC, 2>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
@@ -355,7 +359,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     }
     if ((rc = launch_ok()) != HET_OK) return rc;
     if (!trim) { c->last_trim_skipped = true; c->order_valid = false; return HET_OK; }
-    return run_trim<VEC>(c, carried);
+    return run_trim<VEC>(c, 1 + carried);
 }
 
 int sync_all(het_cache *c)
@@ -426,7 +430,7 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     if ((rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
     if (cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
     if ((rc = dev_alloc(c, &cv.slot_key, P)) || (rc = dev_alloc(c, &cv.meta, P))) return rc;
-    if ((rc = dev_alloc(c, &cv.free_list, (size_t)max_batch_ids))) return rc;
+    if ((rc = dev_alloc(c, &cv.free_list, (size_t)max_batch_ids)) || (rc = dev_alloc(c, &cv.was_free, P))) return rc;
     if ((rc = dev_alloc(c, &cv.ds, 1))) return rc;
     // hash table: at most a quarter of the entries are ever used
     c->n_buckets = pow2_at_least(std::max<uint64_t>(1, cdiv(P * 4, BUCKET_ENTRIES)));
