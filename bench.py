@@ -31,7 +31,7 @@ HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
 # HBM bytes per launch (fetch + write) read from rocprofv3 FETCH_SIZE / WRITE_SIZE counters and
 # scaled by a 256 MiB device copy of the same run (profiles/config2_hbm_traffic.md).  Keyed by
 # (kernel, workload); a workload that was not measured reports null.
-MEASURED_TRAFFIC = {("apply_kernel", 2): 86.0e6}
+MEASURED_TRAFFIC = {("apply_kernel", 2): 88.8e6}
 
 
 def algorithmic_bytes(w, c):
@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefetch", action="store_true", help="do not announce the next batch's ids")
+    ap.add_argument("--prefetch-order", choices=("between", "after"), default="between",
+                    help="announce the next ids between lookup and update, or after the update")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy five times (a known-size reference for HBM counters)")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0 = auto)")
@@ -111,15 +113,20 @@ def main():
     cache.attach_backing(Wt, At, Cg, hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
 
     def step(t):
-        # lookup t, update t, then the ids of batch t+1 are announced: their sort starts where
-        # lookup t ended and runs beside update t on the library's side stream
+        # lookup t; the ids of batch t+1 are announced (their sort starts where lookup t ended and
+        # runs beside update t on the library's side stream); update t
+        pf = not args.no_prefetch and t + 1 < total
         if w.pooled:
             cache.lookup_pooled(ids[t], offsets, out)
-            cache.update_pooled(ids[t], offsets, grads[t % w.grad_pool], w.lr)
         else:
             cache.lookup(ids[t], out)
+        if pf and args.prefetch_order == "between":
+            cache.prefetch(ids[t + 1])
+        if w.pooled:
+            cache.update_pooled(ids[t], offsets, grads[t % w.grad_pool], w.lr)
+        else:
             cache.update(ids[t], grads[t % w.grad_pool], w.lr)
-        if not args.no_prefetch and t + 1 < total:
+        if pf and args.prefetch_order == "after":
             cache.prefetch(ids[t + 1])
 
     if args.calibrate_copy:
