@@ -71,8 +71,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefetch", action="store_true", help="do not announce the next batch's ids")
-    ap.add_argument("--prefetch-order", choices=("between", "after"), default="between",
-                    help="announce the next ids between lookup and update, or after the update")
+    ap.add_argument("--prefetch-order", choices=("before", "between", "after"), default="before",
+                    help="announce the next ids before the lookup, between lookup and update, or after the update")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy five times (a known-size reference for HBM counters)")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0 = auto)")
@@ -113,9 +113,11 @@ def main():
     cache.attach_backing(Wt, At, Cg, hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
 
     def step(t):
-        # lookup t; the ids of batch t+1 are announced (their sort starts where lookup t ended and
-        # runs beside update t on the library's side stream); update t
+        # the ids of batch t+1 are announced (the kernels of lookup t and update t carry their
+        # sort); lookup t; update t
         pf = not args.no_prefetch and t + 1 < total
+        if pf and args.prefetch_order == "before":
+            cache.prefetch(ids[t + 1])
         if w.pooled:
             cache.lookup_pooled(ids[t], offsets, out)
         else:

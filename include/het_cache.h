@@ -13,10 +13,9 @@
  *   - Every function returns an int status: HET_OK (0) or a negative het_status.
  *   - "device" pointers are HIP device allocations of the current device, owned by the caller
  *     and only borrowed for the duration stated; "host" pointers are ordinary host memory.
- *   - het_lookup* / het_update* only enqueue work and return; their results are valid in the
- *     order of the configured stream.  (Internally a second stream carries work that does not
- *     depend on the caller's data order; it is joined to the configured stream by events.)  het_flush, het_stats, het_export_*, het_last_* and
- *     het_cache_destroy wait for the stream.
+ *   - het_lookup* / het_update* only enqueue work on the configured stream and return; their
+ *     results are valid in the order of that stream (the library uses no other stream).
+ *     het_flush, het_stats, het_export_*, het_last_* and het_cache_destroy wait for the stream.
  *   - Errors the host can see (NULL, sizes out of range, wrong call order) are returned at
  *     once and change nothing.  Errors only the device can see (an id outside [0, vocab), an
  *     update of an id that is not cached) set a sticky bit that the next waiting call returns
@@ -117,14 +116,16 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
 int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out);
 
 /*
- * Optional: announces the ids of the NEXT lookup so that their sort (the dedup of Algorithm 1)
- * runs on an internal side stream next to the calls in between, typically the current update
- * (Section 4.2: the indices of the next minibatch are fetched in advance).  The sort starts
- * where the most recent het_lookup ended in stream order (or at this call, if there was none),
- * whether this call comes before or after the het_update of that lookup: ids[n] must be
- * complete in stream order before that het_lookup was called, and must stay unchanged until
- * the lookup that passes the same pointer and n; that lookup then skips its sort.  Results are
- * identical with and without the announcement; a lookup with other ids simply ignores it.
+ * Optional: announces the ids of a coming lookup (Section 4.2: the indices of the next minibatch
+ * are known in advance).  Their sort, the dedup of Algorithm 1, touches no cache state, so the
+ * kernels of the calls made between this call and that lookup carry it in extra workgroups, one
+ * stage per kernel; whatever is still missing runs when the lookup comes.  One lookup plus one
+ * update carry a whole sort for vocabularies up to 2^22 ids, so the best place for this call is
+ * just before the lookup of the batch BEFORE the announced one.  ids[n] (device) must be
+ * complete in stream order when this call is made and stay unchanged until the lookup that
+ * passes the same pointer and n.  Two batches can stand announced at a time (a third replaces
+ * the oldest).  Results are identical with and without the announcement; a lookup with other
+ * ids leaves it standing for a later one.  Nothing is launched by this call.
  */
 int het_prefetch(het_cache *c, const int64_t *ids, int64_t n);
 

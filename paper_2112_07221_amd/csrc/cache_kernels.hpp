@@ -172,6 +172,13 @@ struct TrimLds {
     uint32_t scan[TRIM_WAVES + 1];
 };
 
+// Kernels that carry a stage of the next minibatch's sort give it their first workgroups (its
+// chain of dependent steps is the longest, so it starts first) and number their own from
+// there.  All roles of a kernel share one dynamically sized LDS buffer; the host sizes it for
+// the largest role present.
+extern __shared__ __align__(16) unsigned char dyn_lds[];
+template <typename T> __device__ __forceinline__ T &lds_as() { return *reinterpret_cast<T *>(dyn_lds); }
+
 // One histogram pass of the select over the rows whose key matches the prefix chosen so far.
 // Runs in `nblocks` workgroups of TRIM_THREADS threads; `vblock` is this one's index.
 // `new_rows` > 0 (first pass, running beside the lookup's fetches): slots that were free when
@@ -291,10 +298,11 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         atomicAdd(&ds->total.n, (unsigned long long)n);
         if (LOOKUP) ds->t = t_now;
     }
-    bool head = false, miss = false, stale = false, hit = false, absent = false;
+    bool head = false, miss = false, stale = false, hit = false, absent = false, bad = false;
     if (j < n) {
         const uint32_t key = ws.skey[j];
         if (key == vocab) {                                   // id outside the vocabulary
+            bad = true;
             if (LOOKUP) ws.src[j] = SRC_ZERO;
             ws.head_slot[j] = SLOT_NONE;
             if (j == 0) ds->n_valid = 0;                      // not one valid id in the call
@@ -331,6 +339,7 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         }
     }
 
+    if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
     if (LOOKUP) {
         // stage this tile's missed and stale keys, in key order, for the fill kernel
         uint32_t tot_miss, tot_stale;
@@ -411,27 +420,35 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // values the fetch copies), so it does not wait for the fetch: the first `fill_blocks`
 // workgroups fetch, the others gather, side by side.
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
-template <int VEC, bool POOLED>
+struct FillLds {
+    uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
+    uint32_t scan[4 + 1];
+};
+template <int VEC, bool POOLED, bool RIDE>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
-                                                          const uint32_t *__restrict__ inv)
+                                                          const uint32_t *__restrict__ inv, SortStage ride)
 {
     using V = typename VecT<VEC>::type;
+    uint32_t bid = blockIdx.x, nblk = gridDim.x;
+    if (RIDE) {
+        if (bid < ride.blocks) { sort_stage_body(ride, bid, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
+        bid -= ride.blocks; nblk -= ride.blocks;
+    }
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
-    if (blockIdx.x < fill_blocks) {
-        __shared__ uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
-        __shared__ uint32_t scan[4 + 1];
-        const uint32_t tot_miss = tile_prefix_to_lds<4>(ws.tile_miss, ptiles, pre_miss, scan);
-        const uint32_t tot_stale = tile_prefix_to_lds<4>(ws.tile_stale, ptiles, pre_stale, scan);
-        const uint32_t gid = blockIdx.x * groups_per_block + threadIdx.x / g.lanes;
+    if (bid < fill_blocks) {
+        FillLds &fl = lds_as<FillLds>();
+        const uint32_t tot_miss = tile_prefix_to_lds<4>(ws.tile_miss, ptiles, fl.pre_miss, fl.scan);
+        const uint32_t tot_stale = tile_prefix_to_lds<4>(ws.tile_stale, ptiles, fl.pre_stale, fl.scan);
+        const uint32_t gid = bid * groups_per_block + threadIdx.x / g.lanes;
         const uint32_t ngroups = fill_blocks * groups_per_block;
         const uint32_t t = t_now;
-        if (blockIdx.x == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // for an update that reuses this order
+        if (bid == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // for an update that reuses this order
         for (uint32_t m = gid; m < tot_miss; m += ngroups) {                 // Fetch(k) into a new slot
-            const uint32_t tl = tile_of(pre_miss, ptiles, m);
-            const uint2 jk = ws.miss_stage[tl * PT_TILE + (m - pre_miss[tl])];
+            const uint32_t tl = tile_of(fl.pre_miss, ptiles, m);
+            const uint2 jk = ws.miss_stage[tl * PT_TILE + (m - fl.pre_miss[tl])];
             const uint32_t slot = cv.free_list[m];
             const uint32_t j = jk.x, key = jk.y;
             const uint32_t cg = cv.Cg[key];
@@ -444,8 +461,8 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             }
         }
         for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
-            const uint32_t tl = tile_of(pre_stale, ptiles, m);
-            const uint2 jk = ws.stale_stage[tl * PT_TILE + (m - pre_stale[tl])];
+            const uint32_t tl = tile_of(fl.pre_stale, ptiles, m);
+            const uint2 jk = ws.stale_stage[tl * PT_TILE + (m - fl.pre_stale[tl])];
             const uint32_t key = jk.y;
             const uint32_t slot = (uint32_t)ws.head_slot[jk.x];
             const bool has_updates = cv.meta[slot].cc > cv.meta[slot].cs;
@@ -460,17 +477,17 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         return;
     }
 
-    if (blockIdx.x < fill_blocks + hist_blocks) {
+    if (bid < fill_blocks + hist_blocks) {
         // first pass of the coming trim's select, over the rows cached before this lookup plus the
         // rows being fetched right now (counted, not read)
-        __shared__ TrimLds tl;
+        TrimLds &tl = lds_as<TrimLds>();
         const uint32_t new_rows = block_sum_array<TRIM_WAVES>(ws.tile_miss, ptiles, tl.scan);
-        trim_hist_body(cv, tp, 0, blockIdx.x - fill_blocks, hist_blocks, tl, true, new_rows, t_now);
+        trim_hist_body(cv, tp, 0, bid - fill_blocks, hist_blocks, tl, true, new_rows, t_now);
         return;
     }
     const uint32_t first_gather = fill_blocks + hist_blocks;
-    const uint32_t gid = (blockIdx.x - first_gather) * groups_per_block + threadIdx.x / g.lanes;
-    const uint32_t ngroups = (gridDim.x - first_gather) * groups_per_block;
+    const uint32_t gid = (bid - first_gather) * groups_per_block + threadIdx.x / g.lanes;
+    const uint32_t ngroups = (nblk - first_gather) * groups_per_block;
     if (!POOLED) {
         for (uint32_t j = gid; j < n; j += ngroups) {                    // Get
             const int32_t s = ws.src[j];
@@ -558,21 +575,23 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 template <int VEC, int MAXC, bool VERIFY>
 __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, const int64_t *__restrict__ ids,
                                                     const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
-                                                    float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage)
+                                                    float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
+                                                    SortStage ride)
 {
     using V = typename VecT<VEC>::type;
-    if (blockIdx.x >= work_blocks) {     // extra workgroups: a stage of the coming trim's select
-        __shared__ TrimLds tl;
-        trim_stage_body(cv, tp, stage, blockIdx.x - work_blocks, gridDim.x - work_blocks, tl);
+    if (blockIdx.x < ride.blocks) { sort_stage_body(ride, blockIdx.x, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
+    const uint32_t bid = blockIdx.x - ride.blocks, nblk = gridDim.x - ride.blocks;
+    if (bid >= work_blocks) {            // extra workgroups: a stage of the coming trim's select
+        trim_stage_body(cv, tp, stage, bid - work_blocks, nblk - work_blocks, lds_as<TrimLds>());
         return;
     }
     const RowGeom g = cv.geom;
-    const uint32_t gid = (blockIdx.x * 256u + threadIdx.x) / g.lanes;
+    const uint32_t gid = (bid * 256u + threadIdx.x) / g.lanes;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t ngroups = work_blocks * 256u / g.lanes;
     const uint32_t nv = cv.ds->n_valid;
     const uint32_t *skey = ws.skey;
-    if (VERIFY && blockIdx.x == 0 && threadIdx.x == 0) {
+    if (VERIFY && bid == 0 && threadIdx.x == 0) {
         // this call did not sort: its per-call counters start here, with the lookup's key count
         DState *ds = cv.ds;
         Counters z{};
@@ -709,19 +728,27 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 // shares are added in group order.  Either way the order of additions is fixed by the sorted
 // order alone.
 constexpr int FIN_NEAR = 4;
+template <int VEC> struct FinishLds {
+    double share[256 * VEC];
+    uint32_t long_c[256], long_c1[256];
+    int32_t long_slot[256];
+    uint32_t n_long;
+};
 template <int VEC, int MAXC>
 __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
-                                                           uint32_t work_blocks, TrimPlan tp, int stage)
+                                                           uint32_t work_blocks, TrimPlan tp, int stage, SortStage ride)
 {
-    if (blockIdx.x >= work_blocks) {     // extra workgroups: the next stage of the trim's select
-        __shared__ TrimLds tl;
-        trim_stage_body(cv, tp, stage, blockIdx.x - work_blocks, gridDim.x - work_blocks, tl);
+    if (blockIdx.x < ride.blocks) { sort_stage_body(ride, blockIdx.x, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
+    const uint32_t bid = blockIdx.x - ride.blocks, nblk = gridDim.x - ride.blocks;
+    if (bid >= work_blocks) {            // extra workgroups: the next stage of the trim's select
+        trim_stage_body(cv, tp, stage, bid - work_blocks, nblk - work_blocks, lds_as<TrimLds>());
         return;
     }
-    __shared__ uint32_t long_c[256], long_c1[256];
-    __shared__ int32_t long_slot[256];
-    __shared__ uint32_t n_long;
-    __shared__ double share[256 * VEC];
+    FinishLds<VEC> &fl = lds_as<FinishLds<VEC>>();
+    uint32_t *long_c = fl.long_c, *long_c1 = fl.long_c1;
+    int32_t *long_slot = fl.long_slot;
+    uint32_t &n_long = fl.n_long;
+    double *share = fl.share;
     const RowGeom g = cv.geom;
     const uint32_t groups_per_block = 256u / g.lanes;
     const uint32_t group = threadIdx.x / g.lanes;
@@ -733,7 +760,7 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
     if (threadIdx.x == 0) n_long = 0;
     __syncthreads();
 
-    for (uint32_t base = blockIdx.x * groups_per_block; base < nchunks_max; base += work_blocks * groups_per_block) {
+    for (uint32_t base = bid * groups_per_block; base < nchunks_max; base += work_blocks * groups_per_block) {
         const uint32_t c = base + group;
         const uint32_t jb = (c + 1) * CHUNK;                       // first position of the next chunk
         int32_t slot = SLOT_NONE;
@@ -836,13 +863,22 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
 // accumulator) to the global table: Evict's push (Section 3.1).  Four workgroups share a
 // 1024-slot tile of the free-list kernel; each adds its free slots to the tile's count
 // (tile_free is zero when the trim starts).
-template <int VEC>
-__global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, TrimPlan tp)
+struct EvictLds {
+    uint32_t scan[TRIM_WAVES + 1];
+    uint32_t v_slot[EV_SLOTS], v_key[EV_SLOTS];
+    uint32_t n_push, ev_base;
+};
+template <int VEC, bool RIDE>
+__global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, TrimPlan tp, SortStage ride)
 {
-    __shared__ uint32_t scan[TRIM_WAVES + 1];
-    __shared__ uint32_t v_slot[EV_SLOTS], v_key[EV_SLOTS];
-    __shared__ uint32_t n_push, ev_base;
-    const uint32_t blk = blockIdx.x;
+    uint32_t blk = blockIdx.x;
+    if (RIDE) {
+        if (blk < ride.blocks) { sort_stage_body(ride, blk, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
+        blk -= ride.blocks;
+    }
+    EvictLds &el = lds_as<EvictLds>();
+    uint32_t *scan = el.scan, *v_slot = el.v_slot, *v_key = el.v_key;
+    uint32_t &n_push = el.n_push, &ev_base = el.ev_base;
     const uint32_t slot = blk * EV_SLOTS + threadIdx.x;
     const bool in = slot < cv.n_slots;
     // everything this thread may need, requested at once

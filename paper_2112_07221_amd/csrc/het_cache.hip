@@ -19,14 +19,24 @@ using namespace het;
 
 // Kernels of the path, as named in profiles and by het_profile_kernel_name.
 enum KernelId {
-    K_DEDUP_HIST, K_SORT_PASS, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_APPLY_FINISH, K_TRIM_STAGE,
+    K_SORT_STAGE, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_APPLY_FINISH, K_TRIM_STAGE,
     K_TRIM_EVICT, K_FLUSH, K_MISC, K_NUM
 };
 static const char *const kKernelNames[K_NUM] = {
-    "dedup_hist_kernel", "sort_pass_kernel", "probe_kernel", "pooled_index_kernel", "fill_gather_kernel",
+    "sort_stage_kernel", "probe_kernel", "pooled_index_kernel", "fill_gather_kernel",
     "apply_kernel", "apply_finish_kernel", "trim_stage_kernel", "trim_evict_kernel", "flush_kernel", "misc"};
 
 struct ProfSpan { int id; hipEvent_t start, stop; };
+
+constexpr int SORT_SETS = 3;
+
+// A batch announced by het_prefetch: its ids, the buffer set its sort uses and how far the sort has come.
+struct Announced {
+    const int64_t *ids = nullptr;
+    uint32_t n = 0;
+    int set = 0;
+    int next_stage = 0;              // stages [0, next_stage) are enqueued; 2 * passes stages in all
+};
 
 struct het_cache {
     // creation parameters
@@ -43,19 +53,14 @@ struct het_cache {
     CacheView cv{};
     Workspace ws{};
     TrimPlan tp{};
-    // two complete sets of sort buffers: the order of the current batch stays intact for the
-    // update while the next batch is sorted into the other set
-    uint32_t *keys[2][2] = {}, *idx[2][2] = {};
-    uint32_t *sort_hist[2][SORT_MAX_PASSES] = {};
+    // Three sets of sort buffers: the order of the current batch (kept for its update) and up to
+    // two batches announced ahead by het_prefetch, whose sorts are carried by the kernels of the
+    // calls in between.
+    uint32_t *keys[SORT_SETS][2] = {}, *idx[SORT_SETS][2] = {};
+    uint32_t *sort_hist[SORT_SETS] = {};
     int sort_set = 0;                // the set that holds the current batch's order
-    // side stream: the next batch's sort and the trim's select run beside the main stream
-    hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_sort = nullptr;
-    const int64_t *prefetch_ids = nullptr;   // ids sorted ahead of their lookup by het_prefetch
-    uint32_t prefetch_n = 0;
-    bool prefetched = false;
-    bool fork_recorded = false;      // ev_fork marks the end of the last lookup
-    int prefetch_buf = 0;
+    Announced ann[2];                // announced batches, oldest first
+    int n_ann = 0;
     TrimPlan sel_tp{};               // the select plan of the rows now cached (fixed at the lookup)
     bool last_trim_skipped = false;  // the last update had nothing to trim: its evicted-id list is empty
     int cslot = 0;                   // which of the two per-call counter blocks the current call uses
@@ -137,7 +142,9 @@ struct LaunchScope {
     {
         if (!on) return;
         sp.id = id;
-        if (hipEventCreate(&sp.start) != hipSuccess || hipEventCreate(&sp.stop) != hipSuccess) { on = false; return; }
+        // timing only: no system-scope fence, whose cache write-back would be billed to the kernels
+        if (hipEventCreateWithFlags(&sp.start, hipEventDisableSystemFence) != hipSuccess ||
+            hipEventCreateWithFlags(&sp.stop, hipEventDisableSystemFence) != hipSuccess) { on = false; return; }
         (void)hipEventRecord(sp.start, st);
     }
     ~LaunchScope()
@@ -175,12 +182,42 @@ SortPlan make_sort_plan(const het_cache *c, uint32_t n, int set)
     sp.vocab = c->cv.vocab;
     const int bits = bit_width(sp.vocab);               // the key `vocab` itself marks a bad id
     sp.passes = std::max(1, (bits + SORT_MAX_BITS - 1) / SORT_MAX_BITS);
-    sp.width = std::max(2, (bits + sp.passes - 1) / sp.passes);      // the pass kernel reads four digits' counts at a time
-    const int items = n <= 32u * 4096u ? 8 : (n <= 32u * 8192u ? 16 : 32);   // keep the tile count small
-    sp.tile = SORT_THREADS * items;
-    sp.ntiles = cdiv(n, sp.tile);
-    for (int p = 0; p < SORT_MAX_PASSES; ++p) sp.hist[p] = c->sort_hist[set][p];
+    sp.width = std::max(SORT_MIN_BITS, (bits + sp.passes - 1) / sp.passes);
+    sp.ntiles = cdiv(n, SORT_TILE);
+    sp.hist = c->sort_hist[set];
     return sp;
+}
+
+int sort_stages(const het_cache *c) { return 2 * make_sort_plan(c, 1, 0).passes; }
+int sort_result_buffer(const het_cache *c) { return (make_sort_plan(c, 1, 0).passes - 1) & 1; }
+
+// Stage `stage` of the sort of ids[n] into buffer set `set`.  Pass p writes buffer p & 1 of the
+// set and reads the other one; stage 0 leaves the ids, converted to keys, where pass 0 reads.
+SortStage make_stage(const het_cache *c, const int64_t *ids, uint32_t n, int set, int stage)
+{
+    SortStage s{};
+    s.sp = make_sort_plan(c, n, set);
+    const int pass = stage >> 1, out = pass & 1, in = 1 - out;
+    s.ids = ids;
+    s.keys_in = c->keys[set][in]; s.idx_in = c->idx[set][in];
+    s.keys_out = stage == 0 ? c->keys[set][in] : c->keys[set][out];
+    s.idx_out = c->idx[set][out];
+    s.stage = stage;
+    s.blocks = s.sp.ntiles;
+    return s;
+}
+
+SortStage no_stage()
+{
+    SortStage s{};
+    s.stage = -1;
+    return s;
+}
+
+// LDS a kernel needs: its own roles' or, if larger, the carried stage's.
+uint32_t lds_bytes(size_t own, const SortStage &ride)
+{
+    return std::max<uint32_t>((uint32_t)own, ride.blocks ? sort_stage_lds_bytes(ride.sp.width, ride.stage) : 0u);
 }
 
 // Begins a call that touches the cache: per-call counters go to the other counter block.
@@ -191,37 +228,35 @@ void begin_call(het_cache *c)
     c->cv.next_call = &c->cv.ds->call[1 - c->cslot];
 }
 
-template <int ITEMS>
-void launch_sort(het_cache *c, hipStream_t st, const int64_t *ids, const SortPlan &sp, int set, int *result_buffer)
+// Stages [first_stage, end) of a sort as kernels of their own.
+void sort_now(het_cache *c, const int64_t *ids, uint32_t n, int set, int first_stage)
 {
-    LAUNCH_ON(c, st, K_DEDUP_HIST, dedup_hist_kernel<ITEMS><<<sp.ntiles, SORT_THREADS, 0, st>>>(ids, sp, c->cv.ds));
-    int in = 0;
-    for (int p = 0; p < sp.passes; ++p) {
-        const int out = p == 0 ? 0 : 1 - in;
-        if (p == 0)
-            LAUNCH_ON(c, st, K_SORT_PASS, sort_pass_kernel<ITEMS, true><<<sp.ntiles, SORT_THREADS, 0, st>>>(
-                                              ids, nullptr, nullptr, c->keys[set][out], c->idx[set][out], sp, p));
-        else
-            LAUNCH_ON(c, st, K_SORT_PASS, sort_pass_kernel<ITEMS, false><<<sp.ntiles, SORT_THREADS, 0, st>>>(
-                                              nullptr, c->keys[set][in], c->idx[set][in], c->keys[set][out], c->idx[set][out], sp, p));
-        in = out;
+    for (int st = first_stage; st < sort_stages(c); ++st) {
+        const SortStage s = make_stage(c, ids, n, set, st);
+        LAUNCH(c, K_SORT_STAGE, sort_stage_kernel<<<s.blocks, SORT_THREADS, sort_stage_lds_bytes(s.sp.width, s.stage), c->stream>>>(s));
     }
-    *result_buffer = in;
 }
 
-// Sorts ids[n] into buffer set `set` on stream `st`; returns which buffer of the set holds the result.
-int sort_ids(het_cache *c, hipStream_t st, const int64_t *ids, uint32_t n, int set)
+// The next stage of the oldest announced batch whose sort is not complete yet, for the kernel
+// that is about to be launched to carry.
+SortStage next_ride(het_cache *c)
 {
-    const SortPlan sp = make_sort_plan(c, n, set);
-    int buf = 0;
-    if (sp.tile == SORT_THREADS * 8) launch_sort<8>(c, st, ids, sp, set, &buf);
-    else if (sp.tile == SORT_THREADS * 16) launch_sort<16>(c, st, ids, sp, set, &buf);
-    else launch_sort<32>(c, st, ids, sp, set, &buf);
-    return buf;
+    for (int a = 0; a < c->n_ann; ++a) {
+        Announced &an = c->ann[a];
+        if (an.next_stage < sort_stages(c)) return make_stage(c, an.ids, an.n, an.set, an.next_stage++);
+    }
+    return no_stage();
 }
 
-void use_order(het_cache *c, int set, int buf)
+void drop_oldest_announcement(het_cache *c)
 {
+    c->ann[0] = c->ann[1];
+    c->n_ann -= 1;
+}
+
+void use_order(het_cache *c, int set)
+{
+    const int buf = sort_result_buffer(c);
     c->sort_set = set;
     c->ws.skey = c->keys[set][buf];
     c->ws.perm = c->idx[set][buf];
@@ -258,7 +293,12 @@ int run_trim(het_cache *c, int first_stage)
     tp.tile_free = c->tile_free[fill];
     tp.ev_slot = fill;
     tp.ev_ids = c->ev_ids[fill];
-    LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC><<<cdiv(c->cv.n_slots, EV_SLOTS), TRIM_THREADS, 0, c->stream>>>(c->cv, tp));
+    const SortStage ride = next_ride(c);
+    const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
+    if (ride.blocks)
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true><<<ride.blocks + ev_blocks, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride));
+    else
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false><<<ev_blocks, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride));
     c->tf_last = fill;
     c->overflow_pending = false;
     c->last_trim_skipped = false;
@@ -273,17 +313,22 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     c->t_host += 1;
     int rc;
     if (c->overflow_pending && (rc = run_trim<VEC>(c, 1)) != HET_OK) return rc;   // a Read that follows a Read (stage 0 rode with its fetches)
-    // the sorted order: already made by het_prefetch on the side stream, or made here
-    const int set = 1 - c->sort_set;
-    if (c->prefetched && ids == c->prefetch_ids && n == c->prefetch_n) {
-        HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_sort, 0));
-        use_order(c, set, c->prefetch_buf);
+    // The sorted order: announced by het_prefetch and sorted inside the kernels launched since
+    // (what is left of it runs now), or sorted here.  Announcements older than the one used are
+    // void; with no match they all stand (a later lookup may still use them).
+    int match = -1;
+    for (int a = 0; a < c->n_ann && match < 0; ++a)
+        if (c->ann[a].ids == ids && c->ann[a].n == n) match = a;
+    if (match >= 0) {
+        for (int a = 0; a < match; ++a) drop_oldest_announcement(c);
+        const Announced an = c->ann[0];
+        drop_oldest_announcement(c);
+        sort_now(c, ids, n, an.set, an.next_stage);
+        use_order(c, an.set);
     } else {
-        if (c->prefetched) HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_sort, 0));   // an unused prefetch still owns the set
-        const int buf = sort_ids(c, c->stream, ids, n, set);
-        use_order(c, set, buf);
+        sort_now(c, ids, n, c->sort_set, 0);             // over the previous batch's order: it is not needed any more
+        use_order(c, c->sort_set);
     }
-    c->prefetched = false;
     const uint32_t t_now = (uint32_t)c->t_host;
     const uint32_t ptiles = cdiv(n, PT_TILE), stiles = cdiv(c->cv.n_slots, PT_TILE);
     LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + stiles, PT_THREADS, 0, c->stream>>>(
@@ -293,17 +338,18 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const TrimPlan &tp = c->sel_tp;
     const uint32_t hist_blocks = stage_blocks(c, tp, 0);       // stage 0 of the select rides with the fetches
     const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 1024u);     // they come first: theirs is the longer chain
-    if (!offsets) {
-        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false><<<fill_blocks + hist_blocks + row_grid(c->cv.geom, n), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, tp, hist_blocks, out, nullptr, 0, nullptr));
-    } else {
+    if (offsets)
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
-        LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, true><<<fill_blocks + hist_blocks + row_grid(c->cv.geom, n_bags), 256, 0, c->stream>>>(
-                                     c->cv, c->ws, n, t_now, ptiles, fill_blocks, tp, hist_blocks, out, offsets, n_bags, c->inv));
-    }
+    const SortStage ride = next_ride(c);
+    const uint32_t blocks = ride.blocks + fill_blocks + hist_blocks + row_grid(c->cv.geom, offsets ? n_bags : n);
+    const uint32_t lds = lds_bytes(std::max(sizeof(FillLds), sizeof(TrimLds)), ride);
+#define FILL_GATHER(POOLED, RIDE)                                                                                         \
+    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<blocks, 256, lds, c->stream>>>(                        \
+                                 c->cv, c->ws, n, t_now, ptiles, fill_blocks, tp, hist_blocks, out, offsets, n_bags, c->inv, ride))
+    if (!offsets) { if (ride.blocks) FILL_GATHER(false, true); else FILL_GATHER(false, false); }
+    else { if (ride.blocks) FILL_GATHER(true, true); else FILL_GATHER(true, false); }
+#undef FILL_GATHER
     if ((rc = launch_ok()) != HET_OK) return rc;
-    HIP_TRY(hipEventRecord(c->ev_fork, c->stream));      // a prefetch may start from here
-    c->fork_recorded = true;
     c->overflow_pending = true;
     c->last_lookup_n = n;
     c->order_ids = ids; c->order_n = n; c->order_valid = true;
@@ -320,11 +366,15 @@ void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, con
     // stage 0 rode with the lookup's fetches; this call's two kernels carry stages 1 and 2
     const uint32_t extra0 = stages_carried > 0 ? stage_blocks(c, tp, 1) : 0u;
     const uint32_t extra1 = stages_carried > 1 ? stage_blocks(c, tp, 2) : 0u;
+    const SortStage ride0 = next_ride(c);
+    const uint32_t lds0 = lds_bytes(sizeof(TrimLds), ride0);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1, ride0));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<grid + extra0, 256, 0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1));
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<grid + extra1, 256, 0, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, 2));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1, ride0));
+    const SortStage ride1 = next_ride(c);
+    const uint32_t lds1 = lds_bytes(std::max(sizeof(TrimLds), sizeof(FinishLds<VEC>)), ride1);
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<ride1.blocks + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, 2, ride1));
 }
 
 template <int VEC>
@@ -335,11 +385,11 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     int rc;
     // The ids of the preceding lookup, passed again: reuse its sorted order (the apply kernel
     // checks every id against it).  Anything else is sorted and probed afresh, into the current
-    // set of sort buffers (a prefetch under way uses the other set).
+    // set of sort buffers (announced batches use the other sets).
     const bool reuse = c->order_valid && ids == c->order_ids && n == c->order_n;
     if (!reuse) {
-        const int buf = sort_ids(c, c->stream, ids, n, c->sort_set);
-        use_order(c, c->sort_set, buf);
+        sort_now(c, ids, n, c->sort_set, 0);
+        use_order(c, c->sort_set);
         LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
                                c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u));
     }
@@ -365,7 +415,6 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 int sync_all(het_cache *c)
 {
     HIP_TRY(hipStreamSynchronize(c->stream));
-    if (c->side) HIP_TRY(hipStreamSynchronize(c->side));
     return HET_OK;
 }
 
@@ -444,17 +493,13 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     Workspace &ws = c->ws;
     const size_t N = (size_t)max_batch_ids;
     const size_t ptiles = cdiv(N, PT_TILE);
-    const size_t sort_tiles = std::max<size_t>(32, cdiv(N, SORT_THREADS * 32));
+    const size_t sort_tiles = cdiv(N, SORT_TILE);
     const size_t chunks = cdiv(N, CHUNK);
-    for (int set = 0; set < 2; ++set) {
+    for (int set = 0; set < SORT_SETS; ++set) {
         for (int i = 0; i < 2; ++i)
             if ((rc = dev_alloc(c, &c->keys[set][i], N)) || (rc = dev_alloc(c, &c->idx[set][i], N))) return rc;
-        for (int p = 0; p < SORT_MAX_PASSES; ++p)
-            if ((rc = dev_alloc(c, &c->sort_hist[set][p], sort_tiles * SORT_MAX_BINS))) return rc;
+        if ((rc = dev_alloc(c, &c->sort_hist[set], sort_tiles * (SORT_MAX_BINS / 2)))) return rc;
     }
-    HIP_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));       // default priority
-    for (hipEvent_t *e : {&c->ev_fork, &c->ev_sort})
-        HIP_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
     c->cv.last = &cv.ds->call[0];
     c->cv.next_call = &cv.ds->call[1];
     if ((rc = dev_alloc(c, &ws.src, N)) || (rc = dev_alloc(c, &ws.head_slot, N)) || (rc = dev_alloc(c, &ws.cls, N)) ||
@@ -509,20 +554,20 @@ int het_prefetch(het_cache *c, const int64_t *ids, int64_t n)
     if (!ready(c) || n < 0 || n > c->max_ids) return HET_EINVAL;
     if (n == 0) return HET_OK;
     if (!ids) return HET_EINVAL;
-    // The side stream starts where the last lookup ended on the main stream (or here, if there
-    // was none): the last readers of the buffer set it sorts into, the calls before that lookup,
-    // are done by then, and the caller guarantees the ids are.  An update enqueued in between does
-    // not hold the sort back.
-    const int set = 1 - c->sort_set;
-    if (!c->fork_recorded) HIP_TRY(hipEventRecord(c->ev_fork, c->stream));
-    c->fork_recorded = true;
-    HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
-    const int buf = sort_ids(c, c->side, ids, (uint32_t)n, set);
-    int rc = launch_ok();
-    if (rc) return rc;
-    HIP_TRY(hipEventRecord(c->ev_sort, c->side));
-    c->prefetch_ids = ids; c->prefetch_n = (uint32_t)n; c->prefetched = true;
-    c->prefetch_buf = buf;
+    // Nothing is launched here: the kernels of the calls that follow carry the sort, stage by
+    // stage, into a buffer set that neither the current order nor an earlier announcement uses.
+    // With both spare sets taken, the oldest announcement makes room.
+    if (c->n_ann && c->ann[c->n_ann - 1].ids == ids && c->ann[c->n_ann - 1].n == (uint32_t)n) return HET_OK;   // said already
+    if (c->n_ann == SORT_SETS - 1) drop_oldest_announcement(c);
+    for (int set = 0; set < SORT_SETS; ++set) {
+        bool taken = set == c->sort_set;
+        for (int a = 0; a < c->n_ann; ++a) taken = taken || c->ann[a].set == set;
+        if (taken) continue;
+        Announced an;
+        an.ids = ids; an.n = (uint32_t)n; an.set = set; an.next_stage = 0;
+        c->ann[c->n_ann++] = an;
+        break;
+    }
     return HET_OK;
 }
 
@@ -720,9 +765,6 @@ int het_cache_destroy(het_cache *c)
     if (!c) return HET_OK;
     int rc = HET_OK;
     if (c->configured && sync_all(c) != HET_OK) rc = HET_EHIP;
-    for (hipEvent_t e : {c->ev_fork, c->ev_sort})
-        if (e && hipEventDestroy(e) != hipSuccess) rc = HET_EHIP;
-    if (c->side && hipStreamDestroy(c->side) != hipSuccess) rc = HET_EHIP;
     for (void *p : c->owned)
         if (hipFree(p) != hipSuccess) rc = HET_EHIP;
     delete c;

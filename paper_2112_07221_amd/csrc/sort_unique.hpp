@@ -7,19 +7,27 @@
 // A run of equal keys in skey is one unique key; its first position is the key's "head".
 // Ids outside [0, vocab) get the key `vocab`, which sorts behind every valid id.
 //
-// Kernel count is what matters at minibatch sizes (a launch costs more than moving 100k
-// keys), so a pass is a single kernel: every workgroup owns a tile of keys and derives its
-// output offsets itself from the per-tile digit histograms ("count at the producer, prefix at
-// the consumer").  The histograms of the first pass are counted from the ids; while a pass
-// scatters a key it already counts it for the next pass, in the tile where it lands.  No
-// workgroup ever waits for another one.
+// The sort is a sequence of stages, two per pass: a histogram stage counts the pass's digit per
+// tile of 4096 keys, a scatter stage moves the keys.  Every workgroup of a scatter stage derives
+// its output offsets itself from the per-tile histograms ("count at the producer, prefix at the
+// consumer"); no workgroup ever waits for another one, and nothing is counted with global
+// atomics (a popular id would make hundreds of them hit one address).
+//
+// A stage is a device function for workgroups of 256 threads, not a kernel: the sort of the
+// NEXT minibatch (Section 4.2: its indices are known in advance) touches no cache state, so
+// its stages are carried, one per kernel, in extra workgroups of the kernels of the current
+// Read and Write.  At minibatch size those kernels are bound by latency, not by throughput, and
+// the sort disappears inside them; a stage nobody carried runs as a kernel of its own.
 #pragma once
 #include "common.hpp"
 
 namespace het {
 
-constexpr int SORT_THREADS = 512;
+constexpr int SORT_THREADS = 256;
 constexpr int SORT_WAVES = SORT_THREADS / WAVE;
+constexpr int SORT_ITEMS = 16;
+constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;     // keys per workgroup
+constexpr int SORT_MIN_BITS = 3;                         // a histogram row is read 8 digits at a time
 constexpr int SORT_MAX_BITS = 11;
 constexpr int SORT_MAX_BINS = 1 << SORT_MAX_BITS;
 constexpr int SORT_MAX_PASSES = 3;                       // vocab < 2^32
@@ -28,145 +36,171 @@ constexpr int SORT_BINS_PER_THREAD = SORT_MAX_BINS / SORT_THREADS;
 struct SortPlan {
     uint32_t n;            // keys
     uint32_t vocab;
-    uint32_t tile;         // keys per workgroup = SORT_THREADS * items
-    uint32_t ntiles;
+    uint32_t ntiles;       // ceil(n / SORT_TILE)
     int passes;            // 1..3
-    int width;             // bits per digit (<= 11)
-    uint32_t *hist[SORT_MAX_PASSES];   // per pass: [ntiles][1 << width]
+    int width;             // bits per digit (3..11)
+    uint32_t *hist;        // [ntiles][bins / 2]: the current pass's digit counts per tile, two 16-bit counts per word
 };
+
+// One stage of a sort, as handed to the kernel that runs it.
+struct SortStage {
+    SortPlan sp;
+    const int64_t *ids;                    // the caller's ids (read by stage 0 only)
+    const uint32_t *keys_in, *idx_in;      // input of the pass (idx_in unused in pass 0: the payload is the position)
+    uint32_t *keys_out, *idx_out;          // output of the pass; the first stage writes the converted ids to keys_out
+    int stage;                             // 2p: histogram of pass p;  2p + 1: scatter of pass p
+    uint32_t blocks;                       // workgroups the stage needs (sp.ntiles), 0: no stage
+};
+
+__host__ __device__ inline uint32_t sort_stage_lds_bytes(int width, int stage)
+{
+    const uint32_t bins = 1u << width;
+    return (stage & 1) ? (SORT_WAVES + 1) * bins * 4u + 64u : bins * 4u;
+}
 
 __device__ __forceinline__ uint32_t id_to_key(int64_t id, uint32_t vocab)
 {
     return (id >= 0 && id < (int64_t)vocab) ? (uint32_t)id : vocab;
 }
 
-// Position of item `it` of this thread inside its tile: a wave owns ITEMS*64 consecutive keys
-// and walks them 64 at a time, so (wave, item, lane) order is position order.
-template <int ITEMS>
-__device__ __forceinline__ uint32_t sort_pos(uint32_t tile_index, int it)
+// Position of item `it` of this thread inside its tile: a wave owns SORT_ITEMS * 64 consecutive
+// keys and walks them 64 at a time, so (wave, item, lane) order is position order.
+__device__ __forceinline__ uint32_t sort_pos(uint32_t tile, int it)
 {
     const uint32_t w = threadIdx.x / WAVE;
-    return tile_index * (SORT_THREADS * ITEMS) + w * (WAVE * ITEMS) + it * WAVE + lane_id();
+    return tile * SORT_TILE + w * (WAVE * SORT_ITEMS) + it * WAVE + lane_id();
 }
 
-// First kernel of a sort: digit histogram of pass 0 per tile, straight from the ids; flags ids
-// outside the vocabulary; clears the histograms the later passes count into.  It touches no
-// cache state, so the sort of the next minibatch may run beside the current update.
-template <int ITEMS>
-__global__ __launch_bounds__(SORT_THREADS) void dedup_hist_kernel(const int64_t *__restrict__ ids, SortPlan sp, DState *ds)
+// Histogram stage of pass p for one tile.  Pass 0 reads the ids and leaves them as 32-bit keys
+// (keys_out) for its scatter stage.  lds: bins words.
+__device__ __forceinline__ void sort_hist_body(const SortStage &s, uint32_t tile, uint32_t *lds)
 {
-    __shared__ uint32_t hist[SORT_MAX_BINS];
-    const uint32_t tile = blockIdx.x;
-    const uint32_t bins = 1u << sp.width, mask = bins - 1u;
-    for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) hist[b] = 0;
-    for (int p = 1; p < sp.passes; ++p)
-        for (uint32_t i = tile * SORT_THREADS + threadIdx.x; i < sp.ntiles * bins; i += gridDim.x * SORT_THREADS) sp.hist[p][i] = 0;
-    __syncthreads();
-    bool bad = false;
+    const SortPlan &sp = s.sp;
+    const int pass = s.stage >> 1;
+    const uint32_t bins = 1u << sp.width, mask = bins - 1u, shift = (uint32_t)(pass * sp.width);
+    // all of the tile's keys are requested before the first is used (the pass is uniform: no
+    // branch per key)
+    uint32_t key[SORT_ITEMS];
+    if (pass == 0) {
+        int64_t id[SORT_ITEMS];
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const uint32_t i = sort_pos<ITEMS>(tile, it);
+        for (int it = 0; it < SORT_ITEMS; ++it) { const uint32_t i = sort_pos(tile, it); id[it] = i < sp.n ? s.ids[i] : 0; }
+#pragma unroll
+        for (int it = 0; it < SORT_ITEMS; ++it) key[it] = id_to_key(id[it], sp.vocab);
+    } else {
+#pragma unroll
+        for (int it = 0; it < SORT_ITEMS; ++it) { const uint32_t i = sort_pos(tile, it); key[it] = i < sp.n ? s.keys_in[i] : 0u; }
+    }
+    for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) lds[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < SORT_ITEMS; ++it) {
+        const uint32_t i = sort_pos(tile, it);
         if (i < sp.n) {
-            const uint32_t key = id_to_key(ids[i], sp.vocab);
-            bad |= key == sp.vocab;
-            atomicAdd(&hist[key & mask], 1u);
+            atomicAdd(&lds[(key[it] >> shift) & mask], 1u);
+            if (pass == 0) s.keys_out[i] = key[it];
         }
     }
-    if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
     __syncthreads();
-    for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) sp.hist[0][tile * bins + b] = hist[b];
+    for (uint32_t w = threadIdx.x; w < bins / 2; w += SORT_THREADS)
+        sp.hist[(size_t)tile * (bins / 2) + w] = lds[2 * w] | (lds[2 * w + 1] << 16);     // a tile has 4096 keys: counts fit 16 bits
 }
 
-// One stable scatter pass.  FIRST reads the ids (positions are the payload); later passes
-// read the previous pass's keys and payload.
-template <int ITEMS, bool FIRST>
-__global__ __launch_bounds__(SORT_THREADS) void sort_pass_kernel(const int64_t *__restrict__ ids, const uint32_t *__restrict__ keys_in,
-                                                                 const uint32_t *__restrict__ idx_in, uint32_t *__restrict__ keys_out,
-                                                                 uint32_t *__restrict__ idx_out, SortPlan sp, int pass)
+// Scatter stage of pass p for one tile: stable.  lds: (SORT_WAVES + 1) * bins words + 16.
+__device__ __forceinline__ void sort_scatter_body(const SortStage &s, uint32_t tile, uint32_t *lds)
 {
-    __shared__ uint32_t wave_hist[SORT_WAVES][SORT_MAX_BINS];
-    __shared__ uint32_t tile_base[SORT_MAX_BINS];
-    __shared__ uint32_t scan_lds[SORT_WAVES + 1];
-    const uint32_t tile = blockIdx.x, w = threadIdx.x / WAVE;
+    const SortPlan &sp = s.sp;
+    const int pass = s.stage >> 1;
     const int width = sp.width;
-    const uint32_t bins = 1u << width, mask = bins - 1u;
-    const uint32_t shift = (uint32_t)(pass * width);
-    const bool last = pass + 1 == sp.passes;
-
-    // the keys (and payload) of this tile: issued first, they arrive while the offsets are computed
-    uint32_t key[ITEMS], pay[ITEMS], lrank[ITEMS];
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const uint32_t i = sort_pos<ITEMS>(tile, it);
-        const bool valid = i < sp.n;
-        key[it] = valid ? (FIRST ? id_to_key(ids[i], sp.vocab) : keys_in[i]) : 0u;
-        pay[it] = FIRST ? i : (valid ? idx_in[i] : 0u);
-    }
-    for (uint32_t b = threadIdx.x; b < SORT_WAVES * SORT_MAX_BINS; b += SORT_THREADS) (&wave_hist[0][0])[b] = 0;
+    const uint32_t bins = 1u << width, mask = bins - 1u, shift = (uint32_t)(pass * width);
+    const uint32_t w = threadIdx.x / WAVE;
+    uint32_t *wave_hist = lds;                         // [SORT_WAVES][bins]
+    uint32_t *tile_base = lds + SORT_WAVES * bins;     // [bins]
+    uint32_t *scan_lds = tile_base + bins;             // [SORT_WAVES + 1]
 
     // Output offset of each digit for this tile: keys of smaller digits anywhere, plus keys of
-    // the same digit in earlier tiles.  A thread adds up four consecutive digits (one 16-byte
+    // the same digit in earlier tiles.  A thread adds up eight consecutive digits (one 16-byte
     // load per tile, many loads in flight) over every TLN-th tile; LDS merges the tile lanes.
     {
-        uint32_t *tot = &wave_hist[0][0], *bef = &wave_hist[1][0];      // borrowed until the ranking starts
-        for (uint32_t b = threadIdx.x; b < bins; b += SORT_THREADS) { tot[b] = 0; bef[b] = 0; }
+        uint32_t *tot = wave_hist, *bef = wave_hist + bins;      // borrowed until the ranking starts
+        for (uint32_t b = threadIdx.x; b < 2 * bins; b += SORT_THREADS) wave_hist[b] = 0;
         __syncthreads();
-        const uint4 *h4 = reinterpret_cast<const uint4 *>(sp.hist[pass]);
-        const uint32_t quads = bins / 4;                                 // width >= 2
-        const uint32_t tln = quads >= SORT_THREADS ? 1u : SORT_THREADS / quads;
-        for (uint32_t item = threadIdx.x; item < quads * tln; item += SORT_THREADS) {
-            const uint32_t bq = item % quads, tl = item / quads;
-            uint4 t4 = make_uint4(0, 0, 0, 0), f4 = make_uint4(0, 0, 0, 0);
-            // sixteen tiles at a time, every load issued before the first add
-            for (uint32_t t0 = tl; t0 < sp.ntiles; t0 += 16 * tln) {
-                uint4 v[16];
+        const uint4 *h4 = reinterpret_cast<const uint4 *>(sp.hist);
+        const uint32_t octs = bins / 8;                                  // width >= 3
+        const uint32_t tln = octs >= SORT_THREADS ? 1u : SORT_THREADS / octs;
+        for (uint32_t item = threadIdx.x; item < octs * tln; item += SORT_THREADS) {
+            const uint32_t bo = item % octs, tl = item / octs;
+            uint32_t t8[8], f8[8];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
+            for (int e = 0; e < 8; ++e) { t8[e] = 0; f8[e] = 0; }
+            // eight tiles at a time, every load issued before the first add
+            for (uint32_t t0 = tl; t0 < sp.ntiles; t0 += 8 * tln) {
+                uint4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
                     const uint32_t t = t0 + u * tln;
-                    v[u] = t < sp.ntiles ? h4[(size_t)t * quads + bq] : make_uint4(0, 0, 0, 0);
+                    v[u] = t < sp.ntiles ? h4[(size_t)t * octs + bo] : make_uint4(0, 0, 0, 0);
                 }
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
+                for (int u = 0; u < 8; ++u) {
                     const uint32_t t = t0 + u * tln;
-                    t4.x += v[u].x; t4.y += v[u].y; t4.z += v[u].z; t4.w += v[u].w;
-                    if (t < tile) { f4.x += v[u].x; f4.y += v[u].y; f4.z += v[u].z; f4.w += v[u].w; }
+                    const uint32_t c[8] = {v[u].x & 0xFFFFu, v[u].x >> 16, v[u].y & 0xFFFFu, v[u].y >> 16,
+                                           v[u].z & 0xFFFFu, v[u].z >> 16, v[u].w & 0xFFFFu, v[u].w >> 16};
+                    const bool earlier = t < tile;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) { t8[e] += c[e]; f8[e] += earlier ? c[e] : 0u; }
                 }
             }
-            const uint32_t b = bq * 4;
-            if (tln == 1) {
-                tot[b] = t4.x; tot[b + 1] = t4.y; tot[b + 2] = t4.z; tot[b + 3] = t4.w;
-                bef[b] = f4.x; bef[b + 1] = f4.y; bef[b + 2] = f4.z; bef[b + 3] = f4.w;
-            } else {
-                atomicAdd(&tot[b], t4.x); atomicAdd(&tot[b + 1], t4.y); atomicAdd(&tot[b + 2], t4.z); atomicAdd(&tot[b + 3], t4.w);
-                atomicAdd(&bef[b], f4.x); atomicAdd(&bef[b + 1], f4.y); atomicAdd(&bef[b + 2], f4.z); atomicAdd(&bef[b + 3], f4.w);
+            const uint32_t b = bo * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (tln == 1) { tot[b + e] = t8[e]; bef[b + e] = f8[e]; }
+                else { if (t8[e]) atomicAdd(&tot[b + e], t8[e]); if (f8[e]) atomicAdd(&bef[b + e], f8[e]); }
             }
         }
         __syncthreads();
         // exclusive scan over the digits; thread t owns SORT_BINS_PER_THREAD consecutive digits
         const uint32_t b0 = threadIdx.x * SORT_BINS_PER_THREAD;
-        uint32_t t8[SORT_BINS_PER_THREAD], f8[SORT_BINS_PER_THREAD], mine = 0;
+        uint32_t tq[SORT_BINS_PER_THREAD], fq[SORT_BINS_PER_THREAD], mine = 0;
 #pragma unroll
         for (int q = 0; q < SORT_BINS_PER_THREAD; ++q) {
-            t8[q] = b0 + q < bins ? tot[b0 + q] : 0u;
-            f8[q] = b0 + q < bins ? bef[b0 + q] : 0u;
-            mine += t8[q];
+            tq[q] = b0 + q < bins ? tot[b0 + q] : 0u;
+            fq[q] = b0 + q < bins ? bef[b0 + q] : 0u;
+            mine += tq[q];
         }
         uint32_t total;
         uint32_t run = block_excl_scan<SORT_WAVES>(mine, scan_lds, total);
 #pragma unroll
         for (int q = 0; q < SORT_BINS_PER_THREAD; ++q) {
-            if (b0 + q < bins) tile_base[b0 + q] = run + f8[q];
-            run += t8[q];
+            if (b0 + q < bins) tile_base[b0 + q] = run + fq[q];
+            run += tq[q];
         }
         __syncthreads();
-        for (uint32_t b = threadIdx.x; b < 2 * SORT_MAX_BINS; b += SORT_THREADS) (&wave_hist[0][0])[b] = 0;
+        for (uint32_t b = threadIdx.x; b < SORT_WAVES * bins; b += SORT_THREADS) wave_hist[b] = 0;
     }
     __syncthreads();
 
-    volatile uint32_t *my_hist = wave_hist[w];
+    // The keys of this tile.  (Requested only now: held across the offset computation they would
+    // cost the kernel that carries this stage a good part of its occupancy.)
+    uint32_t key[SORT_ITEMS], pay[SORT_ITEMS], lrank[SORT_ITEMS];
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const uint32_t i = sort_pos<ITEMS>(tile, it);
+    for (int it = 0; it < SORT_ITEMS; ++it) {
+        const uint32_t i = sort_pos(tile, it);
+        key[it] = i < sp.n ? s.keys_in[i] : 0u;
+    }
+    if (pass == 0) {
+#pragma unroll
+        for (int it = 0; it < SORT_ITEMS; ++it) pay[it] = sort_pos(tile, it);
+    } else {
+#pragma unroll
+        for (int it = 0; it < SORT_ITEMS; ++it) { const uint32_t i = sort_pos(tile, it); pay[it] = i < sp.n ? s.idx_in[i] : 0u; }
+    }
+    // rank of every key among the keys of the same digit before it in the tile: within the wave
+    // by ballots over the digit's bits, across the wave's earlier items by a running count
+    volatile uint32_t *my_hist = wave_hist + w * bins;
+#pragma unroll
+    for (int it = 0; it < SORT_ITEMS; ++it) {
+        const uint32_t i = sort_pos(tile, it);
         const bool valid = i < sp.n;
         const uint32_t d = (key[it] >> shift) & mask;
         uint64_t peers = __ballot(valid);
@@ -190,24 +224,36 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_pass_kernel(const int64_t *
         uint32_t run = tile_base[b];
 #pragma unroll
         for (int ww = 0; ww < SORT_WAVES; ++ww) {
-            const uint32_t c = wave_hist[ww][b];
-            wave_hist[ww][b] = run;
+            const uint32_t c = wave_hist[ww * bins + b];
+            wave_hist[ww * bins + b] = run;
             run += c;
         }
     }
     __syncthreads();
-    uint32_t *next = last ? nullptr : sp.hist[pass + 1];
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const uint32_t i = sort_pos<ITEMS>(tile, it);
+    for (int it = 0; it < SORT_ITEMS; ++it) {
+        const uint32_t i = sort_pos(tile, it);
         if (i < sp.n) {
             const uint32_t d = (key[it] >> shift) & mask;
-            const uint32_t pos = wave_hist[w][d] + lrank[it];
-            keys_out[pos] = key[it];
-            idx_out[pos] = pay[it];
-            if (next) atomicAdd(&next[(size_t)(pos / sp.tile) * bins + ((key[it] >> (shift + width)) & mask)], 1u);
+            const uint32_t pos = wave_hist[w * bins + d] + lrank[it];
+            s.keys_out[pos] = key[it];
+            s.idx_out[pos] = pay[it];
         }
     }
+}
+
+// Runs stage s for tile `tile`; `lds` must hold sort_stage_lds_bytes(width, stage) bytes.
+__device__ __forceinline__ void sort_stage_body(const SortStage &s, uint32_t tile, uint32_t *lds)
+{
+    if (s.stage & 1) sort_scatter_body(s, tile, lds);
+    else sort_hist_body(s, tile, lds);
+}
+
+// A stage nobody carried.
+__global__ __launch_bounds__(SORT_THREADS) void sort_stage_kernel(SortStage s)
+{
+    extern __shared__ __align__(16) uint32_t sort_dyn_lds[];
+    sort_stage_body(s, blockIdx.x, sort_dyn_lds);
 }
 
 // First position of `key` in the sorted keys: lower bound over skey[0 .. hi).

@@ -11,9 +11,10 @@ pytestmark = pytest.mark.gpu
 
 
 def test_prefetch_changes_nothing_and_an_unused_prefetch_is_harmless():
-    """Announcing the next ids only moves their sort to the side stream; a lookup with other ids
-    than the announced ones sorts for itself."""
+    """Announcing the next ids only moves their sort into the kernels of the calls in between; a
+    lookup with other ids than the announced ones sorts for itself."""
     w = wl.WORKLOADS[1].scaled(policy=wl.LFU, s=2)
+    run_workload(w, 25, state_every=1, values_every=5, prefetch="before")
     run_workload(w, 25, state_every=1, values_every=5, prefetch="between")
     run_workload(w, 25, state_every=1, values_every=5, prefetch="after")
     ids_np = wl.IdStream(w).batches(4)
@@ -70,7 +71,7 @@ def test_config2_full_size():
     """Config 2 at full size in the launch configuration the benchmark times: 1M ids, dim 64,
     4096 x 26 lookups, LFU cache of 100k, Adagrad, the next batch's ids announced ahead."""
     w = wl.WORKLOADS[2].scaled(s=5)
-    st = run_workload(w, 24, state_every=6, values_every=12, prefetch="after")
+    st = run_workload(w, 24, state_every=6, values_every=12, prefetch="before")
     assert st["total"]["stale"] > 0 and st["total"]["evicted"] > 0
 
 
