@@ -420,6 +420,7 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // values the fetch copies), so it does not wait for the fetch: the first `fill_blocks`
 // workgroups fetch, the others gather, side by side.
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
+constexpr int GATHER_ROWS = 4;
 struct FillLds {
     uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
     uint32_t scan[4 + 1];
@@ -489,12 +490,32 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
     const uint32_t gid = (bid - first_gather) * groups_per_block + threadIdx.x / g.lanes;
     const uint32_t ngroups = (nblk - first_gather) * groups_per_block;
     if (!POOLED) {
-        for (uint32_t j = gid; j < n; j += ngroups) {                    // Get
-            const int32_t s = ws.src[j];
-            float *dst = out + (size_t)ws.perm[j] * g.dim;
-            if (s == SRC_ZERO) row_zero<VEC>(dst, g.chunks, g.lanes, gl);
-            else if (s == SRC_BACKING) row_copy<VEC>(dst, cv.W + (size_t)ws.skey[j] * g.dim, g.chunks, g.lanes, gl);
-            else row_copy<VEC>(dst, cv.rows + (size_t)(uint32_t)s * g.dim, g.chunks, g.lanes, gl);
+        // Get, GATHER_ROWS positions per row group at a time: where each row comes from is asked
+        // for all of them first, then the rows themselves, so that a group has several rows in
+        // flight (one row per group at a time leaves the memory system idle most of the time)
+        for (uint32_t j0 = gid * GATHER_ROWS; j0 < n; j0 += ngroups * GATHER_ROWS) {
+            int32_t sr[GATHER_ROWS];
+            uint32_t pm[GATHER_ROWS], ky[GATHER_ROWS];
+#pragma unroll
+            for (int r = 0; r < GATHER_ROWS; ++r) {
+                const uint32_t j = j0 + r;
+                const bool in = j < n;
+                sr[r] = in ? ws.src[j] : SRC_ZERO;
+                pm[r] = in ? ws.perm[j] : 0u;
+                ky[r] = in ? ws.skey[j] : 0u;
+            }
+            for (int c = gl; c < g.chunks; c += g.lanes) {
+                V v[GATHER_ROWS];
+#pragma unroll
+                for (int r = 0; r < GATHER_ROWS; ++r) {
+                    const float *row = sr[r] == SRC_BACKING ? cv.W + (size_t)ky[r] * g.dim : cv.rows + (size_t)(uint32_t)(sr[r] < 0 ? 0 : sr[r]) * g.dim;
+                    v[r] = V{};
+                    if (sr[r] != SRC_ZERO) v[r] = reinterpret_cast<const V *>(row)[c];
+                }
+#pragma unroll
+                for (int r = 0; r < GATHER_ROWS; ++r)
+                    if (j0 + r < n) reinterpret_cast<V *>(out + (size_t)pm[r] * g.dim)[c] = v[r];
+            }
         }
     } else {
         for (uint32_t b = gid; b < n_bags; b += ngroups) {
@@ -890,8 +911,9 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     const uint64_t pk = policy_key(tp, my_meta);
     const uint32_t my_cs = my_meta.x, my_cc = my_meta.y;
     uint32_t e = 0;
-    if (over > 0) {
-        // rows equal to tau in earlier slots: whole supers, then the blocks of this super before this one
+    {
+        // rows equal to tau in earlier slots: whole supers, then the blocks of this super before
+        // this one (requested whether or not anything is over capacity: no load waits for another)
         const uint32_t sup = blk / EV_SUPER;
         for (uint32_t i = threadIdx.x; i < sup; i += TRIM_THREADS) e += tp.sup_eq[i];
         const uint32_t b = sup * EV_SUPER + threadIdx.x;

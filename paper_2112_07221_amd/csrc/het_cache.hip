@@ -341,7 +341,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     if (offsets)
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
     const SortStage ride = next_ride(c);
-    const uint32_t blocks = ride.blocks + fill_blocks + hist_blocks + row_grid(c->cv.geom, offsets ? n_bags : n);
+    const uint32_t blocks = ride.blocks + fill_blocks + hist_blocks + row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
     const uint32_t lds = lds_bytes(std::max(sizeof(FillLds), sizeof(TrimLds)), ride);
 #define FILL_GATHER(POOLED, RIDE)                                                                                         \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<blocks, 256, lds, c->stream>>>(                        \

@@ -245,6 +245,9 @@ __device__ __forceinline__ void sort_scatter_body(const SortStage &s, uint32_t t
 // Runs stage s for tile `tile`; `lds` must hold sort_stage_lds_bytes(width, stage) bytes.
 __device__ __forceinline__ void sort_stage_body(const SortStage &s, uint32_t tile, uint32_t *lds)
 {
+    // few workgroups with a long chain of dependent steps, among the many of the carrying kernel:
+    // their waves go first when a SIMD has to choose
+    __builtin_amdgcn_s_setprio(3);
     if (s.stage & 1) sort_scatter_body(s, tile, lds);
     else sort_hist_body(s, tile, lds);
 }
