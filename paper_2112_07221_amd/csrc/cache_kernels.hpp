@@ -29,11 +29,23 @@ __device__ __forceinline__ void store_meta(SlotMeta *m, uint32_t slot, uint32_t 
     reinterpret_cast<uint4 *>(m)[slot] = make_uint4(cs, cc, lu, fr);
 }
 
+// A global table in pinned host memory is written behind the step: a trim copies the rows it
+// evicts (those that hold updates) into a staging buffer in HBM, and the copy over the host link
+// travels inside the next Read's fetch kernel, where it shares the link, which is full duplex,
+// with the fetches going the other way.  `pend` lets a fetch find a row that is still on its way.
+struct HostLink {
+    float *rows[2], *acc[2];      // staging, [max_ids][dim] each; trims alternate between the two
+    uint32_t *keys[2], *cg[2];    // per staged row: its key and the global clock it will carry
+    uint64_t *pend;               // [vocab]: (serial number of the trim << 32) | staging index of the key's staged row
+};
+
 // Everything a kernel needs to know about one cache, passed by value.
 struct CacheView {
     // global table (Section 3.1): rows, optimizer state, global clock c_g
     float *W, *A;
-    uint32_t *Cg;
+    uint32_t *Cg;         // the clocks the kernels work on: the caller's array, or its mirror in HBM for a host-backed table
+    uint32_t *Cg_host;    // host-backed table: the caller's array, written through; else null
+    HostLink hl;
     uint32_t vocab;
     // cache slots
     float *rows, *acc;
@@ -105,12 +117,14 @@ struct TrimPlan {
     int bits;         // bits per policy field
     int key_bits;     // bits of the packed policy key
     int passes;       // select passes
-    uint32_t *hist;   // [SEL_MAX_PASSES][SEL_BINS] followed by sup_eq: zeroed together before the first pass
+    uint32_t *hist;   // [SEL_MAX_PASSES][SEL_BINS] followed by sup_cnt: zeroed together before the first pass
     uint32_t zero_words;
-    uint32_t *blk_eq, *sup_eq;         // rows tied at the threshold: per 256 slots, and per EV_SUPER such blocks
+    uint4 *blk_cnt, *sup_cnt;          // per 1024 slots, and per EV_SUPER such blocks: cached rows with a policy key
+                                       // below the threshold (x), equal to it (y), and those of each that hold updates (z, w)
     uint32_t *tile_free;               // free slots per 1024-slot tile
     uint32_t *ev_ids;                  // ids dropped by this trim
-    int ev_slot;                       // which of the two evicted-id counts this trim appends to
+    int ev_slot;                       // which of the two evicted-id counts (and staging buffers) this trim appends to
+    uint32_t push_seq;                 // host-backed table: serial number of this trim (never 0)
 };
 
 __device__ __forceinline__ uint64_t policy_key(const TrimPlan &tp, const uint4 &meta)
@@ -213,25 +227,80 @@ __device__ __forceinline__ void trim_hist_body(const CacheView &cv, const TrimPl
         if (l.bins[b]) atomicAdd(&tp.hist[pass * SEL_BINS + b], l.bins[b]);
 }
 
-// Last stage of the select: finds tau (replaying the passes) and counts, per block of 256
-// slots, the cached rows whose policy key equals tau; sup_eq adds these up per EV_SUPER blocks
-// (zero when the select starts).  One workgroup per 256 slots.
-constexpr int EV_SLOTS = 256;
+// Sums eight values per thread over the block at once (every thread gets all sums).
+// `lds` needs TRIM_WAVES * 8 words.
+__device__ __forceinline__ void block_sum8(uint32_t (&v)[8], uint32_t *lds)
+{
+    const uint32_t lane = lane_id(), w = threadIdx.x / WAVE;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = wave_sum(v[k]);
+    __syncthreads();
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) lds[w * 8 + k] = v[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        uint32_t t = 0;
+#pragma unroll
+        for (int ww = 0; ww < TRIM_WAVES; ++ww) t += lds[ww * 8 + k];
+        v[k] = t;
+    }
+}
+
+// Last stage of the select: finds tau (replaying the passes) and counts, per block of 1024
+// slots, the cached rows whose policy key lies below tau and those whose key equals it, and how
+// many of each hold updates; sup_cnt adds these up per EV_SUPER blocks (zero when the select
+// starts).  With these counts the eviction places every victim by arithmetic alone (count at
+// the producer, prefix at the consumer).  One workgroup per 1024 slots, four consecutive slots
+// per thread.
+constexpr int EV_ITEMS = 4;
+constexpr int EV_SLOTS = TRIM_THREADS * EV_ITEMS;
 constexpr int EV_SUPER = 32;
+static_assert(EV_SLOTS == TRIM_TILE, "one eviction workgroup per free-list tile");
+
+// The four slots of a thread: keys (KEY_NONE beyond the end) and metadata.
+__device__ __forceinline__ void load_slots4(const CacheView &cv, uint32_t slot0, uint32_t (&key)[EV_ITEMS], uint4 (&meta)[EV_ITEMS])
+{
+#pragma unroll
+    for (int i = 0; i < EV_ITEMS; ++i) {
+        const bool in = slot0 + i < cv.n_slots;
+        key[i] = in ? cv.slot_key[slot0 + i] : KEY_NONE;
+        meta[i] = in ? load_meta(cv.meta, slot0 + i) : make_uint4(0, 0, 0, 0);
+    }
+}
+
 __device__ __forceinline__ void trim_count_body(const CacheView &cv, const TrimPlan &tp, uint32_t vblock, TrimLds &l)
 {
     const int32_t over = cv.ds->size - (int32_t)cv.capacity;
     if (vblock == 0 && threadIdx.x == 0) cv.ds->over = over;
     if (over <= 0) return;
-    const uint32_t slot = vblock * EV_SLOTS + threadIdx.x;       // loads first: they overlap the replay
-    const bool cached = slot < cv.n_slots && cv.slot_key[slot] != KEY_NONE;
-    const uint64_t key = slot < cv.n_slots ? policy_key(tp, load_meta(cv.meta, slot)) : 0;
+    uint32_t key[EV_ITEMS];
+    uint4 meta[EV_ITEMS];
+    load_slots4(cv, vblock * EV_SLOTS + threadIdx.x * EV_ITEMS, key, meta);      // loads first: they overlap the replay
     uint64_t tau; uint32_t take_eq;
     sel_replay(tp, tp.passes, (uint32_t)over, tau, take_eq, l.pick, l.scan);
-    const uint32_t eq = block_sum<TRIM_WAVES>((cached && key == tau) ? 1u : 0u, l.scan);
+    uint32_t lt = 0, eq = 0, dlt = 0, deq = 0;
+#pragma unroll
+    for (int i = 0; i < EV_ITEMS; ++i) {
+        if (key[i] == KEY_NONE) continue;
+        const uint64_t pk = policy_key(tp, meta[i]);
+        const bool dirty = meta[i].y > meta[i].x;
+        if (pk < tau) { lt += 1; dlt += dirty; }
+        else if (pk == tau) { eq += 1; deq += dirty; }
+    }
+    // counts of a block stay below 2^16: two to a word
+    const uint32_t a = block_sum<TRIM_WAVES>(lt | (eq << 16), l.scan);
+    const uint32_t b = block_sum<TRIM_WAVES>(dlt | (deq << 16), l.scan);
     if (threadIdx.x == 0) {
-        tp.blk_eq[vblock] = eq;
-        if (eq) atomicAdd(&tp.sup_eq[vblock / EV_SUPER], eq);
+        const uint4 c = make_uint4(a & 0xFFFFu, a >> 16, b & 0xFFFFu, b >> 16);
+        tp.blk_cnt[vblock] = c;
+        uint32_t *sup = reinterpret_cast<uint32_t *>(&tp.sup_cnt[vblock / EV_SUPER]);
+        if (c.x) atomicAdd(&sup[0], c.x);
+        if (c.y) atomicAdd(&sup[1], c.y);
+        if (c.z) atomicAdd(&sup[2], c.z);
+        if (c.w) atomicAdd(&sup[3], c.w);
         if (vblock == 0) { cv.ds->sel_tau = tau; cv.ds->sel_take = take_eq; }
     }
 }
@@ -259,7 +328,7 @@ __device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32
                                                uint32_t tile, uint32_t *lds)
 {
     if (threadIdx.x == 0) tile_free_idle[tile] = 0;
-    if (tile == 0 && threadIdx.x == 0) cv.ds->ev_n[ev_idle] = 0;
+    if (tile == 0 && threadIdx.x == 0) { cv.ds->ev_n[ev_idle] = 0; cv.ds->push_n[ev_idle] = 0; }
     const uint32_t slot = tile * PT_TILE + threadIdx.x;
     const bool fr = slot < cv.n_slots && cv.slot_key[slot] == KEY_NONE;
     if (slot < cv.n_slots) cv.was_free[slot] = fr ? 1 : 0;
@@ -374,7 +443,10 @@ __device__ __forceinline__ void push_row(const CacheView &cv, uint32_t key, uint
     row_copy<VEC>(cv.W + (size_t)key * g.dim, cv.rows + (size_t)slot * g.dim, g.chunks, g.lanes, gl);
     if (cv.adagrad)
         row_copy<VEC>(cv.A + (size_t)key * g.dim, cv.acc + (size_t)slot * g.dim, g.chunks, g.lanes, gl);
-    if (gl == 0) { const uint32_t cc = cv.meta[slot].cc; if (cc > cv.Cg[key]) cv.Cg[key] = cc; }
+    if (gl == 0) {
+        const uint32_t cc = cv.meta[slot].cc;
+        if (cc > cv.Cg[key]) { cv.Cg[key] = cc; if (cv.Cg_host) cv.Cg_host[key] = cc; }
+    }
 }
 
 // Fetch's pull for one row: copy the global row (and the accumulator) into the slot.
@@ -385,6 +457,39 @@ __device__ __forceinline__ void pull_row(const CacheView &cv, uint32_t key, uint
     row_copy<VEC>(cv.rows + (size_t)slot * g.dim, cv.W + (size_t)key * g.dim, g.chunks, g.lanes, gl);
     if (cv.adagrad)
         row_copy<VEC>(cv.acc + (size_t)slot * g.dim, cv.A + (size_t)key * g.dim, g.chunks, g.lanes, gl);
+}
+
+// The same from explicit sources (a staged row).
+template <int VEC>
+__device__ __forceinline__ void pull_row_from(const CacheView &cv, const float *row, const float *acc, uint32_t slot, int gl)
+{
+    const RowGeom g = cv.geom;
+    row_copy<VEC>(cv.rows + (size_t)slot * g.dim, row, g.chunks, g.lanes, gl);
+    if (cv.adagrad) row_copy<VEC>(cv.acc + (size_t)slot * g.dim, acc, g.chunks, g.lanes, gl);
+}
+
+// Host-backed table: writes the rows staged by trim `buf` to the global table, with their clocks.
+// Runs in `nblocks` workgroups of 256 threads; `vblock` is this one's index.
+template <int VEC>
+__device__ __forceinline__ void deferred_push_body(const CacheView &cv, int buf, uint32_t vblock, uint32_t nblocks)
+{
+    const RowGeom g = cv.geom;
+    const uint32_t n = cv.ds->push_n[buf];
+    const uint32_t gid = (vblock * 256u + threadIdx.x) / g.lanes, ngroups = nblocks * 256u / g.lanes;
+    const int gl = threadIdx.x % g.lanes;
+    for (uint32_t r = gid; r < n; r += ngroups) {
+        const uint32_t key = cv.hl.keys[buf][r];
+        if (key == KEY_NONE) continue;                   // a tied victim without updates
+        row_copy<VEC>(cv.W + (size_t)key * g.dim, cv.hl.rows[buf] + (size_t)r * g.dim, g.chunks, g.lanes, gl);
+        if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)key * g.dim, cv.hl.acc[buf] + (size_t)r * g.dim, g.chunks, g.lanes, gl);
+        if (gl == 0) cv.Cg_host[key] = cv.hl.cg[buf][r];
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256) void deferred_push_kernel(CacheView cv, int buf)
+{
+    deferred_push_body<VEC>(cv, buf, blockIdx.x, gridDim.x);
 }
 
 // Exclusive prefix of per-tile counts into LDS (ntiles <= capacity of `pre`), total returned.
@@ -428,7 +533,8 @@ struct FillLds {
 template <int VEC, bool POOLED, bool RIDE>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
-                                                          const uint32_t *__restrict__ inv, SortStage ride)
+                                                          const uint32_t *__restrict__ inv, SortStage ride,
+                                                          uint32_t push_blocks, int push_buf, uint32_t push_seq)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
@@ -436,6 +542,8 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         if (bid < ride.blocks) { sort_stage_body(ride, bid, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
         bid -= ride.blocks; nblk -= ride.blocks;
     }
+    if (bid < push_blocks) { deferred_push_body<VEC>(cv, push_buf, bid, push_blocks); return; }    // host-backed table: the last trim's write-back
+    bid -= push_blocks; nblk -= push_blocks;
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
@@ -453,12 +561,22 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             const uint32_t slot = cv.free_list[m];
             const uint32_t j = jk.x, key = jk.y;
             const uint32_t cg = cv.Cg[key];
-            pull_row<VEC>(cv, key, slot, gl);
+            // host-backed table: a row the last trim evicted may still be on its way to the table
+            // (its write-back travels in this very kernel); then the staged copy is the global row
+            const uint64_t pe = cv.Cg_host ? cv.hl.pend[key] : 0ull;
+            if (cv.Cg_host && push_seq && (uint32_t)(pe >> 32) == push_seq) {
+                const size_t at = (size_t)(uint32_t)pe * g.dim;
+                pull_row_from<VEC>(cv, cv.hl.rows[push_buf] + at, cv.adagrad ? cv.hl.acc[push_buf] + at : nullptr, slot, gl);
+            } else {
+                pull_row<VEC>(cv, key, slot, gl);
+            }
             if (gl == 0) {
                 store_meta(cv.meta, slot, cg, cg, t, 1u);                    // c_s = c_c = c_g; first use
                 cv.slot_key[slot] = key;
                 ws.head_slot[j] = (int32_t)slot;
                 if (!ht_insert(cv.ht, key, slot)) atomicOr(&cv.ds->err, ERRBIT_INTERNAL);
+                // host-backed table: the gather runs after this kernel and reads the cached copy
+                if (cv.Cg_host) for (uint32_t jj = j; jj < n && ws.skey[jj] == key; ++jj) ws.src[jj] = (int32_t)slot;
             }
         }
         for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
@@ -473,6 +591,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
                 const uint32_t cg = cv.Cg[key];
                 cv.meta[slot].cs = cg; cv.meta[slot].cc = cg;
                 if (has_updates) count2(&cv.last->stale_dirty, &cv.ds->total.stale_dirty, 1u);
+                if (cv.Cg_host && !has_updates) for (uint32_t jj = jk.x; jj < n && ws.skey[jj] == key; ++jj) ws.src[jj] = (int32_t)slot;
             }
         }
         return;
@@ -676,6 +795,9 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
                     if (((heads >> i) & 1u) && k[i] == last_key && !(i == 0 && open_front)) cross = hs[i];
             }
             ws.cross_slot[c] = cross;
+            // Clock(k) of that run is taken here already: the second kernel carries the stage of
+            // the trim's select that counts which rows hold updates, and must not move clocks under it
+            if (cross != SLOT_NONE) cv.meta[cross].cc += 1;
         }
 #pragma unroll
         for (int q = 0; q < MAXC; ++q) {
@@ -743,7 +865,8 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 }
 
 // Second kernel of Write: finishes the runs that cross chunk borders.  The group of the chunk
-// in which such a run starts adds the run's partial sums in chunk order and applies the step.
+// in which such a run starts adds the run's partial sums in chunk order and applies the step
+// (the run's clock was advanced by the first kernel).
 // A run spread over more than FIN_NEAR + 1 chunks (a very popular key) is summed by the whole
 // workgroup instead: every group adds a contiguous share of the partial sums in order, and the
 // shares are added in group order.  Either way the order of additions is fixed by the sorted
@@ -826,7 +949,6 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
                     for (int e = 0; e < VEC; ++e) sum[e] += part[d][e];
                 apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps);
             }
-            if (gl == 0) cv.meta[slot].cc += 1;                    // Clock(k)
         }
         __syncthreads();
         const uint32_t nl = n_long;
@@ -871,7 +993,6 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
                     apply_step<VEC>(cv, (uint32_t)lslot, cidx, tot, lr, eps);
                 }
             }
-            if (threadIdx.x == 0) cv.meta[lslot].cc += 1;          // Clock(k)
         }
         __syncthreads();
         if (threadIdx.x == 0) n_long = 0;
@@ -879,15 +1000,18 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
     }
 }
 
-// Drops the victims among 256 consecutive slots, one thread per slot: erase the key, free the
-// slot, raise c_g; then one row group per victim that holds updates copies its row (and
-// accumulator) to the global table: Evict's push (Section 3.1).  Four workgroups share a
-// 1024-slot tile of the free-list kernel; each adds its free slots to the tile's count
-// (tile_free is zero when the trim starts).
+// Drops the victims among 1024 consecutive slots, four per thread: erase the key, free the slot,
+// raise c_g; then one row group per victim that holds updates copies its row (and accumulator)
+// to the global table: Evict's push (Section 3.1).  Where a victim goes in the evicted-id list
+// and (host-backed table) in the staging buffer follows from the select's per-block counts, so
+// the kernel has no counter that every workgroup would have to add to: at a few nanoseconds
+// per addition to one address, thousands of workgroups made those additions the kernel's
+// duration.  The workgroup that holds the last victim among the rows tied at the threshold
+// writes the call's counters.
 struct EvictLds {
-    uint32_t scan[TRIM_WAVES + 1];
-    uint32_t v_slot[EV_SLOTS], v_key[EV_SLOTS];
-    uint32_t n_push, ev_base;
+    uint32_t scan[TRIM_WAVES * 8 + 8];
+    uint32_t v_slot[EV_SLOTS], v_key[EV_SLOTS], v_cg[EV_SLOTS], v_at[EV_SLOTS];
+    uint32_t n_push;
 };
 template <int VEC, bool RIDE>
 __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, TrimPlan tp, SortStage ride)
@@ -898,66 +1022,131 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
         blk -= ride.blocks;
     }
     EvictLds &el = lds_as<EvictLds>();
-    uint32_t *scan = el.scan, *v_slot = el.v_slot, *v_key = el.v_key;
-    uint32_t &n_push = el.n_push, &ev_base = el.ev_base;
-    const uint32_t slot = blk * EV_SLOTS + threadIdx.x;
-    const bool in = slot < cv.n_slots;
+    uint32_t *scan = el.scan, *v_slot = el.v_slot, *v_key = el.v_key, *v_cg = el.v_cg, *v_at = el.v_at;
+    DState *ds = cv.ds;
+    const uint32_t slot0 = blk * EV_SLOTS + threadIdx.x * EV_ITEMS;
     // everything this thread may need, requested at once
-    const int32_t over = cv.ds->over;                  // snapshot taken by the select: size changes below
-    const uint64_t tau = cv.ds->sel_tau;
-    const uint32_t take_eq = cv.ds->sel_take;
-    const uint32_t my_key = in ? cv.slot_key[slot] : KEY_NONE;
-    const uint4 my_meta = in ? load_meta(cv.meta, slot) : make_uint4(0, 0, 0, 0);
-    const uint64_t pk = policy_key(tp, my_meta);
-    const uint32_t my_cs = my_meta.x, my_cc = my_meta.y;
-    uint32_t e = 0;
+    const int32_t over = ds->over;                     // snapshot taken by the select
+    const uint64_t tau = ds->sel_tau;
+    const uint32_t take_eq = ds->sel_take;
+    uint32_t key[EV_ITEMS];
+    uint4 meta[EV_ITEMS];
+    load_slots4(cv, slot0, key, meta);
+    // counts over the blocks before this one (whole supers, then the blocks of this super), and over all blocks
+    uint32_t c8[8] = {0, 0, 0, 0, 0, 0, 0, 0};         // before: lt, eq, dirty lt, dirty eq;  all: dirty lt
     {
-        // rows equal to tau in earlier slots: whole supers, then the blocks of this super before
-        // this one (requested whether or not anything is over capacity: no load waits for another)
+        const uint32_t nblocks = (cv.n_slots + EV_SLOTS - 1) / EV_SLOTS, nsup = (nblocks + EV_SUPER - 1) / EV_SUPER;
         const uint32_t sup = blk / EV_SUPER;
-        for (uint32_t i = threadIdx.x; i < sup; i += TRIM_THREADS) e += tp.sup_eq[i];
+        for (uint32_t i = threadIdx.x; i < nsup; i += TRIM_THREADS) {
+            const uint4 v = tp.sup_cnt[i];
+            c8[4] += v.z;
+            if (i < sup) { c8[0] += v.x; c8[1] += v.y; c8[2] += v.z; c8[3] += v.w; }
+        }
         const uint32_t b = sup * EV_SUPER + threadIdx.x;
-        if (threadIdx.x < EV_SUPER && b < blk) e += tp.blk_eq[b];
-    }
-    const uint32_t eq_before = block_sum<TRIM_WAVES>(e, scan);
-    if (threadIdx.x == 0) n_push = 0;
-    const bool is_free = in && my_key == KEY_NONE;
-    const bool cached = in && my_key != KEY_NONE && over > 0;
-    const bool lt = cached && pk < tau, eq = cached && pk == tau;
-    uint32_t tot_eq;
-    const uint32_t eq_rank = eq_before + block_excl_scan<TRIM_WAVES>(eq ? 1u : 0u, scan, tot_eq);   // slot order
-    const bool victim = lt || (eq && eq_rank < take_eq);
-    const bool has_updates = victim && my_cc > my_cs;
-    if (victim) {
-        const uint32_t cg = has_updates ? cv.Cg[my_key] : 0u;                  // in flight together with the erase's loads
-        ht_erase(cv.ht, my_key);
-        cv.slot_key[slot] = KEY_NONE;
-        if (has_updates) {
-            if (my_cc > cg) cv.Cg[my_key] = my_cc;                             // c_g = max(c_g, c_c)
-            const uint32_t at = atomicAdd(&n_push, 1u);
-            v_slot[at] = slot; v_key[at] = my_key;
+        if (threadIdx.x < EV_SUPER && b < blk) {
+            const uint4 v = tp.blk_cnt[b];
+            c8[0] += v.x; c8[1] += v.y; c8[2] += v.z; c8[3] += v.w;
         }
     }
-    const uint32_t nv = block_sum<TRIM_WAVES>(victim ? 1u : 0u, scan);
-    const uint32_t free_here = block_sum<TRIM_WAVES>(is_free ? 1u : 0u, scan);
-    if (threadIdx.x == 0 && nv) ev_base = atomicAdd(&cv.ds->ev_n[tp.ev_slot], nv);          // one append per workgroup
-    uint32_t dummy;
-    const uint32_t ev_at = block_excl_scan<TRIM_WAVES>(victim ? 1u : 0u, scan, dummy);
-    if (victim) tp.ev_ids[ev_base + ev_at] = my_key;
-    const uint32_t np = n_push;
+    block_sum8(c8, scan);
+    const uint32_t lt_before = c8[0], eq_before = c8[1], dlt_before = c8[2], deq_before = c8[3], dlt_total = c8[4];
+    if (threadIdx.x == 0) el.n_push = 0;
+
+    // this thread's four slots: below tau / tied with tau, in slot order
+    bool lt[EV_ITEMS], eq[EV_ITEMS];
+    uint32_t n_lt = 0, n_eq = 0, n_free = 0;
+#pragma unroll
+    for (int i = 0; i < EV_ITEMS; ++i) {
+        const bool cached = key[i] != KEY_NONE && over > 0;
+        const uint64_t pk = policy_key(tp, meta[i]);
+        lt[i] = cached && pk < tau; eq[i] = cached && pk == tau;
+        n_lt += lt[i]; n_eq += eq[i];
+        n_free += (slot0 + i < cv.n_slots && key[i] == KEY_NONE) ? 1u : 0u;
+    }
+    uint32_t tot1;
+    const uint32_t ex1 = block_excl_scan<TRIM_WAVES>(n_lt | (n_eq << 16), scan, tot1);
+    uint32_t eq_rank = eq_before + (ex1 >> 16);        // rank of the thread's first tied row among all tied rows
+    const uint32_t eq_here = tot1 >> 16;
+    bool victim[EV_ITEMS], dirty[EV_ITEMS];
+    uint32_t eq_at[EV_ITEMS];
+    uint32_t n_vic = 0, n_dlt = 0, n_deq_vic = 0;
+#pragma unroll
+    for (int i = 0; i < EV_ITEMS; ++i) {
+        eq_at[i] = eq_rank;
+        victim[i] = lt[i] || (eq[i] && eq_rank < take_eq);
+        dirty[i] = victim[i] && meta[i].y > meta[i].x;
+        eq_rank += eq[i];
+        n_vic += victim[i]; n_dlt += dirty[i] && lt[i]; n_deq_vic += dirty[i] && eq[i];
+    }
+    uint32_t tot2;
+    const uint32_t ex2 = block_excl_scan<TRIM_WAVES>(n_vic | (n_dlt << 16), scan, tot2);
+    const uint32_t nv = tot2 & 0xFFFFu;
+    // victims in earlier blocks: their rows below tau, and their tied rows up to the cut
+    uint32_t ev_at = lt_before + min(eq_before, take_eq) + (ex2 & 0xFFFFu);
+    uint32_t dlt_at = dlt_before + (ex2 >> 16);
+    const int buf = tp.ev_slot;
+#pragma unroll
+    for (int i = 0; i < EV_ITEMS; ++i) {
+        if (!victim[i]) continue;
+        const uint32_t slot = slot0 + i, k = key[i], my_cc = meta[i].y;
+        tp.ev_ids[ev_at++] = k;
+        const uint32_t cg = dirty[i] ? cv.Cg[k] : 0u;                         // in flight together with the erase's loads
+        ht_erase(cv.ht, k);
+        cv.slot_key[slot] = KEY_NONE;
+        // host-backed table: rows below tau that hold updates are staged in slot order, then one
+        // place per tied victim (left empty by those without updates)
+        const uint32_t stage_at = lt[i] ? dlt_at : dlt_total + eq_at[i];
+        if (dirty[i]) {
+            if (my_cc > cg) cv.Cg[k] = my_cc;                                 // c_g = max(c_g, c_c)
+            const uint32_t at = atomicAdd(&el.n_push, 1u);
+            v_slot[at] = slot; v_key[at] = k; v_cg[at] = my_cc > cg ? my_cc : cg; v_at[at] = stage_at;
+            dlt_at += lt[i];
+        } else if (cv.Cg_host && eq[i]) {
+            cv.hl.keys[buf][stage_at] = KEY_NONE;
+        }
+    }
+    uint32_t s2[8] = {n_free, n_deq_vic, 0, 0, 0, 0, 0, 0};
+    block_sum8(s2, scan);                              // also makes the push list visible to every thread
+    const uint32_t free_here = s2[0], deq_vic_here = s2[1];
+    const uint32_t np = el.n_push;
     const int lanes = cv.geom.lanes;
     const int group = threadIdx.x / lanes, gl = threadIdx.x % lanes, ngroups = TRIM_THREADS / lanes;
     const RowGeom g = cv.geom;
     for (uint32_t v = group; v < np; v += ngroups) {
         const uint32_t vs = v_slot[v], vk = v_key[v];
-        row_copy<VEC>(cv.W + (size_t)vk * g.dim, cv.rows + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
-        if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)vk * g.dim, cv.acc + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
+        if (!cv.Cg_host) {
+            row_copy<VEC>(cv.W + (size_t)vk * g.dim, cv.rows + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
+            if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)vk * g.dim, cv.acc + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
+        } else {
+            // the rows go to the staging buffer; the next Read's fetch kernel (or a waiting call)
+            // sends them over the host link
+            const uint32_t sa = v_at[v];
+            const size_t at = (size_t)sa * g.dim;
+            row_copy<VEC>(cv.hl.rows[buf] + at, cv.rows + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
+            if (cv.adagrad) row_copy<VEC>(cv.hl.acc[buf] + at, cv.acc + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
+            if (gl == 0) {
+                cv.hl.keys[buf][sa] = vk;
+                cv.hl.cg[buf][sa] = v_cg[v];
+                cv.hl.pend[vk] = ((uint64_t)tp.push_seq << 32) | (uint64_t)sa;
+            }
+        }
     }
     if (threadIdx.x == 0) {
-        if (free_here + nv) atomicAdd(&tp.tile_free[blk * EV_SLOTS / TRIM_TILE], free_here + nv);
-        if (nv) atomicSub(&cv.ds->size, (int32_t)nv);
-        count2(&cv.last->evicted, &cv.ds->total.evicted, nv);
-        count2(&cv.last->evicted_dirty, &cv.ds->total.evicted_dirty, np);
+        tp.tile_free[blk] = free_here + nv;
+        // the call's counters: written by the block that holds the last tied victim (block 0 if there is none)
+        const bool closes = over <= 0 ? blk == 0
+                          : (take_eq == 0 ? blk == 0 : (eq_before < take_eq && take_eq <= eq_before + eq_here));
+        if (closes) {
+            const uint32_t evicted = over > 0 ? (uint32_t)over : 0u;
+            const uint32_t evicted_dirty = over > 0 ? dlt_total + deq_before + deq_vic_here : 0u;
+            ds->ev_n[buf] = evicted;
+            ds->push_n[buf] = over > 0 ? dlt_total + take_eq : 0u;
+            if (evicted) {
+                ds->size -= (int32_t)evicted;
+                cv.last->evicted = evicted; ds->total.evicted += evicted;
+                cv.last->evicted_dirty = evicted_dirty; ds->total.evicted_dirty += evicted_dirty;
+            }
+        }
     }
 }
 

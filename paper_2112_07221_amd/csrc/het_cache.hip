@@ -20,11 +20,11 @@ using namespace het;
 // Kernels of the path, as named in profiles and by het_profile_kernel_name.
 enum KernelId {
     K_SORT_STAGE, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_APPLY_FINISH, K_TRIM_STAGE,
-    K_TRIM_EVICT, K_FLUSH, K_MISC, K_NUM
+    K_TRIM_EVICT, K_DEFERRED_PUSH, K_FLUSH, K_MISC, K_NUM
 };
 static const char *const kKernelNames[K_NUM] = {
     "sort_stage_kernel", "probe_kernel", "pooled_index_kernel", "fill_gather_kernel",
-    "apply_kernel", "apply_finish_kernel", "trim_stage_kernel", "trim_evict_kernel", "flush_kernel", "misc"};
+    "apply_kernel", "apply_finish_kernel", "trim_stage_kernel", "trim_evict_kernel", "deferred_push_kernel", "flush_kernel", "misc"};
 
 struct ProfSpan { int id; hipEvent_t start, stop; };
 
@@ -71,6 +71,10 @@ struct het_cache {
     uint32_t n_buckets = 0;
     int max_chunks_per_lane = 1;     // row chunks one lane handles in the apply kernel
     std::vector<void *> owned;       // every device allocation, for destroy
+    // host-backed table: write-back of the last trim's victims still to be enqueued
+    bool push_pending = false;
+    int push_buf = 0;
+    uint32_t push_seq = 0, trim_seq = 0;
     // host-side bookkeeping
     uint64_t t_host = 0;             // non-empty lookups so far (equals the device's t)
     bool overflow_pending = false;   // a lookup ran and no trim since
@@ -271,7 +275,7 @@ TrimPlan make_trim_plan(const het_cache *c)
     tp.bits = std::max(1, bit_width(c->t_host));
     tp.key_bits = tp.lfu ? 2 * tp.bits : tp.bits;
     tp.passes = (tp.key_bits + SEL_BITS - 1) / SEL_BITS;
-    tp.sup_eq = tp.hist + SEL_MAX_PASSES * SEL_BINS;
+    tp.sup_cnt = reinterpret_cast<uint4 *>(tp.hist + SEL_MAX_PASSES * SEL_BINS);
     return tp;
 }
 
@@ -281,18 +285,32 @@ uint32_t stage_blocks(const het_cache *c, const TrimPlan &tp, int stage)
     return cdiv(c->cv.n_slots, EV_SLOTS);
 }
 
+constexpr uint32_t PUSH_BLOCKS = 256;      // few workgroups keep the host link full; more only contend
+
+// Host-backed table: enqueues the write-back a trim left staged, if nobody carried it yet.
+void drain_pushes(het_cache *c)
+{
+    if (!c->push_pending) return;
+    if (c->cv.geom.vec == 4) LAUNCH(c, K_DEFERRED_PUSH, deferred_push_kernel<4><<<PUSH_BLOCKS, 256, 0, c->stream>>>(c->cv, c->push_buf));
+    else LAUNCH(c, K_DEFERRED_PUSH, deferred_push_kernel<1><<<PUSH_BLOCKS, 256, 0, c->stream>>>(c->cv, c->push_buf));
+    c->push_pending = false;
+}
+
 // Evict(): the select stages from `first_stage` on (earlier ones rode along with the update's
 // kernels), then the eviction itself.
 template <int VEC>
 int run_trim(het_cache *c, int first_stage)
 {
     TrimPlan tp = c->sel_tp;
+    drain_pushes(c);                                 // the staging buffers alternate: the one before last must be gone
     for (int st = first_stage; st <= tp.passes; ++st)
         LAUNCH(c, K_TRIM_STAGE, trim_stage_kernel<<<stage_blocks(c, tp, st), TRIM_THREADS, 0, c->stream>>>(c->cv, tp, st));
     const int fill = 1 - c->tf_last;                 // the idle array: cleared by the lookup in between
     tp.tile_free = c->tile_free[fill];
     tp.ev_slot = fill;
     tp.ev_ids = c->ev_ids[fill];
+    tp.push_seq = ++c->trim_seq;
+    if (c->trim_seq == 0xFFFFFFFFu) c->trim_seq = 0;        // 0 means "none"; a wrap is harmless (see HostLink::pend)
     const SortStage ride = next_ride(c);
     const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
     if (ride.blocks)
@@ -300,6 +318,7 @@ int run_trim(het_cache *c, int first_stage)
     else
         LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false><<<ev_blocks, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride));
     c->tf_last = fill;
+    if (c->location == HET_BACKING_PINNED_HOST) { c->push_pending = true; c->push_buf = fill; c->push_seq = tp.push_seq; }
     c->overflow_pending = false;
     c->last_trim_skipped = false;
     c->order_valid = false;          // slots recorded for the sorted order may be gone now
@@ -340,14 +359,37 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 1024u);     // they come first: theirs is the longer chain
     if (offsets)
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
-    const SortStage ride = next_ride(c);
-    const uint32_t blocks = ride.blocks + fill_blocks + hist_blocks + row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
-    const uint32_t lds = lds_bytes(std::max(sizeof(FillLds), sizeof(TrimLds)), ride);
-#define FILL_GATHER(POOLED, RIDE)                                                                                         \
-    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<blocks, 256, lds, c->stream>>>(                        \
-                                 c->cv, c->ws, n, t_now, ptiles, fill_blocks, tp, hist_blocks, out, offsets, n_bags, c->inv, ride))
-    if (!offsets) { if (ride.blocks) FILL_GATHER(false, true); else FILL_GATHER(false, false); }
-    else { if (ride.blocks) FILL_GATHER(true, true); else FILL_GATHER(true, false); }
+    const uint32_t lds_own = (uint32_t)std::max(sizeof(FillLds), sizeof(TrimLds));
+#define FILL_GATHER(POOLED, RIDE, GRID, FILLB, HISTB, PUSHB)                                                              \
+    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>(     \
+                                 c->cv, c->ws, n, t_now, ptiles, FILLB, tp, HISTB, out, offsets, n_bags, c->inv, ride,     \
+                                 PUSHB, c->push_buf, c->push_seq))
+#define FILL_GATHER_ANY(GRID, FILLB, HISTB, PUSHB)                                                                        \
+    do {                                                                                                                  \
+        if (!offsets) { if (ride.blocks) FILL_GATHER(false, true, GRID, FILLB, HISTB, PUSHB); else FILL_GATHER(false, false, GRID, FILLB, HISTB, PUSHB); } \
+        else { if (ride.blocks) FILL_GATHER(true, true, GRID, FILLB, HISTB, PUSHB); else FILL_GATHER(true, false, GRID, FILLB, HISTB, PUSHB); }           \
+    } while (0)
+    const uint32_t gather_blocks = row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
+    if (c->location == HET_BACKING_HBM) {
+        // one kernel: the gather reads a missed key's row from the global table, beside the fetch
+        const SortStage ride = next_ride(c);
+        FILL_GATHER_ANY(ride.blocks + fill_blocks + hist_blocks + gather_blocks, fill_blocks, hist_blocks, 0u);
+    } else {
+        // Host-backed table: the fetches come over the host link, and the last trim's write-back
+        // goes the other way in the same kernel; the gather follows and reads the cached copies.
+        const uint32_t push_blocks = c->push_pending ? PUSH_BLOCKS : 0u;
+        const uint32_t fetch_blocks = std::min(fill_blocks, PUSH_BLOCKS);
+        {
+            const SortStage ride = next_ride(c);
+            FILL_GATHER_ANY(ride.blocks + push_blocks + fetch_blocks + hist_blocks, fetch_blocks, hist_blocks, push_blocks);
+        }
+        c->push_pending = false;
+        {
+            const SortStage ride = next_ride(c);
+            FILL_GATHER_ANY(ride.blocks + gather_blocks, 0u, 0u, 0u);
+        }
+    }
+#undef FILL_GATHER_ANY
 #undef FILL_GATHER
     if ((rc = launch_ok()) != HET_OK) return rc;
     c->overflow_pending = true;
@@ -356,25 +398,31 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     return HET_OK;
 }
 
-// The two kernels of Write; each carries one stage of the coming trim's select in extra workgroups.
+// The two kernels of Write; each carries a stage of the coming trim's select in extra workgroups
+// (stage 0 rode with the lookup's fetches).  The first kernel moves the clocks, so it may carry
+// a histogram stage (policy fields only) but not the final count, which looks at the clocks.
+// `trim`: a trim follows.  Returns the first stage that is still to run.
 template <int VEC, int MAXC>
-void launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
-                  int stages_carried)
+int launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
+                 bool trim)
 {
     const uint32_t grid = row_grid(c->cv.geom, cdiv(n, CHUNK));
     const TrimPlan &tp = c->sel_tp;
-    // stage 0 rode with the lookup's fetches; this call's two kernels carry stages 1 and 2
-    const uint32_t extra0 = stages_carried > 0 ? stage_blocks(c, tp, 1) : 0u;
-    const uint32_t extra1 = stages_carried > 1 ? stage_blocks(c, tp, 2) : 0u;
+    int next = 1;
+    const int stage0 = trim && next < tp.passes ? next++ : -1;
+    const int stage1 = trim && next <= tp.passes ? next++ : -1;
+    const uint32_t extra0 = stage0 >= 0 ? stage_blocks(c, tp, stage0) : 0u;
+    const uint32_t extra1 = stage1 >= 0 ? stage_blocks(c, tp, stage1) : 0u;
     const SortStage ride0 = next_ride(c);
     const uint32_t lds0 = lds_bytes(sizeof(TrimLds), ride0);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1, ride0));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, 1, ride0));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
     const SortStage ride1 = next_ride(c);
     const uint32_t lds1 = lds_bytes(std::max(sizeof(TrimLds), sizeof(FinishLds<VEC>)), ride1);
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<ride1.blocks + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, 2, ride1));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<ride1.blocks + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, stage1, ride1));
+    return next;
 }
 
 template <int VEC>
@@ -400,20 +448,21 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     }
     // Only a lookup leaves rows above capacity; an update that follows no lookup has nothing to trim.
     const bool trim = c->overflow_pending;
-    const int carried = trim ? std::min(2, c->sel_tp.passes) : 0;     // of the stages 1 .. passes still to run
+    int next_stage = 1;
     switch (c->max_chunks_per_lane) {
-    case 1: launch_apply<VEC, 1>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
-    case 2: launch_apply<VEC, 2>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
-    case 4: launch_apply<VEC, 4>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
-    default: launch_apply<VEC, 16>(c, reuse, ids, n, grads, grad_row, lr, carried); break;
+    case 1: next_stage = launch_apply<VEC, 1>(c, reuse, ids, n, grads, grad_row, lr, trim); break;
+    case 2: next_stage = launch_apply<VEC, 2>(c, reuse, ids, n, grads, grad_row, lr, trim); break;
+    case 4: next_stage = launch_apply<VEC, 4>(c, reuse, ids, n, grads, grad_row, lr, trim); break;
+    default: next_stage = launch_apply<VEC, 16>(c, reuse, ids, n, grads, grad_row, lr, trim); break;
     }
     if ((rc = launch_ok()) != HET_OK) return rc;
     if (!trim) { c->last_trim_skipped = true; c->order_valid = false; return HET_OK; }
-    return run_trim<VEC>(c, 1 + carried);
+    return run_trim<VEC>(c, next_stage);
 }
 
 int sync_all(het_cache *c)
 {
+    drain_pushes(c);
     HIP_TRY(hipStreamSynchronize(c->stream));
     return HET_OK;
 }
@@ -509,8 +558,8 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
         (rc = dev_alloc(c, &ws.partial, chunks * 2 * (size_t)c->dim)) || (rc = dev_alloc(c, &ws.cross_slot, chunks)))
         return rc;
     const size_t slot_tiles = cdiv(P, TRIM_TILE), ev_blocks = cdiv(P, EV_SLOTS), ev_supers = cdiv(ev_blocks, EV_SUPER);
-    c->tp.zero_words = (uint32_t)(SEL_MAX_PASSES * SEL_BINS + ev_supers);
-    if ((rc = dev_alloc(c, &c->tp.hist, (size_t)c->tp.zero_words)) || (rc = dev_alloc(c, &c->tp.blk_eq, ev_blocks)) ||
+    c->tp.zero_words = (uint32_t)(SEL_MAX_PASSES * SEL_BINS + 4 * ev_supers);
+    if ((rc = dev_alloc(c, &c->tp.hist, (size_t)c->tp.zero_words)) || (rc = dev_alloc(c, &c->tp.blk_cnt, ev_blocks)) ||
         (rc = dev_alloc(c, &c->tile_free[0], slot_tiles)) ||
         (rc = dev_alloc(c, &c->tile_free[1], slot_tiles)) || (rc = dev_alloc(c, &c->ev_ids[0], P)) || (rc = dev_alloc(c, &c->ev_ids[1], P)))
         return rc;
@@ -543,7 +592,26 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
         if (state) HIP_TRY(hipHostGetDevicePointer(&dst, state, 0));
         table = static_cast<float *>(dt); cg = static_cast<uint32_t *>(dcg); state = static_cast<float *>(dst);
     }
-    c->cv.W = table; c->cv.A = state; c->cv.Cg = cg; c->cv.vocab = (uint32_t)vocab;
+    c->cv.W = table; c->cv.A = state; c->cv.Cg = cg; c->cv.Cg_host = nullptr; c->cv.vocab = (uint32_t)vocab;
+    if (location == HET_BACKING_PINNED_HOST) {
+        // The kernels work on a mirror of the global clocks in HBM (a probe must not cross the host
+        // link for four bytes per key); the caller's array is written through.  Evicted rows are
+        // staged in HBM and written back behind the step (HostLink).
+        int rc;
+        uint32_t *mirror = nullptr;
+        if ((rc = dev_alloc(c, &mirror, (size_t)vocab))) return rc;
+        HIP_TRY(hipMemcpy(mirror, cg, (size_t)vocab * sizeof(uint32_t), hipMemcpyDefault));
+        c->cv.Cg_host = cg;
+        c->cv.Cg = mirror;
+        HostLink &hl = c->cv.hl;
+        const size_t N = (size_t)c->max_ids, row_elems = N * (size_t)c->dim;
+        if ((rc = dev_alloc(c, &hl.pend, (size_t)vocab))) return rc;
+        HIP_TRY(hipMemset(hl.pend, 0, (size_t)vocab * sizeof(uint64_t)));
+        for (int b = 0; b < 2; ++b) {
+            if ((rc = dev_alloc(c, &hl.rows[b], row_elems)) || (rc = dev_alloc(c, &hl.keys[b], N)) || (rc = dev_alloc(c, &hl.cg[b], N))) return rc;
+            if (state && (rc = dev_alloc(c, &hl.acc[b], row_elems))) return rc;
+        }
+    }
     c->location = location;
     c->attached = true;
     return HET_OK;

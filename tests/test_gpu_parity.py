@@ -94,6 +94,33 @@ def test_config3_pinned_host_backing_reduced():
     run_workload(w, 16, state_every=4, values_every=8)
 
 
+@pytest.mark.parametrize("policy,opt", [(wl.LRU, wl.SGD), (wl.LFU, wl.ADAGRAD)])
+def test_host_backed_table_rows_evicted_and_fetched_again_at_once(policy, opt):
+    """A small vocabulary behind a small cache in pinned host memory: keys evicted by one update are
+    missed again by the next lookup, while their write-back is still on its way to the table."""
+    w = wl.WORKLOADS[1].scaled(vocab=3000, capacity=150, s=2, policy=policy, optimizer=opt, backing="host")
+    st = run_workload(w, 30, state_every=1, values_every=3, prefetch="before")
+    assert st["total"]["evicted_dirty"] > 1000
+    # Read after Read, and a waiting call between update and lookup (it sends the staged rows itself)
+    ids_np = wl.IdStream(w).batches(6)
+    g = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        for t in range(6):
+            p.lookup(ids_np[t])
+            if t % 2 == 0:
+                p.lookup(ids_np[(t + 3) % 6])
+                p.update(ids_np[(t + 3) % 6], g[t % len(g)])
+            else:
+                p.update(ids_np[t], g[t % len(g)])
+            if t == 3:
+                p.cache.stats()
+            p.compare_state(values=True); p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_ragged_and_degenerate_batches():
     """Batches of 1, 63, 64, 65, 1023, 1025, 2047, 2049 ids, all-equal ids, already-unique ids."""
     w = wl.WORKLOADS[1].scaled(capacity=300, s=1)
