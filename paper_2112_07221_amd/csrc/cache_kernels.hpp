@@ -37,6 +37,11 @@ struct HostLink {
     float *rows[2], *acc[2];      // staging, [max_ids][dim] each; trims alternate between the two
     uint32_t *keys[2], *cg[2];    // per staged row: its key and the global clock it will carry
     uint64_t *pend;               // [vocab]: (serial number of the trim << 32) | staging index of the key's staged row
+    // (selected, not indexed: indexing kernel arguments at run time would put them in scratch memory)
+    __device__ __forceinline__ float *rows_of(int b) const { return b ? rows[1] : rows[0]; }
+    __device__ __forceinline__ float *acc_of(int b) const { return b ? acc[1] : acc[0]; }
+    __device__ __forceinline__ uint32_t *keys_of(int b) const { return b ? keys[1] : keys[0]; }
+    __device__ __forceinline__ uint32_t *cg_of(int b) const { return b ? cg[1] : cg[0]; }
 };
 
 // Everything a kernel needs to know about one cache, passed by value.
@@ -284,11 +289,11 @@ __device__ __forceinline__ void trim_count_body(const CacheView &cv, const TrimP
     uint32_t lt = 0, eq = 0, dlt = 0, deq = 0;
 #pragma unroll
     for (int i = 0; i < EV_ITEMS; ++i) {
-        if (key[i] == KEY_NONE) continue;
+        const bool cached = key[i] != KEY_NONE;
         const uint64_t pk = policy_key(tp, meta[i]);
         const bool dirty = meta[i].y > meta[i].x;
-        if (pk < tau) { lt += 1; dlt += dirty; }
-        else if (pk == tau) { eq += 1; deq += dirty; }
+        if (cached && pk < tau) { lt += 1; dlt += dirty; }
+        else if (cached && pk == tau) { eq += 1; deq += dirty; }
     }
     // counts of a block stay below 2^16: two to a word
     const uint32_t a = block_sum<TRIM_WAVES>(lt | (eq << 16), l.scan);
@@ -478,11 +483,11 @@ __device__ __forceinline__ void deferred_push_body(const CacheView &cv, int buf,
     const uint32_t gid = (vblock * 256u + threadIdx.x) / g.lanes, ngroups = nblocks * 256u / g.lanes;
     const int gl = threadIdx.x % g.lanes;
     for (uint32_t r = gid; r < n; r += ngroups) {
-        const uint32_t key = cv.hl.keys[buf][r];
+        const uint32_t key = cv.hl.keys_of(buf)[r];
         if (key == KEY_NONE) continue;                   // a tied victim without updates
-        row_copy<VEC>(cv.W + (size_t)key * g.dim, cv.hl.rows[buf] + (size_t)r * g.dim, g.chunks, g.lanes, gl);
-        if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)key * g.dim, cv.hl.acc[buf] + (size_t)r * g.dim, g.chunks, g.lanes, gl);
-        if (gl == 0) cv.Cg_host[key] = cv.hl.cg[buf][r];
+        row_copy<VEC>(cv.W + (size_t)key * g.dim, cv.hl.rows_of(buf) + (size_t)r * g.dim, g.chunks, g.lanes, gl);
+        if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)key * g.dim, cv.hl.acc_of(buf) + (size_t)r * g.dim, g.chunks, g.lanes, gl);
+        if (gl == 0) cv.Cg_host[key] = cv.hl.cg_of(buf)[r];
     }
 }
 
@@ -566,7 +571,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             const uint64_t pe = cv.Cg_host ? cv.hl.pend[key] : 0ull;
             if (cv.Cg_host && push_seq && (uint32_t)(pe >> 32) == push_seq) {
                 const size_t at = (size_t)(uint32_t)pe * g.dim;
-                pull_row_from<VEC>(cv, cv.hl.rows[push_buf] + at, cv.adagrad ? cv.hl.acc[push_buf] + at : nullptr, slot, gl);
+                pull_row_from<VEC>(cv, cv.hl.rows_of(push_buf) + at, cv.adagrad ? cv.hl.acc_of(push_buf) + at : nullptr, slot, gl);
             } else {
                 pull_row<VEC>(cv, key, slot, gl);
             }
@@ -623,17 +628,19 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
                 pm[r] = in ? ws.perm[j] : 0u;
                 ky[r] = in ? ws.skey[j] : 0u;
             }
+            const float *row[GATHER_ROWS];
+#pragma unroll
+            for (int r = 0; r < GATHER_ROWS; ++r)     // (an id outside the vocabulary reads some row and drops it: no branch between the loads)
+                row[r] = sr[r] == SRC_BACKING ? cv.W + (size_t)ky[r] * g.dim : cv.rows + (size_t)(uint32_t)(sr[r] < 0 ? 0 : sr[r]) * g.dim;
             for (int c = gl; c < g.chunks; c += g.lanes) {
                 V v[GATHER_ROWS];
 #pragma unroll
-                for (int r = 0; r < GATHER_ROWS; ++r) {
-                    const float *row = sr[r] == SRC_BACKING ? cv.W + (size_t)ky[r] * g.dim : cv.rows + (size_t)(uint32_t)(sr[r] < 0 ? 0 : sr[r]) * g.dim;
-                    v[r] = V{};
-                    if (sr[r] != SRC_ZERO) v[r] = reinterpret_cast<const V *>(row)[c];
-                }
+                for (int r = 0; r < GATHER_ROWS; ++r) v[r] = reinterpret_cast<const V *>(row[r])[c];
 #pragma unroll
-                for (int r = 0; r < GATHER_ROWS; ++r)
+                for (int r = 0; r < GATHER_ROWS; ++r) {
+                    if (sr[r] == SRC_ZERO) v[r] = V{};
                     if (j0 + r < n) reinterpret_cast<V *>(out + (size_t)pm[r] * g.dim)[c] = v[r];
+                }
             }
         }
     } else {
@@ -786,19 +793,17 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) if ((uint32_t)i < cnt) p[i] = grad_row[p[i]];
         }
+        // the run that starts here and leaves through the back border is finished by the second kernel
+        int32_t cross = SLOT_NONE;
         if (gl == 0) {
-            // the run that starts here and leaves through the back border is finished by the second kernel
-            int32_t cross = SLOT_NONE;
             if (open_back) {
 #pragma unroll
                 for (int i = 0; i < CHUNK; ++i)
                     if (((heads >> i) & 1u) && k[i] == last_key && !(i == 0 && open_front)) cross = hs[i];
             }
             ws.cross_slot[c] = cross;
-            // Clock(k) of that run is taken here already: the second kernel carries the stage of
-            // the trim's select that counts which rows hold updates, and must not move clocks under it
-            if (cross != SLOT_NONE) cv.meta[cross].cc += 1;
         }
+        uint32_t cross_cc = 0;
 #pragma unroll
         for (int q = 0; q < MAXC; ++q) {
             const int cidx = gl + q * g.lanes;
@@ -808,6 +813,7 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) {
                 v[i] = V{}; xr[i] = V{}; ar[i] = V{}; ccv[i] = 0;
+                if (q == 0 && i == 0 && cross != SLOT_NONE) cross_cc = cv.meta[cross].cc;       // (lane 0 only)
                 if (q == 0 && gl == 0 && ((whole >> i) & 1u)) ccv[i] = cv.meta[hs[i]].cc;
                 if (act && ((use >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
                 if (act && ((whole >> i) & 1u)) {
@@ -861,6 +867,10 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
                 }
             }
         }
+        // Clock(k) of the run that leaves through the back border is taken here already: the second
+        // kernel carries the stage of the trim's select that counts which rows hold updates, and
+        // must not move clocks under it
+        if (cross != SLOT_NONE) cv.meta[cross].cc = cross_cc + 1;
     }
 }
 
@@ -1087,7 +1097,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     const int buf = tp.ev_slot;
 #pragma unroll
     for (int i = 0; i < EV_ITEMS; ++i) {
-        if (!victim[i]) continue;
+        if (victim[i]) {
         const uint32_t slot = slot0 + i, k = key[i], my_cc = meta[i].y;
         tp.ev_ids[ev_at++] = k;
         const uint32_t cg = dirty[i] ? cv.Cg[k] : 0u;                         // in flight together with the erase's loads
@@ -1102,7 +1112,8 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
             v_slot[at] = slot; v_key[at] = k; v_cg[at] = my_cc > cg ? my_cc : cg; v_at[at] = stage_at;
             dlt_at += lt[i];
         } else if (cv.Cg_host && eq[i]) {
-            cv.hl.keys[buf][stage_at] = KEY_NONE;
+            cv.hl.keys_of(buf)[stage_at] = KEY_NONE;
+        }
         }
     }
     uint32_t s2[8] = {n_free, n_deq_vic, 0, 0, 0, 0, 0, 0};
@@ -1112,22 +1123,52 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     const int lanes = cv.geom.lanes;
     const int group = threadIdx.x / lanes, gl = threadIdx.x % lanes, ngroups = TRIM_THREADS / lanes;
     const RowGeom g = cv.geom;
-    for (uint32_t v = group; v < np; v += ngroups) {
-        const uint32_t vs = v_slot[v], vk = v_key[v];
-        if (!cv.Cg_host) {
-            row_copy<VEC>(cv.W + (size_t)vk * g.dim, cv.rows + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
-            if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)vk * g.dim, cv.acc + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
-        } else {
-            // the rows go to the staging buffer; the next Read's fetch kernel (or a waiting call)
-            // sends them over the host link
-            const uint32_t sa = v_at[v];
-            const size_t at = (size_t)sa * g.dim;
-            row_copy<VEC>(cv.hl.rows[buf] + at, cv.rows + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
-            if (cv.adagrad) row_copy<VEC>(cv.hl.acc[buf] + at, cv.acc + (size_t)vs * g.dim, g.chunks, g.lanes, gl);
-            if (gl == 0) {
-                cv.hl.keys[buf][sa] = vk;
-                cv.hl.cg[buf][sa] = v_cg[v];
-                cv.hl.pend[vk] = ((uint64_t)tp.push_seq << 32) | (uint64_t)sa;
+    // Evict's push, PUSH_ROWS victims per row group at a time (all their loads before the first
+    // store).  Host-backed table: the rows go to the staging buffer instead; the next Read's fetch
+    // kernel (or a waiting call) sends them over the host link.
+    using V = typename VecT<VEC>::type;
+    constexpr int PUSH_ROWS = 4;
+    static_assert(PUSH_ROWS == 4, "the copy below is written out for four rows");
+    const bool host = cv.Cg_host != nullptr;
+    const float *src_x = cv.rows, *src_a = cv.acc;
+    float *dst_x = host ? cv.hl.rows_of(buf) : cv.W, *dst_a = host ? cv.hl.acc_of(buf) : cv.A;
+    for (uint32_t v0 = group * PUSH_ROWS; v0 < np; v0 += ngroups * PUSH_ROWS) {
+        uint32_t from[PUSH_ROWS], to[PUSH_ROWS];
+#pragma unroll
+        for (int r = 0; r < PUSH_ROWS; ++r) {
+            const uint32_t v = min(v0 + r, np - 1);
+            from[r] = v_slot[v];
+            to[r] = host ? v_at[v] : v_key[v];
+            if (host && gl == 0 && v0 + r < np) {
+                const uint32_t vk = v_key[v];
+                cv.hl.keys_of(buf)[to[r]] = vk;
+                cv.hl.cg_of(buf)[to[r]] = v_cg[v];
+                cv.hl.pend[vk] = ((uint64_t)tp.push_seq << 32) | (uint64_t)to[r];
+            }
+        }
+        const bool adagrad = cv.adagrad != 0;
+        for (int c = gl; c < g.chunks; c += g.lanes) {
+            V x0, x1, x2, x3, a0{}, a1{}, a2{}, a3{};
+            x0 = reinterpret_cast<const V *>(src_x + (size_t)from[0] * g.dim)[c];
+            x1 = reinterpret_cast<const V *>(src_x + (size_t)from[1] * g.dim)[c];
+            x2 = reinterpret_cast<const V *>(src_x + (size_t)from[2] * g.dim)[c];
+            x3 = reinterpret_cast<const V *>(src_x + (size_t)from[3] * g.dim)[c];
+            if (adagrad) {
+                a0 = reinterpret_cast<const V *>(src_a + (size_t)from[0] * g.dim)[c];
+                a1 = reinterpret_cast<const V *>(src_a + (size_t)from[1] * g.dim)[c];
+                a2 = reinterpret_cast<const V *>(src_a + (size_t)from[2] * g.dim)[c];
+                a3 = reinterpret_cast<const V *>(src_a + (size_t)from[3] * g.dim)[c];
+            }
+            // rows past the end repeat the last one: the same values to the same place
+            reinterpret_cast<V *>(dst_x + (size_t)to[0] * g.dim)[c] = x0;
+            reinterpret_cast<V *>(dst_x + (size_t)to[1] * g.dim)[c] = x1;
+            reinterpret_cast<V *>(dst_x + (size_t)to[2] * g.dim)[c] = x2;
+            reinterpret_cast<V *>(dst_x + (size_t)to[3] * g.dim)[c] = x3;
+            if (adagrad) {
+                reinterpret_cast<V *>(dst_a + (size_t)to[0] * g.dim)[c] = a0;
+                reinterpret_cast<V *>(dst_a + (size_t)to[1] * g.dim)[c] = a1;
+                reinterpret_cast<V *>(dst_a + (size_t)to[2] * g.dim)[c] = a2;
+                reinterpret_cast<V *>(dst_a + (size_t)to[3] * g.dim)[c] = a3;
             }
         }
     }
