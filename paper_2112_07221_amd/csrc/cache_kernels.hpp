@@ -531,6 +531,7 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // workgroups fetch, the others gather, side by side.
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
 constexpr int GATHER_ROWS = 4;
+constexpr int POOL_ROWS = 8;
 struct FillLds {
     uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
     uint32_t scan[4 + 1];
@@ -647,16 +648,34 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         for (uint32_t b = gid; b < n_bags; b += ngroups) {
             int64_t lo = offsets[b], hi = offsets[b + 1];
             lo = lo < 0 ? 0 : lo; hi = hi > (int64_t)n ? (int64_t)n : hi;
+            // POOL_ROWS ids of the bag at a time: their sorted positions, then where their rows come
+            // from, then the rows, each step for all of them at once; added in bag order
             for (int c = gl; c < g.chunks; c += g.lanes) {
                 V sum{};
-                for (int64_t i = lo; i < hi; ++i) {
-                    const uint32_t j = inv[i];
-                    const int32_t s = ws.src[j];
-                    if (s == SRC_ZERO) continue;
-                    const float *row = s == SRC_BACKING ? cv.W + (size_t)ws.skey[j] * g.dim : cv.rows + (size_t)(uint32_t)s * g.dim;
-                    const V v = reinterpret_cast<const V *>(row)[c];
-                    if constexpr (VEC == 4) { sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w; }
-                    else sum += v;
+                for (int64_t i0 = lo; i0 < hi; i0 += POOL_ROWS) {
+                    uint32_t jj[POOL_ROWS];
+#pragma unroll
+                    for (int r = 0; r < POOL_ROWS; ++r) jj[r] = inv[i0 + r < hi ? i0 + r : hi - 1];
+                    int32_t sr[POOL_ROWS];
+                    uint32_t ky[POOL_ROWS];
+#pragma unroll
+                    for (int r = 0; r < POOL_ROWS; ++r) { sr[r] = ws.src[jj[r]]; ky[r] = ws.skey[jj[r]]; }
+                    V v[POOL_ROWS];
+#pragma unroll
+                    for (int r = 0; r < POOL_ROWS; ++r) {
+                        const float *row = sr[r] == SRC_BACKING ? cv.W + (size_t)ky[r] * g.dim : cv.rows + (size_t)(uint32_t)(sr[r] < 0 ? 0 : sr[r]) * g.dim;
+                        v[r] = reinterpret_cast<const V *>(row)[c];
+                    }
+#pragma unroll
+                    for (int r = 0; r < POOL_ROWS; ++r) {
+                        const bool counts = i0 + r < hi && sr[r] != SRC_ZERO;
+                        if constexpr (VEC == 4) {
+                            sum.x += counts ? v[r].x : 0.f; sum.y += counts ? v[r].y : 0.f;
+                            sum.z += counts ? v[r].z : 0.f; sum.w += counts ? v[r].w : 0.f;
+                        } else {
+                            sum += counts ? v[r] : 0.f;
+                        }
+                    }
                 }
                 reinterpret_cast<V *>(out + (size_t)b * g.dim)[c] = sum;
             }
