@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--no-prefetch", action="store_true", help="do not announce the next batch's ids")
     ap.add_argument("--prefetch-order", choices=("before", "between", "after"), default="before",
                     help="announce the next ids before the lookup, between lookup and update, or after the update")
+    ap.add_argument("--no-cache", action="store_true",
+                    help="context figure: the same step without the cache (reads and writes go to the global table)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy five times (a known-size reference for HBM counters)")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0 = auto)")
@@ -109,7 +111,7 @@ def main():
     offsets = torch.from_numpy(wl.bag_offsets(w)).to(dev) if w.pooled else None
     out = torch.empty(w.n_grad_rows, w.dim, device=dev)
 
-    cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps)
+    cache = hc.HetCache(w.capacity, w.dim, w.s, hc.POLICY_NONE if args.no_cache else w.policy, w.n, w.optimizer, w.eps)
     cache.attach_backing(Wt, At, Cg, hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
 
     def step(t):
@@ -196,7 +198,8 @@ def main():
         "config": {"workload": f"config {w.index} ({w.name}): vocab {w.vocab}, dim {w.dim}, "
                                f"{w.batch}x{w.width} ids/batch, Zipf {w.alpha}, cache {w.capacity} "
                                f"{'LFU' if w.policy else 'LRU'}, s={w.s}, "
-                               f"{'Adagrad' if w.optimizer else 'SGD'}, backing {w.backing}",
+                               f"{'Adagrad' if w.optimizer else 'SGD'}, backing {w.backing}"
+                               + (" -- WITHOUT the cache (context figure)" if args.no_cache else ""),
                    "ids_per_step": w.n, "unique_per_step": per_step["unique_lookup"],
                    "miss_per_step": per_step["miss"], "stale_per_step": per_step["stale"],
                    "evicted_dirty_per_step": per_step["evicted_dirty"],
@@ -210,6 +213,8 @@ def main():
     if host:
         link = (per_step["miss"] + per_step["stale_dirty"] + per_step["evicted_dirty"]) * 4 * w.dim \
             * (2 if w.optimizer else 1)
+        if args.no_cache:       # every row of the gather and both ways of every updated row cross the link
+            link = (w.n_grad_rows * (w.width if w.pooled else 1) + 2 * per_step["unique_lookup"] * (2 if w.optimizer else 1)) * 4 * w.dim
         result["host_link"] = {"bytes_per_step": link, "achieved_GBps": link / (ms_per_step * 1e-3) / 1e9}
 
     # ---- CPU oracle on a bounded sample of the same stream (reported baseline, not a target)

@@ -45,7 +45,8 @@ typedef enum het_status {
     HET_ESTATE = -5   /* sticky: het_update saw an id that is not cached (no het_lookup before) */
 } het_status;
 
-enum { HET_POLICY_LRU = 0, HET_POLICY_LFU = 1 };       /* Section 4.3 */
+enum { HET_POLICY_LRU = 0, HET_POLICY_LFU = 1,          /* Section 4.3 */
+       HET_POLICY_NONE = 2 };                            /* no cache at all: the baseline "Hybrid (w/o Cache)" of Section 5 */
 enum { HET_OPT_SGD = 0, HET_OPT_ADAGRAD = 1 };
 enum { HET_BACKING_HBM = 0, HET_BACKING_PINNED_HOST = 1 };
 enum { HET_CLASS_HIT = 0, HET_CLASS_STALE = 1, HET_CLASS_MISS = 2 };
@@ -76,6 +77,10 @@ typedef struct het_stats_t {
  * Creates an empty cache for `capacity` rows of `dim` floats with staleness bound `s`
  * (CheckValid, Section 3.1: a cached row is valid iff c_c <= c_s + s and c_g <= c_c + s) and
  * eviction `policy`.  s may be HET_S_INFINITE.  No device memory is taken yet.
+ * With HET_POLICY_NONE there is no cache (capacity and s are ignored, vocab must stay below
+ * 2^31): het_lookup gathers from the global table, het_update applies the coalesced gradients
+ * to it, nothing is ever cached, there are no clocks, and het_flush has nothing to do.  It is
+ * the yardstick for what the cache buys (table in host memory) or costs (table in HBM).
  * HET_EINVAL: out == NULL, capacity <= 0, dim <= 0, s < 0, unknown policy.
  */
 int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, int32_t policy);

@@ -68,6 +68,7 @@ struct CacheView {
     Counters *next_call;  // the other one: cleared by this call for the next
     RowGeom geom;
     int adagrad;
+    int direct;           // no cache: rows/acc alias the global table, a key is its own slot, there are no clocks
 };
 
 constexpr int32_t SRC_BACKING = -1;   // gather reads the global row: the key was not cached (or is refetched)
@@ -439,6 +440,43 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
     }
 }
 
+// No cache (the paper's baseline "Hybrid (w/o Cache)", Section 5): Read and Write go straight to
+// the global table.  The sorted order is used as it is; a key stands for its own row.
+template <bool LOOKUP>
+__global__ __launch_bounds__(PT_THREADS) void direct_probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now)
+{
+    __shared__ uint32_t lds[PT_WAVES + 1];
+    const uint32_t j = blockIdx.x * PT_TILE + threadIdx.x;
+    const uint32_t vocab = cv.vocab;
+    DState *ds = cv.ds;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        Counters z{};
+        *cv.next_call = z;
+        cv.last->n = n;
+        atomicAdd(&ds->total.n, (unsigned long long)n);
+        if (LOOKUP) ds->t = t_now;
+    }
+    bool head = false, bad = false;
+    if (j < n) {
+        const uint32_t key = ws.skey[j];
+        if (key == vocab) {
+            bad = true;
+            if (LOOKUP) ws.src[j] = SRC_ZERO;
+            ws.head_slot[j] = SLOT_NONE;
+            if (j == 0) ds->n_valid = 0;
+        } else {
+            head = j == 0 || ws.skey[j - 1] != key;
+            if (j + 1 == n || ws.skey[j + 1] == vocab) ds->n_valid = j + 1;
+            if (LOOKUP) ws.src[j] = (int32_t)key;
+            ws.head_slot[j] = (int32_t)key;
+            if (LOOKUP && head) ws.cls[j] = (uint8_t)CLS_MISS;        // every key comes from the global table
+        }
+    }
+    if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
+    const uint32_t tot_heads = block_sum<PT_WAVES>(head ? 1u : 0u, lds);
+    if (threadIdx.x == 0) count2(&cv.last->unique, &ds->total.unique, tot_heads);
+}
+
 // Evict's push for one row (Section 3.1): copy the row (and the accumulator) to the global
 // table; the group's first lane sets c_g = max(c_g, c_c).  Called by a whole row group.
 template <int VEC>
@@ -612,6 +650,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         return;
     }
     const uint32_t first_gather = fill_blocks + hist_blocks;
+    if (fill_blocks == 0 && bid == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // (no fetch workgroup did)
     const uint32_t gid = (bid - first_gather) * groups_per_block + threadIdx.x / g.lanes;
     const uint32_t ngroups = (nblk - first_gather) * groups_per_block;
     if (!POOLED) {
@@ -832,8 +871,8 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) {
                 v[i] = V{}; xr[i] = V{}; ar[i] = V{}; ccv[i] = 0;
-                if (q == 0 && i == 0 && cross != SLOT_NONE) cross_cc = cv.meta[cross].cc;       // (lane 0 only)
-                if (q == 0 && gl == 0 && ((whole >> i) & 1u)) ccv[i] = cv.meta[hs[i]].cc;
+                if (q == 0 && i == 0 && cross != SLOT_NONE && !cv.direct) cross_cc = cv.meta[cross].cc;       // (lane 0 only)
+                if (q == 0 && gl == 0 && ((whole >> i) & 1u) && !cv.direct) ccv[i] = cv.meta[hs[i]].cc;
                 if (act && ((use >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
                 if (act && ((whole >> i) & 1u)) {
                     xr[i] = reinterpret_cast<const V *>(cv.rows + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
@@ -876,7 +915,7 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
                         reinterpret_cast<V *>(cv.rows + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_x;
                         if (cv.adagrad) reinterpret_cast<V *>(cv.acc + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_a;
                     }
-                    if (q == 0 && gl == 0) cv.meta[cur_slot].cc = cur_cc + 1;       // Clock(k)
+                    if (q == 0 && gl == 0 && !cv.direct) cv.meta[cur_slot].cc = cur_cc + 1;       // Clock(k)
                 } else if (act && (cur_front || (k[i] == last_key && open_back))) {
                     // slot 0 of the chunk: a run that came in through the front border;
                     // slot 1: a run that starts here and leaves through the back border
@@ -889,7 +928,7 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         // Clock(k) of the run that leaves through the back border is taken here already: the second
         // kernel carries the stage of the trim's select that counts which rows hold updates, and
         // must not move clocks under it
-        if (cross != SLOT_NONE) cv.meta[cross].cc = cross_cc + 1;
+        if (cross != SLOT_NONE && !cv.direct) cv.meta[cross].cc = cross_cc + 1;
     }
 }
 

@@ -349,6 +349,26 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         use_order(c, c->sort_set);
     }
     const uint32_t t_now = (uint32_t)c->t_host;
+    if (c->cv.direct) {
+        // no cache: mark the runs, then gather straight from the global table
+        LAUNCH(c, K_PROBE, direct_probe_kernel<true><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now));
+        if (offsets)
+            LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
+        const SortStage ride = next_ride(c);
+        const uint32_t grid = ride.blocks + row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
+        const uint32_t lds = lds_bytes(std::max(sizeof(FillLds), sizeof(TrimLds)), ride);
+        const TrimPlan none{};
+#define GATHER_ONLY(POOLED, RIDE)                                                                                        \
+    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<grid, 256, lds, c->stream>>>(                          \
+                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride, 0u, 0, 0u))
+        if (!offsets) { if (ride.blocks) GATHER_ONLY(false, true); else GATHER_ONLY(false, false); }
+        else { if (ride.blocks) GATHER_ONLY(true, true); else GATHER_ONLY(true, false); }
+#undef GATHER_ONLY
+        if ((rc = launch_ok()) != HET_OK) return rc;
+        c->last_lookup_n = n;
+        c->order_ids = ids; c->order_n = n; c->order_valid = true;
+        return HET_OK;
+    }
     const uint32_t ptiles = cdiv(n, PT_TILE), stiles = cdiv(c->cv.n_slots, PT_TILE);
     LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + stiles, PT_THREADS, 0, c->stream>>>(
                            c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last),
@@ -438,8 +458,11 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     if (!reuse) {
         sort_now(c, ids, n, c->sort_set, 0);
         use_order(c, c->sort_set);
-        LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
-                               c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u));
+        if (c->cv.direct)
+            LAUNCH(c, K_PROBE, direct_probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
+        else
+            LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
+                                   c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u));
     }
     const uint32_t *grad_row = nullptr;
     if (offsets) {
@@ -494,7 +517,7 @@ extern "C" {
 int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, int32_t policy)
 {
     if (!out || capacity <= 0 || dim <= 0 || s < 0) return HET_EINVAL;
-    if (policy != HET_POLICY_LRU && policy != HET_POLICY_LFU) return HET_EINVAL;
+    if (policy != HET_POLICY_LRU && policy != HET_POLICY_LFU && policy != HET_POLICY_NONE) return HET_EINVAL;
     if (capacity >= (1ll << 30) || dim > (1 << 20)) return HET_EINVAL;
     het_cache *c = new (std::nothrow) het_cache();
     if (!c) return HET_ENOMEM;
@@ -512,7 +535,9 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     c->stream = static_cast<hipStream_t>(hip_stream);
 
     CacheView &cv = c->cv;
-    const uint64_t P = (uint64_t)c->capacity + (uint64_t)max_batch_ids;
+    const bool direct = c->policy == HET_POLICY_NONE;       // no cache: rows and accumulators are the global table's (set at attach)
+    cv.direct = direct;
+    const uint64_t P = direct ? 1 : (uint64_t)c->capacity + (uint64_t)max_batch_ids;
     cv.n_slots = (uint32_t)P; cv.capacity = (uint32_t)c->capacity; cv.max_ids = (uint32_t)max_batch_ids;
     cv.s = c->s; cv.adagrad = optimizer == HET_OPT_ADAGRAD;
     RowGeom g;
@@ -525,8 +550,8 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
 
     int rc = HET_OK;
     const size_t row_elems = (size_t)P * (size_t)c->dim;
-    if ((rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
-    if (cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
+    if (!direct && (rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
+    if (!direct && cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
     if ((rc = dev_alloc(c, &cv.slot_key, P)) || (rc = dev_alloc(c, &cv.meta, P))) return rc;
     if ((rc = dev_alloc(c, &cv.free_list, (size_t)max_batch_ids)) || (rc = dev_alloc(c, &cv.was_free, P))) return rc;
     if ((rc = dev_alloc(c, &cv.ds, 1))) return rc;
@@ -593,7 +618,10 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
         table = static_cast<float *>(dt); cg = static_cast<uint32_t *>(dcg); state = static_cast<float *>(dst);
     }
     c->cv.W = table; c->cv.A = state; c->cv.Cg = cg; c->cv.Cg_host = nullptr; c->cv.vocab = (uint32_t)vocab;
-    if (location == HET_BACKING_PINNED_HOST) {
+    if (c->cv.direct) {
+        if (vocab >= (1ll << 31)) return HET_EINVAL;        // a key stands for its own slot
+        c->cv.rows = table; c->cv.acc = state;
+    } else if (location == HET_BACKING_PINNED_HOST) {
         // The kernels work on a mirror of the global clocks in HBM (a probe must not cross the host
         // link for four bytes per key); the caller's array is written through.  Evicted rows are
         // staged in HBM and written back behind the step (HostLink).

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhet_cache.so")
 
 HET_OK, HET_EINVAL, HET_ENOMEM, HET_EHIP, HET_ERANGE, HET_ESTATE = 0, -1, -2, -3, -4, -5
-POLICY_LRU, POLICY_LFU = 0, 1
+POLICY_LRU, POLICY_LFU, POLICY_NONE = 0, 1, 2
 OPT_SGD, OPT_ADAGRAD = 0, 1
 BACKING_HBM, BACKING_PINNED_HOST = 0, 1
 CLASS_HIT, CLASS_STALE, CLASS_MISS = 0, 1, 2

@@ -121,6 +121,66 @@ def test_host_backed_table_rows_evicted_and_fetched_again_at_once(policy, opt):
         p.close()
 
 
+@pytest.mark.parametrize("cfg,opt,host", [(1, wl.SGD, False), (1, wl.ADAGRAD, True), (5, wl.ADAGRAD, False)])
+def test_no_cache_mode_is_uncached_training(cfg, opt, host):
+    """HET_POLICY_NONE reads and writes the global table itself.  The oracle's cache is
+    transparent (its pins: every Read equals uncached training, and after a flush so does the
+    table), so its outputs and its flushed table are what uncached training gives."""
+    from oracle.het_oracle import Oracle
+    w = wl.WORKLOADS[cfg].scaled(optimizer=opt)
+    if cfg == 5:
+        w = w.scaled(vocab=50_000, batch=128, capacity=2_000)
+    table = wl.table_init(w)
+    ids_np = wl.IdStream(w).batches(12)
+    g_np = wl.grad_pool(w)
+    oracle = Oracle(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps, table)
+    cache = hc.HetCache(1, w.dim, 0, hc.POLICY_NONE, w.n, w.optimizer, w.eps)
+    dev = torch.device("cuda:0")
+    V = table.shape[0]
+    W = torch.from_numpy(table.astype(np.float32))
+    W = W.pin_memory() if host else W.to(dev)
+    A = None
+    if w.optimizer:
+        A = torch.zeros(V, w.dim).pin_memory() if host else torch.zeros(V, w.dim, device=dev)
+    Cg = torch.zeros(V, dtype=torch.int32).pin_memory() if host else torch.zeros(V, dtype=torch.int32, device=dev)
+    cache.attach_backing(W, A, Cg, hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
+    offs_np = wl.bag_offsets(w) if w.pooled else None
+    offs = torch.from_numpy(offs_np).to(dev) if w.pooled else None
+    try:
+        d = torch.from_numpy(ids_np).to(dev)
+        for t in range(12):
+            out = torch.full((w.n_grad_rows, w.dim), float("nan"), device=dev)
+            g = torch.from_numpy(g_np[t % len(g_np)]).to(dev)
+            if t + 1 < 12:
+                cache.prefetch(d[t + 1])
+            if w.pooled:
+                cache.lookup_pooled(d[t], offs, out)
+                want, _ = oracle.lookup_pooled(ids_np[t], offs_np)
+            else:
+                cache.lookup(d[t], out)
+                want, _ = oracle.lookup(ids_np[t])
+            close(out.cpu().numpy(), want, "lookup output")
+            keys, cls, slots = cache.last_lookup()
+            assert np.array_equal(keys, oracle.last_lookup()[0]) and np.array_equal(slots, keys)
+            # every other update hands over a copy of the ids: the path that sorts for itself
+            ids_for_update = d[t] if t % 2 == 0 else d[t].clone()
+            if w.pooled:
+                cache.update_pooled(ids_for_update, offs, g, w.lr)
+                oracle.update_pooled(ids_np[t], offs_np, g_np[t % len(g_np)], w.lr)
+            else:
+                cache.update(ids_for_update, g, w.lr)
+                oracle.update(ids_np[t], g_np[t % len(g_np)], w.lr)
+        st = cache.stats()
+        assert st["resident"] == 0 and st["error_bits"] == 0 and st["total"]["unique"] == oracle.stats()[1]["U"]
+        assert cache.flush() == 0
+        oracle.flush()
+        close(W.cpu().numpy(), oracle.W, "global table")
+        if A is not None:
+            close(A.cpu().numpy(), oracle.A, "global accumulators")
+    finally:
+        cache.close(); oracle.close()
+
+
 def test_ragged_and_degenerate_batches():
     """Batches of 1, 63, 64, 65, 1023, 1025, 2047, 2049 ids, all-equal ids, already-unique ids."""
     w = wl.WORKLOADS[1].scaled(capacity=300, s=1)
