@@ -75,6 +75,25 @@ def test_config2_full_size():
     assert st["total"]["stale"] > 0 and st["total"]["evicted"] > 0
 
 
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_configs_4_and_5_full_size(cfg):
+    """Configs 4 (skip-gram, 4M nodes, dim 128) and 5 (bag-of-words, pooled, dim 256, more unique ids
+    than cache rows) at full size, in the benchmark's launch configuration, for a few iterations."""
+    w = wl.WORKLOADS[cfg]
+    w = w.scaled(s=2) if cfg == 4 else w.scaled(s=3)
+    st = run_workload(w, 8, state_every=4, values_every=4, prefetch="before")
+    assert st["total"]["evicted_dirty"] > 0
+
+
+def test_config3_full_batch_and_cache_host_backed():
+    """Config 3's launch shapes (8192 x 26 ids, dim 128, cache of 2M rows, LRU, table in pinned host
+    memory), with the vocabulary cut to 4M so that the oracle's fp64 table fits in host memory.
+    (The cache starts cold and holds every row for the length of this run; evictions over the
+    host link are covered by the smaller host-backed cases.)"""
+    w = wl.WORKLOADS[3].scaled(vocab=4_000_000, s=2)
+    run_workload(w, 6, state_every=3, values_every=3, prefetch="before")
+
+
 def test_config4_shape_reduced():
     w = wl.WORKLOADS[4].scaled(vocab=400_000, batch=2048, capacity=40_000, s=4)
     run_workload(w, 30, state_every=5, values_every=10)
