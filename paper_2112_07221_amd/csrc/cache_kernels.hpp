@@ -77,7 +77,8 @@ constexpr int32_t SRC_ZERO = -2;      // id outside the vocabulary: the output r
 constexpr int PT_THREADS = 1024;                // probe tiles: 1024 sorted positions per workgroup,
 constexpr int PT_WAVES = PT_THREADS / WAVE;     // one per thread, so every probe's loads are in flight at once
 constexpr int PT_TILE = PT_THREADS;
-constexpr int CHUNK = 8;                        // sorted positions per row group in the apply kernel
+constexpr int CHUNK_SHORT = 4, CHUNK_LONG = 8;       // sorted positions per row group in the apply kernel (template parameter CHUNK):
+                                                     // four keep the kernel's registers low; eight halve the partial sums of very long runs
 
 // Per-call workspaces (sized by max_batch_ids unless noted).  Per-key facts are stored at the
 // key's head position in the sorted order.
@@ -777,7 +778,7 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // VERIFY: the ids must be the ones the sorted order was built from (an update that reuses the
 // preceding lookup's order); a position whose id differs is skipped and flagged.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
-template <int VEC, int MAXC, bool VERIFY>
+template <int VEC, int MAXC, bool VERIFY, int CHUNK>
 __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, const int64_t *__restrict__ ids,
                                                     const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                     float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
@@ -834,19 +835,32 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         const bool open_front = prev_key == k[0];           // the first run began in an earlier chunk
         const bool open_back = next_key == last_key;        // the last run goes on in a later chunk
 
-        uint32_t use = 0, heads = 0, whole = 0;             // bit i: gradient counts / run head / head of a run inside the chunk
+        // VERIFY: the caller's id at every position, requested here and looked at only after the
+        // gradient rows have been requested too (the check is not a step of its own on the way)
+        // (With eight positions per group the registers for that are not there: the ids are
+        // compared before the gradient rows are requested.)
+        constexpr bool LATE_CHECK = VERIFY && CHUNK <= 4;
+        constexpr int NIDV = LATE_CHECK ? CHUNK : 1;
+        int64_t idv[NIDV];
+        const uint32_t inm = (1u << cnt) - 1u;
+        uint32_t use = inm, heads = 0, whole = 0;           // bit i: gradient counts / run head / head of a run inside the chunk
+        if (LATE_CHECK) {
+#pragma unroll
+            for (int i = 0; i < NIDV; ++i) idv[i] = (uint32_t)i < cnt ? ids[p[i]] : (int64_t)k[i];
+        } else if (VERIFY) {
+            use = 0;
+#pragma unroll
+            for (int i = 0; i < CHUNK; ++i) use |= ((uint32_t)i < cnt && ids[p[i]] == (int64_t)k[i]) ? (1u << i) : 0u;
+            if (gl == 0 && use != inm) atomicOr(&cv.ds->err, ERRBIT_STATE);
+        }
 #pragma unroll
         for (int i = 0; i < CHUNK; ++i) {
             const bool in = (uint32_t)i < cnt;
-            bool ok = in;
-            if (VERIFY && in) ok = ids[p[i]] == (int64_t)k[i];
-            use |= ok ? (1u << i) : 0u;
             const bool head = in && (i == 0 || k[i] != k[i - 1]);
             heads |= head ? (1u << i) : 0u;
             const bool inside = head && !(i == 0 && open_front) && !(k[i] == last_key && open_back);
             whole |= (inside && hs[i] != SLOT_NONE) ? (1u << i) : 0u;
         }
-        if (VERIFY && gl == 0 && use != ((1u << cnt) - 1u)) atomicOr(&cv.ds->err, ERRBIT_STATE);
         if (grad_row) {
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) if ((uint32_t)i < cnt) p[i] = grad_row[p[i]];
@@ -873,11 +887,21 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
                 v[i] = V{}; xr[i] = V{}; ar[i] = V{}; ccv[i] = 0;
                 if (q == 0 && i == 0 && cross != SLOT_NONE && !cv.direct) cross_cc = cv.meta[cross].cc;       // (lane 0 only)
                 if (q == 0 && gl == 0 && ((whole >> i) & 1u) && !cv.direct) ccv[i] = cv.meta[hs[i]].cc;
-                if (act && ((use >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
+                if (act && (((LATE_CHECK ? inm : use) >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
                 if (act && ((whole >> i) & 1u)) {
                     xr[i] = reinterpret_cast<const V *>(cv.rows + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
                     if (cv.adagrad) ar[i] = reinterpret_cast<const V *>(cv.acc + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
                 }
+            }
+            if (LATE_CHECK) {
+                if (q == 0) {
+                    use = 0;
+#pragma unroll
+                    for (int i = 0; i < NIDV; ++i) use |= (((inm >> i) & 1u) && idv[i] == (int64_t)k[i]) ? (1u << i) : 0u;
+                    if (gl == 0 && use != inm) atomicOr(&cv.ds->err, ERRBIT_STATE);
+                }
+#pragma unroll
+                for (int i = 0; i < CHUNK; ++i) if (!((use >> i) & 1u)) v[i] = V{};     // a position whose id changed does not count
             }
             double acc64[VEC];
             V cur_x{}, cur_a{};
@@ -946,7 +970,7 @@ template <int VEC> struct FinishLds {
     int32_t long_slot[256];
     uint32_t n_long;
 };
-template <int VEC, int MAXC>
+template <int VEC, int MAXC, int CHUNK>
 __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
                                                            uint32_t work_blocks, TrimPlan tp, int stage, SortStage ride)
 {

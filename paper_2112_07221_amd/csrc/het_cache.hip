@@ -422,8 +422,8 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 // (stage 0 rode with the lookup's fetches).  The first kernel moves the clocks, so it may carry
 // a histogram stage (policy fields only) but not the final count, which looks at the clocks.
 // `trim`: a trim follows.  Returns the first stage that is still to run.
-template <int VEC, int MAXC>
-int launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
+template <int VEC, int MAXC, int CHUNK>
+int launch_apply_chunk(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
                  bool trim)
 {
     const uint32_t grid = row_grid(c->cv.geom, cdiv(n, CHUNK));
@@ -436,13 +436,22 @@ int launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, cons
     const SortStage ride0 = next_ride(c);
     const uint32_t lds0 = lds_bytes(sizeof(TrimLds), ride0);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, CHUNK><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, CHUNK><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
     const SortStage ride1 = next_ride(c);
     const uint32_t lds1 = lds_bytes(std::max(sizeof(TrimLds), sizeof(FinishLds<VEC>)), ride1);
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC><<<ride1.blocks + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, stage1, ride1));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC, CHUNK><<<ride1.blocks + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, stage1, ride1));
     return next;
+}
+
+// Very large batches (their popular keys' runs are very long) take eight positions per row group, others four.
+template <int VEC, int MAXC>
+int launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
+                 bool trim)
+{
+    return n > (1u << 18) ? launch_apply_chunk<VEC, MAXC, CHUNK_LONG>(c, verify, ids, n, grads, grad_row, lr, trim)
+                          : launch_apply_chunk<VEC, MAXC, CHUNK_SHORT>(c, verify, ids, n, grads, grad_row, lr, trim);
 }
 
 template <int VEC>
@@ -568,7 +577,7 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     const size_t N = (size_t)max_batch_ids;
     const size_t ptiles = cdiv(N, PT_TILE);
     const size_t sort_tiles = cdiv(N, SORT_TILE);
-    const size_t chunks = cdiv(N, CHUNK);
+    const size_t chunks = cdiv(N, CHUNK_SHORT);
     for (int set = 0; set < SORT_SETS; ++set) {
         for (int i = 0; i < 2; ++i)
             if ((rc = dev_alloc(c, &c->keys[set][i], N)) || (rc = dev_alloc(c, &c->idx[set][i], N))) return rc;
