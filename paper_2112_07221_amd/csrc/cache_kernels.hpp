@@ -575,7 +575,9 @@ struct FillLds {
     uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
     uint32_t scan[4 + 1];
 };
-template <int VEC, bool POOLED, bool RIDE>
+// RIDE: 0 carries no sort stage, 1 a histogram stage (cheap in registers: the gather keeps its
+// occupancy), 2 any stage.
+template <int VEC, bool POOLED, int RIDE>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv, SortStage ride,
@@ -584,7 +586,11 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
     if (RIDE) {
-        if (bid < ride.blocks) { sort_stage_body(ride, bid, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
+        if (bid < ride.blocks) {
+            if (RIDE == 1) { __builtin_amdgcn_s_setprio(3); sort_hist_body(ride, bid, reinterpret_cast<uint32_t *>(dyn_lds)); }
+            else sort_stage_body(ride, bid, reinterpret_cast<uint32_t *>(dyn_lds));
+            return;
+        }
         bid -= ride.blocks; nblk -= ride.blocks;
     }
     if (bid < push_blocks) { deferred_push_body<VEC>(cv, push_buf, bid, push_blocks); return; }    // host-backed table: the last trim's write-back

@@ -361,8 +361,9 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 #define GATHER_ONLY(POOLED, RIDE)                                                                                        \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<grid, 256, lds, c->stream>>>(                          \
                                  c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride, 0u, 0, 0u))
-        if (!offsets) { if (ride.blocks) GATHER_ONLY(false, true); else GATHER_ONLY(false, false); }
-        else { if (ride.blocks) GATHER_ONLY(true, true); else GATHER_ONLY(true, false); }
+        const int kind = !ride.blocks ? 0 : ((ride.stage & 1) ? 2 : 1);
+        if (!offsets) { if (kind == 0) GATHER_ONLY(false, 0); else if (kind == 1) GATHER_ONLY(false, 1); else GATHER_ONLY(false, 2); }
+        else { if (kind == 0) GATHER_ONLY(true, 0); else if (kind == 1) GATHER_ONLY(true, 1); else GATHER_ONLY(true, 2); }
 #undef GATHER_ONLY
         if ((rc = launch_ok()) != HET_OK) return rc;
         c->last_lookup_n = n;
@@ -386,8 +387,16 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
                                  PUSHB, c->push_buf, c->push_seq))
 #define FILL_GATHER_ANY(GRID, FILLB, HISTB, PUSHB)                                                                        \
     do {                                                                                                                  \
-        if (!offsets) { if (ride.blocks) FILL_GATHER(false, true, GRID, FILLB, HISTB, PUSHB); else FILL_GATHER(false, false, GRID, FILLB, HISTB, PUSHB); } \
-        else { if (ride.blocks) FILL_GATHER(true, true, GRID, FILLB, HISTB, PUSHB); else FILL_GATHER(true, false, GRID, FILLB, HISTB, PUSHB); }           \
+        const int kind = !ride.blocks ? 0 : ((ride.stage & 1) ? 2 : 1);                                                   \
+        if (!offsets) {                                                                                                   \
+            if (kind == 0) FILL_GATHER(false, 0, GRID, FILLB, HISTB, PUSHB);                                              \
+            else if (kind == 1) FILL_GATHER(false, 1, GRID, FILLB, HISTB, PUSHB);                                         \
+            else FILL_GATHER(false, 2, GRID, FILLB, HISTB, PUSHB);                                                        \
+        } else {                                                                                                          \
+            if (kind == 0) FILL_GATHER(true, 0, GRID, FILLB, HISTB, PUSHB);                                               \
+            else if (kind == 1) FILL_GATHER(true, 1, GRID, FILLB, HISTB, PUSHB);                                          \
+            else FILL_GATHER(true, 2, GRID, FILLB, HISTB, PUSHB);                                                         \
+        }                                                                                                                 \
     } while (0)
     const uint32_t gather_blocks = row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
     if (c->location == HET_BACKING_HBM) {

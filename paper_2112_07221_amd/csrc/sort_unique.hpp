@@ -118,6 +118,7 @@ __device__ __forceinline__ void sort_scatter_body(const SortStage &s, uint32_t t
     uint32_t *tile_base = lds + SORT_WAVES * bins;     // [bins]
     uint32_t *scan_lds = tile_base + bins;             // [SORT_WAVES + 1]
 
+    uint32_t key[SORT_ITEMS], pay[SORT_ITEMS], lrank[SORT_ITEMS];
     // Output offset of each digit for this tile: keys of smaller digits anywhere, plus keys of
     // the same digit in earlier tiles.  A thread adds up eight consecutive digits (one 16-byte
     // load per tile, many loads in flight) over every TLN-th tile; LDS merges the tile lanes.
@@ -158,6 +159,21 @@ __device__ __forceinline__ void sort_scatter_body(const SortStage &s, uint32_t t
                 else { if (t8[e]) atomicAdd(&tot[b + e], t8[e]); if (f8[e]) atomicAdd(&bef[b + e], f8[e]); }
             }
         }
+        // The keys (and payload) of this tile are requested here: the offsets' registers are free
+        // again, and the loads are on their way while the digits are scanned.  (Held across the
+        // whole offset computation they would cost the carrying kernel part of its occupancy.)
+#pragma unroll
+        for (int it = 0; it < SORT_ITEMS; ++it) {
+            const uint32_t i = sort_pos(tile, it);
+            key[it] = i < sp.n ? s.keys_in[i] : 0u;
+        }
+        if (pass == 0) {
+#pragma unroll
+            for (int it = 0; it < SORT_ITEMS; ++it) pay[it] = sort_pos(tile, it);
+        } else {
+#pragma unroll
+            for (int it = 0; it < SORT_ITEMS; ++it) { const uint32_t i = sort_pos(tile, it); pay[it] = i < sp.n ? s.idx_in[i] : 0u; }
+        }
         __syncthreads();
         // exclusive scan over the digits; thread t owns SORT_BINS_PER_THREAD consecutive digits
         const uint32_t b0 = threadIdx.x * SORT_BINS_PER_THREAD;
@@ -180,24 +196,11 @@ __device__ __forceinline__ void sort_scatter_body(const SortStage &s, uint32_t t
     }
     __syncthreads();
 
-    // The keys of this tile.  (Requested only now: held across the offset computation they would
-    // cost the kernel that carries this stage a good part of its occupancy.)
-    uint32_t key[SORT_ITEMS], pay[SORT_ITEMS], lrank[SORT_ITEMS];
-#pragma unroll
-    for (int it = 0; it < SORT_ITEMS; ++it) {
-        const uint32_t i = sort_pos(tile, it);
-        key[it] = i < sp.n ? s.keys_in[i] : 0u;
-    }
-    if (pass == 0) {
-#pragma unroll
-        for (int it = 0; it < SORT_ITEMS; ++it) pay[it] = sort_pos(tile, it);
-    } else {
-#pragma unroll
-        for (int it = 0; it < SORT_ITEMS; ++it) { const uint32_t i = sort_pos(tile, it); pay[it] = i < sp.n ? s.idx_in[i] : 0u; }
-    }
     // rank of every key among the keys of the same digit before it in the tile: within the wave
     // by ballots over the digit's bits, across the wave's earlier items by a running count
-    volatile uint32_t *my_hist = wave_hist + w * bins;
+    // First all the ballots (registers only), then the running counts (LDS only): interleaved,
+    // every item would wait for both in turn.
+    uint32_t lead[SORT_ITEMS];          // for the first lane of each group of equal digits: the group's size
 #pragma unroll
     for (int it = 0; it < SORT_ITEMS; ++it) {
         const uint32_t i = sort_pos(tile, it);
@@ -207,16 +210,24 @@ __device__ __forceinline__ void sort_scatter_body(const SortStage &s, uint32_t t
 #pragma unroll
         for (int b = 0; b < SORT_MAX_BITS; ++b) {
             if (b < width) {
-                const bool bit = (d >> b) & 1u;
-                const uint64_t bal = __ballot(bit);
-                peers &= bit ? bal : ~bal;
+                const uint64_t bal = __ballot((d >> b) & 1u);
+                const uint32_t flip = ((d >> b) & 1u) - 1u;               // all ones where the lane's bit is clear
+                const uint32_t lo = (uint32_t)bal ^ flip, hi = (uint32_t)(bal >> 32) ^ flip;
+                peers &= ((uint64_t)hi << 32) | lo;
             }
         }
         const uint32_t r = mask_rank(peers);
+        lrank[it] = r;
+        lead[it] = (valid && r == 0) ? (uint32_t)__popcll(peers) : 0u;
+    }
+    volatile uint32_t *my_hist = wave_hist + w * bins;
+#pragma unroll
+    for (int it = 0; it < SORT_ITEMS; ++it) {
+        const uint32_t d = (key[it] >> shift) & mask;
         const uint32_t before = my_hist[d];
-        lrank[it] = before + r;
+        lrank[it] += before;
         __builtin_amdgcn_wave_barrier();
-        if (valid && r == 0) my_hist[d] = before + (uint32_t)__popcll(peers);
+        if (lead[it]) my_hist[d] = before + lead[it];
         __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
