@@ -115,11 +115,15 @@ def main():
     cache.attach_backing(Wt, At, Cg, hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
 
     def step(t):
-        # the ids of batch t+1 are announced (the kernels of lookup t and update t carry their
+        # the ids of batch t+2 are announced (the kernels of this step and the next carry their
         # sort); lookup t; update t
         pf = not args.no_prefetch and t + 1 < total
         if pf and args.prefetch_order == "before":
-            cache.prefetch(ids[t + 1])
+            # two ahead: a sort has more stages than one step has kernels to carry them
+            if t == 0:
+                cache.prefetch(ids[1])
+            if t + 2 < total:
+                cache.prefetch(ids[t + 2])
         if w.pooled:
             cache.lookup_pooled(ids[t], offsets, out)
         else:

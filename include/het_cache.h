@@ -124,11 +124,12 @@ int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out);
  * Optional: announces the ids of a coming lookup (Section 4.2: the indices of the next minibatch
  * are known in advance).  Their sort, the dedup of Algorithm 1, touches no cache state, so the
  * kernels of the calls made between this call and that lookup carry it in extra workgroups, one
- * stage per kernel; whatever is still missing runs when the lookup comes.  One lookup plus one
- * update carry a whole sort for vocabularies up to 2^22 ids, so the best place for this call is
- * just before the lookup of the batch BEFORE the announced one.  ids[n] (device) must be
+ * stage per kernel (two, if two announced batches are under way); whatever is still missing runs
+ * when the lookup comes.  A sort has two stages per eight bits of the vocabulary's width, a
+ * lookup plus an update have four kernels that can carry: announce two batches ahead (before the
+ * lookup of batch t, the ids of batch t + 2) and the sort is never seen.  ids[n] (device) must be
  * complete in stream order when this call is made and stay unchanged until the lookup that
- * passes the same pointer and n.  Two batches can stand announced at a time (a third replaces
+ * passes the same pointer and n.  Three batches can stand announced at a time (a fourth replaces
  * the oldest).  Results are identical with and without the announcement; a lookup with other
  * ids leaves it standing for a later one.  Nothing is launched by this call.
  */

@@ -200,6 +200,25 @@ struct TrimLds {
 extern __shared__ __align__(16) unsigned char dyn_lds[];
 template <typename T> __device__ __forceinline__ T &lds_as() { return *reinterpret_cast<T *>(dyn_lds); }
 
+// Up to two sort stages, of two different announced batches, travel in one kernel.  Returns
+// true if this workgroup ran one of them; otherwise bid / nblk number the kernel's own workgroups.
+// HIST_ONLY: both are known to be histogram stages (cheap in registers).
+template <bool HIST_ONLY = false>
+__device__ __forceinline__ bool run_carried(const SortStage &a, const SortStage &b, uint32_t &bid, uint32_t &nblk)
+{
+    uint32_t *lds = reinterpret_cast<uint32_t *>(dyn_lds);
+    if (bid < a.blocks + b.blocks) {
+        const bool first = bid < a.blocks;
+        const SortStage &st = first ? a : b;
+        const uint32_t tile = first ? bid : bid - a.blocks;
+        if (HIST_ONLY) { __builtin_amdgcn_s_setprio(3); sort_hist_body(st, tile, lds); }
+        else sort_stage_body(st, tile, lds);
+        return true;
+    }
+    bid -= a.blocks + b.blocks; nblk -= a.blocks + b.blocks;
+    return false;
+}
+
 // One histogram pass of the select over the rows whose key matches the prefix chosen so far.
 // Runs in `nblocks` workgroups of TRIM_THREADS threads; `vblock` is this one's index.
 // `new_rows` > 0 (first pass, running beside the lookup's fetches): slots that were free when
@@ -580,19 +599,13 @@ struct FillLds {
 template <int VEC, bool POOLED, int RIDE>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
-                                                          const uint32_t *__restrict__ inv, SortStage ride,
+                                                          const uint32_t *__restrict__ inv, SortStage ride, SortStage ride2,
                                                           uint32_t push_blocks, int push_buf, uint32_t push_seq)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
-    if (RIDE) {
-        if (bid < ride.blocks) {
-            if (RIDE == 1) { __builtin_amdgcn_s_setprio(3); sort_hist_body(ride, bid, reinterpret_cast<uint32_t *>(dyn_lds)); }
-            else sort_stage_body(ride, bid, reinterpret_cast<uint32_t *>(dyn_lds));
-            return;
-        }
-        bid -= ride.blocks; nblk -= ride.blocks;
-    }
+    if (RIDE == 1 && run_carried<true>(ride, ride2, bid, nblk)) return;
+    if (RIDE == 2 && run_carried<false>(ride, ride2, bid, nblk)) return;
     if (bid < push_blocks) { deferred_push_body<VEC>(cv, push_buf, bid, push_blocks); return; }    // host-backed table: the last trim's write-back
     bid -= push_blocks; nblk -= push_blocks;
     const RowGeom g = cv.geom;
@@ -788,11 +801,11 @@ template <int VEC, int MAXC, bool VERIFY, int CHUNK>
 __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, const int64_t *__restrict__ ids,
                                                     const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                     float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
-                                                    SortStage ride)
+                                                    SortStage ride, SortStage ride2)
 {
     using V = typename VecT<VEC>::type;
-    if (blockIdx.x < ride.blocks) { sort_stage_body(ride, blockIdx.x, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
-    const uint32_t bid = blockIdx.x - ride.blocks, nblk = gridDim.x - ride.blocks;
+    uint32_t bid = blockIdx.x, nblk = gridDim.x;
+    if (run_carried(ride, ride2, bid, nblk)) return;
     if (bid >= work_blocks) {            // extra workgroups: a stage of the coming trim's select
         trim_stage_body(cv, tp, stage, bid - work_blocks, nblk - work_blocks, lds_as<TrimLds>());
         return;
@@ -978,10 +991,10 @@ template <int VEC> struct FinishLds {
 };
 template <int VEC, int MAXC, int CHUNK>
 __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
-                                                           uint32_t work_blocks, TrimPlan tp, int stage, SortStage ride)
+                                                           uint32_t work_blocks, TrimPlan tp, int stage, SortStage ride, SortStage ride2)
 {
-    if (blockIdx.x < ride.blocks) { sort_stage_body(ride, blockIdx.x, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
-    const uint32_t bid = blockIdx.x - ride.blocks, nblk = gridDim.x - ride.blocks;
+    uint32_t bid = blockIdx.x, nblk = gridDim.x;
+    if (run_carried(ride, ride2, bid, nblk)) return;
     if (bid >= work_blocks) {            // extra workgroups: the next stage of the trim's select
         trim_stage_body(cv, tp, stage, bid - work_blocks, nblk - work_blocks, lds_as<TrimLds>());
         return;
@@ -1112,13 +1125,10 @@ struct EvictLds {
     uint32_t n_push;
 };
 template <int VEC, bool RIDE>
-__global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, TrimPlan tp, SortStage ride)
+__global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, TrimPlan tp, SortStage ride, SortStage ride2)
 {
-    uint32_t blk = blockIdx.x;
-    if (RIDE) {
-        if (blk < ride.blocks) { sort_stage_body(ride, blk, reinterpret_cast<uint32_t *>(dyn_lds)); return; }
-        blk -= ride.blocks;
-    }
+    uint32_t blk = blockIdx.x, nblk_ = gridDim.x;
+    if (RIDE && run_carried(ride, ride2, blk, nblk_)) return;
     EvictLds &el = lds_as<EvictLds>();
     uint32_t *scan = el.scan, *v_slot = el.v_slot, *v_key = el.v_key, *v_cg = el.v_cg, *v_at = el.v_at;
     DState *ds = cv.ds;

@@ -28,7 +28,7 @@ static const char *const kKernelNames[K_NUM] = {
 
 struct ProfSpan { int id; hipEvent_t start, stop; };
 
-constexpr int SORT_SETS = 3;
+constexpr int SORT_SETS = 4;
 
 // A batch announced by het_prefetch: its ids, the buffer set its sort uses and how far the sort has come.
 struct Announced {
@@ -53,13 +53,14 @@ struct het_cache {
     CacheView cv{};
     Workspace ws{};
     TrimPlan tp{};
-    // Three sets of sort buffers: the order of the current batch (kept for its update) and up to
-    // two batches announced ahead by het_prefetch, whose sorts are carried by the kernels of the
-    // calls in between.
+    // Four sets of sort buffers: the order of the current batch (kept for its update) and up to
+    // three batches announced ahead by het_prefetch, whose sorts are carried by the kernels of the
+    // calls in between (a sort is more stages long than a lookup and an update have kernels, so
+    // in steady state two announced batches are being sorted and a third stands ready).
     uint32_t *keys[SORT_SETS][2] = {}, *idx[SORT_SETS][2] = {};
     uint32_t *sort_hist[SORT_SETS] = {};
     int sort_set = 0;                // the set that holds the current batch's order
-    Announced ann[2];                // announced batches, oldest first
+    Announced ann[SORT_SETS - 1];    // announced batches, oldest first
     int n_ann = 0;
     TrimPlan sel_tp{};               // the select plan of the rows now cached (fixed at the lookup)
     bool last_trim_skipped = false;  // the last update had nothing to trim: its evicted-id list is empty
@@ -218,12 +219,6 @@ SortStage no_stage()
     return s;
 }
 
-// LDS a kernel needs: its own roles' or, if larger, the carried stage's.
-uint32_t lds_bytes(size_t own, const SortStage &ride)
-{
-    return std::max<uint32_t>((uint32_t)own, ride.blocks ? sort_stage_lds_bytes(ride.sp.width, ride.stage) : 0u);
-}
-
 // Begins a call that touches the cache: per-call counters go to the other counter block.
 void begin_call(het_cache *c)
 {
@@ -243,18 +238,46 @@ void sort_now(het_cache *c, const int64_t *ids, uint32_t n, int set, int first_s
 
 // The next stage of the oldest announced batch whose sort is not complete yet, for the kernel
 // that is about to be launched to carry.
-SortStage next_ride(het_cache *c)
+SortStage next_ride_of(het_cache *c, int a)
 {
-    for (int a = 0; a < c->n_ann; ++a) {
-        Announced &an = c->ann[a];
-        if (an.next_stage < sort_stages(c)) return make_stage(c, an.ids, an.n, an.set, an.next_stage++);
+    Announced &an = c->ann[a];
+    return make_stage(c, an.ids, an.n, an.set, an.next_stage++);
+}
+
+// What the kernel about to be launched carries: the next stage of the oldest announced batch whose
+// sort is not complete yet and, since stages of one sort need a kernel boundary between them, the
+// next stage of the batch announced after it.
+struct Rides {
+    SortStage a, b;
+    uint32_t blocks() const { return a.blocks + b.blocks; }
+    // 0: nothing, 1: histogram stages only, 2: a scatter stage among them
+    int kind() const { return !blocks() ? 0 : (((a.blocks && (a.stage & 1)) || (b.blocks && (b.stage & 1))) ? 2 : 1); }
+};
+
+// LDS a kernel needs: its own roles' or, if larger, a carried stage's.
+uint32_t lds_bytes(size_t own, const Rides &r)
+{
+    uint32_t need = (uint32_t)own;
+    if (r.a.blocks) need = std::max(need, sort_stage_lds_bytes(r.a.sp.width, r.a.stage));
+    if (r.b.blocks) need = std::max(need, sort_stage_lds_bytes(r.b.sp.width, r.b.stage));
+    return need;
+}
+
+Rides next_rides(het_cache *c)
+{
+    Rides r{no_stage(), no_stage()};
+    int got = 0;
+    for (int a = 0; a < c->n_ann && got < 2; ++a) {
+        if (c->ann[a].next_stage >= sort_stages(c)) continue;
+        (got == 0 ? r.a : r.b) = next_ride_of(c, a);
+        ++got;
     }
-    return no_stage();
+    return r;
 }
 
 void drop_oldest_announcement(het_cache *c)
 {
-    c->ann[0] = c->ann[1];
+    for (int a = 0; a + 1 < c->n_ann; ++a) c->ann[a] = c->ann[a + 1];
     c->n_ann -= 1;
 }
 
@@ -311,12 +334,12 @@ int run_trim(het_cache *c, int first_stage)
     tp.ev_ids = c->ev_ids[fill];
     tp.push_seq = ++c->trim_seq;
     if (c->trim_seq == 0xFFFFFFFFu) c->trim_seq = 0;        // 0 means "none"; a wrap is harmless (see HostLink::pend)
-    const SortStage ride = next_ride(c);
+    const Rides ride = next_rides(c);
     const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
-    if (ride.blocks)
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true><<<ride.blocks + ev_blocks, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride));
+    if (ride.blocks())
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true><<<ride.blocks() + ev_blocks, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
     else
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false><<<ev_blocks, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride));
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false><<<ev_blocks, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride.a, ride.b));
     c->tf_last = fill;
     if (c->location == HET_BACKING_PINNED_HOST) { c->push_pending = true; c->push_buf = fill; c->push_seq = tp.push_seq; }
     c->overflow_pending = false;
@@ -354,14 +377,14 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         LAUNCH(c, K_PROBE, direct_probe_kernel<true><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now));
         if (offsets)
             LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
-        const SortStage ride = next_ride(c);
-        const uint32_t grid = ride.blocks + row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
+        const Rides ride = next_rides(c);
+        const uint32_t grid = ride.blocks() + row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
         const uint32_t lds = lds_bytes(std::max(sizeof(FillLds), sizeof(TrimLds)), ride);
         const TrimPlan none{};
 #define GATHER_ONLY(POOLED, RIDE)                                                                                        \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<grid, 256, lds, c->stream>>>(                          \
-                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride, 0u, 0, 0u))
-        const int kind = !ride.blocks ? 0 : ((ride.stage & 1) ? 2 : 1);
+                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u))
+        const int kind = ride.kind();
         if (!offsets) { if (kind == 0) GATHER_ONLY(false, 0); else if (kind == 1) GATHER_ONLY(false, 1); else GATHER_ONLY(false, 2); }
         else { if (kind == 0) GATHER_ONLY(true, 0); else if (kind == 1) GATHER_ONLY(true, 1); else GATHER_ONLY(true, 2); }
 #undef GATHER_ONLY
@@ -383,11 +406,11 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const uint32_t lds_own = (uint32_t)std::max(sizeof(FillLds), sizeof(TrimLds));
 #define FILL_GATHER(POOLED, RIDE, GRID, FILLB, HISTB, PUSHB)                                                              \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>(     \
-                                 c->cv, c->ws, n, t_now, ptiles, FILLB, tp, HISTB, out, offsets, n_bags, c->inv, ride,     \
+                                 c->cv, c->ws, n, t_now, ptiles, FILLB, tp, HISTB, out, offsets, n_bags, c->inv, ride.a, ride.b, \
                                  PUSHB, c->push_buf, c->push_seq))
 #define FILL_GATHER_ANY(GRID, FILLB, HISTB, PUSHB)                                                                        \
     do {                                                                                                                  \
-        const int kind = !ride.blocks ? 0 : ((ride.stage & 1) ? 2 : 1);                                                   \
+        const int kind = ride.kind();                                                                                     \
         if (!offsets) {                                                                                                   \
             if (kind == 0) FILL_GATHER(false, 0, GRID, FILLB, HISTB, PUSHB);                                              \
             else if (kind == 1) FILL_GATHER(false, 1, GRID, FILLB, HISTB, PUSHB);                                         \
@@ -401,21 +424,21 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const uint32_t gather_blocks = row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
     if (c->location == HET_BACKING_HBM) {
         // one kernel: the gather reads a missed key's row from the global table, beside the fetch
-        const SortStage ride = next_ride(c);
-        FILL_GATHER_ANY(ride.blocks + fill_blocks + hist_blocks + gather_blocks, fill_blocks, hist_blocks, 0u);
+        const Rides ride = next_rides(c);
+        FILL_GATHER_ANY(ride.blocks() + fill_blocks + hist_blocks + gather_blocks, fill_blocks, hist_blocks, 0u);
     } else {
         // Host-backed table: the fetches come over the host link, and the last trim's write-back
         // goes the other way in the same kernel; the gather follows and reads the cached copies.
         const uint32_t push_blocks = c->push_pending ? PUSH_BLOCKS : 0u;
         const uint32_t fetch_blocks = std::min(fill_blocks, PUSH_BLOCKS);
         {
-            const SortStage ride = next_ride(c);
-            FILL_GATHER_ANY(ride.blocks + push_blocks + fetch_blocks + hist_blocks, fetch_blocks, hist_blocks, push_blocks);
+            const Rides ride = next_rides(c);
+            FILL_GATHER_ANY(ride.blocks() + push_blocks + fetch_blocks + hist_blocks, fetch_blocks, hist_blocks, push_blocks);
         }
         c->push_pending = false;
         {
-            const SortStage ride = next_ride(c);
-            FILL_GATHER_ANY(ride.blocks + gather_blocks, 0u, 0u, 0u);
+            const Rides ride = next_rides(c);
+            FILL_GATHER_ANY(ride.blocks() + gather_blocks, 0u, 0u, 0u);
         }
     }
 #undef FILL_GATHER_ANY
@@ -442,15 +465,15 @@ int launch_apply_chunk(het_cache *c, bool verify, const int64_t *ids, uint32_t n
     const int stage1 = trim && next <= tp.passes ? next++ : -1;
     const uint32_t extra0 = stage0 >= 0 ? stage_blocks(c, tp, stage0) : 0u;
     const uint32_t extra1 = stage1 >= 0 ? stage_blocks(c, tp, stage1) : 0u;
-    const SortStage ride0 = next_ride(c);
+    const Rides ride0 = next_rides(c);
     const uint32_t lds0 = lds_bytes(sizeof(TrimLds), ride0);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, CHUNK><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, CHUNK><<<ride0.blocks() + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, CHUNK><<<ride0.blocks + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0));
-    const SortStage ride1 = next_ride(c);
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, CHUNK><<<ride0.blocks() + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
+    const Rides ride1 = next_rides(c);
     const uint32_t lds1 = lds_bytes(std::max(sizeof(TrimLds), sizeof(FinishLds<VEC>)), ride1);
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC, CHUNK><<<ride1.blocks + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, stage1, ride1));
+    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC, CHUNK><<<ride1.blocks() + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, stage1, ride1.a, ride1.b));
     return next;
 }
 
@@ -670,7 +693,7 @@ int het_prefetch(het_cache *c, const int64_t *ids, int64_t n)
     if (!ids) return HET_EINVAL;
     // Nothing is launched here: the kernels of the calls that follow carry the sort, stage by
     // stage, into a buffer set that neither the current order nor an earlier announcement uses.
-    // With both spare sets taken, the oldest announcement makes room.
+    // With every spare set taken, the oldest announcement makes room.
     if (c->n_ann && c->ann[c->n_ann - 1].ids == ids && c->ann[c->n_ann - 1].n == (uint32_t)n) return HET_OK;   // said already
     if (c->n_ann == SORT_SETS - 1) drop_oldest_announcement(c);
     for (int set = 0; set < SORT_SETS; ++set) {

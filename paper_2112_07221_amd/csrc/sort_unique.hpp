@@ -1,14 +1,16 @@
 // Dedup of a minibatch's ids: the "unique embedding key set" of Algorithm 1 of the paper.
 //
 // A stable least-significant-digit radix sort of (id, position) pairs over just the bits the
-// vocabulary needs, in one to three passes of up to 11 bits.  The result is
+// vocabulary needs, in one to four passes of up to 8 bits.  The result is
 //   skey[j], perm[j]   ids ascending with the original position of each; equal ids keep their
 //                      original order, so a key's occurrences come in increasing position.
 // A run of equal keys in skey is one unique key; its first position is the key's "head".
 // Ids outside [0, vocab) get the key `vocab`, which sorts behind every valid id.
 //
 // The sort is a sequence of stages, two per pass: a histogram stage counts the pass's digit per
-// tile of 4096 keys, a scatter stage moves the keys.  Every workgroup of a scatter stage derives
+// tile of 1024 keys, a scatter stage moves the keys.  Narrow digits and small tiles keep every
+// stage a few microseconds long (the ranking of a key costs one ballot per digit bit, and a
+// workgroup ranks its keys one after the other), which is what lets other kernels carry them.  Every workgroup of a scatter stage derives
 // its output offsets itself from the per-tile histograms ("count at the producer, prefix at the
 // consumer"); no workgroup ever waits for another one, and nothing is counted with global
 // atomics (a popular id would make hundreds of them hit one address).
@@ -25,20 +27,20 @@ namespace het {
 
 constexpr int SORT_THREADS = 256;
 constexpr int SORT_WAVES = SORT_THREADS / WAVE;
-constexpr int SORT_ITEMS = 16;
+constexpr int SORT_ITEMS = 4;
 constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS;     // keys per workgroup
 constexpr int SORT_MIN_BITS = 3;                         // a histogram row is read 8 digits at a time
-constexpr int SORT_MAX_BITS = 11;
+constexpr int SORT_MAX_BITS = 8;
 constexpr int SORT_MAX_BINS = 1 << SORT_MAX_BITS;
-constexpr int SORT_MAX_PASSES = 3;                       // vocab < 2^32
+constexpr int SORT_MAX_PASSES = 4;                       // vocab < 2^32
 constexpr int SORT_BINS_PER_THREAD = SORT_MAX_BINS / SORT_THREADS;
 
 struct SortPlan {
     uint32_t n;            // keys
     uint32_t vocab;
     uint32_t ntiles;       // ceil(n / SORT_TILE)
-    int passes;            // 1..3
-    int width;             // bits per digit (3..11)
+    int passes;            // 1..4
+    int width;             // bits per digit (3..8)
     uint32_t *hist;        // [ntiles][bins / 2]: the current pass's digit counts per tile, two 16-bit counts per word
 };
 
@@ -103,7 +105,7 @@ __device__ __forceinline__ void sort_hist_body(const SortStage &s, uint32_t tile
     }
     __syncthreads();
     for (uint32_t w = threadIdx.x; w < bins / 2; w += SORT_THREADS)
-        sp.hist[(size_t)tile * (bins / 2) + w] = lds[2 * w] | (lds[2 * w + 1] << 16);     // a tile has 4096 keys: counts fit 16 bits
+        sp.hist[(size_t)tile * (bins / 2) + w] = lds[2 * w] | (lds[2 * w + 1] << 16);     // a tile has 1024 keys: counts fit 16 bits
 }
 
 // Scatter stage of pass p for one tile: stable.  lds: (SORT_WAVES + 1) * bins words + 16.

@@ -127,7 +127,7 @@ class Pair:
 def run_workload(w: wl.Workload, iters: int, state_every: int = 1, table=None, ids=None, grads=None,
                  values_every: int = 0, prefetch=False):
     """Runs `iters` lookup+update iterations of workload `w` on both sides.  With `prefetch` the
-    ids of iteration t+1 are announced before lookup t (prefetch="before", as the benchmark
+    ids of iteration t+2 are announced before lookup t (prefetch="before", as the benchmark
     does), between lookup t and update t (prefetch=True or "between") or after update t
     (prefetch="after")."""
     table = wl.table_init(w) if table is None else table
@@ -137,8 +137,11 @@ def run_workload(w: wl.Workload, iters: int, state_every: int = 1, table=None, i
     try:
         ids_dev = torch.from_numpy(ids).to(p.dev) if prefetch else None
         for t in range(iters):
-            if prefetch == "before" and t + 1 < iters:
-                p.cache.prefetch(ids_dev[t + 1])
+            if prefetch == "before":        # two batches ahead, as the benchmark does
+                if t == 0 and iters > 1:
+                    p.cache.prefetch(ids_dev[1])
+                if t + 2 < iters:
+                    p.cache.prefetch(ids_dev[t + 2])
             p.lookup(ids[t], ids_dev=ids_dev[t] if prefetch else None)
             if prefetch and prefetch not in ("after", "before") and t + 1 < iters:
                 p.cache.prefetch(ids_dev[t + 1])
