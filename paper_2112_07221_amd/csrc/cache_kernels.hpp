@@ -275,22 +275,27 @@ __device__ __forceinline__ void block_sum8(uint32_t (&v)[8], uint32_t *lds)
     }
 }
 
-// Last stage of the select: finds tau (replaying the passes) and counts, per block of 1024
-// slots, the cached rows whose policy key lies below tau and those whose key equals it, and how
-// many of each hold updates; sup_cnt adds these up per EV_SUPER blocks (zero when the select
-// starts).  With these counts the eviction places every victim by arithmetic alone (count at
-// the producer, prefix at the consumer).  One workgroup per 1024 slots, four consecutive slots
-// per thread.
-constexpr int EV_ITEMS = 4;
+// Last stage of the select: finds tau (replaying the passes) and counts, per block of EV_SLOTS
+// slots (the eviction's workgroups), the cached rows whose policy key lies below tau and those
+// whose key equals it, and how many of each hold updates; sup_cnt adds these up per EV_SUPER
+// blocks (zero when the select starts).  With these counts the eviction places every victim by
+// arithmetic alone (count at the producer, prefix at the consumer).  A workgroup of the count
+// covers COUNT_SLOTS slots, a wave of it one block of EV_SLOTS (the replay is paid once per
+// workgroup, so the count uses few, the eviction many).
+constexpr int EV_ITEMS = 1;
 constexpr int EV_SLOTS = TRIM_THREADS * EV_ITEMS;
 constexpr int EV_SUPER = 32;
-static_assert(EV_SLOTS == TRIM_TILE, "one eviction workgroup per free-list tile");
+constexpr int COUNT_ITEMS = EV_SLOTS / WAVE;                   // consecutive slots per lane: a wave covers EV_SLOTS
+constexpr int COUNT_SLOTS = TRIM_THREADS * COUNT_ITEMS;
+static_assert(TRIM_TILE % EV_SLOTS == 0, "eviction workgroups do not straddle free-list tiles");
+static_assert(EV_SLOTS % WAVE == 0, "a wave of the count covers one eviction block");
 
-// The four slots of a thread: keys (KEY_NONE beyond the end) and metadata.
-__device__ __forceinline__ void load_slots4(const CacheView &cv, uint32_t slot0, uint32_t (&key)[EV_ITEMS], uint4 (&meta)[EV_ITEMS])
+// The slots of a thread: keys (KEY_NONE beyond the end) and metadata.
+template <int ITEMS>
+__device__ __forceinline__ void load_slots(const CacheView &cv, uint32_t slot0, uint32_t (&key)[ITEMS], uint4 (&meta)[ITEMS])
 {
 #pragma unroll
-    for (int i = 0; i < EV_ITEMS; ++i) {
+    for (int i = 0; i < ITEMS; ++i) {
         const bool in = slot0 + i < cv.n_slots;
         key[i] = in ? cv.slot_key[slot0 + i] : KEY_NONE;
         meta[i] = in ? load_meta(cv.meta, slot0 + i) : make_uint4(0, 0, 0, 0);
@@ -302,33 +307,34 @@ __device__ __forceinline__ void trim_count_body(const CacheView &cv, const TrimP
     const int32_t over = cv.ds->size - (int32_t)cv.capacity;
     if (vblock == 0 && threadIdx.x == 0) cv.ds->over = over;
     if (over <= 0) return;
-    uint32_t key[EV_ITEMS];
-    uint4 meta[EV_ITEMS];
-    load_slots4(cv, vblock * EV_SLOTS + threadIdx.x * EV_ITEMS, key, meta);      // loads first: they overlap the replay
+    uint32_t key[COUNT_ITEMS];
+    uint4 meta[COUNT_ITEMS];
+    load_slots<COUNT_ITEMS>(cv, vblock * COUNT_SLOTS + threadIdx.x * COUNT_ITEMS, key, meta);      // loads first: they overlap the replay
     uint64_t tau; uint32_t take_eq;
     sel_replay(tp, tp.passes, (uint32_t)over, tau, take_eq, l.pick, l.scan);
     uint32_t lt = 0, eq = 0, dlt = 0, deq = 0;
 #pragma unroll
-    for (int i = 0; i < EV_ITEMS; ++i) {
+    for (int i = 0; i < COUNT_ITEMS; ++i) {
         const bool cached = key[i] != KEY_NONE;
         const uint64_t pk = policy_key(tp, meta[i]);
         const bool dirty = meta[i].y > meta[i].x;
         if (cached && pk < tau) { lt += 1; dlt += dirty; }
         else if (cached && pk == tau) { eq += 1; deq += dirty; }
     }
-    // counts of a block stay below 2^16: two to a word
-    const uint32_t a = block_sum<TRIM_WAVES>(lt | (eq << 16), l.scan);
-    const uint32_t b = block_sum<TRIM_WAVES>(dlt | (deq << 16), l.scan);
-    if (threadIdx.x == 0) {
+    // counts of an eviction block stay below 2^16: two to a word
+    const uint32_t a = wave_sum(lt | (eq << 16));
+    const uint32_t b = wave_sum(dlt | (deq << 16));
+    const uint32_t eblk = vblock * TRIM_WAVES + threadIdx.x / WAVE;               // the eviction block this wave covered
+    if (lane_id() == 0 && eblk * EV_SLOTS < cv.n_slots) {
         const uint4 c = make_uint4(a & 0xFFFFu, a >> 16, b & 0xFFFFu, b >> 16);
-        tp.blk_cnt[vblock] = c;
-        uint32_t *sup = reinterpret_cast<uint32_t *>(&tp.sup_cnt[vblock / EV_SUPER]);
+        tp.blk_cnt[eblk] = c;
+        uint32_t *sup = reinterpret_cast<uint32_t *>(&tp.sup_cnt[eblk / EV_SUPER]);
         if (c.x) atomicAdd(&sup[0], c.x);
         if (c.y) atomicAdd(&sup[1], c.y);
         if (c.z) atomicAdd(&sup[2], c.z);
         if (c.w) atomicAdd(&sup[3], c.w);
-        if (vblock == 0) { cv.ds->sel_tau = tau; cv.ds->sel_take = take_eq; }
     }
+    if (vblock == 0 && threadIdx.x == 0) { cv.ds->sel_tau = tau; cv.ds->sel_take = take_eq; }
 }
 
 // Stage `stage` of the select: the histogram passes first, then the count.  Kernels that have
@@ -806,10 +812,12 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
     if (run_carried(ride, ride2, bid, nblk)) return;
-    if (bid >= work_blocks) {            // extra workgroups: a stage of the coming trim's select
-        trim_stage_body(cv, tp, stage, bid - work_blocks, nblk - work_blocks, lds_as<TrimLds>());
+    const uint32_t stage_blocks = nblk - work_blocks;
+    if (bid < stage_blocks) {            // extra workgroups (ahead of the others: their chain of steps is long): a stage of the coming trim's select
+        trim_stage_body(cv, tp, stage, bid, stage_blocks, lds_as<TrimLds>());
         return;
     }
+    bid -= stage_blocks;
     const RowGeom g = cv.geom;
     const uint32_t gid = (bid * 256u + threadIdx.x) / g.lanes;
     const int gl = threadIdx.x % g.lanes;
@@ -995,10 +1003,12 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
 {
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
     if (run_carried(ride, ride2, bid, nblk)) return;
-    if (bid >= work_blocks) {            // extra workgroups: the next stage of the trim's select
-        trim_stage_body(cv, tp, stage, bid - work_blocks, nblk - work_blocks, lds_as<TrimLds>());
+    const uint32_t stage_blocks = nblk - work_blocks;
+    if (bid < stage_blocks) {            // extra workgroups, ahead of the others: the next stage of the trim's select
+        trim_stage_body(cv, tp, stage, bid, stage_blocks, lds_as<TrimLds>());
         return;
     }
+    bid -= stage_blocks;
     FinishLds<VEC> &fl = lds_as<FinishLds<VEC>>();
     uint32_t *long_c = fl.long_c, *long_c1 = fl.long_c1;
     int32_t *long_slot = fl.long_slot;
@@ -1139,7 +1149,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     const uint32_t take_eq = ds->sel_take;
     uint32_t key[EV_ITEMS];
     uint4 meta[EV_ITEMS];
-    load_slots4(cv, slot0, key, meta);
+    load_slots<EV_ITEMS>(cv, slot0, key, meta);
     // counts over the blocks before this one (whole supers, then the blocks of this super), and over all blocks
     uint32_t c8[8] = {0, 0, 0, 0, 0, 0, 0, 0};         // before: lt, eq, dirty lt, dirty eq;  all: dirty lt
     {
@@ -1271,7 +1281,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
         }
     }
     if (threadIdx.x == 0) {
-        tp.tile_free[blk] = free_here + nv;
+        if (free_here + nv) atomicAdd(&tp.tile_free[blk / (TRIM_TILE / EV_SLOTS)], free_here + nv);     // (zero when the trim starts; a few workgroups per tile)
         // the call's counters: written by the block that holds the last tied victim (block 0 if there is none)
         const bool closes = over <= 0 ? blk == 0
                           : (take_eq == 0 ? blk == 0 : (eq_before < take_eq && take_eq <= eq_before + eq_here));

@@ -305,7 +305,7 @@ TrimPlan make_trim_plan(const het_cache *c)
 uint32_t stage_blocks(const het_cache *c, const TrimPlan &tp, int stage)
 {
     if (stage < tp.passes) return std::min(cdiv(c->cv.n_slots, TRIM_TILE), 1024u);
-    return cdiv(c->cv.n_slots, EV_SLOTS);
+    return cdiv(c->cv.n_slots, COUNT_SLOTS);
 }
 
 constexpr uint32_t PUSH_BLOCKS = 256;      // few workgroups keep the host link full; more only contend
@@ -400,7 +400,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     c->sel_tp = make_trim_plan(c);
     const TrimPlan &tp = c->sel_tp;
     const uint32_t hist_blocks = stage_blocks(c, tp, 0);       // stage 0 of the select rides with the fetches
-    const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 1024u);     // they come first: theirs is the longer chain
+    const uint32_t fill_blocks = std::min(row_grid(c->cv.geom, n), 2048u);     // they come first: theirs is the longer chain
     if (offsets)
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
     const uint32_t lds_own = (uint32_t)std::max(sizeof(FillLds), sizeof(TrimLds));
