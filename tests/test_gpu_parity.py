@@ -113,6 +113,29 @@ def test_config3_pinned_host_backing_reduced():
     run_workload(w, 16, state_every=4, values_every=8)
 
 
+def test_announcements_far_ahead_out_of_order_and_too_many():
+    """Up to three batches stand announced; a fourth replaces the oldest; lookups may come in another
+    order than the announcements, or with ids never announced.  Nothing of it changes a result."""
+    w = wl.WORKLOADS[1].scaled(vocab=100_000, batch=300, capacity=2_000, s=1, policy=wl.LFU)   # 17-bit ids: three passes
+    ids_np = wl.IdStream(w).batches(10)
+    g = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        d = torch.from_numpy(ids_np).cuda()
+        for t in (1, 2, 3, 4):                      # four announcements: the one for batch 1 is dropped
+            p.cache.prefetch(d[t])
+        order = [0, 1, 3, 2, 4, 5]                  # 0 never announced, 1 dropped, 3 before 2 (which voids 2's announcement)
+        for i, t in enumerate(order):
+            if t == 4:
+                p.cache.prefetch(d[5])
+            p.lookup(ids_np[t], ids_dev=d[t])
+            p.update(ids_np[t], g[i % len(g)], ids_dev=d[t])
+            p.compare_state(values=True); p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 @pytest.mark.parametrize("policy,opt", [(wl.LRU, wl.SGD), (wl.LFU, wl.ADAGRAD)])
 def test_host_backed_table_rows_evicted_and_fetched_again_at_once(policy, opt):
     """A small vocabulary behind a small cache in pinned host memory: keys evicted by one update are
