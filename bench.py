@@ -62,6 +62,58 @@ def kernel_bytes(w, c, name):
     return None
 
 
+def policy_study(args, w, dev):
+    """Miss rate against cache size and policy (Section 5.2, Figure 8) on the synthetic stream of
+    config `w`: one JSON line with a row per (size, policy)."""
+    import torch
+    from paper_2112_07221_amd import hetcache as hc
+    from paper_2112_07221_amd import workloads as wl
+    W, K = args.warmup, args.steps
+    ids = torch.from_numpy(wl.IdStream(w).batches(W + K)).to(dev)
+    grads = torch.from_numpy(wl.grad_pool(w)).to(dev)
+    out = torch.empty(w.n_grad_rows, w.dim, device=dev)
+    offsets = torch.from_numpy(wl.bag_offsets(w)).to(dev) if w.pooled else None
+    table = wl.table_init(w)
+    rows = []
+    for frac in (0.03, 0.05, 0.10, 0.15):
+        for policy, pname in ((wl.LRU, "LRU"), (wl.LFU, "LFU")):
+            Wt = torch.from_numpy(table).to(dev)
+            At = torch.zeros_like(Wt) if w.optimizer else None
+            Cg = torch.zeros(w.vocab, dtype=torch.int32, device=dev)
+            cache = hc.HetCache(int(w.vocab * frac), w.dim, w.s, policy, w.n, w.optimizer, w.eps)
+            cache.attach_backing(Wt, At, Cg, hc.BACKING_HBM)
+
+            def step(t):
+                if t == 0 and W + K > 1:
+                    cache.prefetch(ids[1])
+                if t + 2 < W + K:
+                    cache.prefetch(ids[t + 2])
+                if w.pooled:
+                    cache.lookup_pooled(ids[t], offsets, out)
+                    cache.update_pooled(ids[t], offsets, grads[t % w.grad_pool], w.lr)
+                else:
+                    cache.lookup(ids[t], out)
+                    cache.update(ids[t], grads[t % w.grad_pool], w.lr)
+            for t in range(W):
+                step(t)
+            before = cache.stats()["total"]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for t in range(W, W + K):
+                step(t)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / K
+            tot = cache.stats()["total"]
+            miss = tot["miss"] - before["miss"]
+            uniq = (tot["unique"] - before["unique"]) / 2.0
+            rows.append({"cache_frac": frac, "policy": pname, "miss_rate_per_unique": miss / uniq,
+                         "miss_rate_per_lookup": miss / (K * w.n), "ms_per_step": ms})
+            cache.close()
+            del Wt, At, Cg
+    print(json.dumps({"study": "miss rate against cache size and policy", "config": w.index, "steps": K, "warmup": W,
+                      "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +130,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy five times (a known-size reference for HBM counters)")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0 = auto)")
+    ap.add_argument("--policy-study", action="store_true",
+                    help="instead of the benchmark: miss rate and step time of the chosen config for cache sizes of "
+                         "3, 5, 10 and 15 %% of the vocabulary under LRU and LFU (the experiment of the paper's Figure 8)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -90,6 +145,9 @@ def main():
 
     w = wl.WORKLOADS[args.config]
     dev = torch.device("cuda:0")
+    if args.policy_study:
+        policy_study(args, w, dev)
+        return
     K, W = args.steps, args.warmup
     total = W + K + args.profile_steps
 
