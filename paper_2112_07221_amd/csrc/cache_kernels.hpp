@@ -77,6 +77,7 @@ constexpr int32_t SRC_ZERO = -2;      // id outside the vocabulary: the output r
 constexpr int PT_THREADS = 1024;                // probe tiles: 1024 sorted positions per workgroup,
 constexpr int PT_WAVES = PT_THREADS / WAVE;     // one per thread, so every probe's loads are in flight at once
 constexpr int PT_TILE = PT_THREADS;
+constexpr int VERIFY_TILE = 1024;                    // positions one workgroup of the id check covers
 constexpr int CHUNK_SHORT = 4, CHUNK_LONG = 8;       // sorted positions per row group in the apply kernel (template parameter CHUNK):
                                                      // four keep the kernel's registers low; eight halve the partial sums of very long runs
 
@@ -801,7 +802,7 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // crosses a chunk border leaves one partial sum per chunk for the second kernel; the chunk in
 // which it starts also leaves the run's slot in cross_slot.
 // VERIFY: the ids must be the ones the sorted order was built from (an update that reuses the
-// preceding lookup's order); a position whose id differs is skipped and flagged.
+// preceding lookup's order); extra workgroups compare them and flag any difference.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
 template <int VEC, int MAXC, bool VERIFY, int CHUNK>
 __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, const int64_t *__restrict__ ids,
@@ -812,12 +813,28 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
     if (run_carried(ride, ride2, bid, nblk)) return;
-    const uint32_t stage_blocks = nblk - work_blocks;
+    const uint32_t verify_blocks = VERIFY ? (n_ids + VERIFY_TILE - 1) / VERIFY_TILE : 0u;
+    const uint32_t stage_blocks = nblk - work_blocks - verify_blocks;
     if (bid < stage_blocks) {            // extra workgroups (ahead of the others: their chain of steps is long): a stage of the coming trim's select
         trim_stage_body(cv, tp, stage, bid, stage_blocks, lds_as<TrimLds>());
         return;
     }
     bid -= stage_blocks;
+    if (VERIFY && bid < verify_blocks) {
+        // The ids must be the ones the sorted order was built from: every position's id against the
+        // sorted key, by workgroups of their own (in the row groups the check cost registers, and
+        // with them a fifth of the kernel's occupancy).  A difference is flagged; the update goes on.
+        const uint32_t nvv = cv.ds->n_valid;
+        bool bad = false;
+#pragma unroll
+        for (int i = 0; i < VERIFY_TILE / 256; ++i) {
+            const uint32_t j = bid * VERIFY_TILE + i * 256u + threadIdx.x;
+            if (j < nvv) bad |= ids[ws.perm[j]] != (int64_t)ws.skey[j];
+        }
+        if (__any(bad) && lane_id() == 0) atomicOr(&cv.ds->err, ERRBIT_STATE);
+        return;
+    }
+    bid -= verify_blocks;
     const RowGeom g = cv.geom;
     const uint32_t gid = (bid * 256u + threadIdx.x) / g.lanes;
     const int gl = threadIdx.x % g.lanes;
@@ -862,24 +879,8 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         const bool open_front = prev_key == k[0];           // the first run began in an earlier chunk
         const bool open_back = next_key == last_key;        // the last run goes on in a later chunk
 
-        // VERIFY: the caller's id at every position, requested here and looked at only after the
-        // gradient rows have been requested too (the check is not a step of its own on the way)
-        // (With eight positions per group the registers for that are not there: the ids are
-        // compared before the gradient rows are requested.)
-        constexpr bool LATE_CHECK = VERIFY && CHUNK <= 4;
-        constexpr int NIDV = LATE_CHECK ? CHUNK : 1;
-        int64_t idv[NIDV];
         const uint32_t inm = (1u << cnt) - 1u;
-        uint32_t use = inm, heads = 0, whole = 0;           // bit i: gradient counts / run head / head of a run inside the chunk
-        if (LATE_CHECK) {
-#pragma unroll
-            for (int i = 0; i < NIDV; ++i) idv[i] = (uint32_t)i < cnt ? ids[p[i]] : (int64_t)k[i];
-        } else if (VERIFY) {
-            use = 0;
-#pragma unroll
-            for (int i = 0; i < CHUNK; ++i) use |= ((uint32_t)i < cnt && ids[p[i]] == (int64_t)k[i]) ? (1u << i) : 0u;
-            if (gl == 0 && use != inm) atomicOr(&cv.ds->err, ERRBIT_STATE);
-        }
+        uint32_t heads = 0, whole = 0;                      // bit i: run head / head of a run inside the chunk
 #pragma unroll
         for (int i = 0; i < CHUNK; ++i) {
             const bool in = (uint32_t)i < cnt;
@@ -914,21 +915,11 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
                 v[i] = V{}; xr[i] = V{}; ar[i] = V{}; ccv[i] = 0;
                 if (q == 0 && i == 0 && cross != SLOT_NONE && !cv.direct) cross_cc = cv.meta[cross].cc;       // (lane 0 only)
                 if (q == 0 && gl == 0 && ((whole >> i) & 1u) && !cv.direct) ccv[i] = cv.meta[hs[i]].cc;
-                if (act && (((LATE_CHECK ? inm : use) >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
+                if (act && ((inm >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
                 if (act && ((whole >> i) & 1u)) {
                     xr[i] = reinterpret_cast<const V *>(cv.rows + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
                     if (cv.adagrad) ar[i] = reinterpret_cast<const V *>(cv.acc + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
                 }
-            }
-            if (LATE_CHECK) {
-                if (q == 0) {
-                    use = 0;
-#pragma unroll
-                    for (int i = 0; i < NIDV; ++i) use |= (((inm >> i) & 1u) && idv[i] == (int64_t)k[i]) ? (1u << i) : 0u;
-                    if (gl == 0 && use != inm) atomicOr(&cv.ds->err, ERRBIT_STATE);
-                }
-#pragma unroll
-                for (int i = 0; i < CHUNK; ++i) if (!((use >> i) & 1u)) v[i] = V{};     // a position whose id changed does not count
             }
             double acc64[VEC];
             V cur_x{}, cur_a{};

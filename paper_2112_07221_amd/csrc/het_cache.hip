@@ -468,7 +468,7 @@ int launch_apply_chunk(het_cache *c, bool verify, const int64_t *ids, uint32_t n
     const Rides ride0 = next_rides(c);
     const uint32_t lds0 = lds_bytes(sizeof(TrimLds), ride0);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, CHUNK><<<ride0.blocks() + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, CHUNK><<<ride0.blocks() + grid + extra0 + cdiv(n, VERIFY_TILE), 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
     else
         LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, CHUNK><<<ride0.blocks() + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
     const Rides ride1 = next_rides(c);
