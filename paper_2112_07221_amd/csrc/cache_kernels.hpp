@@ -1077,17 +1077,17 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
                 double sum[VEC];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
-                for (uint32_t i0 = lo; i0 < hi; i0 += 8) {
-                    double part[8][VEC];
+                for (uint32_t i0 = lo; i0 < hi; i0 += 4) {
+                    double part[4][VEC];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
+                    for (int u = 0; u < 4; ++u) {
                         const uint32_t i = i0 + u;
                         const double *pp = ws.partial + ((size_t)(lc + i) * 2 + (i == 0 ? 1 : 0)) * pstride + (size_t)cidx * VEC;
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) part[u][e] = (act && i < hi) ? pp[e] : 0.0;
                     }
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
+                    for (int u = 0; u < 4; ++u)
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
                 }

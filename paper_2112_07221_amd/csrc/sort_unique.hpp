@@ -136,16 +136,16 @@ __device__ __forceinline__ void sort_scatter_body(const SortStage &s, uint32_t t
             uint32_t t8[8], f8[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) { t8[e] = 0; f8[e] = 0; }
-            // eight tiles at a time, every load issued before the first add
-            for (uint32_t t0 = tl; t0 < sp.ntiles; t0 += 8 * tln) {
-                uint4 v[8];
+            // four tiles at a time (more would cost the carrying kernels occupancy), every load issued before the first add
+            for (uint32_t t0 = tl; t0 < sp.ntiles; t0 += 4 * tln) {
+                uint4 v[4];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 4; ++u) {
                     const uint32_t t = t0 + u * tln;
                     v[u] = t < sp.ntiles ? h4[(size_t)t * octs + bo] : make_uint4(0, 0, 0, 0);
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 4; ++u) {
                     const uint32_t t = t0 + u * tln;
                     const uint32_t c[8] = {v[u].x & 0xFFFFu, v[u].x >> 16, v[u].y & 0xFFFFu, v[u].y >> 16,
                                            v[u].z & 0xFFFFu, v[u].z >> 16, v[u].w & 0xFFFFu, v[u].w >> 16};
