@@ -977,16 +977,17 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 // Second kernel of Write: finishes the runs that cross chunk borders.  The group of the chunk
 // in which such a run starts adds the run's partial sums in chunk order and applies the step
 // (the run's clock was advanced by the first kernel).
-// A run spread over more than FIN_NEAR + 1 chunks (a very popular key) is summed by the whole
-// workgroup instead: every group adds a contiguous share of the partial sums in order, and the
-// shares are added in group order.  Either way the order of additions is fixed by the sorted
+// A run spread over more than FIN_NEAR + 1 chunks (a popular key) is summed by a wave, and one
+// over more than FIN_WAVE chunks by the whole workgroup: every group adds a contiguous share of
+// the partial sums in order, and the shares are added in group order.  Either way the order of additions is fixed by the sorted
 // order alone.
 constexpr int FIN_NEAR = 4;
+constexpr int FIN_WAVE = 48;        // partial sums up to which one wave finishes a run
 template <int VEC> struct FinishLds {
     double share[256 * VEC];
-    uint32_t long_c[256], long_c1[256];
-    int32_t long_slot[256];
-    uint32_t n_long;
+    uint32_t long_c[256], long_c1[256], mid_c[256], mid_c1[256];
+    int32_t long_slot[256], mid_slot[256];
+    uint32_t n_long, n_mid;
 };
 template <int VEC, int MAXC, int CHUNK>
 __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
@@ -1013,7 +1014,7 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
     const uint32_t nchunks_max = (n_ids + CHUNK - 1) / CHUNK;
     const uint32_t *skey = ws.skey;
     const size_t pstride = (size_t)g.dim;
-    if (threadIdx.x == 0) n_long = 0;
+    if (threadIdx.x == 0) { n_long = 0; fl.n_mid = 0; }
     __syncthreads();
 
     for (uint32_t base = bid * groups_per_block; base < nchunks_max; base += work_blocks * groups_per_block) {
@@ -1035,9 +1036,15 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
             open = open && (jb + (d + 1) * CHUNK < nv) && nxt[d] == key;
             if (open) c1 = c + 2 + d;
         }
-        if (open) {                                                // reaches past the near chunks: a long run
-            c1 = (run_end(skey, jb + FIN_NEAR * CHUNK, nv, key) - 1) / CHUNK;
-            if (gl == 0) { const uint32_t at = atomicAdd(&n_long, 1u); long_c[at] = c; long_c1[at] = c1; long_slot[at] = slot; }
+        // where a run that reaches past the near chunks ends (all lanes of the wave take part in the search)
+        const uint32_t far_end = g.lanes >= 4 ? group_run_end(skey, jb + FIN_NEAR * CHUNK, nv, key, open, g.lanes)
+                                              : (open ? run_end(skey, jb + FIN_NEAR * CHUNK, nv, key) : 0u);
+        if (open) {                                                // for a wave, or for the whole workgroup
+            c1 = (far_end - 1) / CHUNK;
+            if (gl == 0) {
+                if (c1 - c + 1 > FIN_WAVE) { const uint32_t at = atomicAdd(&n_long, 1u); long_c[at] = c; long_c1[at] = c1; long_slot[at] = slot; }
+                else { const uint32_t at = atomicAdd(&fl.n_mid, 1u); fl.mid_c[at] = c; fl.mid_c1[at] = c1; fl.mid_slot[at] = slot; }
+            }
         } else if (mine) {
 #pragma unroll
             for (int q = 0; q < MAXC; ++q) {
@@ -1063,8 +1070,49 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
             }
         }
         __syncthreads();
+        {   // runs of middling length: one per wave, the waves side by side.  The row groups of the
+            // wave add contiguous shares of the run's partial sums in order (four at a time), and the
+            // shares are added in group order, fetched from the other groups' lanes.
+            const uint32_t wave = threadIdx.x / WAVE, gpw = WAVE / g.lanes, gw = (threadIdx.x % WAVE) / g.lanes;
+            const uint32_t nm = fl.n_mid;
+            for (uint32_t mi = wave; mi < nm; mi += 256 / WAVE) {
+                const uint32_t mc = fl.mid_c[mi], m = fl.mid_c1[mi] - mc + 1;
+                const int32_t mslot = fl.mid_slot[mi];
+                const uint32_t per = (m + gpw - 1) / gpw;
+                const uint32_t lo = min(gw * per, m), hi = min(lo + per, m);
+#pragma unroll
+                for (int q = 0; q < MAXC; ++q) {
+                    const int cidx = gl + q * g.lanes;
+                    const bool act = cidx < g.chunks;
+                    double sum[VEC];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
+                    for (uint32_t i0 = lo; i0 < hi; i0 += 4) {
+                        double part[4][VEC];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const uint32_t i = i0 + u;
+                            const double *pp = ws.partial + ((size_t)(mc + i) * 2 + (i == 0 ? 1 : 0)) * pstride + (size_t)cidx * VEC;
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) part[u][e] = (act && i < hi) ? pp[e] : 0.0;
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
+                    }
+                    double tot[VEC];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) tot[e] = 0.0;
+                    for (uint32_t gi = 0; gi < gpw; ++gi)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) tot[e] += __shfl(sum[e], (int)(gi * g.lanes + gl), WAVE);
+                    if (gw == 0 && act) apply_step<VEC>(cv, (uint32_t)mslot, cidx, tot, lr, eps);
+                }
+            }
+        }
         const uint32_t nl = n_long;
-        for (uint32_t li = 0; li < nl; ++li) {                     // long runs, one at a time, whole workgroup
+        for (uint32_t li = 0; li < nl; ++li) {                     // very long runs, one at a time, whole workgroup
             const uint32_t lc = long_c[li], lc1 = long_c1[li];
             const int32_t lslot = long_slot[li];
             const uint32_t m = lc1 - lc + 1;                       // partial sums of the run
@@ -1107,7 +1155,7 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
             }
         }
         __syncthreads();
-        if (threadIdx.x == 0) n_long = 0;
+        if (threadIdx.x == 0) { n_long = 0; fl.n_mid = 0; }
         __syncthreads();
     }
 }

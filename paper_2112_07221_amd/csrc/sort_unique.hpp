@@ -294,4 +294,31 @@ __device__ __forceinline__ uint32_t run_end(const uint32_t *skey, uint32_t lo, u
     return lo;
 }
 
+// One past the last position of the run of `key` that is known to hold position lo - 1, found by
+// a row group of `lanes` lanes together: every lane looks at one position per round, the
+// spacing grows sixteenfold (by `lanes`) while all of them still hold the key and shrinks again
+// once they do not, so a run of a few hundred positions takes three rounds of one load each where
+// a binary search over the whole batch takes seventeen.  Called by every lane of the wave (a
+// group that has nothing to look for passes active = false); lanes is a power of two <= 64.
+__device__ __forceinline__ uint32_t group_run_end(const uint32_t *skey, uint32_t lo, uint32_t n, uint32_t key, bool active, int lanes)
+{
+    const uint32_t lane = lane_id(), gl = lane % (uint32_t)lanes;
+    const uint32_t shift = lane - gl;                                   // first lane of this group in the wave
+    const uint64_t gmask = lanes == 64 ? ~0ull : (((1ull << lanes) - 1ull) << shift);
+    uint32_t base = lo, step = 1;                                       // positions below base hold the key
+    bool going = active && lo < n;
+    while (__any(going)) {
+        const uint64_t idx = (uint64_t)base + (uint64_t)gl * step + (step - 1);      // the last position of the lane's stretch
+        const bool hit = going && idx < n && skey[idx] == key;
+        const uint32_t cnt = (uint32_t)__popcll(__ballot(hit) & gmask);   // hits are the first lanes: the keys are sorted
+        if (going) {
+            base += cnt * step;
+            if (cnt == (uint32_t)lanes && (uint64_t)base < n) step *= (uint32_t)lanes;        // all hold it: look further out
+            else if (step == 1 || (uint64_t)base >= n) going = false;                        // the end is exactly here
+            else step = step / (uint32_t)lanes > 0 ? step / (uint32_t)lanes : 1;             // it ends inside the next stretch: look closer
+        }
+    }
+    return base < n ? base : n;
+}
+
 } // namespace het
