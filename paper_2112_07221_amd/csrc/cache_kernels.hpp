@@ -444,13 +444,14 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
     if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
     if (LOOKUP) {
         // stage this tile's missed and stale keys, in key order, for the fill kernel
-        uint32_t tot_miss, tot_stale;
-        const uint32_t mo = block_excl_scan<PT_WAVES>(miss ? 1u : 0u, lds, tot_miss);
-        const uint32_t so = block_excl_scan<PT_WAVES>(stale ? 1u : 0u, lds, tot_stale);
+        // (a tile has 1024 positions: two counts to a word, one pass of barriers for each pair)
+        uint32_t tot_ms;
+        const uint32_t ms = block_excl_scan<PT_WAVES>((miss ? 1u : 0u) | (stale ? 1u << 16 : 0u), lds, tot_ms);
+        const uint32_t mo = ms & 0xFFFFu, so = ms >> 16, tot_miss = tot_ms & 0xFFFFu, tot_stale = tot_ms >> 16;
         if (miss) ws.miss_stage[tile * PT_TILE + mo] = make_uint2(j, ws.skey[j]);
         if (stale) ws.stale_stage[tile * PT_TILE + so] = make_uint2(j, ws.skey[j]);
-        const uint32_t tot_hit = block_sum<PT_WAVES>(hit ? 1u : 0u, lds);
-        const uint32_t tot_heads = block_sum<PT_WAVES>(head ? 1u : 0u, lds);
+        const uint32_t tot_hh = block_sum<PT_WAVES>((hit ? 1u : 0u) | (head ? 1u << 16 : 0u), lds);
+        const uint32_t tot_hit = tot_hh & 0xFFFFu, tot_heads = tot_hh >> 16;
         if (threadIdx.x == 0) {
             ws.tile_miss[tile] = tot_miss;
             ws.tile_stale[tile] = tot_stale;
