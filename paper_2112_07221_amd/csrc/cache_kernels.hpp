@@ -619,20 +619,19 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
+    const uint32_t ins_blocks = fill_blocks ? ptiles : 0u;
     if (bid < fill_blocks) {
         FillLds &fl = lds_as<FillLds>();
         const uint32_t tot_miss = tile_prefix_to_lds<4>(ws.tile_miss, ptiles, fl.pre_miss, fl.scan);
         const uint32_t tot_stale = tile_prefix_to_lds<4>(ws.tile_stale, ptiles, fl.pre_stale, fl.scan);
         const uint32_t gid = bid * groups_per_block + threadIdx.x / g.lanes;
         const uint32_t ngroups = fill_blocks * groups_per_block;
-        const uint32_t t = t_now;
         if (bid == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // for an update that reuses this order
         for (uint32_t m = gid; m < tot_miss; m += ngroups) {                 // Fetch(k) into a new slot
             const uint32_t tl = tile_of(fl.pre_miss, ptiles, m);
             const uint2 jk = ws.miss_stage[tl * PT_TILE + (m - fl.pre_miss[tl])];
             const uint32_t slot = cv.free_list[m];
-            const uint32_t j = jk.x, key = jk.y;
-            const uint32_t cg = cv.Cg[key];
+            const uint32_t key = jk.y;
             // host-backed table: a row the last trim evicted may still be on its way to the table
             // (its write-back travels in this very kernel); then the staged copy is the global row
             const uint64_t pe = cv.Cg_host ? cv.hl.pend[key] : 0ull;
@@ -642,15 +641,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             } else {
                 pull_row<VEC>(cv, key, slot, gl);
             }
-            if (gl == 0) {
-                store_meta(cv.meta, slot, cg, cg, t, 1u);                    // c_s = c_c = c_g; first use
-                cv.slot_key[slot] = key;
-                ws.head_slot[j] = (int32_t)slot;
-                if (!ht_insert(cv.ht, key, slot)) atomicOr(&cv.ds->err, ERRBIT_INTERNAL);
-                // host-backed table: the gather runs after this kernel and reads the cached copy
-                if (cv.Cg_host) for (uint32_t jj = j; jj < n && ws.skey[jj] == key; ++jj) ws.src[jj] = (int32_t)slot;
-            }
-        }
+        }                                        // (clocks, key and index entry: the workgroups below)
         for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
             const uint32_t tl = tile_of(fl.pre_stale, ptiles, m);
             const uint2 jk = ws.stale_stage[tl * PT_TILE + (m - fl.pre_stale[tl])];
@@ -669,6 +660,27 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         return;
     }
 
+    // Fetch's bookkeeping, one thread per missed key and one workgroup per probe tile, beside the row
+    // copies above (done by the same lanes it would stand behind them: two more dependent steps)
+    if (bid < fill_blocks + ins_blocks) {
+        const uint32_t tl = bid - fill_blocks;
+        const uint32_t here = ws.tile_miss[tl];
+        const uint32_t before = block_sum_array<4>(ws.tile_miss, tl, lds_as<FillLds>().scan);
+        for (uint32_t ml = threadIdx.x; ml < here; ml += 256u) {
+            const uint2 jk = ws.miss_stage[tl * PT_TILE + ml];
+            const uint32_t slot = cv.free_list[before + ml];
+            const uint32_t j = jk.x, key = jk.y;
+            const uint32_t cg = cv.Cg[key];
+            store_meta(cv.meta, slot, cg, cg, t_now, 1u);                    // c_s = c_c = c_g; first use
+            cv.slot_key[slot] = key;
+            ws.head_slot[j] = (int32_t)slot;
+            if (!ht_insert(cv.ht, key, slot)) atomicOr(&cv.ds->err, ERRBIT_INTERNAL);
+            // host-backed table: the gather runs after this kernel and reads the cached copy
+            if (cv.Cg_host) for (uint32_t jj = j; jj < n && ws.skey[jj] == key; ++jj) ws.src[jj] = (int32_t)slot;
+        }
+        return;
+    }
+    bid -= ins_blocks; nblk -= ins_blocks;
     if (bid < fill_blocks + hist_blocks) {
         // first pass of the coming trim's select, over the rows cached before this lookup plus the
         // rows being fetched right now (counted, not read)

@@ -425,7 +425,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     if (c->location == HET_BACKING_HBM) {
         // one kernel: the gather reads a missed key's row from the global table, beside the fetch
         const Rides ride = next_rides(c);
-        FILL_GATHER_ANY(ride.blocks() + fill_blocks + hist_blocks + gather_blocks, fill_blocks, hist_blocks, 0u);
+        FILL_GATHER_ANY(ride.blocks() + fill_blocks + ptiles + hist_blocks + gather_blocks, fill_blocks, hist_blocks, 0u);
     } else {
         // Host-backed table: the fetches come over the host link, and the last trim's write-back
         // goes the other way in the same kernel; the gather follows and reads the cached copies.
@@ -433,7 +433,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         const uint32_t fetch_blocks = std::min(fill_blocks, PUSH_BLOCKS);
         {
             const Rides ride = next_rides(c);
-            FILL_GATHER_ANY(ride.blocks() + push_blocks + fetch_blocks + hist_blocks, fetch_blocks, hist_blocks, push_blocks);
+            FILL_GATHER_ANY(ride.blocks() + push_blocks + fetch_blocks + ptiles + hist_blocks, fetch_blocks, hist_blocks, push_blocks);
         }
         c->push_pending = false;
         {
