@@ -598,6 +598,40 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
 constexpr int GATHER_ROWS = 4;
 constexpr int POOL_ROWS = 8;
+#ifndef FILL_ROWS_N
+#define FILL_ROWS_N 2
+#endif
+constexpr int FILL_ROWS = FILL_ROWS_N;              // missed keys a row group fetches at a time
+// A row chunk as the compiler's own vector type (arrays of these stay in registers where arrays
+// of the HIP struct type of the same size did not).
+typedef float raw_float4 __attribute__((ext_vector_type(4)));
+template <int VEC> struct RawVecT { using type = float; };
+template <> struct RawVecT<4> { using type = raw_float4; };
+
+// Fetch's pull for FILL_ROWS rows at once (all loads first).  Called by a whole row group.
+template <int VEC, bool WITH_ACC>
+__device__ __forceinline__ void fetch_rows(const CacheView &cv, const float *const (&srow)[FILL_ROWS], const float *const (&sacc)[FILL_ROWS],
+                                           const uint32_t (&slot)[FILL_ROWS], int nin, int gl)
+{
+    using V = typename RawVecT<VEC>::type;
+    const RowGeom g = cv.geom;
+    for (int c = gl; c < g.chunks; c += g.lanes) {
+        V v[FILL_ROWS], a[FILL_ROWS];
+#pragma unroll
+        for (int r = 0; r < FILL_ROWS; ++r) {
+            v[r] = reinterpret_cast<const V *>(srow[r])[c];
+            if constexpr (WITH_ACC) a[r] = reinterpret_cast<const V *>(sacc[r])[c];
+        }
+#pragma unroll
+        for (int r = 0; r < FILL_ROWS; ++r) {
+            if (r < nin) {
+                reinterpret_cast<V *>(cv.rows + (size_t)slot[r] * g.dim)[c] = v[r];
+                if constexpr (WITH_ACC) reinterpret_cast<V *>(cv.acc + (size_t)slot[r] * g.dim)[c] = a[r];
+            }
+        }
+    }
+}
+
 struct FillLds {
     uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
     uint32_t scan[4 + 1];
@@ -627,20 +661,32 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         const uint32_t gid = bid * groups_per_block + threadIdx.x / g.lanes;
         const uint32_t ngroups = fill_blocks * groups_per_block;
         if (bid == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // for an update that reuses this order
-        for (uint32_t m = gid; m < tot_miss; m += ngroups) {                 // Fetch(k) into a new slot
-            const uint32_t tl = tile_of(fl.pre_miss, ptiles, m);
-            const uint2 jk = ws.miss_stage[tl * PT_TILE + (m - fl.pre_miss[tl])];
-            const uint32_t slot = cv.free_list[m];
-            const uint32_t key = jk.y;
-            // host-backed table: a row the last trim evicted may still be on its way to the table
-            // (its write-back travels in this very kernel); then the staged copy is the global row
-            const uint64_t pe = cv.Cg_host ? cv.hl.pend[key] : 0ull;
-            if (cv.Cg_host && push_seq && (uint32_t)(pe >> 32) == push_seq) {
+        // Fetch(k) into a new slot, FILL_ROWS keys per row group at a time: where each row comes from
+        // and goes to is asked for all of them first, then the rows (few workgroups with several
+        // rows in flight each leave the chip to the other roles of this kernel from the start)
+        for (uint32_t m0 = gid; m0 < tot_miss; m0 += ngroups * FILL_ROWS) {
+            const float *srow[FILL_ROWS], *sacc[FILL_ROWS];
+            uint32_t slot[FILL_ROWS];
+#pragma unroll
+            for (int r = 0; r < FILL_ROWS; ++r) {
+                const uint32_t m = m0 + r * ngroups < tot_miss ? m0 + r * ngroups : m0;     // (beyond the end: the first row again, not stored)
+                const uint32_t tl = tile_of(fl.pre_miss, ptiles, m);
+                const uint32_t key = ws.miss_stage[tl * PT_TILE + (m - fl.pre_miss[tl])].y;
+                slot[r] = cv.free_list[m];
+                // host-backed table: a row the last trim evicted may still be on its way to the table
+                // (its write-back travels in this very kernel); then the staged copy is the global row
+                const bool link = cv.Cg_host && push_seq;
+                const uint64_t pe = link ? cv.hl.pend[key] : 0ull;
+                const bool staged = link && (uint32_t)(pe >> 32) == push_seq;
                 const size_t at = (size_t)(uint32_t)pe * g.dim;
-                pull_row_from<VEC>(cv, cv.hl.rows_of(push_buf) + at, cv.adagrad ? cv.hl.acc_of(push_buf) + at : nullptr, slot, gl);
-            } else {
-                pull_row<VEC>(cv, key, slot, gl);
+                srow[r] = staged ? cv.hl.rows_of(push_buf) + at : cv.W + (size_t)key * g.dim;
+                sacc[r] = staged ? cv.hl.acc_of(push_buf) + at : cv.A + (size_t)key * g.dim;
             }
+            int nin = 0;                         // rows of this batch that exist (the first ones)
+#pragma unroll
+            for (int r = 0; r < FILL_ROWS; ++r) nin += m0 + r * ngroups < tot_miss ? 1 : 0;
+            if (cv.adagrad) fetch_rows<VEC, true>(cv, srow, sacc, slot, nin, gl);
+            else fetch_rows<VEC, false>(cv, srow, sacc, slot, nin, gl);
         }                                        // (clocks, key and index entry: the workgroups below)
         for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
             const uint32_t tl = tile_of(fl.pre_stale, ptiles, m);
