@@ -912,7 +912,8 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
     }
 
     const uint32_t nchunks_max = (n_ids + CHUNK - 1) / CHUNK;      // known to the host; nv <= n_ids
-    for (uint32_t c = gid; c < nchunks_max; c += ngroups) {
+    uint32_t cb = bid * (256u / g.lanes);                          // first chunk of the workgroup
+    for (uint32_t c = gid; c < nchunks_max; c += ngroups, cb += ngroups) {
         const uint32_t j0 = c * CHUNK;
         // loaded for every position the call has, then masked by the valid count (read meanwhile)
         uint32_t k[CHUNK], p[CHUNK];
@@ -926,6 +927,13 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         }
         const uint32_t before_key = j0 > 0 ? skey[j0 - 1] : KEY_NONE;
         const uint32_t after_key = j0 + CHUNK < n_ids ? skey[j0 + CHUNK] : KEY_NONE;
+        // a workgroup whose chunks all lie inside one run (a popular key) leaves one partial sum,
+        // not one per chunk: the keys just outside its positions are equal
+        // (uniform over the workgroup: read through the scalar unit, the keys are not written here)
+        typedef const uint32_t __attribute__((address_space(4))) *scalar_u32;
+        const uint32_t bj0 = cb * CHUNK, bj1 = bj0 + (256u / g.lanes) * CHUNK;
+        bool through = false;
+        if (bj0 > 0 && bj1 < nv) through = ((scalar_u32)(uintptr_t)skey)[bj0 - 1] == ((scalar_u32)(uintptr_t)skey)[bj1];
         if (j0 >= nv) break;
         const uint32_t cnt = min((uint32_t)CHUNK, nv - j0);
 #pragma unroll
@@ -952,6 +960,45 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) if ((uint32_t)i < cnt) p[i] = grad_row[p[i]];
         }
+        if (through) {
+            // every position of every chunk belongs to the run: the chunks' sums are added in chunk
+            // order and stored where the workgroup's first chunk would have put its own
+            if (gl == 0) ws.cross_slot[c] = SLOT_NONE;
+            double *share = reinterpret_cast<double *>(dyn_lds);
+#pragma unroll
+            for (int q = 0; q < MAXC; ++q) {
+                const int cidx = gl + q * g.lanes;
+                const bool act = cidx < g.chunks;
+                V v[CHUNK];
+#pragma unroll
+                for (int i = 0; i < CHUNK; ++i) v[i] = act ? reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx] : V{};
+                double acc64[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
+#pragma unroll
+                for (int i = 0; i < CHUNK; ++i) {
+                    const float *vf = reinterpret_cast<const float *>(&v[i]);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc64[e] += (double)vf[e];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) share[threadIdx.x * VEC + e] = acc64[e];
+                __syncthreads();
+                if (threadIdx.x < (uint32_t)g.lanes && act) {
+                    double tot[VEC];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) tot[e] = 0.0;
+                    for (uint32_t gi = 0; gi < 256u / g.lanes; ++gi)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) tot[e] += share[(gi * g.lanes + gl) * VEC + e];
+                    double *mine = ws.partial + (size_t)c * 2 * (size_t)g.dim + (size_t)cidx * VEC;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) mine[e] = tot[e];
+                }
+            }
+            continue;
+        }
         // the run that starts here and leaves through the back border is finished by the second kernel
         int32_t cross = SLOT_NONE;
         if (gl == 0) {
@@ -962,18 +1009,14 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
             }
             ws.cross_slot[c] = cross;
         }
-        uint32_t cross_cc = 0;
 #pragma unroll
         for (int q = 0; q < MAXC; ++q) {
             const int cidx = gl + q * g.lanes;
             const bool act = cidx < g.chunks;
             V v[CHUNK], xr[CHUNK], ar[CHUNK];
-            uint32_t ccv[CHUNK];
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) {
-                v[i] = V{}; xr[i] = V{}; ar[i] = V{}; ccv[i] = 0;
-                if (q == 0 && i == 0 && cross != SLOT_NONE && !cv.direct) cross_cc = cv.meta[cross].cc;       // (lane 0 only)
-                if (q == 0 && gl == 0 && ((whole >> i) & 1u) && !cv.direct) ccv[i] = cv.meta[hs[i]].cc;
+                v[i] = V{}; xr[i] = V{}; ar[i] = V{};
                 if (act && ((inm >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
                 if (act && ((whole >> i) & 1u)) {
                     xr[i] = reinterpret_cast<const V *>(cv.rows + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
@@ -983,7 +1026,6 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
             double acc64[VEC];
             V cur_x{}, cur_a{};
             int32_t cur_slot = SLOT_NONE;
-            uint32_t cur_cc = 0;
             bool cur_whole = false, cur_front = false;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
@@ -991,7 +1033,7 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
             for (int i = 0; i < CHUNK; ++i) {
                 const bool in = (uint32_t)i < cnt;
                 if ((heads >> i) & 1u) {
-                    cur_x = xr[i]; cur_a = ar[i]; cur_slot = hs[i]; cur_cc = ccv[i];
+                    cur_x = xr[i]; cur_a = ar[i]; cur_slot = hs[i];
                     cur_whole = (whole >> i) & 1u;
                     cur_front = i == 0 && open_front;
 #pragma unroll
@@ -1016,7 +1058,7 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
                         reinterpret_cast<V *>(cv.rows + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_x;
                         if (cv.adagrad) reinterpret_cast<V *>(cv.acc + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_a;
                     }
-                    if (q == 0 && gl == 0 && !cv.direct) cv.meta[cur_slot].cc = cur_cc + 1;       // Clock(k)
+                    if (q == 0 && gl == 0 && !cv.direct) atomicAdd(&cv.meta[cur_slot].cc, 1u);      // Clock(k) (nothing to wait for)
                 } else if (act && (cur_front || (k[i] == last_key && open_back))) {
                     // slot 0 of the chunk: a run that came in through the front border;
                     // slot 1: a run that starts here and leaves through the back border
@@ -1029,7 +1071,7 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         // Clock(k) of the run that leaves through the back border is taken here already: the second
         // kernel carries the stage of the trim's select that counts which rows hold updates, and
         // must not move clocks under it
-        if (cross != SLOT_NONE && !cv.direct) cv.meta[cross].cc = cross_cc + 1;
+        if (cross != SLOT_NONE && !cv.direct) atomicAdd(&cv.meta[cross].cc, 1u);
     }
 }
 
@@ -1040,6 +1082,26 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
 // over more than FIN_WAVE chunks by the whole workgroup: every group adds a contiguous share of
 // the partial sums in order, and the shares are added in group order.  Either way the order of additions is fixed by the sorted
 // order alone.
+// The partial sums of a run whose head lies in chunk c and whose last position lies in chunk c1,
+// in order: those of the chunks up to the first workgroup of the first kernel that lay inside the
+// run as a whole, one per such workgroup (G chunks each), those of the chunks after the last.
+struct RunParts {
+    uint32_t c, G, h, nb, b0, t0, m;       // m = h + nb + tail items
+    __device__ __forceinline__ RunParts(uint32_t c_, uint32_t c1, uint32_t G_) : c(c_), G(G_)
+    {
+        b0 = c / G + 1;
+        const uint32_t b1 = c1 / G;                      // workgroups b0 .. b1 - 1 lay inside the run
+        if (b1 > b0) { h = b0 * G - c; nb = b1 - b0; t0 = b1 * G; m = h + nb + (c1 - t0 + 1); }
+        else { h = c1 - c + 1; nb = 0; t0 = 0; m = h; }
+    }
+    // where item i is in units of chunk slots (a chunk has two: run came in / run goes out)
+    __device__ __forceinline__ size_t at(uint32_t i) const
+    {
+        const uint32_t chunk = i < h ? c + i : (i < h + nb ? (b0 + (i - h)) * G : t0 + (i - h - nb));
+        return (size_t)chunk * 2 + (i == 0 ? 1 : 0);
+    }
+};
+
 constexpr int FIN_NEAR = 4;
 constexpr int FIN_WAVE = 48;        // partial sums up to which one wave finishes a run
 template <int VEC> struct FinishLds {
@@ -1101,7 +1163,7 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
         if (open) {                                                // for a wave, or for the whole workgroup
             c1 = (far_end - 1) / CHUNK;
             if (gl == 0) {
-                if (c1 - c + 1 > FIN_WAVE) { const uint32_t at = atomicAdd(&n_long, 1u); long_c[at] = c; long_c1[at] = c1; long_slot[at] = slot; }
+                if (RunParts(c, c1, groups_per_block).m > FIN_WAVE) { const uint32_t at = atomicAdd(&n_long, 1u); long_c[at] = c; long_c1[at] = c1; long_slot[at] = slot; }
                 else { const uint32_t at = atomicAdd(&fl.n_mid, 1u); fl.mid_c[at] = c; fl.mid_c1[at] = c1; fl.mid_slot[at] = slot; }
             }
         } else if (mine) {
@@ -1135,7 +1197,8 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
             const uint32_t wave = threadIdx.x / WAVE, gpw = WAVE / g.lanes, gw = (threadIdx.x % WAVE) / g.lanes;
             const uint32_t nm = fl.n_mid;
             for (uint32_t mi = wave; mi < nm; mi += 256 / WAVE) {
-                const uint32_t mc = fl.mid_c[mi], m = fl.mid_c1[mi] - mc + 1;
+                const RunParts rp(fl.mid_c[mi], fl.mid_c1[mi], groups_per_block);
+                const uint32_t m = rp.m;
                 const int32_t mslot = fl.mid_slot[mi];
                 const uint32_t per = (m + gpw - 1) / gpw;
                 const uint32_t lo = min(gw * per, m), hi = min(lo + per, m);
@@ -1151,7 +1214,7 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
                             const uint32_t i = i0 + u;
-                            const double *pp = ws.partial + ((size_t)(mc + i) * 2 + (i == 0 ? 1 : 0)) * pstride + (size_t)cidx * VEC;
+                            const double *pp = ws.partial + rp.at(i < m ? i : 0u) * pstride + (size_t)cidx * VEC;
 #pragma unroll
                             for (int e = 0; e < VEC; ++e) part[u][e] = (act && i < hi) ? pp[e] : 0.0;
                         }
@@ -1172,9 +1235,9 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
         }
         const uint32_t nl = n_long;
         for (uint32_t li = 0; li < nl; ++li) {                     // very long runs, one at a time, whole workgroup
-            const uint32_t lc = long_c[li], lc1 = long_c1[li];
+            const RunParts rp(long_c[li], long_c1[li], groups_per_block);
             const int32_t lslot = long_slot[li];
-            const uint32_t m = lc1 - lc + 1;                       // partial sums of the run
+            const uint32_t m = rp.m;                               // partial sums of the run
             const uint32_t per = (m + groups_per_block - 1) / groups_per_block;
             const uint32_t lo = min(group * per, m), hi = min(lo + per, m);
 #pragma unroll
@@ -1189,7 +1252,7 @@ __global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspa
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const uint32_t i = i0 + u;
-                        const double *pp = ws.partial + ((size_t)(lc + i) * 2 + (i == 0 ? 1 : 0)) * pstride + (size_t)cidx * VEC;
+                        const double *pp = ws.partial + rp.at(i < m ? i : 0u) * pstride + (size_t)cidx * VEC;
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) part[u][e] = (act && i < hi) ? pp[e] : 0.0;
                     }

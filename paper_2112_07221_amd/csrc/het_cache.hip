@@ -469,7 +469,7 @@ int launch_apply_chunk(het_cache *c, bool verify, const int64_t *ids, uint32_t n
     const uint32_t extra0 = stage0 >= 0 ? stage_blocks(c, tp, stage0) : 0u;
     const uint32_t extra1 = stage1 >= 0 ? stage_blocks(c, tp, stage1) : 0u;
     const Rides ride0 = next_rides(c);
-    const uint32_t lds0 = lds_bytes(sizeof(TrimLds), ride0);
+    const uint32_t lds0 = lds_bytes(std::max(sizeof(TrimLds), 256 * VEC * sizeof(double)), ride0);     // (the sums of a workgroup inside one run)
     if (verify)
         LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, CHUNK><<<ride0.blocks() + grid + extra0 + cdiv(n, VERIFY_TILE), 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
     else
