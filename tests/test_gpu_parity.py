@@ -248,6 +248,90 @@ def test_ragged_and_degenerate_batches():
         p.close()
 
 
+@pytest.mark.parametrize("dim,n", [(10, 3000), (64, 3000), (260, 2000), (64, 300_000)])
+def test_long_runs_that_cover_whole_workgroups(dim, n):
+    """A few keys hold most of the batch: the optimizer step's workgroups that lie inside one run
+    leave one partial sum each (row groups of 1, 16 and 64 lanes; both chunk sizes)."""
+    w = wl.WORKLOADS[1].scaled(dim=dim, capacity=400, s=2, optimizer=wl.ADAGRAD, eps=1e-8, policy=wl.LFU)
+    table = wl.table_init(w)
+    rng = np.random.default_rng(11)
+    p = Pair(w, table, max_ids=n)
+    try:
+        hot = rng.permutation(w.vocab)[:3]
+        for it in range(3):
+            u = rng.random(n)
+            ids = rng.integers(0, w.vocab, size=n)
+            ids[u < 0.85] = hot[2]; ids[u < 0.65] = hot[1]; ids[u < 0.45] = hot[0]
+            ids = ids.astype(np.int64)
+            g = rng.standard_normal((n, w.dim)).astype(np.float32)
+            p.lookup(ids)
+            p.update(ids, g)
+            p.compare_state(values=True)
+            p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
+@pytest.mark.parametrize("seed,host", [(1, False), (2, False), (3, True), (4, False)])
+def test_random_call_sequences(seed, host):
+    """Seeded random mixes of the calls: batches of random size and skew, announcements of coming
+    (and of never used) batches, lookups that no update follows, updates that sort their own ids,
+    flushes in between.  State and counters are compared after every iteration."""
+    rng = np.random.default_rng(100 + seed)
+    N = 6000
+    w = wl.WORKLOADS[1].scaled(dim=int(rng.choice([8, 16, 48])), capacity=int(rng.choice([150, 700, 3000])),
+                               s=int(rng.choice([0, 2, 50])), policy=int(rng.choice([wl.LRU, wl.LFU])),
+                               optimizer=int(rng.choice([wl.SGD, wl.ADAGRAD])), eps=1e-8)
+    table = wl.table_init(w)
+
+    def batch():
+        n = int(rng.choice([1, 7, 64, 255, 1024, 1025, 2500, 4097, N]))
+        kind = rng.integers(4)
+        if kind == 0:
+            ids = rng.zipf(1.2, size=n) % w.vocab
+        elif kind == 1:
+            ids = rng.integers(0, w.vocab, size=n)
+        elif kind == 2:
+            ids = rng.integers(0, w.vocab, size=n)
+            ids[rng.random(n) < 0.7] = int(rng.integers(w.vocab))
+        else:
+            ids = rng.permutation(w.vocab)[:n]
+        return ids.astype(np.int64)
+
+    T = 36
+    p = Pair(w, table, max_ids=N, host_backing=host)
+    try:
+        batches = [batch() for _ in range(T)]
+        dev = [torch.from_numpy(b).to(p.dev) for b in batches]
+        extra = [batch() for _ in range(6)]
+        extra_dev = [torch.from_numpy(b).to(p.dev) for b in extra]
+        for t in range(T):
+            for _ in range(int(rng.integers(0, 3))):
+                k = t + int(rng.integers(0, 4))
+                if k < T:
+                    p.cache.prefetch(dev[k])
+            if rng.random() < 0.15:
+                p.cache.prefetch(extra_dev[int(rng.integers(3))])          # never looked up
+            if rng.random() < 0.15:
+                e = 3 + int(rng.integers(3))
+                p.lookup(extra[e], ids_dev=extra_dev[e])                   # a lookup that no update follows
+            p.lookup(batches[t], ids_dev=dev[t])
+            g = rng.standard_normal((len(batches[t]), w.dim)).astype(np.float32)
+            mode = rng.random()
+            if mode < 0.7:
+                p.update(batches[t], g, ids_dev=dev[t])
+            elif mode < 0.85:
+                p.update(batches[t], g)                                    # same ids elsewhere: sorted again
+            p.compare_state(values=t % 4 == 0)
+            p.compare_counters()
+            if rng.random() < 0.1:
+                p.flush_and_compare()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
