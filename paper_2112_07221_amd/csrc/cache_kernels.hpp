@@ -92,6 +92,7 @@ struct Workspace {
     uint2 *miss_stage, *stale_stage;      // per probe tile: (head position, key) of its missed / stale keys
     uint32_t *bag_of;             // pooled: bag of each original position
     double *partial;              // apply: [chunks][2][dim] partial gradient sums of runs that cross chunk borders
+                                  // (a workgroup that lies inside one run stores one sum, in its first chunk's first place)
     int32_t *cross_slot;          // apply: [chunks] slot of the run that starts in the chunk and crosses its back border
 };
 
@@ -598,10 +599,7 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
 constexpr int GATHER_ROWS = 4;
 constexpr int POOL_ROWS = 8;
-#ifndef FILL_ROWS_N
-#define FILL_ROWS_N 2
-#endif
-constexpr int FILL_ROWS = FILL_ROWS_N;              // missed keys a row group fetches at a time
+constexpr int FILL_ROWS = 2;              // missed keys a row group fetches at a time
 // A row chunk as the compiler's own vector type (arrays of these stay in registers where arrays
 // of the HIP struct type of the same size did not).
 typedef float raw_float4 __attribute__((ext_vector_type(4)));
@@ -858,8 +856,9 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // keys that lie inside the chunk.  The gradients of a run are summed in fp64 (the kernel is
 // bound by reading the gradients; summing wide makes a long run of a popular key lose no
 // digits) and rounded once to fp32.  A run inside the chunk is applied at once.  A run that
-// crosses a chunk border leaves one partial sum per chunk for the second kernel; the chunk in
-// which it starts also leaves the run's slot in cross_slot.
+// crosses a chunk border leaves one partial sum per chunk for the second kernel (one per
+// workgroup where all of a workgroup's chunks lie inside the run); the chunk in which it starts
+// also leaves the run's slot in cross_slot.
 // VERIFY: the ids must be the ones the sorted order was built from (an update that reuses the
 // preceding lookup's order); extra workgroups compare them and flag any difference.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).

@@ -29,6 +29,7 @@ static const char *const kKernelNames[K_NUM] = {
 struct ProfSpan { int id; hipEvent_t start, stop; };
 
 constexpr int SORT_SETS = 4;
+constexpr uint32_t FILL_MAX_BLOCKS = 1024;     // workgroups that fetch missed rows (more only queue up ahead of the gather's)
 
 // A batch announced by het_prefetch: its ids, the buffer set its sort uses and how far the sort has come.
 struct Announced {
@@ -400,10 +401,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     c->sel_tp = make_trim_plan(c);
     const TrimPlan &tp = c->sel_tp;
     const uint32_t hist_blocks = stage_blocks(c, tp, 0);       // stage 0 of the select rides with the fetches
-    #ifndef FILL_CAP
-#define FILL_CAP 1024u
-#endif
-    const uint32_t fill_blocks = std::min(cdiv(row_grid(c->cv.geom, n), (uint32_t)FILL_ROWS), FILL_CAP);     // they come first: theirs is the longer chain
+        const uint32_t fill_blocks = std::min(cdiv(row_grid(c->cv.geom, n), (uint32_t)FILL_ROWS), FILL_MAX_BLOCKS);     // they come first: theirs is the longer chain
     if (offsets)
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
     const uint32_t lds_own = (uint32_t)std::max(sizeof(FillLds), sizeof(TrimLds));
