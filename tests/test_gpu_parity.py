@@ -332,6 +332,31 @@ def test_random_call_sequences(seed, host):
         p.close()
 
 
+@pytest.mark.parametrize("policy", [wl.LRU, wl.LFU])
+def test_beyond_2048_iterations_the_select_takes_more_passes(policy):
+    """The policy keys grow with the iteration count: past iteration 2047 they need one more
+    select pass (LRU two, LFU three), and more stages than the update's kernels can carry."""
+    w = wl.WORKLOADS[1].scaled(batch=40, capacity=600, s=5, policy=policy, optimizer=wl.ADAGRAD, eps=1e-8)
+    T = 2120
+    table = wl.table_init(w)
+    ids = wl.IdStream(w).batches(T)
+    grads = wl.grad_pool(w)
+    p = Pair(w, table)
+    try:
+        ids_dev = torch.from_numpy(ids).to(p.dev)
+        for t in range(T):
+            if t + 2 < T:
+                p.cache.prefetch(ids_dev[t + 2])
+            p.lookup(ids[t], check_values=t % 64 == 0 or t >= 2040, ids_dev=ids_dev[t])
+            p.update(ids[t], grads[t % len(grads)], ids_dev=ids_dev[t])
+            if t % 128 == 0 or t >= 2040:
+                p.compare_state(values=t % 16 == 0)
+                p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
