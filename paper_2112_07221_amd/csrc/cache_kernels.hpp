@@ -126,6 +126,7 @@ struct TrimPlan {
     int bits;         // bits per policy field
     int key_bits;     // bits of the packed policy key
     int passes;       // select passes
+    int h0_kept;      // the first pass's histogram is kept up to date between trims (by the probe and the eviction), not counted anew
     uint32_t *hist;   // [SEL_MAX_PASSES][SEL_BINS] followed by sup_cnt: zeroed together before the first pass
     uint32_t zero_words;
     uint4 *blk_cnt, *sup_cnt;          // per 1024 slots, and per EV_SUPER such blocks: cached rows with a policy key
@@ -223,24 +224,27 @@ __device__ __forceinline__ bool run_carried(const SortStage &a, const SortStage 
 
 // One histogram pass of the select over the rows whose key matches the prefix chosen so far.
 // Runs in `nblocks` workgroups of TRIM_THREADS threads; `vblock` is this one's index.
-// `new_rows` > 0 (first pass, running beside the lookup's fetches): slots that were free when
-// the lookup began are skipped - they are being filled right now - and the rows fetched into
-// them, which all carry the policy key (freq 1, last_use t_now), are counted from their number.
+// `beside_fill` (the pass runs beside the lookup's fetches): slots that were free when the lookup
+// began are skipped - they are being filled right now - and the rows fetched into them, which
+// all carry the policy key (freq 1, last_use t_now), are counted from their number `new_rows`.
+// `always`: counts even if nothing has to be evicted (the first pass's histogram is kept from
+// here on, see h0_shift).
 __device__ __forceinline__ void trim_hist_body(const CacheView &cv, const TrimPlan &tp, int pass, uint32_t vblock, uint32_t nblocks, TrimLds &l,
-                                               bool beside_fill = false, uint32_t new_rows = 0, uint32_t t_now = 0)
+                                               bool beside_fill = false, uint32_t new_rows = 0, uint32_t t_now = 0, bool always = false)
 {
     const int32_t over = cv.ds->size - (int32_t)cv.capacity;
-    if (over <= 0) return;
-    if (beside_fill && vblock == 0 && threadIdx.x == 0 && new_rows) {
-        const uint64_t k = policy_key(tp, make_uint4(0, 0, t_now, 1));
-        atomicAdd(&tp.hist[pass * SEL_BINS + ((uint32_t)(k >> sel_shift(tp, pass)) & ((1u << sel_width(tp, pass)) - 1u))], new_rows);
-    }
+    if (over <= 0 && !always) return;
     uint64_t prefix; uint32_t remaining;
     sel_replay(tp, pass, (uint32_t)over, prefix, remaining, l.pick, l.scan);
     for (int b = threadIdx.x; b < SEL_BINS; b += TRIM_THREADS) l.bins[b] = 0;
     __syncthreads();
     const int shift = sel_shift(tp, pass), width = sel_width(tp, pass);
     const int decided = shift + width;                 // bits above are fixed by the prefix
+    if (beside_fill && vblock == 0 && threadIdx.x == 0 && new_rows) {
+        const uint64_t k = policy_key(tp, make_uint4(0, 0, t_now, 1));
+        if (decided >= 64 || (k >> decided) == (prefix >> decided))
+            atomicAdd(&tp.hist[pass * SEL_BINS + ((uint32_t)(k >> shift) & ((1u << width) - 1u))], new_rows);
+    }
     for (uint32_t slot = vblock * TRIM_THREADS + threadIdx.x; slot < cv.n_slots; slot += nblocks * TRIM_THREADS) {
         const uint32_t sk = cv.slot_key[slot];
         const uint4 m = load_meta(cv.meta, slot);
@@ -253,6 +257,30 @@ __device__ __forceinline__ void trim_hist_body(const CacheView &cv, const TrimPl
     __syncthreads();
     for (int b = threadIdx.x; b < SEL_BINS; b += TRIM_THREADS)
         if (l.bins[b]) atomicAdd(&tp.hist[pass * SEL_BINS + b], l.bins[b]);
+}
+
+// The first pass's histogram (policy keys of all cached rows by their top digit) need not be
+// counted anew for every trim: a Read changes the keys of the rows it finds and adds the rows it
+// fetches, a trim removes its victims, nothing else touches policy keys.  So the probe moves the
+// rows it touches from their old bin to their new one, and the eviction takes its victims out
+// (h0_remove_victims); the select of the next trim starts at its second pass.  The digit layout
+// depends on the width of the iteration count: when that grows, the histogram is counted afresh.
+__device__ __forceinline__ uint32_t h0_bin(const TrimPlan &tp, uint64_t key)
+{
+    return (uint32_t)(key >> sel_shift(tp, 0)) & ((1u << sel_width(tp, 0)) - 1u);
+}
+
+// All rows in bins below the threshold's first digit were evicted, and of that digit's bin as
+// many as the select still had to find there.  One workgroup of TRIM_THREADS threads.
+__device__ __forceinline__ void h0_remove_victims(const CacheView &cv, const TrimPlan &tp, uint32_t *lds_pick, uint32_t *lds_scan)
+{
+    const int32_t over = cv.ds->over;
+    if (over <= 0) return;
+    uint64_t prefix; uint32_t remaining;
+    sel_replay(tp, 1, (uint32_t)over, prefix, remaining, lds_pick, lds_scan);       // (ends with a barrier: every thread has read its bins)
+    const uint32_t d0 = h0_bin(tp, prefix);
+    for (uint32_t b = threadIdx.x; b < d0; b += TRIM_THREADS) tp.hist[b] = 0;
+    if (threadIdx.x == 0) tp.hist[d0] -= remaining;
 }
 
 // Sums eight values per thread over the block at once (every thread gets all sums).
@@ -380,9 +408,10 @@ __device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32
 template <bool LOOKUP>
 __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
                                                            const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle,
-                                                           uint32_t *zero_from, uint32_t zero_words)
+                                                           uint32_t *zero_from, uint32_t zero_words, TrimPlan tp)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
+    __shared__ uint32_t h0_delta[LOOKUP ? SEL_BINS : 1];       // rows entering (+) and leaving (-) each bin of the kept histogram
     if (blockIdx.x >= ptiles) {          // extra workgroups of a lookup: the free list for the fill kernel
         // ... and clean select histograms for the trim that follows this lookup
         for (uint32_t i = (blockIdx.x - ptiles) * PT_THREADS + threadIdx.x; i < zero_words; i += (gridDim.x - ptiles) * PT_THREADS) zero_from[i] = 0;
@@ -393,6 +422,11 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
     const uint32_t vocab = cv.vocab;
     const uint32_t j = tile * PT_TILE + threadIdx.x;
     DState *ds = cv.ds;
+    const bool keep_h0 = LOOKUP && tp.h0_kept;
+    if (keep_h0) {
+        for (int b = threadIdx.x; b < SEL_BINS; b += PT_THREADS) h0_delta[b] = 0;
+        __syncthreads();
+    }
 
     if (tile == 0 && threadIdx.x == 0) {                      // this call's bookkeeping
         Counters z{};
@@ -433,6 +467,10 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
                     else {
                         hit = valid; stale = !valid;
                         store_meta(cv.meta, (uint32_t)slot, m.x, m.y, t_now, m.w + 1);   // one use per key per Read
+                        if (keep_h0) {
+                            const uint32_t b_old = h0_bin(tp, policy_key(tp, m)), b_new = h0_bin(tp, policy_key(tp, make_uint4(0, 0, t_now, m.w + 1)));
+                            if (b_old != b_new) { atomicSub(&h0_delta[b_old], 1u); atomicAdd(&h0_delta[b_new], 1u); }
+                        }
                     }
                     ws.cls[j] = (uint8_t)(miss ? CLS_MISS : (stale ? CLS_STALE : CLS_HIT));
                 } else {
@@ -461,6 +499,12 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
             count2(&cv.last->miss, &ds->total.miss, tot_miss);
             count2(&cv.last->unique, &ds->total.unique, tot_heads);
             if (tot_miss) atomicAdd(&ds->size, (int32_t)tot_miss);
+            if (keep_h0 && tot_miss) atomicAdd(&h0_delta[h0_bin(tp, policy_key(tp, make_uint4(0, 0, t_now, 1)))], tot_miss);   // the rows being fetched
+        }
+        if (keep_h0) {
+            __syncthreads();
+            for (int b = threadIdx.x; b < SEL_BINS; b += PT_THREADS)
+                if (h0_delta[b]) atomicAdd(&tp.hist[b], h0_delta[b]);          // (differences, modulo 2^32)
         }
     } else {
         if (__any(absent) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_STATE);
@@ -640,7 +684,7 @@ template <int VEC, bool POOLED, int RIDE>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv, SortStage ride, SortStage ride2,
-                                                          uint32_t push_blocks, int push_buf, uint32_t push_seq)
+                                                          uint32_t push_blocks, int push_buf, uint32_t push_seq, int hist_pass)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
@@ -726,11 +770,12 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
     }
     bid -= ins_blocks; nblk -= ins_blocks;
     if (bid < fill_blocks + hist_blocks) {
-        // first pass of the coming trim's select, over the rows cached before this lookup plus the
-        // rows being fetched right now (counted, not read)
+        // a pass of the coming trim's select (the first, or the second if the first pass's histogram
+        // is kept), over the rows cached before this lookup plus the rows being fetched right now
+        // (counted, not read)
         TrimLds &tl = lds_as<TrimLds>();
         const uint32_t new_rows = block_sum_array<TRIM_WAVES>(ws.tile_miss, ptiles, tl.scan);
-        trim_hist_body(cv, tp, 0, bid - fill_blocks, hist_blocks, tl, true, new_rows, t_now);
+        trim_hist_body(cv, tp, hist_pass, bid - fill_blocks, hist_blocks, tl, true, new_rows, t_now, hist_pass == 0);
         return;
     }
     const uint32_t first_gather = fill_blocks + hist_blocks;
@@ -1301,6 +1346,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
     if (RIDE && run_carried(ride, ride2, blk, nblk_)) return;
     EvictLds &el = lds_as<EvictLds>();
     uint32_t *scan = el.scan, *v_slot = el.v_slot, *v_key = el.v_key, *v_cg = el.v_cg, *v_at = el.v_at;
+    if (blk + 1 == nblk_) { h0_remove_victims(cv, tp, v_slot, scan); return; }      // the last workgroup: keeps the first pass's histogram
     DState *ds = cv.ds;
     const uint32_t slot0 = blk * EV_SLOTS + threadIdx.x * EV_ITEMS;
     // everything this thread may need, requested at once

@@ -64,6 +64,8 @@ struct het_cache {
     Announced ann[SORT_SETS - 1];    // announced batches, oldest first
     int n_ann = 0;
     TrimPlan sel_tp{};               // the select plan of the rows now cached (fixed at the lookup)
+    int sel_next = 1;                // first stage of that select which the lookup's kernels did not carry
+    int h0_bits = 0;                 // iteration-count width the kept first-pass histogram was counted for (0: not counted yet)
     bool last_trim_skipped = false;  // the last update had nothing to trim: its evicted-id list is empty
     int cslot = 0;                   // which of the two per-call counter blocks the current call uses
     uint32_t *inv = nullptr;
@@ -338,9 +340,9 @@ int run_trim(het_cache *c, int first_stage)
     const Rides ride = next_rides(c);
     const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
     if (ride.blocks())
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true><<<ride.blocks() + ev_blocks, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
     else
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false><<<ev_blocks, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride.a, ride.b));
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false><<<ev_blocks + 1, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride.a, ride.b));
     c->tf_last = fill;
     if (c->location == HET_BACKING_PINNED_HOST) { c->push_pending = true; c->push_buf = fill; c->push_seq = tp.push_seq; }
     c->overflow_pending = false;
@@ -355,7 +357,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     begin_call(c);
     c->t_host += 1;
     int rc;
-    if (c->overflow_pending && (rc = run_trim<VEC>(c, 1)) != HET_OK) return rc;   // a Read that follows a Read (stage 0 rode with its fetches)
+    if (c->overflow_pending && (rc = run_trim<VEC>(c, c->sel_next)) != HET_OK) return rc;   // a Read that follows a Read
     // The sorted order: announced by het_prefetch and sorted inside the kernels launched since
     // (what is left of it runs now), or sorted here.  Announcements older than the one used are
     // void; with no match they all stand (a later lookup may still use them).
@@ -384,7 +386,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         const TrimPlan none{};
 #define GATHER_ONLY(POOLED, RIDE)                                                                                        \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<grid, 256, lds, c->stream>>>(                          \
-                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u))
+                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u, 0))
         const int kind = ride.kind();
         if (!offsets) { if (kind == 0) GATHER_ONLY(false, 0); else if (kind == 1) GATHER_ONLY(false, 1); else GATHER_ONLY(false, 2); }
         else { if (kind == 0) GATHER_ONLY(true, 0); else if (kind == 1) GATHER_ONLY(true, 1); else GATHER_ONLY(true, 2); }
@@ -395,12 +397,23 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         return HET_OK;
     }
     const uint32_t ptiles = cdiv(n, PT_TILE), stiles = cdiv(c->cv.n_slots, PT_TILE);
+    // The select plan of the trim that follows this lookup.  Its first pass's histogram is kept
+    // between trims as long as the digit layout (the width of the iteration count) stays the same;
+    // otherwise this lookup counts it afresh, beside its fetches.
+    c->sel_tp = make_trim_plan(c);
+    c->sel_tp.h0_kept = c->h0_bits == c->sel_tp.bits;
+    c->h0_bits = c->sel_tp.bits;
+    const TrimPlan &tp = c->sel_tp;
+    const uint32_t kept_words = tp.h0_kept ? (uint32_t)SEL_BINS : 0u;
     LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + stiles, PT_THREADS, 0, c->stream>>>(
                            c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last),
-                           c->tp.hist, c->tp.zero_words));
-    c->sel_tp = make_trim_plan(c);
-    const TrimPlan &tp = c->sel_tp;
-    const uint32_t hist_blocks = stage_blocks(c, tp, 0);       // stage 0 of the select rides with the fetches
+                           c->tp.hist + kept_words, c->tp.zero_words - kept_words, tp));
+    const int hist_pass = tp.h0_kept ? 1 : 0;                  // this pass of the select rides with the fetches
+    // (with the first pass kept, a select of two passes fits into the update's two kernels: second
+    // pass and tie count; the fetch kernel is the longer for every workgroup it carries)
+    const bool carry = !tp.h0_kept || tp.passes >= 3;
+    const uint32_t hist_blocks = carry && hist_pass < tp.passes ? stage_blocks(c, tp, hist_pass) : 0u;
+    c->sel_next = hist_blocks ? hist_pass + 1 : hist_pass;     // (a select of one pass whose histogram is kept: only the tie count is left)
         const uint32_t fill_blocks = std::min(cdiv(row_grid(c->cv.geom, n), (uint32_t)FILL_ROWS), FILL_MAX_BLOCKS);     // they come first: theirs is the longer chain
     if (offsets)
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
@@ -408,7 +421,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 #define FILL_GATHER(POOLED, RIDE, GRID, FILLB, HISTB, PUSHB)                                                              \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>(     \
                                  c->cv, c->ws, n, t_now, ptiles, FILLB, tp, HISTB, out, offsets, n_bags, c->inv, ride.a, ride.b, \
-                                 PUSHB, c->push_buf, c->push_seq))
+                                 PUSHB, c->push_buf, c->push_seq, hist_pass))
 #define FILL_GATHER_ANY(GRID, FILLB, HISTB, PUSHB)                                                                        \
     do {                                                                                                                  \
         const int kind = ride.kind();                                                                                     \
@@ -452,7 +465,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 }
 
 // The two kernels of Write; each carries a stage of the coming trim's select in extra workgroups
-// (stage 0 rode with the lookup's fetches).  The first kernel moves the clocks, so it may carry
+// (the stages before c->sel_next are done: the kept first pass, and what rode with the lookup.s fetches).  The first kernel moves the clocks, so it may carry
 // a histogram stage (policy fields only) but not the final count, which looks at the clocks.
 // `trim`: a trim follows.  Returns the first stage that is still to run.
 template <int VEC, int MAXC, int CHUNK>
@@ -461,7 +474,7 @@ int launch_apply_chunk(het_cache *c, bool verify, const int64_t *ids, uint32_t n
 {
     const uint32_t grid = row_grid(c->cv.geom, cdiv(n, CHUNK));
     const TrimPlan &tp = c->sel_tp;
-    int next = 1;
+    int next = c->sel_next;
     const int stage0 = trim && next < tp.passes ? next++ : -1;
     const int stage1 = trim && next <= tp.passes ? next++ : -1;
     const uint32_t extra0 = stage0 >= 0 ? stage_blocks(c, tp, stage0) : 0u;
@@ -504,7 +517,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
             LAUNCH(c, K_PROBE, direct_probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
         else
             LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
-                                   c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u));
+                                   c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u, TrimPlan{}));
     }
     const uint32_t *grad_row = nullptr;
     if (offsets) {

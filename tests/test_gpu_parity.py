@@ -357,6 +357,43 @@ def test_beyond_2048_iterations_the_select_takes_more_passes(policy):
         p.close()
 
 
+def test_beyond_65536_iterations_lfu_select_of_four_passes():
+    """LFU keys are twice as wide as the iteration count: from iteration 65536 the select has four
+    passes, one stage more than the update's kernels carry.  Most iterations run unchecked (both
+    sides get the same calls); the integers of the state (keys, slots, clocks, policy fields,
+    evicted ids, counters) are compared now and then and over the last 200 iterations.  Row values
+    are not: fp32 rounding against the fp64 oracle adds up over 65 000 optimizer steps."""
+    w = wl.WORKLOADS[1].scaled(batch=8, capacity=300, s=5, policy=wl.LFU, optimizer=wl.SGD)
+    T = 65_700
+    table = wl.table_init(w)
+    ids = wl.IdStream(w).batches(T)
+    grads = wl.grad_pool(w)
+    p = Pair(w, table)
+    try:
+        ids_dev = torch.from_numpy(ids).to(p.dev)
+        gdev = [torch.from_numpy(g).to(p.dev) for g in grads]
+        out = torch.empty(ids.shape[1], w.dim, device=p.dev)
+        for t in range(T):
+            checked = t % 8192 == 0 or t >= T - 200
+            if checked:
+                p.lookup(ids[t], check_values=False, ids_dev=ids_dev[t])
+                p.update(ids[t], grads[t % len(grads)], ids_dev=ids_dev[t])
+                p.compare_state(values=False)
+                p.compare_counters()
+            else:
+                p.cache.lookup(ids_dev[t], out)
+                p.oracle.lookup(ids[t])
+                p.cache.update(ids_dev[t], gdev[t % len(grads)], w.lr)
+                p.oracle.update(ids[t], grads[t % len(grads)], w.lr)
+        assert p.cache.flush() == 0
+        p.oracle.flush()
+        assert np.array_equal(p.Cg.cpu().numpy().view(np.uint32), p.oracle.Cg), "global clocks differ"
+        p.compare_state(values=False)
+        p.compare_counters()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
