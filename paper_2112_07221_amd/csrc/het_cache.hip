@@ -465,8 +465,9 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 }
 
 // The two kernels of Write; each carries a stage of the coming trim's select in extra workgroups
-// (the stages before c->sel_next are done: the kept first pass, and what rode with the lookup.s fetches).  The first kernel moves the clocks, so it may carry
-// a histogram stage (policy fields only) but not the final count, which looks at the clocks.
+// (the stages before c->sel_next are done: the kept first pass, and what rode with the lookup's
+// fetches).  The first kernel moves the clocks, so it may carry a histogram stage (policy fields
+// only) but not the final count, which looks at the clocks.
 // `trim`: a trim follows.  Returns the first stage that is still to run.
 template <int VEC, int MAXC, int CHUNK>
 int launch_apply_chunk(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
