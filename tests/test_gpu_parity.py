@@ -75,6 +75,52 @@ def test_config2_full_size():
     assert st["total"]["stale"] > 0 and st["total"]["evicted"] > 0
 
 
+def test_two_runs_are_bit_identical():
+    """No ordering decision and no floating-point sum depends on the arrival order of atomics:
+    two runs of the same stream (config 2 at full size, batches announced ahead) end with the
+    same bits in every cached row and accumulator, every slot's state and the whole global table."""
+    w = wl.WORKLOADS[2].scaled(s=5)
+    T = 12
+    table = wl.table_init(w)
+    ids = wl.IdStream(w).batches(T)
+    grads = wl.grad_pool(w)
+    dev = torch.device("cuda:0")
+    ids_dev = torch.from_numpy(ids).to(dev)
+    gdev = [torch.from_numpy(g).to(dev) for g in grads]
+    results = []
+    for _ in range(2):
+        W = torch.from_numpy(table.astype(np.float32)).to(dev)
+        A = torch.zeros_like(W)
+        Cg = torch.zeros(w.vocab, dtype=torch.int32, device=dev)
+        cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps)
+        try:
+            cache.attach_backing(W, A, Cg, hc.BACKING_HBM)
+            out = torch.empty(w.n, w.dim, device=dev)
+            outs = []
+            for t in range(T):
+                if t == 0:
+                    cache.prefetch(ids_dev[1])
+                if t + 2 < T:
+                    cache.prefetch(ids_dev[t + 2])
+                cache.lookup(ids_dev[t], out)
+                outs.append(out.cpu().numpy().copy())
+                cache.update(ids_dev[t], gdev[t % len(gdev)], w.lr)
+            st = cache.export_state()
+            rows, acc = cache.export_rows()
+            assert cache.flush() == 0
+            results.append((outs, st, rows, acc, W.cpu().numpy(), A.cpu().numpy(), Cg.cpu().numpy()))
+        finally:
+            cache.close()
+    a, b = results
+    for x, y in zip(a[0], b[0]):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), "lookup outputs differ between runs"
+    for col in a[1]:
+        assert np.array_equal(a[1][col], b[1][col]), f"cache column {col} differs between runs"
+    for i, what in ((2, "cached rows"), (3, "cached accumulators"), (4, "global table"), (5, "global accumulators")):
+        assert np.array_equal(a[i].view(np.uint32), b[i].view(np.uint32)), f"{what} differ between runs"
+    assert np.array_equal(a[6], b[6])
+
+
 @pytest.mark.parametrize("cfg", [4, 5])
 def test_configs_4_and_5_full_size(cfg):
     """Configs 4 (skip-gram, 4M nodes, dim 128) and 5 (bag-of-words, pooled, dim 256, more unique ids
