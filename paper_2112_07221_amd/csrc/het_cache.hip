@@ -764,6 +764,7 @@ int het_flush(het_cache *c)
 {
     if (!ready(c)) return HET_EINVAL;
     begin_call(c);
+    drain_pushes(c);             // (a staged copy of a row reaches the table before anything the flush writes)
     const uint32_t grid = row_grid(c->cv.geom, c->cv.n_slots);
     if (c->cv.geom.vec == 4) LAUNCH(c, K_FLUSH, flush_kernel<4><<<grid, 256, 0, c->stream>>>(c->cv));
     else LAUNCH(c, K_FLUSH, flush_kernel<1><<<grid, 256, 0, c->stream>>>(c->cv));
