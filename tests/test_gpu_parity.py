@@ -440,6 +440,30 @@ def test_beyond_65536_iterations_lfu_select_of_four_passes():
         p.close()
 
 
+def test_largest_batch_the_library_accepts():
+    """2^20 ids in one call (1024 probe tiles, 1024 sort tiles, the long-chunk optimizer step), one
+    id more is refused at configuration."""
+    n = 1 << 20
+    w = wl.WORKLOADS[1].scaled(vocab=300_000, dim=8, capacity=50_000, s=1, policy=wl.LFU, optimizer=wl.ADAGRAD, eps=1e-8)
+    table = wl.table_init(w)
+    rng = np.random.default_rng(21)
+    p = Pair(w, table, max_ids=n)
+    try:
+        for it in range(2):
+            ids = (rng.zipf(1.1, size=n) % w.vocab).astype(np.int64)
+            ids[: n // 8] = rng.integers(0, w.vocab, size=n // 8)
+            g = rng.standard_normal((n, w.dim)).astype(np.float32)
+            p.lookup(ids)
+            p.update(ids, g)
+            p.compare_state(values=True)
+            p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+    with pytest.raises(Exception):
+        hc.HetCache(w.capacity, w.dim, w.s, w.policy, n + 1, w.optimizer, w.eps)
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
