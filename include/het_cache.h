@@ -92,6 +92,9 @@ int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, 
  * the capacity and the overflow is trimmed at the end of the update, Algorithm 2 / 3), the
  * id->slot hash table and the per-call workspaces.  Must be called once, before attach.
  * eps is Adagrad's epsilon (ignored for SGD).
+ * HET_EINVAL: max_batch_ids <= 0 or above 2^20, unknown optimizer, eps < 0, a second call, or
+ * rows wider than the kernels take (dim above 4096, or above 1024 if dim is no multiple of 4).
+ * HET_ENOMEM: the device allocation failed.
  */
 int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps,
                         void *hip_stream);

@@ -52,9 +52,10 @@ def test_policies_optimizers_staleness(policy, opt, s):
     run_workload(w, 30, state_every=1, values_every=7)
 
 
-@pytest.mark.parametrize("dim", [1, 10, 16, 64, 128, 256, 260])
+@pytest.mark.parametrize("dim", [1, 10, 16, 64, 128, 130, 256, 260, 1000, 1023, 4096])
 def test_row_widths(dim):
-    """Row groups of 1..64 lanes, the vector and the scalar row path."""
+    """Row groups of 1..64 lanes, the vector and the scalar row path, one to sixteen row pieces per
+    lane (the widest rows the library takes: 4096 floats, or 1024 if the width is no multiple of 4)."""
     w = wl.WORKLOADS[1].scaled(dim=dim, optimizer=wl.ADAGRAD, eps=1e-8, policy=wl.LFU, s=2)
     run_workload(w, 12, state_every=3, values_every=3)
 
