@@ -465,6 +465,32 @@ def test_largest_batch_the_library_accepts():
         hc.HetCache(w.capacity, w.dim, w.s, w.policy, n + 1, w.optimizer, w.eps)
 
 
+def test_pooled_with_bags_of_uneven_size_and_empty_bags():
+    """Bags of 0 to several hundred ids (the regular layouts have equal bags): pooled gather in bag
+    order, bag gradients spread to the bag's ids."""
+    w = wl.WORKLOADS[5].scaled(vocab=20_000, dim=24, batch=300, width=10, capacity=1_500, s=3)
+    n = w.n
+    table = wl.table_init(w)
+    rng = np.random.default_rng(31)
+    p = Pair(w, table)
+    try:
+        for it in range(6):
+            cuts = np.sort(rng.integers(0, n + 1, size=w.batch - 1))
+            cuts[rng.random(w.batch - 1) < 0.2] = cuts[0]                   # a fifth of the cuts coincide: empty bags
+            offsets = np.concatenate([[0], np.sort(cuts), [n]]).astype(np.int64)
+            p.offsets_np = offsets
+            p.offsets = torch.from_numpy(offsets).to(p.dev)
+            ids = (rng.zipf(1.2, size=n) % w.vocab).astype(np.int64)
+            g = rng.standard_normal((w.batch, w.dim)).astype(np.float32)
+            p.lookup(ids)
+            p.update(ids, g)
+            p.compare_state(values=True)
+            p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
