@@ -491,6 +491,26 @@ def test_pooled_with_bags_of_uneven_size_and_empty_bags():
         p.close()
 
 
+@pytest.mark.parametrize("vocab,capacity", [(1, 1), (2, 1), (7, 3), (7, 100), (300, 1)])
+def test_smallest_tables_and_caches(vocab, capacity):
+    """A table of one row, a cache of one row, a cache larger than the table."""
+    w = wl.WORKLOADS[1].scaled(vocab=vocab, dim=5, capacity=capacity, s=1, policy=wl.LRU, optimizer=wl.ADAGRAD, eps=1e-8)
+    table = wl.table_init(w)
+    rng = np.random.default_rng(41)
+    p = Pair(w, table, max_ids=700)
+    try:
+        for n in (1, 2, 65, 700, 3):
+            ids = rng.integers(0, vocab, size=n).astype(np.int64)
+            g = rng.standard_normal((n, w.dim)).astype(np.float32)
+            p.lookup(ids)
+            p.update(ids, g)
+            p.compare_state(values=True)
+            p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
