@@ -511,6 +511,15 @@ def test_smallest_tables_and_caches(vocab, capacity):
         p.close()
 
 
+def test_ids_of_25_bits_sort_in_four_passes():
+    """A vocabulary of 20 M ids: the radix sort takes four passes (the configurations up to 4 M ids
+    take three at most)."""
+    w = wl.WORKLOADS[1].scaled(vocab=20_000_000, dim=4, batch=300, capacity=3_000, s=2, policy=wl.LFU,
+                               optimizer=wl.ADAGRAD, eps=1e-8)
+    st = run_workload(w, 10, state_every=2, values_every=5, prefetch="before")
+    assert st["total"]["evicted"] > 0
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
