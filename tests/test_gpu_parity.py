@@ -320,6 +320,9 @@ def test_long_runs_that_cover_whole_workgroups(dim, n):
         p.close()
 
 
+FUZZ_ITERATIONS = 36
+
+
 @pytest.mark.parametrize("seed,host", [(1, False), (2, False), (3, True), (4, False)])
 def test_random_call_sequences(seed, host):
     """Seeded random mixes of the calls: batches of random size and skew, announcements of coming
@@ -346,7 +349,7 @@ def test_random_call_sequences(seed, host):
             ids = rng.permutation(w.vocab)[:n]
         return ids.astype(np.int64)
 
-    T = 36
+    T = FUZZ_ITERATIONS
     p = Pair(w, table, max_ids=N, host_backing=host)
     try:
         batches = [batch() for _ in range(T)]
