@@ -819,7 +819,9 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             // POOL_ROWS ids of the bag at a time: their sorted positions, then where their rows come
             // from, then the rows, each step for all of them at once; added in bag order
             for (int c = gl; c < g.chunks; c += g.lanes) {
-                V sum{};
+                double sum[VEC];                 // summed wide and rounded once: a bag may hold hundreds of rows
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
                 for (int64_t i0 = lo; i0 < hi; i0 += POOL_ROWS) {
                     uint32_t jj[POOL_ROWS];
 #pragma unroll
@@ -837,15 +839,16 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
 #pragma unroll
                     for (int r = 0; r < POOL_ROWS; ++r) {
                         const bool counts = i0 + r < hi && sr[r] != SRC_ZERO;
-                        if constexpr (VEC == 4) {
-                            sum.x += counts ? v[r].x : 0.f; sum.y += counts ? v[r].y : 0.f;
-                            sum.z += counts ? v[r].z : 0.f; sum.w += counts ? v[r].w : 0.f;
-                        } else {
-                            sum += counts ? v[r] : 0.f;
-                        }
+                        const float *vf = reinterpret_cast<const float *>(&v[r]);
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) sum[e] += counts ? (double)vf[e] : 0.0;
                     }
                 }
-                reinterpret_cast<V *>(out + (size_t)b * g.dim)[c] = sum;
+                V res;
+                float *rf = reinterpret_cast<float *>(&res);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) rf[e] = (float)sum[e];
+                reinterpret_cast<V *>(out + (size_t)b * g.dim)[c] = res;
             }
         }
     }
