@@ -140,7 +140,8 @@ int het_prefetch(het_cache *c, const int64_t *ids, int64_t n);
 
 /*
  * Pooled Read for multi-hot inputs: bag b holds ids[offsets[b] .. offsets[b+1]) and
- * out[b][:] = sum of its rows, added in bag order in fp32 (device, float[n_bags][dim]).
+ * out[b][:] = sum of its rows, added in bag order in fp64 and rounded once (device,
+ * float[n_bags][dim]).
  * offsets: device, int64[n_bags + 1], non-decreasing, offsets[0] = 0, offsets[n_bags] = n.
  */
 int het_lookup_pooled(het_cache *c, const int64_t *ids, int64_t n, const int64_t *offsets,
@@ -155,6 +156,13 @@ int het_lookup_pooled(het_cache *c, const int64_t *ids, int64_t n, const int64_t
  * and c_c grows by one (once per key per call).  Then Evict(): while more than `capacity` rows
  * are cached, the rows smallest in (last_use, slot) for LRU or (freq, last_use, slot) for LFU
  * are dropped, those with c_c > c_s being written back first (c_g = max(c_g, c_c)).
+ * ids (device, int64[n]) may be any buffer that holds ids cached by that lookup, in any order
+ * and number: they are sorted afresh.  If it is the very pointer and n of the preceding lookup,
+ * the lookup's sorted order is reused instead, so the buffer must still hold what it held then.
+ * Every id is checked against that order on the device; a buffer whose contents changed sets
+ * error bit 2 (HET_ESTATE at the next status query) and the gradients have gone to the wrong
+ * rows: the cache and what it later writes back are then no longer meaningful.  An id that is
+ * not cached sets the same bit and is skipped; ids outside the vocabulary set error bit 1.
  */
 int het_update(het_cache *c, const int64_t *ids, const float *grads, int64_t n, float lr);
 

@@ -523,6 +523,33 @@ def test_ids_of_25_bits_sort_in_four_passes():
     assert st["total"]["evicted"] > 0
 
 
+@pytest.mark.parametrize("opt", [wl.SGD, wl.ADAGRAD])
+def test_update_with_part_or_a_reordering_of_the_looked_up_ids(opt):
+    """The update's ids need not be the lookup's list: a permutation of it, a part of it, its
+    unique keys, each in a buffer of its own (the lookup's buffer stays alive, so that no other
+    buffer can get its address and be taken for it)."""
+    w = wl.WORKLOADS[1].scaled(vocab=5_000, capacity=700, s=3, policy=wl.LFU, optimizer=opt, eps=1e-8)
+    table = wl.table_init(w)
+    rng = np.random.default_rng(51)
+    p = Pair(w, table, max_ids=3000)
+    try:
+        for t in range(24):
+            n = int(rng.choice([17, 256, 1025, 3000]))
+            ids = (rng.zipf(1.15, size=n) % w.vocab).astype(np.int64)
+            keep = torch.from_numpy(ids).to(p.dev)
+            p.lookup(ids, ids_dev=keep)
+            uids = [rng.permutation(ids), ids[rng.random(n) < 0.5], np.unique(ids), ids[::-1].copy()][t % 4]
+            if len(uids) == 0:
+                uids = ids[:1]
+            g = rng.standard_normal((len(uids), w.dim)).astype(np.float32)
+            p.update(uids, g)
+            p.compare_state(values=True)
+            p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
