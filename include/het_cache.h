@@ -132,7 +132,9 @@ int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out);
  * lookup plus an update have four kernels that can carry: announce two batches ahead (before the
  * lookup of batch t, the ids of batch t + 2) and the sort is never seen.  ids[n] (device) must be
  * complete in stream order when this call is made and stay unchanged until the lookup that
- * passes the same pointer and n.  Three batches can stand announced at a time (a fourth replaces
+ * passes the same pointer and n (that lookup checks the order sorted ahead against the ids as
+ * they are then; ids that changed set error bit 2, HET_ESTATE, and its results are not
+ * meaningful).  Three batches can stand announced at a time (a fourth replaces
  * the oldest).  Results are identical with and without the announcement; a lookup with other
  * ids leaves it standing for a later one.  Nothing is launched by this call.
  */

@@ -408,14 +408,31 @@ __device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32
 template <bool LOOKUP>
 __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
                                                            const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle,
-                                                           uint32_t *zero_from, uint32_t zero_words, TrimPlan tp)
+                                                           uint32_t *zero_from, uint32_t zero_words, TrimPlan tp,
+                                                           const int64_t *__restrict__ check_ids)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
     __shared__ uint32_t h0_delta[LOOKUP ? SEL_BINS : 1];       // rows entering (+) and leaving (-) each bin of the kept histogram
+    const uint32_t check_blocks = LOOKUP && check_ids ? ptiles : 0u;
+    if (blockIdx.x >= ptiles && blockIdx.x < ptiles + check_blocks) {
+        // An order that was sorted ahead of this call (an announced batch) is checked against the ids
+        // as they are now: the announcement promised they would not change.  Workgroups of their own,
+        // on compute units the probe leaves idle.
+        const uint32_t jc = (blockIdx.x - ptiles) * PT_TILE + threadIdx.x;
+        bool changed = false;
+        if (jc < n) {
+            const int64_t id = check_ids[ws.perm[jc]];
+            const uint32_t expect = (id < 0 || id >= (int64_t)cv.vocab) ? cv.vocab : (uint32_t)id;
+            changed = expect != ws.skey[jc];
+        }
+        if (__any(changed) && lane_id() == 0) atomicOr(&cv.ds->err, ERRBIT_STATE);
+        return;
+    }
     if (blockIdx.x >= ptiles) {          // extra workgroups of a lookup: the free list for the fill kernel
         // ... and clean select histograms for the trim that follows this lookup
-        for (uint32_t i = (blockIdx.x - ptiles) * PT_THREADS + threadIdx.x; i < zero_words; i += (gridDim.x - ptiles) * PT_THREADS) zero_from[i] = 0;
-        free_list_body(cv, tile_free, tile_free_idle, ev_idle, blockIdx.x - ptiles, lds);
+        const uint32_t first = ptiles + check_blocks;
+        for (uint32_t i = (blockIdx.x - first) * PT_THREADS + threadIdx.x; i < zero_words; i += (gridDim.x - first) * PT_THREADS) zero_from[i] = 0;
+        free_list_body(cv, tile_free, tile_free_idle, ev_idle, blockIdx.x - first, lds);
         return;
     }
     const uint32_t tile = blockIdx.x;

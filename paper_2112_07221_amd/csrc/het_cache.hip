@@ -405,9 +405,9 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     c->h0_bits = c->sel_tp.bits;
     const TrimPlan &tp = c->sel_tp;
     const uint32_t kept_words = tp.h0_kept ? (uint32_t)SEL_BINS : 0u;
-    LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + stiles, PT_THREADS, 0, c->stream>>>(
+    LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + (match >= 0 ? ptiles : 0u) + stiles, PT_THREADS, 0, c->stream>>>(
                            c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last),
-                           c->tp.hist + kept_words, c->tp.zero_words - kept_words, tp));
+                           c->tp.hist + kept_words, c->tp.zero_words - kept_words, tp, match >= 0 ? ids : nullptr));
     const int hist_pass = tp.h0_kept ? 1 : 0;                  // this pass of the select rides with the fetches
     // (with the first pass kept, a select of two passes fits into the update's two kernels: second
     // pass and tie count; the fetch kernel is the longer for every workgroup it carries)
@@ -518,7 +518,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
             LAUNCH(c, K_PROBE, direct_probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
         else
             LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
-                                   c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u, TrimPlan{}));
+                                   c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u, TrimPlan{}, nullptr));
     }
     const uint32_t *grad_row = nullptr;
     if (offsets) {

@@ -614,6 +614,28 @@ def test_everything_fits_no_eviction():
     assert st["total"]["evicted"] == 0
 
 
+def test_an_announced_buffer_that_changed_is_flagged_at_the_lookup():
+    """An announcement promises that the ids stay as they are until their lookup; if they do not,
+    the order sorted ahead no longer fits them and the lookup says so."""
+    w = wl.WORKLOADS[1].scaled(capacity=400, s=3)
+    ids_np = wl.IdStream(w).batches(4)
+    g_np = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        dev = [torch.from_numpy(b).cuda() for b in ids_np]
+        g = torch.from_numpy(g_np[0]).cuda()
+        out = torch.empty(w.n, w.dim, device="cuda")
+        p.cache.prefetch(dev[1]); p.cache.prefetch(dev[2])
+        p.cache.lookup(dev[0], out); p.cache.update(dev[0], g, w.lr)       # these carry the announced sorts
+        p.cache.lookup(dev[1], out); p.cache.update(dev[1], g, w.lr)       # unchanged: fine
+        assert p.cache.stats()["error_bits"] == 0
+        dev[2][:50] = (dev[2][:50] + 1) % w.vocab                          # changed after it was announced (and sorted)
+        p.cache.lookup(dev[2], out)
+        assert p.cache.stats()["error_bits"] & 2
+    finally:
+        p.close()
+
+
 def test_update_reuses_the_lookup_order_only_for_the_same_ids():
     """An update handed the lookup's own id buffer reuses its sorted order and checks every id
     against it on the device; a buffer whose contents changed in between is flagged, not
