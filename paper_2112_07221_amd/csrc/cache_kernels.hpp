@@ -405,6 +405,19 @@ __device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32
 // the policy's use count.  LOOKUP: classifies HIT / STALE / MISS, stages missed and stale keys
 // per tile for the fill kernel and tells the gather where each position's row comes from.
 // Otherwise (update that sorted its own ids): only resolves slots and flags keys not cached.
+// Compares one tile of a sorted order with the ids it was built from (PT_THREADS threads).
+__device__ __forceinline__ void check_order_body(const CacheView &cv, const Workspace &ws, const int64_t *__restrict__ ids, uint32_t n, uint32_t tile)
+{
+    const uint32_t j = tile * PT_TILE + threadIdx.x;
+    bool changed = false;
+    if (j < n) {
+        const int64_t id = ids[ws.perm[j]];
+        const uint32_t expect = (id < 0 || id >= (int64_t)cv.vocab) ? cv.vocab : (uint32_t)id;
+        changed = expect != ws.skey[j];
+    }
+    if (__any(changed) && lane_id() == 0) atomicOr(&cv.ds->err, ERRBIT_STATE);
+}
+
 template <bool LOOKUP>
 __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
                                                            const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle,
@@ -418,14 +431,7 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         // An order that was sorted ahead of this call (an announced batch) is checked against the ids
         // as they are now: the announcement promised they would not change.  Workgroups of their own,
         // on compute units the probe leaves idle.
-        const uint32_t jc = (blockIdx.x - ptiles) * PT_TILE + threadIdx.x;
-        bool changed = false;
-        if (jc < n) {
-            const int64_t id = check_ids[ws.perm[jc]];
-            const uint32_t expect = (id < 0 || id >= (int64_t)cv.vocab) ? cv.vocab : (uint32_t)id;
-            changed = expect != ws.skey[jc];
-        }
-        if (__any(changed) && lane_id() == 0) atomicOr(&cv.ds->err, ERRBIT_STATE);
+        check_order_body(cv, ws, check_ids, n, blockIdx.x - ptiles);
         return;
     }
     if (blockIdx.x >= ptiles) {          // extra workgroups of a lookup: the free list for the fill kernel
@@ -533,9 +539,11 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
 // No cache (the paper's baseline "Hybrid (w/o Cache)", Section 5): Read and Write go straight to
 // the global table.  The sorted order is used as it is; a key stands for its own row.
 template <bool LOOKUP>
-__global__ __launch_bounds__(PT_THREADS) void direct_probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now)
+__global__ __launch_bounds__(PT_THREADS) void direct_probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
+                                                                  const int64_t *__restrict__ check_ids)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
+    if (blockIdx.x >= ptiles) { check_order_body(cv, ws, check_ids, n, blockIdx.x - ptiles); return; }     // (an order sorted ahead, see probe_kernel)
     const uint32_t j = blockIdx.x * PT_TILE + threadIdx.x;
     const uint32_t vocab = cv.vocab;
     DState *ds = cv.ds;

@@ -377,7 +377,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const uint32_t t_now = (uint32_t)c->t_host;
     if (c->cv.direct) {
         // no cache: mark the runs, then gather straight from the global table
-        LAUNCH(c, K_PROBE, direct_probe_kernel<true><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now));
+        LAUNCH(c, K_PROBE, direct_probe_kernel<true><<<cdiv(n, PT_TILE) * (match >= 0 ? 2u : 1u), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now, cdiv(n, PT_TILE), match >= 0 ? ids : nullptr));
         if (offsets)
             LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
         const Rides ride = next_rides(c);
@@ -515,7 +515,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         sort_now(c, ids, n, c->sort_set, 0);
         use_order(c, c->sort_set);
         if (c->cv.direct)
-            LAUNCH(c, K_PROBE, direct_probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host));
+            LAUNCH(c, K_PROBE, direct_probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr));
         else
             LAUNCH(c, K_PROBE, probe_kernel<false><<<cdiv(n, PT_TILE), PT_THREADS, 0, c->stream>>>(
                                    c->cv, c->ws, n, (uint32_t)c->t_host, cdiv(n, PT_TILE), nullptr, nullptr, 0u, nullptr, 0u, TrimPlan{}, nullptr));
