@@ -550,6 +550,43 @@ def test_update_with_part_or_a_reordering_of_the_looked_up_ids(opt):
         p.close()
 
 
+@pytest.mark.parametrize("opt", [wl.SGD, wl.ADAGRAD])
+def test_checkvalid_condition_two_after_another_writers_pushes(opt):
+    """CheckValid's second condition (c_g <= c_c + s, Section 3.1) never fails with one worker.
+    Another worker's pushes are emulated by changing global rows and advancing their c_g behind
+    the cache's back: cached rows without updates of their own are refetched and show the new
+    values, rows with updates are pushed first."""
+    w = wl.WORKLOADS[1].scaled(capacity=600, s=2, policy=wl.LFU, optimizer=opt, eps=1e-8)
+    T = 18
+    table = wl.table_init(w)
+    ids = wl.IdStream(w).batches(T)
+    grads = wl.grad_pool(w)
+    rng = np.random.default_rng(61)
+    p = Pair(w, table)
+    try:
+        stale_seen = 0
+        for t in range(T):
+            p.lookup(ids[t])
+            stale_seen += int((p.oracle.last_lookup()[1] == 1).sum())
+            if t % 2 == 0:
+                p.update(ids[t], grads[t % len(grads)])
+            p.compare_state(values=True)
+            p.compare_counters()
+            cached = p.oracle.export_state()["key"]
+            pick = rng.choice(cached, size=min(80, len(cached)), replace=False).astype(np.int64)
+            bump = rng.integers(1, 7, size=len(pick)).astype(np.uint32)
+            rows = rng.standard_normal((len(pick), w.dim)).astype(np.float32)
+            p.oracle.Cg[pick] += bump
+            p.oracle.W[pick] = rows
+            pick_t = torch.from_numpy(pick).to(p.dev)
+            p.Cg[pick_t] += torch.from_numpy(bump.astype(np.int32)).to(p.dev)
+            p.W[pick_t] = torch.from_numpy(rows).to(p.dev)
+        assert stale_seen > 0
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
