@@ -587,6 +587,32 @@ def test_checkvalid_condition_two_after_another_writers_pushes(opt):
         p.close()
 
 
+def test_per_kernel_timing_counts_the_launches_and_changes_nothing():
+    """het_profile_begin / het_profile_end (what the benchmark's roofline figures are made of):
+    one launch of each of the step's kernels per iteration, positive durations, same results."""
+    w = wl.WORKLOADS[1].scaled(capacity=400, s=3, policy=wl.LFU, optimizer=wl.ADAGRAD, eps=1e-8)
+    T = 6
+    ids = wl.IdStream(w).batches(T)
+    grads = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        dev = [torch.from_numpy(b).to(p.dev) for b in ids]
+        for t in range(2):                       # fill the cache first: from here on every update trims
+            p.lookup(ids[t], ids_dev=dev[t]); p.update(ids[t], grads[t], ids_dev=dev[t])
+        p.cache.profile_begin()
+        for t in range(2, T):
+            p.lookup(ids[t], ids_dev=dev[t]); p.update(ids[t], grads[t], ids_dev=dev[t])
+        prof = p.cache.profile_end()
+        for name in ("probe_kernel", "fill_gather_kernel", "apply_kernel", "apply_finish_kernel", "trim_evict_kernel"):
+            ms, launches = prof[name]
+            assert launches == T - 2 and ms > 0, (name, prof[name])
+        p.compare_state(values=True)
+        p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
