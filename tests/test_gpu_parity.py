@@ -613,6 +613,17 @@ def test_per_kernel_timing_counts_the_launches_and_changes_nothing():
         p.close()
 
 
+def test_on_a_stream_of_the_callers():
+    """All work is enqueued on the stream given at configuration: here a stream of the test's own
+    (default priority), on which the test's tensor operations run as well."""
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        w = wl.WORKLOADS[1].scaled(capacity=500, s=2, policy=wl.LFU, optimizer=wl.ADAGRAD, eps=1e-8)
+        st = run_workload(w, 16, state_every=2, values_every=4, prefetch="before")
+        assert st["total"]["evicted"] > 0
+    stream.synchronize()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
