@@ -624,6 +624,30 @@ def test_on_a_stream_of_the_callers():
     stream.synchronize()
 
 
+def test_two_caches_side_by_side():
+    """Two caches of different shape in one process, their calls interleaved: nothing is shared."""
+    wa = wl.WORKLOADS[1].scaled(capacity=300, s=1, policy=wl.LRU, optimizer=wl.SGD)
+    wb = wl.WORKLOADS[1].scaled(vocab=3_000, dim=40, batch=50, capacity=900, s=4, policy=wl.LFU, optimizer=wl.ADAGRAD, eps=1e-8)
+    ia, ib = wl.IdStream(wa).batches(12), wl.IdStream(wb).batches(12)
+    ga, gb = wl.grad_pool(wa), wl.grad_pool(wb)
+    pa, pb = Pair(wa, wl.table_init(wa)), Pair(wb, wl.table_init(wb))
+    try:
+        da = [torch.from_numpy(b).to(pa.dev) for b in ia]
+        db = [torch.from_numpy(b).to(pb.dev) for b in ib]
+        for t in range(12):
+            if t + 1 < 12:
+                pa.cache.prefetch(da[t + 1]); pb.cache.prefetch(db[t + 1])
+            pa.lookup(ia[t], ids_dev=da[t])
+            pb.lookup(ib[t], ids_dev=db[t])
+            pb.update(ib[t], gb[t % len(gb)], ids_dev=db[t])
+            pa.update(ia[t], ga[t % len(ga)], ids_dev=da[t])
+            pa.compare_state(values=t % 3 == 0); pb.compare_state(values=t % 3 == 0)
+            pa.compare_counters(); pb.compare_counters()
+        pa.flush_and_compare(); pb.flush_and_compare()
+    finally:
+        pa.close(); pb.close()
+
+
 def test_lookup_after_lookup_trims_first_and_empty_batch_is_a_no_op():
     w = wl.WORKLOADS[1].scaled(capacity=200, s=2)
     ids = wl.IdStream(w).batches(6)
