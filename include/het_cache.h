@@ -137,8 +137,18 @@ int het_lookup(het_cache *c, const int64_t *ids, int64_t n, float *out);
  * meaningful).  Three batches can stand announced at a time (a fourth replaces
  * the oldest).  Results are identical with and without the announcement; a lookup with other
  * ids leaves it standing for a later one.  Nothing is launched by this call.
+ * Lifetime of the buffer: the kernels of LATER calls read it (the first sort stage converts the
+ * ids), so it must stay allocated until its lookup has been enqueued, or until
+ * het_prefetch_cancel / het_flush has withdrawn the announcement and the work enqueued before
+ * that has completed.  An announcement is matched by pointer and n alone: a new buffer that an
+ * allocator places at the same address with the same n while the old announcement stands is
+ * taken for the old one (and then flagged HET_ESTATE by the check above); cancel first.
  */
 int het_prefetch(het_cache *c, const int64_t *ids, int64_t n);
+
+/* Withdraws every standing announcement: sort stages not yet enqueued never run, the buffers are
+ * not read by anything enqueued after this call.  het_flush does the same. */
+int het_prefetch_cancel(het_cache *c);
 
 /*
  * Pooled Read for multi-hot inputs: bag b holds ids[offsets[b] .. offsets[b+1]) and

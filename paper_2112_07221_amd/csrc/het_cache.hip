@@ -105,6 +105,12 @@ void report(const char *what, hipError_t e)
         if (e_ != hipSuccess) { report(#expr, e_); return HET_EHIP; } \
     } while (0)
 
+// Frees the device allocations made after the first `keep` (a call that fails midway leaves none behind).
+void free_owned_from(het_cache *c, size_t keep)
+{
+    while (c->owned.size() > keep) { (void)hipFree(c->owned.back()); c->owned.pop_back(); }
+}
+
 template <typename T>
 int dev_alloc(het_cache *c, T **p, size_t count)
 {
@@ -582,7 +588,7 @@ int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, 
     return HET_OK;
 }
 
-int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps, void *hip_stream)
+static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps, void *hip_stream)
 {
     if (!c || c->configured || max_batch_ids <= 0 || max_batch_ids > (int64_t)MAX_PROBE_TILES * PT_TILE) return HET_EINVAL;
     if (optimizer != HET_OPT_SGD && optimizer != HET_OPT_ADAGRAD) return HET_EINVAL;
@@ -659,7 +665,15 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
     return HET_OK;
 }
 
-int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, int64_t vocab, int32_t location)
+int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps, void *hip_stream)
+{
+    const size_t keep = c ? c->owned.size() : 0;
+    const int rc = configure_impl(c, max_batch_ids, optimizer, eps, hip_stream);
+    if (rc != HET_OK && c && !c->configured) free_owned_from(c, keep);     // a retry starts from nothing
+    return rc;
+}
+
+static int attach_impl(het_cache *c, float *table, float *state, uint32_t *cg, int64_t vocab, int32_t location)
 {
     if (!c || !c->configured || !table || !cg || vocab <= 0 || vocab >= 0xFFFFFFFFll) return HET_EINVAL;
     if (location != HET_BACKING_HBM && location != HET_BACKING_PINNED_HOST) return HET_EINVAL;
@@ -698,6 +712,24 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
     }
     c->location = location;
     c->attached = true;
+    return HET_OK;
+}
+
+int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, int64_t vocab, int32_t location)
+{
+    const size_t keep = c ? c->owned.size() : 0;
+    const bool was = c && c->attached;
+    const int rc = attach_impl(c, table, state, cg, vocab, location);
+    if (rc != HET_OK && c && !was) free_owned_from(c, keep);
+    return rc;
+}
+
+int het_prefetch_cancel(het_cache *c)
+{
+    if (!c || !c->configured) return HET_EINVAL;
+    // stages already enqueued read their buffer in stream order before anything enqueued from now on;
+    // stages not enqueued yet never will be
+    c->n_ann = 0;
     return HET_OK;
 }
 
@@ -764,6 +796,7 @@ int het_flush(het_cache *c)
 {
     if (!ready(c)) return HET_EINVAL;
     begin_call(c);
+    c->n_ann = 0;                // announcements do not outlive a flush
     drain_pushes(c);             // (a staged copy of a row reaches the table before anything the flush writes)
     const uint32_t grid = row_grid(c->cv.geom, c->cv.n_slots);
     if (c->cv.geom.vec == 4) LAUNCH(c, K_FLUSH, flush_kernel<4><<<grid, 256, 0, c->stream>>>(c->cv));
@@ -826,14 +859,27 @@ int het_export_rows(het_cache *c, float *rows, float *acc)
     if (!c || !c->configured) return HET_EINVAL;
     { int rc0 = sync_all(c); if (rc0) return rc0; }
     const size_t P = c->cv.n_slots, D = (size_t)c->dim;
+    if (c->cv.direct) return HET_OK;                 // no cache: nothing is ever cached
     std::vector<uint32_t> k(P);
     HIP_TRY(hipMemcpy(k.data(), c->cv.slot_key, P * 4, hipMemcpyDeviceToHost));
-    size_t r = 0;
-    for (size_t slot = 0; slot < P; ++slot) {
-        if (k[slot] == KEY_NONE) continue;
-        if (rows) HIP_TRY(hipMemcpy(rows + r * D, c->cv.rows + slot * D, D * 4, hipMemcpyDeviceToHost));
-        if (acc && c->cv.acc) HIP_TRY(hipMemcpy(acc + r * D, c->cv.acc + slot * D, D * 4, hipMemcpyDeviceToHost));
-        ++r;
+    // the slot arrays come over in a few large copies (a copy per row would be one synchronous
+    // transfer per cached row) and are compacted here
+    const size_t step = std::max<size_t>(1, ((size_t)64 << 20) / (D * 4));
+    std::vector<float> buf(std::min(step, P) * D);
+    for (int which = 0; which < 2; ++which) {
+        float *dst = which ? acc : rows;
+        const float *src = which ? c->cv.acc : c->cv.rows;
+        if (!dst || !src) continue;
+        size_t r = 0;
+        for (size_t s0 = 0; s0 < P; s0 += step) {
+            const size_t cnt = std::min(step, P - s0);
+            bool any = false;
+            for (size_t i = 0; i < cnt && !any; ++i) any = k[s0 + i] != KEY_NONE;
+            if (!any) continue;
+            HIP_TRY(hipMemcpy(buf.data(), src + s0 * D, cnt * D * 4, hipMemcpyDeviceToHost));
+            for (size_t i = 0; i < cnt; ++i)
+                if (k[s0 + i] != KEY_NONE) { std::memcpy(dst + r * D, buf.data() + i * D, D * 4); ++r; }
+        }
     }
     return HET_OK;
 }

@@ -22,7 +22,8 @@ CLASS_HIT, CLASS_STALE, CLASS_MISS = 0, 1, 2
 S_INFINITE = (1 << 63) - 1
 
 EXPORTS = (
-    "het_cache_create", "het_cache_configure", "het_attach_backing", "het_prefetch", "het_lookup",
+    "het_cache_create", "het_cache_configure", "het_attach_backing", "het_prefetch",
+    "het_prefetch_cancel", "het_lookup",
     "het_lookup_pooled", "het_update", "het_update_pooled", "het_flush", "het_stats",
     "het_clear_error", "het_export_state", "het_export_rows", "het_last_lookup",
     "het_last_evicted", "het_cache_destroy", "het_strerror", "het_profile_begin",
@@ -72,6 +73,7 @@ def load() -> C.CDLL:
     lib.het_attach_backing.argtypes = [p, p, p, p, i64, i32]
     lib.het_lookup.argtypes = [p, p, i64, p]
     lib.het_prefetch.argtypes = [p, p, i64]
+    lib.het_prefetch_cancel.argtypes = [p]
     lib.het_lookup_pooled.argtypes = [p, p, i64, p, i64, p]
     lib.het_update.argtypes = [p, p, p, i64, C.c_float]
     lib.het_update_pooled.argtypes = [p, p, i64, p, p, i64, C.c_float]
@@ -162,6 +164,9 @@ class HetCache:
         import torch
         _check_dev(ids, torch.int64, "ids")
         self._rc(self.lib.het_prefetch(self.h, ids.data_ptr(), ids.numel()), "het_prefetch")
+
+    def prefetch_cancel(self):
+        self._rc(self.lib.het_prefetch_cancel(self.h), "het_prefetch_cancel")
 
     def lookup(self, ids, out):
         import torch
