@@ -214,6 +214,26 @@ int het_last_lookup(het_cache *c, int64_t *keys, int32_t *cls, int32_t *slots, i
 int het_last_evicted(het_cache *c, int64_t *ids, int64_t *n);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): het_lookup of a cache created with HET_POLICY_NONE,
+ * without a cache object.  out[i][:] = table[ids[i]][:] for ids (device, int64[n]) inside
+ * [0, vocab), zero rows for the others; table is float[vocab][dim] (device, or pinned host memory
+ * mapped into the device), out float[n][dim] (device).  The ids go through the same sort, run
+ * marking and gather kernels as het_lookup; their workspaces (sort buffers, per-position arrays,
+ * scalars) live in a static device array of about 1.8 MB that every GPU the library runs on holds
+ * until the process ends, so the call allocates and frees nothing, on the device or through any
+ * library.  n may be at most HET_NOALLOC_MAX_IDS; dim as for het_cache_configure; vocab below
+ * 2^31.  The work is enqueued on hip_stream (a hipStream_t, NULL = the default stream) and the
+ * call returns without waiting.  err_bits (device, uint32, may be NULL) receives, in stream order,
+ * 1 if some id was outside the vocabulary, else 0.  All calls on one GPU share the array: calls
+ * whose work overlaps on one GPU (two streams, two threads) race and must be serialised by the
+ * caller.  HET_EINVAL: a size out of range or a NULL pointer.  HET_EHIP: the runtime refused.
+ */
+#define HET_NOALLOC_MAX_IDS 65536
+int het_lookup_nocache_static(const float *table, int64_t vocab, int32_t dim, const int64_t *ids, int64_t n,
+                              float *out, uint32_t *err_bits, void *hip_stream);
+
+/*
  * Per-kernel timing for benchmarks.  Between het_profile_begin and het_profile_end every kernel
  * the library launches for this cache is bracketed by a pair of HIP events on the cache's
  * stream (this slows the calls down slightly and creates events: not for timed regions).

@@ -925,6 +925,80 @@ int het_last_evicted(het_cache *c, int64_t *ids, int64_t *n)
     return HET_OK;
 }
 
+// ---- a Read without a cache object and without any allocation ------------------------------
+// Scratch of het_lookup_nocache_static: the sort's double buffers and per-tile histograms, the
+// per-position workspaces of the gather and the block of device-side scalars.  One copy per GPU,
+// held until the process ends; every call on a GPU uses it, so calls that overlap on one GPU race.
+constexpr size_t NOALLOC_MAX_IDS = HET_NOALLOC_MAX_IDS;
+constexpr size_t na_align(size_t v) { return (v + 255) & ~(size_t)255; }
+constexpr size_t NA_WORDS = na_align(NOALLOC_MAX_IDS * 4);                 // one uint32 / int32 per id
+constexpr size_t NA_HIST = na_align((NOALLOC_MAX_IDS / SORT_TILE) * (SORT_MAX_BINS / 2) * 4);
+constexpr size_t NA_OFF_KEYS0 = 0, NA_OFF_KEYS1 = NA_OFF_KEYS0 + NA_WORDS, NA_OFF_IDX0 = NA_OFF_KEYS1 + NA_WORDS,
+                 NA_OFF_IDX1 = NA_OFF_IDX0 + NA_WORDS, NA_OFF_HIST = NA_OFF_IDX1 + NA_WORDS, NA_OFF_SRC = NA_OFF_HIST + NA_HIST,
+                 NA_OFF_HEAD = NA_OFF_SRC + NA_WORDS, NA_OFF_CLS = NA_OFF_HEAD + NA_WORDS,
+                 NA_OFF_DS = NA_OFF_CLS + na_align(NOALLOC_MAX_IDS), NA_BYTES = NA_OFF_DS + na_align(sizeof(DState));
+static __device__ __align__(256) unsigned char scratch[NA_BYTES];
+
+__global__ void na_clear_kernel(DState *ds)
+{
+    uint32_t *w = reinterpret_cast<uint32_t *>(ds);
+    for (uint32_t i = threadIdx.x; i < sizeof(DState) / 4; i += blockDim.x) w[i] = 0;
+}
+__global__ void na_report_kernel(const DState *ds, uint32_t *err_out) { *err_out = ds->err; }
+
+constexpr int NA_MAX_DEVICES = 64;
+static unsigned char *na_scratch_of_device[NA_MAX_DEVICES];      // the array's address on each GPU, asked for once
+
+int het_lookup_nocache_static(const float *table, int64_t vocab, int32_t dim, const int64_t *ids, int64_t n, float *out,
+                              uint32_t *err_bits, void *hip_stream)
+{
+    if (n < 0 || n > (int64_t)NOALLOC_MAX_IDS || dim <= 0 || vocab <= 0 || vocab >= (1ll << 31)) return HET_EINVAL;
+    if (n == 0) return HET_OK;
+    if (!table || !ids || !out) return HET_EINVAL;
+    RowGeom g;
+    g.dim = dim; g.vec = (dim % 4 == 0) ? 4 : 1; g.chunks = dim / g.vec;
+    g.lanes = (int)std::min<uint32_t>(64u, pow2_at_least((uint64_t)g.chunks));
+    if ((g.chunks + g.lanes - 1) / g.lanes > 16) return HET_EINVAL;          // rows wider than the kernels take
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NA_MAX_DEVICES) return HET_EINVAL;
+    if (!na_scratch_of_device[dev]) {
+        // the array's name is a host-side handle; its device address differs from GPU to GPU
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return HET_EHIP;
+        na_scratch_of_device[dev] = static_cast<unsigned char *>(p);
+    }
+    unsigned char *base = na_scratch_of_device[dev];
+    // a cache object that lives for this call only, in the "no cache" mode, over the scratch
+    het_cache tmp;
+    tmp.capacity = 1; tmp.dim = dim; tmp.policy = HET_POLICY_NONE;
+    tmp.configured = tmp.attached = true;
+    tmp.max_ids = (int64_t)NOALLOC_MAX_IDS;
+    tmp.stream = static_cast<hipStream_t>(hip_stream);
+    CacheView &cv = tmp.cv;
+    cv.direct = 1; cv.n_slots = 1; cv.capacity = 1; cv.max_ids = (uint32_t)NOALLOC_MAX_IDS;
+    cv.geom = g;
+    cv.W = const_cast<float *>(table); cv.rows = cv.W; cv.vocab = (uint32_t)vocab;
+    cv.ds = reinterpret_cast<DState *>(base + NA_OFF_DS);
+    cv.last = &cv.ds->call[0]; cv.next_call = &cv.ds->call[1];
+    tmp.keys[0][0] = reinterpret_cast<uint32_t *>(base + NA_OFF_KEYS0);
+    tmp.keys[0][1] = reinterpret_cast<uint32_t *>(base + NA_OFF_KEYS1);
+    tmp.idx[0][0] = reinterpret_cast<uint32_t *>(base + NA_OFF_IDX0);
+    tmp.idx[0][1] = reinterpret_cast<uint32_t *>(base + NA_OFF_IDX1);
+    tmp.sort_hist[0] = reinterpret_cast<uint32_t *>(base + NA_OFF_HIST);
+    tmp.ws.src = reinterpret_cast<int32_t *>(base + NA_OFF_SRC);
+    tmp.ws.head_slot = reinterpret_cast<int32_t *>(base + NA_OFF_HEAD);
+    tmp.ws.cls = reinterpret_cast<uint8_t *>(base + NA_OFF_CLS);
+    // the scratch keeps the last call's contents: the scalars (sticky error bits, counters) start at zero
+    na_clear_kernel<<<1, 64, 0, tmp.stream>>>(cv.ds);
+    const int rc = g.vec == 4 ? run_lookup<4>(&tmp, ids, (uint32_t)n, nullptr, 0, out)
+                              : run_lookup<1>(&tmp, ids, (uint32_t)n, nullptr, 0, out);
+    if (rc != HET_OK) return rc;
+    if (err_bits) na_report_kernel<<<1, 1, 0, tmp.stream>>>(cv.ds, err_bits);
+    return launch_ok();
+}
+
 int het_profile_begin(het_cache *c)
 {
     if (!c || !c->configured || c->profiling) return HET_EINVAL;

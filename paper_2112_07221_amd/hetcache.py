@@ -28,6 +28,7 @@ EXPORTS = (
     "het_clear_error", "het_export_state", "het_export_rows", "het_last_lookup",
     "het_last_evicted", "het_cache_destroy", "het_strerror", "het_profile_begin",
     "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name",
+    "het_lookup_nocache_static",
 )
 
 COUNTER_FIELDS = ("n", "unique", "hit", "stale", "miss", "evicted", "evicted_dirty",
@@ -87,6 +88,7 @@ def load() -> C.CDLL:
     lib.het_cache_destroy.argtypes = [p]
     lib.het_strerror.argtypes = [C.c_int]
     lib.het_strerror.restype = C.c_char_p
+    lib.het_lookup_nocache_static.argtypes = [p, i64, i32, p, i64, p, p, p]
     lib.het_profile_begin.argtypes = [p]
     lib.het_profile_end.argtypes = [p, p, p, i32]
     lib.het_profile_kernel_count.argtypes = []
@@ -112,6 +114,26 @@ def _check_dev(t, dtype, what):
     if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise TypeError(f"{what} must be a contiguous {dtype} tensor on the GPU")
     return t
+
+
+NOALLOC_MAX_IDS = 65536
+
+
+def lookup_nocache_static(table, ids, out, err_bits=None, stream=None):
+    """out[i] = table[ids[i]] through het_lookup_nocache_static (no cache object, no allocation).
+    Returns the status code."""
+    import torch
+    lib = load()
+    _check_dev(ids, torch.int64, "ids"); _check_dev(out, torch.float32, "out")
+    if table.dtype != torch.float32 or not table.is_contiguous() or table.dim() != 2:
+        raise TypeError("table must be a contiguous fp32 matrix")
+    if out.numel() < ids.numel() * table.shape[1]:
+        raise ValueError("out is too small")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    return lib.het_lookup_nocache_static(table.data_ptr(), table.shape[0], table.shape[1], ids.data_ptr(),
+                                         ids.numel(), out.data_ptr(),
+                                         err_bits.data_ptr() if err_bits is not None else None,
+                                         C.c_void_p(st.cuda_stream))
 
 
 class HetCache:
