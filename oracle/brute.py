@@ -18,18 +18,25 @@ class Entry:
     def __init__(self, key, slot, row, acc, clock):
         self.key, self.slot = key, slot
         self.row, self.acc = list(row), list(acc)
+        self.row0, self.acc0 = list(row), list(acc)      # as fetched (several workers: deltas are pushed)
         self.c_s = self.c_c = clock
         self.last_use, self.freq = 0, 0
 
 
 class BruteCache:
-    def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer, eps, table):
+    def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer, eps, table, many=False, server=None):
+        """`many`: one of several workers over one server (Evict pushes what was accumulated since
+        the Fetch, and the server adds it); `server`: another BruteCache whose global table is used."""
         self.C, self.D, self.s = capacity, dim, s
         self.policy, self.opt, self.eps = policy, optimizer, float(eps)
         self.P = capacity + max_batch_ids
-        self.W = [[float(x) for x in r] for r in table]      # global table
-        self.A = [[0.0] * dim for _ in table]
-        self.c_g = [0] * len(table)
+        self.many = many
+        if server is not None:
+            self.W, self.A, self.c_g = server.W, server.A, server.c_g
+        else:
+            self.W = [[float(x) for x in r] for r in table]      # global table
+            self.A = [[0.0] * dim for _ in table]
+            self.c_g = [0] * len(table)
         self.entries = []                                      # the cache embedding table
         self.t = 0
         self.evicted = []
@@ -47,8 +54,14 @@ class BruteCache:
         if e.c_c == e.c_s:
             return False
         self.pushes += 1
-        self.W[e.key] = list(e.row)
-        self.A[e.key] = list(e.acc)
+        if self.many:
+            for j in range(self.D):
+                self.W[e.key][j] = self.W[e.key][j] + (e.row[j] - e.row0[j])
+                if self.opt == 1:
+                    self.A[e.key][j] = self.A[e.key][j] + (e.acc[j] - e.acc0[j])
+        else:
+            self.W[e.key] = list(e.row)
+            self.A[e.key] = list(e.acc)
         self.c_g[e.key] = max(self.c_g[e.key], e.c_c)
         return True
 
@@ -82,6 +95,7 @@ class BruteCache:
                 if not self.check_valid(e):
                     self.push(e)
                     e.row, e.acc = list(self.W[k]), list(self.A[k])
+                    e.row0, e.acc0 = list(e.row), list(e.acc)
                     e.c_s = e.c_c = self.c_g[k]
                     self.classes[k] = STALE
                 else:
@@ -121,6 +135,7 @@ class BruteCache:
         for e in self.entries:
             if self.push(e):
                 e.c_s = e.c_c = self.c_g[e.key]
+                e.row0, e.acc0 = list(e.row), list(e.acc)
 
     def state(self):
         """(key, slot, c_s, c_c, last_use, freq) of every cached row, ascending slot."""

@@ -30,14 +30,28 @@
  *   - Adagrad: a += g*g; x -= lr * g / (sqrt(a) + eps); the accumulator travels with the row.
  *   - flush() writes every dirty resident row back (the paper allows dropping them instead).
  *
+ * Several workers (het_oracle_set_many_writers): the literal form of Evict in Section 3.1.  Every
+ * worker has a cache of its own over the one global table.  Evict pushes what the worker has
+ * accumulated on the row since it fetched it (row now minus row as fetched; for SGD exactly the
+ * scaled sum of its gradients) and the server adds that to the global row, c_g = max(c_g, c_c).
+ * Fetch therefore keeps a copy of the row as fetched.  After a flush the replica keeps its own
+ * view and counts further changes from there.  CheckValid's second condition, c_g <= c_c + s, now
+ * matters: another worker's pushes advance c_g (Lemma 1 bounds the replicas' clocks through it).
+ * het_oracle_foreign_update is a push by a worker that is not modelled otherwise: the server adds
+ * a delta to the global row and advances its clock by one.
+ *
  * Floating point is HET_REAL (double unless overridden at compile time); compile with
  * -ffp-contract=off so that every operation rounds once.
  *
  * Pins (tests/test_oracle_*.py): a hand-worked trace, a list-based brute-force twin on tiny
  * inputs, a dense uncached trainer, the SGD closed form, a library Adagrad, clock-drift and
  * size invariants, the closed-form refresh count when nothing is evicted, and c_g equal to the
- * number of iterations that touched the key.  Which IDs LRU/LFU evict on the paper's own
- * datasets is "parity unpinned": the paper prints no worked example for it.
+ * number of iterations that touched the key.  Several workers (tests/test_oracle_multiwriter.py):
+ * with one worker the delta push equals the write-back; with two workers and SGD the flushed table
+ * equals the initial one minus lr times the sum of all gradients of both; CheckValid's bounds
+ * after every Read and Lemma 1's 2s bound at a common global clock; a two-worker brute-force twin.
+ * Which IDs LRU/LFU evict on the paper's own datasets is "parity unpinned": the paper prints no
+ * worked example for it.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -62,6 +76,7 @@ typedef struct het_oracle {
     /* configuration */
     int64_t C, P, max_ids, s;
     int32_t dim, policy, opt;
+    int32_t many;            /* several workers write the global table: Evict pushes deltas */
     real eps;
     /* global table (caller's arrays) */
     real *W, *A;
@@ -70,6 +85,7 @@ typedef struct het_oracle {
     /* cache slots 0..P-1 */
     int64_t *key;            /* -1 = free */
     real *row, *acc;
+    real *row0, *acc0;       /* many writers: the row (accumulator) as it was fetched */
     uint32_t *cs, *cc, *last_use, *freq;
     int64_t *slot_of;        /* [V], -1 = not cached: Cache.Find */
     int64_t size;
@@ -131,22 +147,53 @@ int het_oracle_attach(het_oracle *o, real *W, real *A, uint32_t *Cg, int64_t V)
 void het_oracle_destroy(het_oracle *o)
 {
     if (!o) return;
-    free(o->key); free(o->row); free(o->acc); free(o->cs); free(o->cc);
+    free(o->key); free(o->row); free(o->acc); free(o->row0); free(o->acc0); free(o->cs); free(o->cc);
     free(o->last_use); free(o->freq); free(o->slot_of);
     free(o->lk_key); free(o->lk_cls); free(o->lk_slot); free(o->ev_id);
     free(o);
 }
 
-/* Evict's push: the server takes the row and c_g = max(c_g, c_c)   (Section 3.1, Evict) */
+/* Call right after create: this cache is one of several workers' over one global table. */
+int het_oracle_set_many_writers(het_oracle *o)
+{
+    if (!o || o->W) return ERR_ARG;
+    o->many = 1;
+    o->row0 = (real *)calloc((size_t)o->P * o->dim, sizeof(real));
+    o->acc0 = (real *)calloc((size_t)o->P * o->dim, sizeof(real));
+    return ERR_NONE;
+}
+
+/* Evict's push: the server takes the row and c_g = max(c_g, c_c)   (Section 3.1, Evict).
+ * Several workers: it takes what this worker accumulated since its Fetch and adds it. */
 static int write_back(het_oracle *o, int64_t slot)
 {
     int64_t k = o->key[slot];
     if (o->cc[slot] == o->cs[slot]) return 0;          /* nothing accumulated */
-    memcpy(o->W + (size_t)k * o->dim, o->row + (size_t)slot * o->dim, sizeof(real) * o->dim);
-    if (o->opt == OPT_ADAGRAD)
-        memcpy(o->A + (size_t)k * o->dim, o->acc + (size_t)slot * o->dim, sizeof(real) * o->dim);
+    if (o->many) {
+        for (int32_t j = 0; j < o->dim; ++j) {
+            real d = o->row[(size_t)slot * o->dim + j] - o->row0[(size_t)slot * o->dim + j];
+            o->W[(size_t)k * o->dim + j] = o->W[(size_t)k * o->dim + j] + d;
+            if (o->opt == OPT_ADAGRAD) {
+                real da = o->acc[(size_t)slot * o->dim + j] - o->acc0[(size_t)slot * o->dim + j];
+                o->A[(size_t)k * o->dim + j] = o->A[(size_t)k * o->dim + j] + da;
+            }
+        }
+    } else {
+        memcpy(o->W + (size_t)k * o->dim, o->row + (size_t)slot * o->dim, sizeof(real) * o->dim);
+        if (o->opt == OPT_ADAGRAD)
+            memcpy(o->A + (size_t)k * o->dim, o->acc + (size_t)slot * o->dim, sizeof(real) * o->dim);
+    }
     if (o->cc[slot] > o->Cg[k]) o->Cg[k] = o->cc[slot];
     return 1;
+}
+
+/* Several workers: from here on the replica counts its changes anew. */
+static void rebase(het_oracle *o, int64_t slot)
+{
+    if (!o->many) return;
+    memcpy(o->row0 + (size_t)slot * o->dim, o->row + (size_t)slot * o->dim, sizeof(real) * o->dim);
+    if (o->opt == OPT_ADAGRAD)
+        memcpy(o->acc0 + (size_t)slot * o->dim, o->acc + (size_t)slot * o->dim, sizeof(real) * o->dim);
 }
 
 /* Fetch: read the global row, c_s = c_c = c_g   (Section 3.1, Fetch) */
@@ -156,6 +203,7 @@ static void fetch_into(het_oracle *o, int64_t k, int64_t slot)
     if (o->opt == OPT_ADAGRAD)
         memcpy(o->acc + (size_t)slot * o->dim, o->A + (size_t)k * o->dim, sizeof(real) * o->dim);
     o->cs[slot] = o->cc[slot] = o->Cg[k];
+    rebase(o, slot);
 }
 
 /* CheckValid: c_c <= c_s + s  and  c_g <= c_c + s   (Section 3.1, CheckValid).  Written as
@@ -373,9 +421,24 @@ int het_oracle_flush(het_oracle *o)
     for (int64_t slot = 0; slot < o->P; ++slot)
         if (o->key[slot] >= 0 && write_back(o, slot)) {
             o->cs[slot] = o->cc[slot] = o->Cg[o->key[slot]];
+            rebase(o, slot);
             st.flushed += 1;
         }
     o->last = st; add_stats(&o->total, &st);
+    return o->err;
+}
+
+/* A push by a worker that is not modelled otherwise (Section 3.1, Evict, the server's side): the
+ * server adds deltas[i][:] to the global row ids[i] and advances its clock by one. */
+int het_oracle_foreign_update(het_oracle *o, const int64_t *ids, const real *deltas, int64_t n)
+{
+    if (!o || !o->W || !ids || !deltas || n < 0) return ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= o->V) { o->err |= ERR_RANGE; continue; }
+        for (int32_t j = 0; j < o->dim; ++j)
+            o->W[(size_t)ids[i] * o->dim + j] = o->W[(size_t)ids[i] * o->dim + j] + deltas[(size_t)i * o->dim + j];
+        o->Cg[ids[i]] += 1;
+    }
     return o->err;
 }
 

@@ -40,6 +40,8 @@ def _load(real: str):
     lib.het_oracle_update.argtypes = [p, p, p, i64, rl]
     lib.het_oracle_update_pooled.argtypes = [p, p, i64, p, p, i64, rl]
     lib.het_oracle_flush.argtypes = [p]
+    lib.het_oracle_set_many_writers.argtypes = [p]
+    lib.het_oracle_foreign_update.argtypes = [p, p, p, i64]
     for f in ("export_state", "export_rows", "last_lookup", "last_evicted", "size", "iteration"):
         getattr(lib, "het_oracle_" + f).restype = i64
     lib.het_oracle_export_state.argtypes = [p] * 7
@@ -66,7 +68,10 @@ class Oracle:
     the oracle's own global table is `self.W` (and `self.A`, `self.Cg`)."""
 
     def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer, eps, table,
-                 real: str = "f64"):
+                 real: str = "f64", many_writers: bool = False, share_with: "Oracle" = None):
+        """`many_writers`: this cache is one of several workers' (Evict pushes deltas).
+        `share_with`: another Oracle whose global table (W, A, Cg) this one works on too;
+        `table` is then ignored."""
         self.lib = _load(real)
         self.dtype = np.float64 if real == "f64" else np.float32
         self.dim, self.P = dim, capacity + max_batch_ids
@@ -74,10 +79,15 @@ class Oracle:
                                             float(eps))
         if not self.h:
             raise ValueError("het_oracle_create rejected the arguments")
-        self.W = np.ascontiguousarray(table, dtype=self.dtype).copy()
+        if many_writers and self.lib.het_oracle_set_many_writers(self.h):
+            raise ValueError("het_oracle_set_many_writers failed")
+        if share_with is not None:
+            self.W, self.A, self.Cg = share_with.W, share_with.A, share_with.Cg
+        else:
+            self.W = np.ascontiguousarray(table, dtype=self.dtype).copy()
+            self.A = np.zeros_like(self.W) if optimizer == 1 else None
+            self.Cg = np.zeros(self.W.shape[0], dtype=np.uint32)
         V = self.W.shape[0]
-        self.A = np.zeros_like(self.W) if optimizer == 1 else None
-        self.Cg = np.zeros(V, dtype=np.uint32)
         rc = self.lib.het_oracle_attach(self.h, _ptr(self.W), _ptr(self.A), _ptr(self.Cg), V)
         if rc:
             raise ValueError("het_oracle_attach rejected the arguments")
@@ -119,6 +129,11 @@ class Oracle:
 
     def flush(self):
         return self.lib.het_oracle_flush(self.h)
+
+    def foreign_update(self, ids, deltas):
+        ids = np.ascontiguousarray(ids, dtype=np.int64)
+        d = np.ascontiguousarray(deltas, dtype=self.dtype)
+        return self.lib.het_oracle_foreign_update(self.h, _ptr(ids), _ptr(d), ids.size)
 
     def export_state(self):
         P = self.P
