@@ -28,10 +28,34 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch (fetch + write) read from rocprofv3 FETCH_SIZE / WRITE_SIZE counters and
-# scaled by a 256 MiB device copy of the same run (profiles/config2_hbm_traffic.md).  Keyed by
-# (kernel, workload); a workload that was not measured reports null.
-MEASURED_TRAFFIC = {("apply_kernel", 2): 92.0e6}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(kernel, config, build_id):
+    """HBM bytes per launch (fetch + write) of `kernel` on workload `config`, from the rocprofv3
+    FETCH_SIZE / WRITE_SIZE counter runs recorded in profiles/hbm_traffic.json (scaled there by a
+    256 MiB device copy of the same run).  The record names the build it was measured on; for any
+    other build of the library, or a workload that was not measured, the answer is None."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            rec = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    entry = rec.get(f"config{config}", {})
+    if entry.get("build_id") != build_id:
+        return None
+    return entry.get("bytes_per_launch", {}).get(kernel)
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown CPU"
 
 
 def algorithmic_bytes(w, c):
@@ -55,10 +79,11 @@ def kernel_bytes(w, c, name):
     U = c["unique_lookup"]
     if name == "apply_kernel":      # grads read, value (+accumulator) read and written, index arrays
         return w.n_grad_rows * R + 2 * U * Q * R + 4 * w.n + 12 * U
-    if name == "gather_kernel":     # cached rows read once per key, out written, index arrays
-        return U * R + w.n * R + 8 * w.n + 4 * U
-    if name == "pooled_gather_kernel":
-        return U * R + w.batch * R + 4 * w.n + 4 * U
+    if name == "fill_gather_kernel":
+        # cached rows read once per key, out written, fetched rows (and refreshed ones) read and
+        # written with their optimizer state, index arrays
+        moved = c["miss"] + c["stale"]
+        return U * R + w.n_grad_rows * R + 2 * moved * Q * R + 8 * w.n + 4 * U
     return None
 
 
@@ -231,7 +256,7 @@ def main():
     per_step["unique_lookup"] = per_step["unique"] / 2.0      # counted by lookup and by update
 
     # ---- per-kernel durations, HIP events around every launch (outside the timed region)
-    roofline, per_step_us = None, {}
+    roofline, per_step_us, kern = None, {}, {}
     if args.profile_steps > 0:
         cache.profile_begin()
         for t in range(W + K, total):
@@ -246,7 +271,7 @@ def main():
         achieved = dom_bytes / (kern[dominant]["avg_us"] * 1e-6) / 1e9
         roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                    "traffic": MEASURED_TRAFFIC.get((dominant, w.index)),
+                    "traffic": measured_traffic(dominant, w.index, hc.build_id()),
                     "bytes_per_launch": dom_bytes, "avg_us": kern[dominant]["avg_us"]}
     step_bytes = algorithmic_bytes(w, per_step)
 
@@ -270,6 +295,8 @@ def main():
                      "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "roofline": roofline,
+        "build_id": hc.build_id(),
+        "kernel_launches_per_step": round(sum(v["launches_per_step"] for v in kern.values()), 2) if per_step_us else None,
         "kernels_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda x: -x[1])},
     }
     if host:
@@ -303,7 +330,7 @@ def main():
             "value": 2.0 * w.n * done / cpu_s, "unit": "lookups+updates/s", "cores": 1,
             "kind": "oracle",
             "sample": f"first {done} iterations of the same stream from a cold cache, fp64 oracle, "
-                      f"{cpu_s:.1f} s on one host core (of {os.cpu_count()} visible)"}
+                      f"{cpu_s:.1f} s on one host core (of {os.cpu_count()} visible; {cpu_model()})"}
     cache.close()
     print(json.dumps(result))
 

@@ -249,6 +249,10 @@ const char *het_profile_kernel_name(int index);
 /* Waits for the stream, frees everything the library allocated.  NULL is allowed. */
 int het_cache_destroy(het_cache *c);
 
+/* Short hash of the sources this library was built from (set by the build script; "unknown"
+ * otherwise): lets a stored measurement say which build it belongs to. */
+const char *het_build_id(void);
+
 /* Static description of a status code. */
 const char *het_strerror(int status);
 

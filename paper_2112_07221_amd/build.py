@@ -2,6 +2,7 @@
 
     python -m paper_2112_07221_amd.build
 """
+import hashlib
 import os
 import subprocess
 
@@ -17,8 +18,20 @@ FLAGS = [
 ]
 
 
+def source_id() -> str:
+    """Short hash of the sources the library is built from (the header and everything in csrc/):
+    what `het_build_id()` returns, so that a measurement can name the build it was taken on."""
+    h = hashlib.sha256()
+    files = [os.path.join(HERE, "..", "include", "het_cache.h")]
+    files += sorted(os.path.join(HERE, "csrc", f) for f in os.listdir(os.path.join(HERE, "csrc")))
+    for f in files:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:12]
+
+
 def build(verbose: bool = False) -> str:
-    cmd = [HIPCC, *FLAGS, SRC, "-o", OUT]
+    cmd = [HIPCC, *FLAGS, f'-DHET_BUILD_ID="{source_id()}"', SRC, "-o", OUT]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

@@ -78,8 +78,6 @@ constexpr int PT_THREADS = 1024;                // probe tiles: 1024 sorted posi
 constexpr int PT_WAVES = PT_THREADS / WAVE;     // one per thread, so every probe's loads are in flight at once
 constexpr int PT_TILE = PT_THREADS;
 constexpr int VERIFY_TILE = 1024;                    // positions one workgroup of the id check covers
-constexpr int CHUNK_SHORT = 4, CHUNK_LONG = 8;       // sorted positions per row group in the apply kernel (template parameter CHUNK):
-                                                     // four keep the kernel's registers low; eight halve the partial sums of very long runs
 
 // Per-call workspaces (sized by max_batch_ids unless noted).  Per-key facts are stored at the
 // key's head position in the sorted order.
@@ -91,9 +89,6 @@ struct Workspace {
     uint32_t *tile_miss, *tile_stale;     // per probe tile counts
     uint2 *miss_stage, *stale_stage;      // per probe tile: (head position, key) of its missed / stale keys
     uint32_t *bag_of;             // pooled: bag of each original position
-    double *partial;              // apply: [chunks][2][dim] partial gradient sums of runs that cross chunk borders
-                                  // (a workgroup that lies inside one run stores one sum, in its first chunk's first place)
-    int32_t *cross_slot;          // apply: [chunks] slot of the run that starts in the chunk and crosses its back border
 };
 
 // CheckValid (Section 3.1): c_c <= c_s + s and c_g <= c_c + s, as differences so that an
@@ -135,6 +130,8 @@ struct TrimPlan {
     uint32_t *ev_ids;                  // ids dropped by this trim
     int ev_slot;                       // which of the two evicted-id counts (and staging buffers) this trim appends to
     uint32_t push_seq;                 // host-backed table: serial number of this trim (never 0)
+    uint32_t dirty_stamp;              // the tie count runs beside the optimizer step of the Read of this iteration's keys (0: it does not):
+                                       // every row that Read touched will hold updates when the step is done, whether its clock has moved yet or not
 };
 
 __device__ __forceinline__ uint64_t policy_key(const TrimPlan &tp, const uint4 &meta)
@@ -347,7 +344,7 @@ __device__ __forceinline__ void trim_count_body(const CacheView &cv, const TrimP
     for (int i = 0; i < COUNT_ITEMS; ++i) {
         const bool cached = key[i] != KEY_NONE;
         const uint64_t pk = policy_key(tp, meta[i]);
-        const bool dirty = meta[i].y > meta[i].x;
+        const bool dirty = meta[i].y > meta[i].x || (tp.dirty_stamp && meta[i].z == tp.dirty_stamp);
         if (cached && pk < tau) { lt += 1; dlt += dirty; }
         else if (cached && pk == tau) { eq += 1; deq += dirty; }
     }
@@ -923,23 +920,140 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
     *xp = xv;
 }
 
-// Update + Clock (Algorithm 3), first of two kernels.  Each row group takes CHUNK consecutive
-// sorted positions.  It loads their keys, original positions and slots, then - all in flight
-// together - their gradient rows and the cached rows (and accumulators) of the runs of equal
-// keys that lie inside the chunk.  The gradients of a run are summed in fp64 (the kernel is
-// bound by reading the gradients; summing wide makes a long run of a popular key lose no
-// digits) and rounded once to fp32.  A run inside the chunk is applied at once.  A run that
-// crosses a chunk border leaves one partial sum per chunk for the second kernel (one per
-// workgroup where all of a workgroup's chunks lie inside the run); the chunk in which it starts
-// also leaves the run's slot in cross_slot.
+// Update + Clock (Algorithm 3) in one kernel.  A workgroup takes a tile of AP_TILE consecutive
+// sorted positions, brings their keys, gradient rows' numbers and slots into LDS and lists the
+// tile's segments (stretches of equal keys; a run of equal keys is one segment unless it crosses a
+// tile border).  Work then goes by segment, not by position:
+//   - a segment of up to AP_SOLO positions is summed by one row group, AP_BATCH gradient rows in
+//     flight at a time, in order of position, in fp64 (the kernel is bound by reading the
+//     gradients; summing wide makes a long run of a popular key lose no digits), rounded once;
+//   - a longer one by all row groups of the workgroup together: contiguous shares, added in group
+//     order through LDS.
+// A segment that is a whole run gets the optimizer step and its clock at once: no partial sum ever
+// leaves the workgroup.  Only a run that crosses a tile border (at most two per tile) leaves one
+// fp64 partial sum per tile it touches in `ApplyBorders::part`, and the tile that arrives last at
+// the run's counter adds them up in tile order and applies the step: which tile is last varies,
+// the order of the additions does not.  Nobody waits for anybody.
 // VERIFY: the ids must be the ones the sorted order was built from (an update that reuses the
 // preceding lookup's order); extra workgroups compare them and flag any difference.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
-template <int VEC, int MAXC, bool VERIFY, int CHUNK>
-__global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, const int64_t *__restrict__ ids,
-                                                    const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
-                                                    float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
-                                                    SortStage ride, SortStage ride2)
+constexpr int AP_THREADS = 256;
+constexpr int AP_BATCH = 8;
+constexpr int AP_SOLO = 32;
+// Positions per tile (template parameter AP_TILE): 64 where a workgroup has eight row groups or
+// more (rows up to 128 floats), 128 for wider rows, whose fewer row groups would otherwise stand
+// idle beside the popular keys' long segments and pay for twice as many border crossings.
+__host__ __device__ constexpr int ap_tile_for(int lanes) { return lanes <= 32 ? 64 : 128; }
+
+template <int VEC, int AP_TILE> struct ApplyLds {
+    static_assert(AP_TILE + 2 <= AP_THREADS && AP_TILE % WAVE == 0, "one thread per position of the tile, two more for the keys outside it");
+    double share[AP_THREADS * VEC];      // the row groups' shares of a long segment
+    uint32_t key[AP_TILE + 2];           // [0]: key before the tile, [1 + i]: position i, [AP_TILE + 1]: key behind the tile
+    uint32_t grow[AP_TILE];              // gradient row of each position
+    int32_t slot[AP_TILE];               // slot of the key, valid at run heads
+    uint32_t seg_start[AP_TILE + 1];     // first position (within the tile) of every segment, then the tile's count
+    uint32_t wave_heads[AP_TILE / WAVE];
+};
+
+// How many of the conditions cond(1), cond(2), ... hold before the first that does not; found by
+// a whole wave, 64 at a time.  cond must be false from some index on.
+template <typename F>
+__device__ __forceinline__ uint32_t wave_count_leading(F cond)
+{
+    uint32_t base = 0;
+    for (;;) {
+        const uint64_t m = __ballot(cond(base + lane_id() + 1));
+        if (~m) return base + (uint32_t)__builtin_ctzll(~m);
+        base += WAVE;
+    }
+}
+
+// Adds the gradient rows of tile positions [lo, hi) for row piece cidx to acc64, in order, in fp64.
+// If `with_row`, the cached row (and accumulator) of `slot` is requested together with the first
+// batch of gradients.
+template <int VEC>
+__device__ __forceinline__ void add_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
+                                              int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
+                                              typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar)
+{
+    using V = typename VecT<VEC>::type;
+    const int dim = cv.geom.dim;
+    for (uint32_t b0 = lo; b0 < hi; b0 += AP_BATCH) {
+        V v[AP_BATCH];
+#pragma unroll
+        for (int r = 0; r < AP_BATCH; ++r) {
+            v[r] = V{};
+            if (act && b0 + r < hi) v[r] = reinterpret_cast<const V *>(grads + (size_t)grow[b0 + r] * dim)[cidx];
+        }
+        if (with_row && b0 == lo && act) {
+            xr = reinterpret_cast<const V *>(cv.rows + (size_t)slot * dim)[cidx];
+            if (cv.adagrad) ar = reinterpret_cast<const V *>(cv.acc + (size_t)slot * dim)[cidx];
+        }
+#pragma unroll
+        for (int r = 0; r < AP_BATCH; ++r) {
+            const float *vf = reinterpret_cast<const float *>(&v[r]);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc64[e] += (double)vf[e];          // zero where there is no position
+        }
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void sum_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
+                                              int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
+                                              typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar)
+{
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
+    add_positions<VEC>(cv, grads, grow, lo, hi, cidx, act, acc64, with_row, slot, xr, ar);
+}
+
+struct SegWork {
+    uint32_t a, b;             // positions [a, b) of the tile
+    int32_t slot;
+    bool is_front, is_back;    // the run began in an earlier tile / goes on in a later one
+};
+
+// The optimizer step from a row already in registers.
+template <int VEC>
+__device__ __forceinline__ void apply_loaded(const CacheView &cv, uint32_t slot, int cidx, const double *g64, float lr, float eps,
+                                             typename VecT<VEC>::type xv, typename VecT<VEC>::type av)
+{
+    using V = typename VecT<VEC>::type;
+    float *x = reinterpret_cast<float *>(&xv), *a = reinterpret_cast<float *>(&av);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const float G = (float)g64[e];                                        // the fp64 sum is rounded once
+        if (cv.adagrad) { a[e] += G * G; x[e] -= lr * G * fast_rcp(fast_sqrt(a[e]) + eps); }
+        else x[e] -= lr * G;
+    }
+    reinterpret_cast<V *>(cv.rows + (size_t)slot * cv.geom.dim)[cidx] = xv;
+    if (cv.adagrad) reinterpret_cast<V *>(cv.acc + (size_t)slot * cv.geom.dim)[cidx] = av;
+}
+
+// What the tiles of one run tell each other inside the kernel goes through loads, stores and
+// read-modify-writes of device scope, which are coherent over the whole GPU by themselves (its
+// L2 caches are per XCD and ordinary stores may stay in one of them until the kernel ends).  So no
+// cache has to be written back or invalidated as a device-scope fence would do, thousands of
+// times per kernel: a tile waits for its own stores to be acknowledged, and only then counts
+// itself as arrived.
+__device__ __forceinline__ void st_device(double *p, double v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ double ld_device(const double *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_device(int32_t *p, int32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ int32_t ld_device(const int32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void stores_acknowledged() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+struct ApplyBorders {
+    double *part;          // [tiles][2][dim]: sum of the segment that came in through the tile's front border / that leaves through its back border
+    int32_t *slot;         // [tiles]: slot of the run that leaves through the tile's back border (it starts in this tile)
+    uint32_t *arrived;     // [tiles]: how many tiles of the run that starts in this tile have stored their sums (zero between kernels)
+};
+
+template <int VEC, int MAXC, bool VERIFY, int AP_TILE>
+__global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
+                                                           const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
+                                                           float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
+                                                           SortStage ride, SortStage ride2)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
@@ -953,13 +1067,12 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
     bid -= stage_blocks;
     if (VERIFY && bid < verify_blocks) {
         // The ids must be the ones the sorted order was built from: every position's id against the
-        // sorted key, by workgroups of their own (in the row groups the check cost registers, and
-        // with them a fifth of the kernel's occupancy).  A difference is flagged; the update goes on.
+        // sorted key, by workgroups of their own.  A difference is flagged; the update goes on.
         const uint32_t nvv = cv.ds->n_valid;
         bool bad = false;
 #pragma unroll
-        for (int i = 0; i < VERIFY_TILE / 256; ++i) {
-            const uint32_t j = bid * VERIFY_TILE + i * 256u + threadIdx.x;
+        for (int i = 0; i < VERIFY_TILE / AP_THREADS; ++i) {
+            const uint32_t j = bid * VERIFY_TILE + i * AP_THREADS + threadIdx.x;
             if (j < nvv) bad |= ids[ws.perm[j]] != (int64_t)ws.skey[j];
         }
         if (__any(bad) && lane_id() == 0) atomicOr(&cv.ds->err, ERRBIT_STATE);
@@ -967,11 +1080,9 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
     }
     bid -= verify_blocks;
     const RowGeom g = cv.geom;
-    const uint32_t gid = (bid * 256u + threadIdx.x) / g.lanes;
+    const uint32_t group = threadIdx.x / g.lanes, ngroups = AP_THREADS / g.lanes;
     const int gl = threadIdx.x % g.lanes;
-    const uint32_t ngroups = work_blocks * 256u / g.lanes;
     const uint32_t nv = cv.ds->n_valid;
-    const uint32_t *skey = ws.skey;
     if (VERIFY && bid == 0 && threadIdx.x == 0) {
         // this call did not sort: its per-call counters start here, with the lookup's key count
         DState *ds = cv.ds;
@@ -982,375 +1093,197 @@ __global__ __launch_bounds__(256) void apply_kernel(CacheView cv, Workspace ws, 
         atomicAdd(&ds->total.unique, (unsigned long long)ds->n_unique);
         if (nv < n_ids) atomicOr(&ds->err, ERRBIT_RANGE);      // the order holds ids outside the vocabulary
     }
-
-    const uint32_t nchunks_max = (n_ids + CHUNK - 1) / CHUNK;      // known to the host; nv <= n_ids
-    uint32_t cb = bid * (256u / g.lanes);                          // first chunk of the workgroup
-    for (uint32_t c = gid; c < nchunks_max; c += ngroups, cb += ngroups) {
-        const uint32_t j0 = c * CHUNK;
-        // loaded for every position the call has, then masked by the valid count (read meanwhile)
-        uint32_t k[CHUNK], p[CHUNK];
-        int32_t hs[CHUNK];
-#pragma unroll
-        for (int i = 0; i < CHUNK; ++i) {
-            const bool in = j0 + i < n_ids;
-            k[i] = in ? skey[j0 + i] : KEY_NONE;
-            p[i] = in ? ws.perm[j0 + i] : 0u;
-            hs[i] = in ? ws.head_slot[j0 + i] : SLOT_NONE;
-        }
-        const uint32_t before_key = j0 > 0 ? skey[j0 - 1] : KEY_NONE;
-        const uint32_t after_key = j0 + CHUNK < n_ids ? skey[j0 + CHUNK] : KEY_NONE;
-        // a workgroup whose chunks all lie inside one run (a popular key) leaves one partial sum,
-        // not one per chunk: the keys just outside its positions are equal
-        // (uniform over the workgroup: read through the scalar unit, the keys are not written here)
-        typedef const uint32_t __attribute__((address_space(4))) *scalar_u32;
-        const uint32_t bj0 = cb * CHUNK, bj1 = bj0 + (256u / g.lanes) * CHUNK;
-        bool through = false;
-        if (bj0 > 0 && bj1 < nv) through = ((scalar_u32)(uintptr_t)skey)[bj0 - 1] == ((scalar_u32)(uintptr_t)skey)[bj1];
-        if (j0 >= nv) break;
-        const uint32_t cnt = min((uint32_t)CHUNK, nv - j0);
-#pragma unroll
-        for (int i = 0; i < CHUNK; ++i) if ((uint32_t)i >= cnt) { k[i] = KEY_NONE; hs[i] = SLOT_NONE; }
-        const uint32_t prev_key = before_key;
-        const uint32_t next_key = cnt == CHUNK && j0 + CHUNK < nv ? after_key : KEY_NONE;
-        uint32_t last_key = KEY_NONE;
-#pragma unroll
-        for (int i = 0; i < CHUNK; ++i) last_key = (uint32_t)i < cnt ? k[i] : last_key;
-        const bool open_front = prev_key == k[0];           // the first run began in an earlier chunk
-        const bool open_back = next_key == last_key;        // the last run goes on in a later chunk
-
-        const uint32_t inm = (1u << cnt) - 1u;
-        uint32_t heads = 0, whole = 0;                      // bit i: run head / head of a run inside the chunk
-#pragma unroll
-        for (int i = 0; i < CHUNK; ++i) {
-            const bool in = (uint32_t)i < cnt;
-            const bool head = in && (i == 0 || k[i] != k[i - 1]);
-            heads |= head ? (1u << i) : 0u;
-            const bool inside = head && !(i == 0 && open_front) && !(k[i] == last_key && open_back);
-            whole |= (inside && hs[i] != SLOT_NONE) ? (1u << i) : 0u;
-        }
-        if (grad_row) {
-#pragma unroll
-            for (int i = 0; i < CHUNK; ++i) if ((uint32_t)i < cnt) p[i] = grad_row[p[i]];
-        }
-        if (through) {
-            // every position of every chunk belongs to the run: the chunks' sums are added in chunk
-            // order and stored where the workgroup's first chunk would have put its own
-            if (gl == 0) ws.cross_slot[c] = SLOT_NONE;
-            double *share = reinterpret_cast<double *>(dyn_lds);
-#pragma unroll
-            for (int q = 0; q < MAXC; ++q) {
-                const int cidx = gl + q * g.lanes;
-                const bool act = cidx < g.chunks;
-                V v[CHUNK];
-#pragma unroll
-                for (int i = 0; i < CHUNK; ++i) v[i] = act ? reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx] : V{};
-                double acc64[VEC];
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
-#pragma unroll
-                for (int i = 0; i < CHUNK; ++i) {
-                    const float *vf = reinterpret_cast<const float *>(&v[i]);
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) acc64[e] += (double)vf[e];
-                }
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) share[threadIdx.x * VEC + e] = acc64[e];
-                __syncthreads();
-                if (threadIdx.x < (uint32_t)g.lanes && act) {
-                    double tot[VEC];
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) tot[e] = 0.0;
-                    for (uint32_t gi = 0; gi < 256u / g.lanes; ++gi)
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) tot[e] += share[(gi * g.lanes + gl) * VEC + e];
-                    double *mine = ws.partial + (size_t)c * 2 * (size_t)g.dim + (size_t)cidx * VEC;
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) mine[e] = tot[e];
-                }
-            }
-            continue;
-        }
-        // the run that starts here and leaves through the back border is finished by the second kernel
-        int32_t cross = SLOT_NONE;
-        if (gl == 0) {
-            if (open_back) {
-#pragma unroll
-                for (int i = 0; i < CHUNK; ++i)
-                    if (((heads >> i) & 1u) && k[i] == last_key && !(i == 0 && open_front)) cross = hs[i];
-            }
-            ws.cross_slot[c] = cross;
-        }
-#pragma unroll
-        for (int q = 0; q < MAXC; ++q) {
-            const int cidx = gl + q * g.lanes;
-            const bool act = cidx < g.chunks;
-            V v[CHUNK], xr[CHUNK], ar[CHUNK];
-#pragma unroll
-            for (int i = 0; i < CHUNK; ++i) {
-                v[i] = V{}; xr[i] = V{}; ar[i] = V{};
-                if (act && ((inm >> i) & 1u)) v[i] = reinterpret_cast<const V *>(grads + (size_t)p[i] * g.dim)[cidx];
-                if (act && ((whole >> i) & 1u)) {
-                    xr[i] = reinterpret_cast<const V *>(cv.rows + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
-                    if (cv.adagrad) ar[i] = reinterpret_cast<const V *>(cv.acc + (size_t)(uint32_t)hs[i] * g.dim)[cidx];
-                }
-            }
-            double acc64[VEC];
-            V cur_x{}, cur_a{};
-            int32_t cur_slot = SLOT_NONE;
-            bool cur_whole = false, cur_front = false;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
-#pragma unroll
-            for (int i = 0; i < CHUNK; ++i) {
-                const bool in = (uint32_t)i < cnt;
-                if ((heads >> i) & 1u) {
-                    cur_x = xr[i]; cur_a = ar[i]; cur_slot = hs[i];
-                    cur_whole = (whole >> i) & 1u;
-                    cur_front = i == 0 && open_front;
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
-                }
-                const float *vf = reinterpret_cast<const float *>(&v[i]);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc64[e] += (double)vf[e];       // v[i] is zero where it does not count
-                bool run_ends = in && (uint32_t)(i + 1) == cnt;
-                if (i + 1 < CHUNK) run_ends = run_ends || (in && (uint32_t)(i + 1) < cnt && k[i + 1] != k[i]);
-                if (!run_ends) continue;
-                if (cur_whole) {
-                    if (act) {
-                        float G[VEC];
-                        float *x = reinterpret_cast<float *>(&cur_x), *a = reinterpret_cast<float *>(&cur_a);
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) {
-                            G[e] = (float)acc64[e];                            // the fp64 sum is rounded once
-                            if (cv.adagrad) { a[e] += G[e] * G[e]; x[e] -= lr * G[e] * fast_rcp(fast_sqrt(a[e]) + eps); }
-                            else x[e] -= lr * G[e];
-                        }
-                        reinterpret_cast<V *>(cv.rows + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_x;
-                        if (cv.adagrad) reinterpret_cast<V *>(cv.acc + (size_t)(uint32_t)cur_slot * g.dim)[cidx] = cur_a;
-                    }
-                    if (q == 0 && gl == 0 && !cv.direct) atomicAdd(&cv.meta[cur_slot].cc, 1u);      // Clock(k) (nothing to wait for)
-                } else if (act && (cur_front || (k[i] == last_key && open_back))) {
-                    // slot 0 of the chunk: a run that came in through the front border;
-                    // slot 1: a run that starts here and leaves through the back border
-                    double *mine = ws.partial + ((size_t)c * 2 + (cur_front ? 0 : 1)) * (size_t)g.dim + (size_t)cidx * VEC;
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) mine[e] = acc64[e];
-                }
-            }
-        }
-        // Clock(k) of the run that leaves through the back border is taken here already: the second
-        // kernel carries the stage of the trim's select that counts which rows hold updates, and
-        // must not move clocks under it
-        if (cross != SLOT_NONE && !cv.direct) atomicAdd(&cv.meta[cross].cc, 1u);
-    }
-}
-
-// Second kernel of Write: finishes the runs that cross chunk borders.  The group of the chunk
-// in which such a run starts adds the run's partial sums in chunk order and applies the step
-// (the run's clock was advanced by the first kernel).
-// A run spread over more than FIN_NEAR + 1 chunks (a popular key) is summed by a wave, and one
-// over more than FIN_WAVE chunks by the whole workgroup: every group adds a contiguous share of
-// the partial sums in order, and the shares are added in group order.  Either way the order of additions is fixed by the sorted
-// order alone.
-// The partial sums of a run whose head lies in chunk c and whose last position lies in chunk c1,
-// in order: those of the chunks up to the first workgroup of the first kernel that lay inside the
-// run as a whole, one per such workgroup (G chunks each), those of the chunks after the last.
-struct RunParts {
-    uint32_t c, G, h, nb, b0, t0, m;       // m = h + nb + tail items
-    __device__ __forceinline__ RunParts(uint32_t c_, uint32_t c1, uint32_t G_) : c(c_), G(G_)
-    {
-        b0 = c / G + 1;
-        const uint32_t b1 = c1 / G;                      // workgroups b0 .. b1 - 1 lay inside the run
-        if (b1 > b0) { h = b0 * G - c; nb = b1 - b0; t0 = b1 * G; m = h + nb + (c1 - t0 + 1); }
-        else { h = c1 - c + 1; nb = 0; t0 = 0; m = h; }
-    }
-    // where item i is in units of chunk slots (a chunk has two: run came in / run goes out)
-    __device__ __forceinline__ size_t at(uint32_t i) const
-    {
-        const uint32_t chunk = i < h ? c + i : (i < h + nb ? (b0 + (i - h)) * G : t0 + (i - h - nb));
-        return (size_t)chunk * 2 + (i == 0 ? 1 : 0);
-    }
-};
-
-constexpr int FIN_NEAR = 4;
-constexpr int FIN_WAVE = 48;        // partial sums up to which one wave finishes a run
-template <int VEC> struct FinishLds {
-    double share[256 * VEC];
-    uint32_t long_c[256], long_c1[256], mid_c[256], mid_c1[256];
-    int32_t long_slot[256], mid_slot[256];
-    uint32_t n_long, n_mid;
-};
-template <int VEC, int MAXC, int CHUNK>
-__global__ __launch_bounds__(256) void apply_finish_kernel(CacheView cv, Workspace ws, float lr, float eps, uint32_t n_ids,
-                                                           uint32_t work_blocks, TrimPlan tp, int stage, SortStage ride, SortStage ride2)
-{
-    uint32_t bid = blockIdx.x, nblk = gridDim.x;
-    if (run_carried(ride, ride2, bid, nblk)) return;
-    const uint32_t stage_blocks = nblk - work_blocks;
-    if (bid < stage_blocks) {            // extra workgroups, ahead of the others: the next stage of the trim's select
-        trim_stage_body(cv, tp, stage, bid, stage_blocks, lds_as<TrimLds>());
-        return;
-    }
-    bid -= stage_blocks;
-    FinishLds<VEC> &fl = lds_as<FinishLds<VEC>>();
-    uint32_t *long_c = fl.long_c, *long_c1 = fl.long_c1;
-    int32_t *long_slot = fl.long_slot;
-    uint32_t &n_long = fl.n_long;
-    double *share = fl.share;
-    const RowGeom g = cv.geom;
-    const uint32_t groups_per_block = 256u / g.lanes;
-    const uint32_t group = threadIdx.x / g.lanes;
-    const int gl = threadIdx.x % g.lanes;
-    const uint32_t nv = cv.ds->n_valid;
-    const uint32_t nchunks_max = (n_ids + CHUNK - 1) / CHUNK;
+    ApplyLds<VEC, AP_TILE> &l = lds_as<ApplyLds<VEC, AP_TILE>>();
+    const uint32_t T = bid, j0 = T * AP_TILE;
     const uint32_t *skey = ws.skey;
-    const size_t pstride = (size_t)g.dim;
-    if (threadIdx.x == 0) { n_long = 0; fl.n_mid = 0; }
+    {   // the tile: one position per thread, and the keys just outside it
+        const uint32_t i = threadIdx.x;
+        if (i < AP_TILE) {
+            const uint32_t j = j0 + i;
+            const bool in = j < n_ids;
+            const uint32_t k = in ? skey[j] : KEY_NONE;
+            uint32_t pm = in ? ws.perm[j] : 0u;
+            const int32_t hs = in ? ws.head_slot[j] : SLOT_NONE;
+            if (grad_row && in) pm = grad_row[pm];
+            l.key[1 + i] = j < nv ? k : KEY_NONE;
+            l.grow[i] = pm;
+            l.slot[i] = hs;
+        } else if (i == AP_TILE) {
+            l.key[0] = j0 > 0 && j0 < n_ids ? skey[j0 - 1] : KEY_NONE;
+        } else if (i == AP_TILE + 1) {
+            const uint32_t jn = j0 + AP_TILE;
+            const uint32_t k = jn < n_ids ? skey[jn] : KEY_NONE;
+            l.key[AP_TILE + 1] = jn < nv ? k : KEY_NONE;
+        }
+    }
+    if (j0 >= nv) return;                                  // (uniform: nothing valid in this tile)
+    const uint32_t cnt = min((uint32_t)AP_TILE, nv - j0);
     __syncthreads();
-
-    for (uint32_t base = bid * groups_per_block; base < nchunks_max; base += work_blocks * groups_per_block) {
-        const uint32_t c = base + group;
-        const uint32_t jb = (c + 1) * CHUNK;                       // first position of the next chunk
-        int32_t slot = SLOT_NONE;
-        uint32_t key = KEY_NONE, nxt[FIN_NEAR];
-        if (c < nchunks_max) {
-            slot = ws.cross_slot[c];
-            key = jb < n_ids ? skey[jb] : KEY_NONE;
-#pragma unroll
-            for (int d = 0; d < FIN_NEAR; ++d) { const uint32_t jj = jb + (d + 1) * CHUNK; nxt[d] = jj < n_ids ? skey[jj] : KEY_NONE; }
-        }
-        const bool mine = c < nchunks_max && jb < nv && slot != SLOT_NONE;
-        uint32_t c1 = c + 1;                                       // last chunk that holds part of the run
-        bool open = mine;
-#pragma unroll
-        for (int d = 0; d < FIN_NEAR; ++d) {
-            open = open && (jb + (d + 1) * CHUNK < nv) && nxt[d] == key;
-            if (open) c1 = c + 2 + d;
-        }
-        // where a run that reaches past the near chunks ends (all lanes of the wave take part in the search)
-        const uint32_t far_end = g.lanes >= 4 ? group_run_end(skey, jb + FIN_NEAR * CHUNK, nv, key, open, g.lanes)
-                                              : (open ? run_end(skey, jb + FIN_NEAR * CHUNK, nv, key) : 0u);
-        if (open) {                                                // for a wave, or for the whole workgroup
-            c1 = (far_end - 1) / CHUNK;
-            if (gl == 0) {
-                if (RunParts(c, c1, groups_per_block).m > FIN_WAVE) { const uint32_t at = atomicAdd(&n_long, 1u); long_c[at] = c; long_c1[at] = c1; long_slot[at] = slot; }
-                else { const uint32_t at = atomicAdd(&fl.n_mid, 1u); fl.mid_c[at] = c; fl.mid_c1[at] = c1; fl.mid_slot[at] = slot; }
-            }
-        } else if (mine) {
-#pragma unroll
-            for (int q = 0; q < MAXC; ++q) {
-                const int cidx = gl + q * g.lanes;
-                if (cidx >= g.chunks) continue;
-                // the run's partial sums (at most FIN_NEAR + 1) and its row, all requested at once
-                double part[FIN_NEAR + 1][VEC];
-#pragma unroll
-                for (int d = 0; d <= FIN_NEAR; ++d) {
-                    const uint32_t cc_ = c + d;
-                    const double *pp = ws.partial + ((size_t)cc_ * 2 + (d == 0 ? 1 : 0)) * pstride + (size_t)cidx * VEC;
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) part[d][e] = cc_ <= c1 ? pp[e] : 0.0;
-                }
-                double sum[VEC];
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) sum[e] = part[0][e];
-#pragma unroll
-                for (int d = 1; d <= FIN_NEAR; ++d)
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) sum[e] += part[d][e];
-                apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps);
-            }
-        }
+    {   // the segments, in order
+        const uint32_t i = threadIdx.x;
+        const bool head = i < cnt && (i == 0 || l.key[i] != l.key[1 + i]);
+        const uint64_t m = __ballot(head);
+        const uint32_t w = i / WAVE;
+        if (i < AP_TILE && lane_id() == 0) l.wave_heads[w] = (uint32_t)__popcll(m);
         __syncthreads();
-        {   // runs of middling length: one per wave, the waves side by side.  The row groups of the
-            // wave add contiguous shares of the run's partial sums in order (four at a time), and the
-            // shares are added in group order, fetched from the other groups' lanes.
-            const uint32_t wave = threadIdx.x / WAVE, gpw = WAVE / g.lanes, gw = (threadIdx.x % WAVE) / g.lanes;
-            const uint32_t nm = fl.n_mid;
-            for (uint32_t mi = wave; mi < nm; mi += 256 / WAVE) {
-                const RunParts rp(fl.mid_c[mi], fl.mid_c1[mi], groups_per_block);
-                const uint32_t m = rp.m;
-                const int32_t mslot = fl.mid_slot[mi];
-                const uint32_t per = (m + gpw - 1) / gpw;
-                const uint32_t lo = min(gw * per, m), hi = min(lo + per, m);
+        uint32_t before = 0, total = 0;
 #pragma unroll
-                for (int q = 0; q < MAXC; ++q) {
-                    const int cidx = gl + q * g.lanes;
-                    const bool act = cidx < g.chunks;
-                    double sum[VEC];
+        for (int ww = 0; ww < AP_TILE / WAVE; ++ww) { const uint32_t c = l.wave_heads[ww]; before += (uint32_t)ww < w ? c : 0u; total += c; }
+        if (head) l.seg_start[before + mask_rank(m)] = i;
+        if (i == 0) l.seg_start[total] = cnt;
+        __syncthreads();
+    }
+    uint32_t nseg = 0;
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
-                    for (uint32_t i0 = lo; i0 < hi; i0 += 4) {
-                        double part[4][VEC];
+    for (int ww = 0; ww < AP_TILE / WAVE; ++ww) nseg += l.wave_heads[ww];
+    const bool front_open = l.key[0] != KEY_NONE && l.key[0] == l.key[1];                   // the first segment's run began in an earlier tile
+    const bool back_open = cnt == AP_TILE && l.key[AP_TILE + 1] != KEY_NONE && l.key[AP_TILE + 1] == l.key[AP_TILE];   // the last one's goes on
+    const size_t pstride = (size_t)g.dim;
+    // Which tiles the runs that cross this tile's borders touch is asked now, by the two waves that
+    // will finish them (see below), so that the answer is there when the sums are.
+    const uint32_t wave = threadIdx.x / WAVE;
+    const bool through = front_open && back_open && nseg == 1;
+    const bool do_front = wave == 0 && front_open, do_back = wave == 1 && back_open && !through;
+    uint32_t T0 = T, T1 = T;
+    if (do_front || do_back) {
+        const uint32_t key = do_front ? l.key[1] : l.key[AP_TILE];
+        if (do_front)            // tiles before this one that the run also entered through their front border
+            T0 = T - 1 - wave_count_leading([&](uint32_t i) { return i < T && skey[(size_t)(T - i) * AP_TILE - 1] == key; });
+        if (do_back || through)  // tiles behind this one that the run also leaves through their back border
+            T1 = T + 1 + wave_count_leading([&](uint32_t i) { const uint64_t je = ((uint64_t)T + i + 1) * AP_TILE; return je < nv && skey[je] == key; });
+    }
+    // (does any segment need the whole workgroup?  every thread looks at one)
+    const bool any_long = __syncthreads_or(threadIdx.x < nseg && l.seg_start[threadIdx.x + 1] - l.seg_start[threadIdx.x] > AP_SOLO) != 0;
+
+    // segments of up to AP_SOLO positions: one row group each
+    auto seg_work = [&](uint32_t sg) {
+        SegWork w;
+        w.a = l.seg_start[sg]; w.b = l.seg_start[sg + 1];
+        w.is_front = sg == 0 && front_open; w.is_back = sg + 1 == nseg && back_open;
+        w.slot = w.is_front ? SLOT_NONE : l.slot[w.a];
+        return w;
+    };
+    // what is left to do once the segment's sum for row piece cidx is there
+    auto finish_piece = [&](const SegWork &w, int cidx, bool act, const double (&acc64)[VEC], V xr, V ar) {
+        const bool closed = !w.is_front && !w.is_back;
+        if (closed) {
+            if (act && w.slot != SLOT_NONE) apply_loaded<VEC>(cv, (uint32_t)w.slot, cidx, acc64, lr, eps, xr, ar);
+        } else if (act) {
+            double *mine = bd.part + ((size_t)T * 2 + (w.is_front ? 0 : 1)) * pstride + (size_t)cidx * VEC;
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const uint32_t i = i0 + u;
-                            const double *pp = ws.partial + rp.at(i < m ? i : 0u) * pstride + (size_t)cidx * VEC;
-#pragma unroll
-                            for (int e = 0; e < VEC; ++e) part[u][e] = (act && i < hi) ? pp[e] : 0.0;
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-#pragma unroll
-                            for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
-                    }
-                    double tot[VEC];
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) tot[e] = 0.0;
-                    for (uint32_t gi = 0; gi < gpw; ++gi)
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) tot[e] += __shfl(sum[e], (int)(gi * g.lanes + gl), WAVE);
-                    if (gw == 0 && act) apply_step<VEC>(cv, (uint32_t)mslot, cidx, tot, lr, eps);
-                }
-            }
+            for (int e = 0; e < VEC; ++e) st_device(mine + e, acc64[e]);
         }
-        const uint32_t nl = n_long;
-        for (uint32_t li = 0; li < nl; ++li) {                     // very long runs, one at a time, whole workgroup
-            const RunParts rp(long_c[li], long_c1[li], groups_per_block);
-            const int32_t lslot = long_slot[li];
-            const uint32_t m = rp.m;                               // partial sums of the run
-            const uint32_t per = (m + groups_per_block - 1) / groups_per_block;
-            const uint32_t lo = min(group * per, m), hi = min(lo + per, m);
+    };
+    auto finish_segment = [&](const SegWork &w) {
+        if (gl == 0) {
+            if (w.is_back && !w.is_front) st_device(&bd.slot[T], w.slot);
+            // Clock(k): once per key per Write; a run that goes on in later tiles takes it where it starts
+            if (!w.is_front && w.slot != SLOT_NONE && !cv.direct) atomicAdd(&cv.meta[w.slot].cc, 1u);
+        }
+        if (w.is_front || w.is_back) stores_acknowledged();   // the partial sum, before this tile is counted as arrived
+    };
+    {
+        for (uint32_t sg = group; sg < nseg; sg += ngroups) {
+            const SegWork w = seg_work(sg);
+            if (w.b - w.a > AP_SOLO) continue;
+            const bool step = !w.is_front && !w.is_back && w.slot != SLOT_NONE;
 #pragma unroll
             for (int q = 0; q < MAXC; ++q) {
                 const int cidx = gl + q * g.lanes;
                 const bool act = cidx < g.chunks;
-                double sum[VEC];
+                double acc64[VEC];
+                V xr{}, ar{};
+                sum_positions<VEC>(cv, grads, l.grow, w.a, w.b, cidx, act, acc64, step, (uint32_t)w.slot, xr, ar);
+                finish_piece(w, cidx, act, acc64, xr, ar);
+            }
+            finish_segment(w);
+        }
+    }
+    if (any_long) {
+        // longer segments (a popular key): all row groups together, one segment at a time
+        for (uint32_t sg = 0; sg < nseg; ++sg) {
+            const uint32_t a = l.seg_start[sg], b = l.seg_start[sg + 1];
+            if (b - a <= AP_SOLO) continue;
+            const bool is_front = sg == 0 && front_open, is_back = sg + 1 == nseg && back_open;
+            const int32_t slot = is_front ? SLOT_NONE : l.slot[a];
+            const bool closed = !is_front && !is_back;
+            const bool step = closed && slot != SLOT_NONE;
+            const uint32_t per = (b - a + ngroups - 1) / ngroups;
+            const uint32_t lo = min(a + group * per, b), hi = min(lo + per, b);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
-                for (uint32_t i0 = lo; i0 < hi; i0 += 4) {
-                    double part[4][VEC];
+            for (int q = 0; q < MAXC; ++q) {
+                const int cidx = gl + q * g.lanes;
+                const bool act = cidx < g.chunks;
+                double acc64[VEC];
+                V xr{}, ar{};
+                sum_positions<VEC>(cv, grads, l.grow, lo, hi, cidx, act, acc64, step && group == 0, (uint32_t)slot, xr, ar);
+                __syncthreads();                            // (the shares of the piece before have been read)
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const uint32_t i = i0 + u;
-                        const double *pp = ws.partial + rp.at(i < m ? i : 0u) * pstride + (size_t)cidx * VEC;
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) part[u][e] = (act && i < hi) ? pp[e] : 0.0;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
-                }
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) share[threadIdx.x * VEC + e] = sum[e];
+                for (int e = 0; e < VEC; ++e) l.share[threadIdx.x * VEC + e] = acc64[e];
                 __syncthreads();
                 if (group == 0 && act) {
                     double tot[VEC];
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) tot[e] = 0.0;
-                    for (uint32_t gi = 0; gi < groups_per_block; ++gi)
+                    for (uint32_t gi = 0; gi < ngroups; ++gi)
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e) tot[e] += share[(gi * g.lanes + gl) * VEC + e];
-                    apply_step<VEC>(cv, (uint32_t)lslot, cidx, tot, lr, eps);
+                        for (int e = 0; e < VEC; ++e) tot[e] += l.share[(gi * g.lanes + gl) * VEC + e];
+                    if (step) apply_loaded<VEC>(cv, (uint32_t)slot, cidx, tot, lr, eps, xr, ar);
+                    else if (!closed) {
+                        double *mine = bd.part + ((size_t)T * 2 + (is_front ? 0 : 1)) * pstride + (size_t)cidx * VEC;
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) st_device(mine + e, tot[e]);
+                    }
                 }
             }
+            if (threadIdx.x == 0) {
+                if (is_back && !is_front) st_device(&bd.slot[T], slot);
+                if (!is_front && slot != SLOT_NONE && !cv.direct) atomicAdd(&cv.meta[slot].cc, 1u);
+            }
+            if (!closed && group == 0) stores_acknowledged();
         }
-        __syncthreads();
-        if (threadIdx.x == 0) { n_long = 0; fl.n_mid = 0; }
-        __syncthreads();
+    }
+    if (!front_open && !back_open) return;
+
+    // Runs that cross this tile's borders.  Every tile such a run touches has stored one sum; each
+    // counts itself as arrived at the run's first tile, and the one that arrives last adds the
+    // sums in tile order and applies the step.  The first wave sees to the run that came in
+    // through the front border, the second to the run that leaves through the back border (a tile
+    // that lies inside one run has only the former).
+    __syncthreads();
+    if (!do_front && !do_back) return;
+    const uint32_t m = T1 - T0 + 1;
+    uint32_t last = 0;
+    if (lane_id() == 0) {
+        // (this tile's sums were acknowledged before the barrier above)
+        last = __hip_atomic_fetch_add(&bd.arrived[T0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == m - 1 ? 1u : 0u;
+        if (last) bd.arrived[T0] = 0;                       // clean for the next kernel
+    }
+    last = __shfl(last, 0, WAVE);
+    if (!last || lane_id() >= (uint32_t)g.lanes) return;
+    const int32_t slot = ld_device(&bd.slot[T0]);           // (SLOT_NONE: a key that is not cached, flagged where the order was probed)
+#pragma unroll
+    for (int q = 0; q < MAXC; ++q) {
+        const int cidx = gl + q * g.lanes;
+        if (cidx >= g.chunks) continue;
+        double sum[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
+        for (uint32_t i0 = 0; i0 < m; i0 += 4) {
+            double part[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t i = i0 + u;
+                const double *pp = bd.part + ((size_t)(T0 + (i < m ? i : 0u)) * 2 + (i == 0 || i >= m ? 1 : 0)) * pstride + (size_t)cidx * VEC;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) part[u][e] = i < m ? ld_device(pp + e) : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
+        }
+        if (slot != SLOT_NONE) apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps);
     }
 }
 

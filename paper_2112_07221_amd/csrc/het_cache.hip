@@ -19,12 +19,12 @@ using namespace het;
 
 // Kernels of the path, as named in profiles and by het_profile_kernel_name.
 enum KernelId {
-    K_SORT_STAGE, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_APPLY_FINISH, K_TRIM_STAGE,
+    K_SORT_STAGE, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_TRIM_STAGE,
     K_TRIM_EVICT, K_DEFERRED_PUSH, K_FLUSH, K_MISC, K_NUM
 };
 static const char *const kKernelNames[K_NUM] = {
     "sort_stage_kernel", "probe_kernel", "pooled_index_kernel", "fill_gather_kernel",
-    "apply_kernel", "apply_finish_kernel", "trim_stage_kernel", "trim_evict_kernel", "deferred_push_kernel", "flush_kernel", "misc"};
+    "apply_kernel", "trim_stage_kernel", "trim_evict_kernel", "deferred_push_kernel", "flush_kernel", "misc"};
 
 struct ProfSpan { int id; hipEvent_t start, stop; };
 
@@ -53,6 +53,7 @@ struct het_cache {
     // device state
     CacheView cv{};
     Workspace ws{};
+    ApplyBorders bd{};
     TrimPlan tp{};
     // Four sets of sort buffers: the order of the current batch (kept for its update) and up to
     // three batches announced ahead by het_prefetch, whose sorts are carried by the kernels of the
@@ -415,10 +416,9 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
                            c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last),
                            c->tp.hist + kept_words, c->tp.zero_words - kept_words, tp, match >= 0 ? ids : nullptr));
     const int hist_pass = tp.h0_kept ? 1 : 0;                  // this pass of the select rides with the fetches
-    // (with the first pass kept, a select of two passes fits into the update's two kernels: second
-    // pass and tie count; the fetch kernel is the longer for every workgroup it carries)
-    const bool carry = !tp.h0_kept || tp.passes >= 3;
-    const uint32_t hist_blocks = carry && hist_pass < tp.passes ? stage_blocks(c, tp, hist_pass) : 0u;
+    // (the update has one kernel to carry a stage: with the first pass kept, a select of two passes
+    // is over when that kernel ends: second pass here, tie count there)
+    const uint32_t hist_blocks = hist_pass < tp.passes ? stage_blocks(c, tp, hist_pass) : 0u;
     c->sel_next = hist_blocks ? hist_pass + 1 : hist_pass;     // (a select of one pass whose histogram is kept: only the tie count is left)
         const uint32_t fill_blocks = std::min(cdiv(row_grid(c->cv.geom, n), (uint32_t)FILL_ROWS), FILL_MAX_BLOCKS);     // they come first: theirs is the longer chain
     if (offsets)
@@ -470,41 +470,40 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     return HET_OK;
 }
 
-// The two kernels of Write; each carries a stage of the coming trim's select in extra workgroups
-// (the stages before c->sel_next are done: the kept first pass, and what rode with the lookup's
-// fetches).  The first kernel moves the clocks, so it may carry a histogram stage (policy fields
-// only) but not the final count, which looks at the clocks.
+// The kernel of Write.  It carries one stage of the coming trim's select in extra workgroups (the
+// stages before c->sel_next are done: the kept first pass, and what rode with the lookup's
+// fetches): a histogram pass (policy fields only), or the tie count.  The count looks at the clocks
+// the kernel is moving, which is sound only when the update is known to touch exactly the rows the
+// last Read touched (it reuses that Read's order): see TrimPlan::dirty_stamp.
 // `trim`: a trim follows.  Returns the first stage that is still to run.
-template <int VEC, int MAXC, int CHUNK>
-int launch_apply_chunk(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
-                 bool trim)
+template <int VEC, int MAXC, int TILE>
+int launch_apply_tile(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
+                      bool trim)
 {
-    const uint32_t grid = row_grid(c->cv.geom, cdiv(n, CHUNK));
-    const TrimPlan &tp = c->sel_tp;
+    const uint32_t grid = cdiv(n, TILE);
+    TrimPlan tp = c->sel_tp;
     int next = c->sel_next;
-    const int stage0 = trim && next < tp.passes ? next++ : -1;
-    const int stage1 = trim && next <= tp.passes ? next++ : -1;
-    const uint32_t extra0 = stage0 >= 0 ? stage_blocks(c, tp, stage0) : 0u;
-    const uint32_t extra1 = stage1 >= 0 ? stage_blocks(c, tp, stage1) : 0u;
-    const Rides ride0 = next_rides(c);
-    const uint32_t lds0 = lds_bytes(std::max(sizeof(TrimLds), 256 * VEC * sizeof(double)), ride0);     // (the sums of a workgroup inside one run)
+    int stage = -1;
+    if (trim && next < tp.passes) stage = next++;
+    else if (trim && next == tp.passes && verify) { stage = next++; tp.dirty_stamp = (uint32_t)c->t_host; }
+    const uint32_t extra = stage >= 0 ? stage_blocks(c, tp, stage) : 0u;
+    const Rides ride = next_rides(c);
+    const uint32_t lds = lds_bytes(std::max(sizeof(TrimLds), sizeof(ApplyLds<VEC, TILE>)), ride);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, CHUNK><<<ride0.blocks() + grid + extra0 + cdiv(n, VERIFY_TILE), 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, TILE><<<ride.blocks() + grid + extra + cdiv(n, VERIFY_TILE), AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, CHUNK><<<ride0.blocks() + grid + extra0, 256, lds0, c->stream>>>(c->cv, c->ws, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage0, ride0.a, ride0.b));
-    const Rides ride1 = next_rides(c);
-    const uint32_t lds1 = lds_bytes(std::max(sizeof(TrimLds), sizeof(FinishLds<VEC>)), ride1);
-    LAUNCH(c, K_APPLY_FINISH, apply_finish_kernel<VEC, MAXC, CHUNK><<<ride1.blocks() + grid + extra1, 256, lds1, c->stream>>>(c->cv, c->ws, lr, c->eps, n, grid, tp, stage1, ride1.a, ride1.b));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, TILE><<<ride.blocks() + grid + extra, AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b));
     return next;
 }
 
-// Very large batches (their popular keys' runs are very long) take eight positions per row group, others four.
 template <int VEC, int MAXC>
 int launch_apply(het_cache *c, bool verify, const int64_t *ids, uint32_t n, const float *grads, const uint32_t *grad_row, float lr,
                  bool trim)
 {
-    return n > (1u << 18) ? launch_apply_chunk<VEC, MAXC, CHUNK_LONG>(c, verify, ids, n, grads, grad_row, lr, trim)
-                          : launch_apply_chunk<VEC, MAXC, CHUNK_SHORT>(c, verify, ids, n, grads, grad_row, lr, trim);
+    // rows of more than 128 floats (64 lanes to a row) have one row piece per lane or more; narrower ones exactly one
+    if constexpr (MAXC == 1)
+        if (ap_tile_for(c->cv.geom.lanes) == 64) return launch_apply_tile<VEC, MAXC, 64>(c, verify, ids, n, grads, grad_row, lr, trim);
+    return launch_apply_tile<VEC, MAXC, 128>(c, verify, ids, n, grads, grad_row, lr, trim);
 }
 
 template <int VEC>
@@ -630,7 +629,7 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
     const size_t N = (size_t)max_batch_ids;
     const size_t ptiles = cdiv(N, PT_TILE);
     const size_t sort_tiles = cdiv(N, SORT_TILE);
-    const size_t chunks = cdiv(N, CHUNK_SHORT);
+    const size_t ap_tiles = cdiv(N, (per_lane <= 1 ? ap_tile_for(g.lanes) : 128));
     for (int set = 0; set < SORT_SETS; ++set) {
         for (int i = 0; i < 2; ++i)
             if ((rc = dev_alloc(c, &c->keys[set][i], N)) || (rc = dev_alloc(c, &c->idx[set][i], N))) return rc;
@@ -642,7 +641,8 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
         (rc = dev_alloc(c, &ws.tile_miss, ptiles)) || (rc = dev_alloc(c, &ws.tile_stale, ptiles)) ||
         (rc = dev_alloc(c, &ws.miss_stage, ptiles * PT_TILE)) || (rc = dev_alloc(c, &ws.stale_stage, ptiles * PT_TILE)) ||
         (rc = dev_alloc(c, &c->inv, N)) || (rc = dev_alloc(c, &ws.bag_of, N)) ||
-        (rc = dev_alloc(c, &ws.partial, chunks * 2 * (size_t)c->dim)) || (rc = dev_alloc(c, &ws.cross_slot, chunks)))
+        (rc = dev_alloc(c, &c->bd.part, ap_tiles * 2 * (size_t)c->dim)) || (rc = dev_alloc(c, &c->bd.slot, ap_tiles)) ||
+        (rc = dev_alloc(c, &c->bd.arrived, ap_tiles)))
         return rc;
     const size_t slot_tiles = cdiv(P, TRIM_TILE), ev_blocks = cdiv(P, EV_SLOTS), ev_supers = cdiv(ev_blocks, EV_SUPER);
     c->tp.zero_words = (uint32_t)(SEL_MAX_PASSES * SEL_BINS + 4 * ev_supers);
@@ -657,6 +657,7 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
     }
     HIP_TRY(hipMemsetAsync(c->tile_free[1], 0, slot_tiles * sizeof(uint32_t), c->stream));
 
+    HIP_TRY(hipMemsetAsync(c->bd.arrived, 0, ap_tiles * sizeof(uint32_t), c->stream));
     HIP_TRY(hipMemsetAsync(cv.ds, 0, sizeof(DState), c->stream));
     init_cache_kernel<<<1024, 256, 0, c->stream>>>(cv, c->n_buckets * BUCKET_ENTRIES, c->n_buckets);
     if ((rc = launch_ok())) return rc;
@@ -1043,6 +1044,11 @@ int het_cache_destroy(het_cache *c)
     delete c;
     return rc;
 }
+
+#ifndef HET_BUILD_ID
+#define HET_BUILD_ID "unknown"
+#endif
+const char *het_build_id(void) { return HET_BUILD_ID; }
 
 const char *het_strerror(int status)
 {

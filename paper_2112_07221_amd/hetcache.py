@@ -28,7 +28,7 @@ EXPORTS = (
     "het_clear_error", "het_export_state", "het_export_rows", "het_last_lookup",
     "het_last_evicted", "het_cache_destroy", "het_strerror", "het_profile_begin",
     "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name",
-    "het_lookup_nocache_static",
+    "het_lookup_nocache_static", "het_build_id",
 )
 
 COUNTER_FIELDS = ("n", "unique", "hit", "stale", "miss", "evicted", "evicted_dirty",
@@ -88,6 +88,8 @@ def load() -> C.CDLL:
     lib.het_cache_destroy.argtypes = [p]
     lib.het_strerror.argtypes = [C.c_int]
     lib.het_strerror.restype = C.c_char_p
+    lib.het_build_id.argtypes = []
+    lib.het_build_id.restype = C.c_char_p
     lib.het_lookup_nocache_static.argtypes = [p, i64, i32, p, i64, p, p, p]
     lib.het_profile_begin.argtypes = [p]
     lib.het_profile_end.argtypes = [p, p, p, i32]
@@ -95,10 +97,14 @@ def load() -> C.CDLL:
     lib.het_profile_kernel_name.argtypes = [C.c_int]
     lib.het_profile_kernel_name.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("het_strerror", "het_profile_kernel_name"):
+        if name not in ("het_strerror", "het_profile_kernel_name", "het_build_id"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
+
+
+def build_id() -> str:
+    return load().het_build_id().decode()
 
 
 def strerror(status: int) -> str:

@@ -603,7 +603,7 @@ def test_per_kernel_timing_counts_the_launches_and_changes_nothing():
         for t in range(2, T):
             p.lookup(ids[t], ids_dev=dev[t]); p.update(ids[t], grads[t], ids_dev=dev[t])
         prof = p.cache.profile_end()
-        for name in ("probe_kernel", "fill_gather_kernel", "apply_kernel", "apply_finish_kernel", "trim_evict_kernel"):
+        for name in ("probe_kernel", "fill_gather_kernel", "apply_kernel", "trim_evict_kernel"):
             ms, launches = prof[name]
             assert launches == T - 2 and ms > 0, (name, prof[name])
         p.compare_state(values=True)
