@@ -86,6 +86,20 @@ typedef struct het_stats_t {
 int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, int32_t policy);
 
 /*
+ * Several workers over one global table (Section 3.1; Lemma 1).  Call between het_cache_create and
+ * het_cache_configure.  The cache then keeps every row as it was fetched, and Evict (of a stale
+ * row at a lookup, of the overflow at an update, and het_flush) pushes what the worker accumulated
+ * since its Fetch: the global row takes row - row_as_fetched (the Adagrad accumulator likewise) and
+ * c_g = max(c_g, c_c), as the paper words Evict, instead of being overwritten.  A stale row is
+ * then really fetched again (other workers' pushes are in the global row), so CheckValid's second
+ * condition c_g <= c_c + s matters.  Several caches of one process may be attached to the same
+ * table, state and cg arrays if they are configured on the same stream: their calls then take
+ * effect in the order they are made.  Costs one more copy of the cached rows in HBM.  The table
+ * must be in HBM.  HET_EINVAL: already configured, or HET_POLICY_NONE.
+ */
+int het_cache_set_many_writers(het_cache *c);
+
+/*
  * Fixes the largest number of ids one call may carry, the optimizer het_update applies and the
  * HIP stream (a hipStream_t, NULL = the default stream) all work is enqueued on, and allocates
  * the cache in HBM: capacity + max_batch_ids row slots (rows fetched on a miss are added beyond
@@ -149,6 +163,15 @@ int het_prefetch(het_cache *c, const int64_t *ids, int64_t n);
 /* Withdraws every standing announcement: sort stages not yet enqueued never run, the buffers are
  * not read by anything enqueued after this call.  het_flush does the same. */
 int het_prefetch_cancel(het_cache *c);
+
+/*
+ * The server's side of Evict for a worker that is not one of this process's caches (Section 3.1):
+ * table[ids[i]][:] += deltas[i][:] and cg[ids[i]] += 1, on the cache's stream.  ids (device,
+ * int64[n]) must be distinct; deltas is device, float[n][dim].  Ids outside the vocabulary are
+ * skipped and set error bit 1.  The table must be in HBM.  Cached copies of these rows turn stale
+ * by CheckValid's second condition once c_g has run more than s ahead of their clock.
+ */
+int het_backing_foreign_update(het_cache *c, const int64_t *ids, const float *deltas, int64_t n);
 
 /*
  * Pooled Read for multi-hot inputs: bag b holds ids[offsets[b] .. offsets[b+1]) and

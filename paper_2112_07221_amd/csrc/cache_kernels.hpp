@@ -54,6 +54,8 @@ struct CacheView {
     uint32_t vocab;
     // cache slots
     float *rows, *acc;
+    float *rows0, *acc0;  // several workers: every cached row (accumulator) as it was fetched; else null
+    int many;             // several workers write the global table: Evict pushes what was accumulated since the Fetch (Section 3.1)
     uint32_t *slot_key;
     SlotMeta *meta;       // start clock, local clock, LRU stamp, LFU count: one 16-byte record per slot
     uint32_t n_slots;     // capacity + max_batch_ids
@@ -587,6 +589,41 @@ __device__ __forceinline__ void push_row(const CacheView &cv, uint32_t key, uint
     }
 }
 
+// Element-wise w + (x - b): what the server holds after a worker that fetched b and now holds x has pushed.
+__device__ __forceinline__ float delta_add(float w, float x, float b) { return w + (x - b); }
+__device__ __forceinline__ float4 delta_add(float4 w, float4 x, float4 b)
+{
+    return make_float4(w.x + (x.x - b.x), w.y + (x.y - b.y), w.z + (x.z - b.z), w.w + (x.w - b.w));
+}
+
+// Several workers (Section 3.1, Evict as the paper words it): the worker pushes what it accumulated on
+// the row since its Fetch and the server adds it to the global row, c_g = max(c_g, c_c).  With
+// `refetch` the cached row then becomes the global row again (the Fetch that follows an Evict(key)
+// in Algorithm 2; a row without updates of its own is only fetched); without, the replica keeps its
+// view (flush).  Either way it counts its changes anew from here.  Called by a whole row group.
+template <int VEC>
+__device__ __forceinline__ void sync_row_many(const CacheView &cv, uint32_t key, uint32_t slot, int gl, bool has_updates, bool refetch)
+{
+    using V = typename VecT<VEC>::type;
+    const RowGeom g = cv.geom;
+    for (int pass = 0; pass < (cv.adagrad ? 2 : 1); ++pass) {
+        V *glob = reinterpret_cast<V *>((pass ? cv.A : cv.W) + (size_t)key * g.dim);
+        V *mine = reinterpret_cast<V *>((pass ? cv.acc : cv.rows) + (size_t)slot * g.dim);
+        V *base = reinterpret_cast<V *>((pass ? cv.acc0 : cv.rows0) + (size_t)slot * g.dim);
+        for (int c = gl; c < g.chunks; c += g.lanes) {
+            V w = glob[c];
+            const V x = mine[c];
+            if (has_updates) { w = delta_add(w, x, base[c]); glob[c] = w; }
+            if (refetch) { mine[c] = w; base[c] = w; }
+            else base[c] = x;
+        }
+    }
+    if (gl == 0 && has_updates) {
+        const uint32_t cc = cv.meta[slot].cc;
+        if (cc > cv.Cg[key]) cv.Cg[key] = cc;
+    }
+}
+
 // Fetch's pull for one row: copy the global row (and the accumulator) into the slot.
 template <int VEC>
 __device__ __forceinline__ void pull_row(const CacheView &cv, uint32_t key, uint32_t slot, int gl)
@@ -691,6 +728,10 @@ __device__ __forceinline__ void fetch_rows(const CacheView &cv, const float *con
             if (r < nin) {
                 reinterpret_cast<V *>(cv.rows + (size_t)slot[r] * g.dim)[c] = v[r];
                 if constexpr (WITH_ACC) reinterpret_cast<V *>(cv.acc + (size_t)slot[r] * g.dim)[c] = a[r];
+                if (cv.many) {                       // several workers: the row as fetched
+                    reinterpret_cast<V *>(cv.rows0 + (size_t)slot[r] * g.dim)[c] = v[r];
+                    if constexpr (WITH_ACC) reinterpret_cast<V *>(cv.acc0 + (size_t)slot[r] * g.dim)[c] = a[r];
+                }
             }
         }
     }
@@ -758,7 +799,8 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             const uint32_t key = jk.y;
             const uint32_t slot = (uint32_t)ws.head_slot[jk.x];
             const bool has_updates = cv.meta[slot].cc > cv.meta[slot].cs;
-            if (has_updates) push_row<VEC>(cv, key, slot, gl);               // now the global row equals the cached one
+            if (cv.many) sync_row_many<VEC>(cv, key, slot, gl, has_updates, true);
+            else if (has_updates) push_row<VEC>(cv, key, slot, gl);          // now the global row equals the cached one
             else pull_row<VEC>(cv, key, slot, gl);
             if (gl == 0) {
                 const uint32_t cg = cv.Cg[key];
@@ -1434,6 +1476,25 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
                 a2 = reinterpret_cast<const V *>(src_a + (size_t)from[2] * g.dim)[c];
                 a3 = reinterpret_cast<const V *>(src_a + (size_t)from[3] * g.dim)[c];
             }
+            if (cv.many) {
+                // several workers: the server adds what this worker accumulated since its Fetch
+                // (rows past the end repeat the last one: only the first of the repeats adds)
+                const bool r1 = v0 + 1 < np, r2 = v0 + 2 < np, r3 = v0 + 3 < np;
+                const V w0 = reinterpret_cast<const V *>(dst_x + (size_t)to[0] * g.dim)[c], b0 = reinterpret_cast<const V *>(cv.rows0 + (size_t)from[0] * g.dim)[c];
+                const V w1 = reinterpret_cast<const V *>(dst_x + (size_t)to[1] * g.dim)[c], b1 = reinterpret_cast<const V *>(cv.rows0 + (size_t)from[1] * g.dim)[c];
+                const V w2 = reinterpret_cast<const V *>(dst_x + (size_t)to[2] * g.dim)[c], b2 = reinterpret_cast<const V *>(cv.rows0 + (size_t)from[2] * g.dim)[c];
+                const V w3 = reinterpret_cast<const V *>(dst_x + (size_t)to[3] * g.dim)[c], b3 = reinterpret_cast<const V *>(cv.rows0 + (size_t)from[3] * g.dim)[c];
+                x0 = delta_add(w0, x0, b0);
+                x1 = r1 ? delta_add(w1, x1, b1) : x0; x2 = r2 ? delta_add(w2, x2, b2) : x1; x3 = r3 ? delta_add(w3, x3, b3) : x2;
+                if (adagrad) {
+                    const V u0 = reinterpret_cast<const V *>(dst_a + (size_t)to[0] * g.dim)[c], d0 = reinterpret_cast<const V *>(cv.acc0 + (size_t)from[0] * g.dim)[c];
+                    const V u1 = reinterpret_cast<const V *>(dst_a + (size_t)to[1] * g.dim)[c], d1 = reinterpret_cast<const V *>(cv.acc0 + (size_t)from[1] * g.dim)[c];
+                    const V u2 = reinterpret_cast<const V *>(dst_a + (size_t)to[2] * g.dim)[c], d2 = reinterpret_cast<const V *>(cv.acc0 + (size_t)from[2] * g.dim)[c];
+                    const V u3 = reinterpret_cast<const V *>(dst_a + (size_t)to[3] * g.dim)[c], d3 = reinterpret_cast<const V *>(cv.acc0 + (size_t)from[3] * g.dim)[c];
+                    a0 = delta_add(u0, a0, d0);
+                    a1 = r1 ? delta_add(u1, a1, d1) : a0; a2 = r2 ? delta_add(u2, a2, d2) : a1; a3 = r3 ? delta_add(u3, a3, d3) : a2;
+                }
+            }
             // rows past the end repeat the last one: the same values to the same place
             reinterpret_cast<V *>(dst_x + (size_t)to[0] * g.dim)[c] = x0;
             reinterpret_cast<V *>(dst_x + (size_t)to[1] * g.dim)[c] = x1;
@@ -1479,12 +1540,32 @@ __global__ __launch_bounds__(256) void flush_kernel(CacheView cv)
     for (uint32_t slot = gid; slot < cv.n_slots; slot += ngroups) {
         const uint32_t key = cv.slot_key[slot];
         if (key == KEY_NONE || cv.meta[slot].cc <= cv.meta[slot].cs) continue;
-        push_row<VEC>(cv, key, slot, gl);
+        if (cv.many) sync_row_many<VEC>(cv, key, slot, gl, true, false);
+        else push_row<VEC>(cv, key, slot, gl);
         if (gl == 0) { const uint32_t cg = cv.Cg[key]; cv.meta[slot].cs = cg; cv.meta[slot].cc = cg; ++pushed; }
     }
     pushed = block_sum<4>(pushed, lds);
     if (blockIdx.x == 0 && threadIdx.x == 0) { Counters z{}; *cv.next_call = z; }
     if (threadIdx.x == 0) count2(&cv.last->flushed, &cv.ds->total.flushed, pushed);
+}
+
+// The server's side of a push by a worker that is not modelled otherwise (Section 3.1, Evict): the
+// global row ids[i] takes deltas[i][:] and its clock advances by one.  One row group per id.
+template <int VEC>
+__global__ __launch_bounds__(256) void foreign_update_kernel(CacheView cv, const int64_t *__restrict__ ids, const float *__restrict__ deltas, uint32_t n)
+{
+    using V = typename VecT<VEC>::type;
+    const RowGeom g = cv.geom;
+    const uint32_t gid = (blockIdx.x * 256u + threadIdx.x) / g.lanes, ngroups = gridDim.x * 256u / g.lanes;
+    const int gl = threadIdx.x % g.lanes;
+    for (uint32_t i = gid; i < n; i += ngroups) {
+        const int64_t id = ids[i];
+        if (id < 0 || id >= (int64_t)cv.vocab) { if (gl == 0) atomicOr(&cv.ds->err, ERRBIT_RANGE); continue; }
+        V *w = reinterpret_cast<V *>(cv.W + (size_t)id * g.dim);
+        const V *d = reinterpret_cast<const V *>(deltas + (size_t)i * g.dim);
+        for (int c = gl; c < g.chunks; c += g.lanes) w[c] = delta_add(w[c], d[c], V{});
+        if (gl == 0) cv.Cg[id] += 1;
+    }
 }
 
 // Initial free list (every slot free) and empty slots / hash table.

@@ -45,6 +45,7 @@ struct het_cache {
     int32_t dim = 0, policy = 0;
     // configuration
     bool configured = false, attached = false;
+    bool many = false;               // one of several workers over one global table (het_cache_set_many_writers)
     int64_t max_ids = 0;
     int32_t optimizer = 0;
     float eps = 0.f;
@@ -442,15 +443,17 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         }                                                                                                                 \
     } while (0)
     const uint32_t gather_blocks = row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
-    if (c->location == HET_BACKING_HBM) {
+    if (c->location == HET_BACKING_HBM && !c->many) {
         // one kernel: the gather reads a missed key's row from the global table, beside the fetch
         const Rides ride = next_rides(c);
         FILL_GATHER_ANY(ride.blocks() + fill_blocks + ptiles + hist_blocks + gather_blocks, fill_blocks, hist_blocks, 0u);
     } else {
         // Host-backed table: the fetches come over the host link, and the last trim's write-back
         // goes the other way in the same kernel; the gather follows and reads the cached copies.
+        // Several workers: a row that is synchronised takes a new value (the server's row plus this
+        // worker's push), which the gather must see, so it follows in a launch of its own too.
         const uint32_t push_blocks = c->push_pending ? PUSH_BLOCKS : 0u;
-        const uint32_t fetch_blocks = std::min(fill_blocks, PUSH_BLOCKS);
+        const uint32_t fetch_blocks = c->location == HET_BACKING_HBM ? fill_blocks : std::min(fill_blocks, PUSH_BLOCKS);
         {
             const Rides ride = next_rides(c);
             FILL_GATHER_ANY(ride.blocks() + push_blocks + fetch_blocks + ptiles + hist_blocks, fetch_blocks, hist_blocks, push_blocks);
@@ -613,6 +616,9 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
     const size_t row_elems = (size_t)P * (size_t)c->dim;
     if (!direct && (rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
     if (!direct && cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
+    cv.many = c->many;
+    if (c->many && (rc = dev_alloc(c, &cv.rows0, row_elems))) return rc;
+    if (c->many && cv.adagrad && (rc = dev_alloc(c, &cv.acc0, row_elems))) return rc;
     if ((rc = dev_alloc(c, &cv.slot_key, P)) || (rc = dev_alloc(c, &cv.meta, P))) return rc;
     if ((rc = dev_alloc(c, &cv.free_list, (size_t)max_batch_ids)) || (rc = dev_alloc(c, &cv.was_free, P))) return rc;
     if ((rc = dev_alloc(c, &cv.ds, 1))) return rc;
@@ -680,6 +686,7 @@ static int attach_impl(het_cache *c, float *table, float *state, uint32_t *cg, i
     if (location != HET_BACKING_HBM && location != HET_BACKING_PINNED_HOST) return HET_EINVAL;
     if (c->optimizer == HET_OPT_ADAGRAD && !state) return HET_EINVAL;
     if (c->attached) return HET_EINVAL;
+    if (c->many && location != HET_BACKING_HBM) return HET_EINVAL;      // several workers: the shared table lives in HBM
     if (location == HET_BACKING_PINNED_HOST) {
         // kernels need the device-side alias of the mapped host memory
         void *dt = nullptr, *dst = nullptr, *dcg = nullptr;
@@ -723,6 +730,24 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
     const int rc = attach_impl(c, table, state, cg, vocab, location);
     if (rc != HET_OK && c && !was) free_owned_from(c, keep);
     return rc;
+}
+
+int het_cache_set_many_writers(het_cache *c)
+{
+    if (!c || c->configured || c->policy == HET_POLICY_NONE) return HET_EINVAL;
+    c->many = true;
+    return HET_OK;
+}
+
+int het_backing_foreign_update(het_cache *c, const int64_t *ids, const float *deltas, int64_t n)
+{
+    if (!ready(c) || n < 0 || n >= (1ll << 31) || c->location != HET_BACKING_HBM) return HET_EINVAL;
+    if (n == 0) return HET_OK;
+    if (!ids || !deltas) return HET_EINVAL;
+    const uint32_t grid = row_grid(c->cv.geom, (uint64_t)n);
+    if (c->cv.geom.vec == 4) LAUNCH(c, K_MISC, foreign_update_kernel<4><<<grid, 256, 0, c->stream>>>(c->cv, ids, deltas, (uint32_t)n));
+    else LAUNCH(c, K_MISC, foreign_update_kernel<1><<<grid, 256, 0, c->stream>>>(c->cv, ids, deltas, (uint32_t)n));
+    return launch_ok();
 }
 
 int het_prefetch_cancel(het_cache *c)

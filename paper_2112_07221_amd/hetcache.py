@@ -28,7 +28,8 @@ EXPORTS = (
     "het_clear_error", "het_export_state", "het_export_rows", "het_last_lookup",
     "het_last_evicted", "het_cache_destroy", "het_strerror", "het_profile_begin",
     "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name",
-    "het_lookup_nocache_static", "het_build_id",
+    "het_lookup_nocache_static", "het_build_id", "het_cache_set_many_writers",
+    "het_backing_foreign_update",
 )
 
 COUNTER_FIELDS = ("n", "unique", "hit", "stale", "miss", "evicted", "evicted_dirty",
@@ -75,6 +76,8 @@ def load() -> C.CDLL:
     lib.het_lookup.argtypes = [p, p, i64, p]
     lib.het_prefetch.argtypes = [p, p, i64]
     lib.het_prefetch_cancel.argtypes = [p]
+    lib.het_cache_set_many_writers.argtypes = [p]
+    lib.het_backing_foreign_update.argtypes = [p, p, p, i64]
     lib.het_lookup_pooled.argtypes = [p, p, i64, p, i64, p]
     lib.het_update.argtypes = [p, p, p, i64, C.c_float]
     lib.het_update_pooled.argtypes = [p, p, i64, p, p, i64, C.c_float]
@@ -148,7 +151,7 @@ class HetCache:
     Calls are enqueued on the current torch stream captured at construction."""
 
     def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer=OPT_SGD, eps=0.0,
-                 stream=None):
+                 stream=None, many_writers=False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("the embedding-cache library needs a GPU; none is visible")
@@ -160,6 +163,8 @@ class HetCache:
         h = C.c_void_p()
         self._rc(self.lib.het_cache_create(C.byref(h), capacity, dim, s, policy), "het_cache_create")
         self.h = h
+        if many_writers:
+            self._rc(self.lib.het_cache_set_many_writers(h), "het_cache_set_many_writers")
         self._rc(self.lib.het_cache_configure(h, max_batch_ids, optimizer, eps,
                                               C.c_void_p(self._stream.cuda_stream)),
                  "het_cache_configure")
@@ -192,6 +197,14 @@ class HetCache:
         import torch
         _check_dev(ids, torch.int64, "ids")
         self._rc(self.lib.het_prefetch(self.h, ids.data_ptr(), ids.numel()), "het_prefetch")
+
+    def foreign_update(self, ids, deltas):
+        import torch
+        _check_dev(ids, torch.int64, "ids"); _check_dev(deltas, torch.float32, "deltas")
+        if deltas.numel() < ids.numel() * self.dim:
+            raise ValueError("deltas is too small")
+        self._rc(self.lib.het_backing_foreign_update(self.h, ids.data_ptr(), deltas.data_ptr(), ids.numel()),
+                 "het_backing_foreign_update")
 
     def prefetch_cancel(self):
         self._rc(self.lib.het_prefetch_cancel(self.h), "het_prefetch_cancel")

@@ -28,22 +28,29 @@ def close(got, want, what):
 class Pair:
     """A HIP cache and an oracle over equal tables."""
 
-    def __init__(self, w: wl.Workload, table: np.ndarray, max_ids=None, host_backing=None):
+    def __init__(self, w: wl.Workload, table: np.ndarray, max_ids=None, host_backing=None, many_writers=False,
+                 share_with: "Pair" = None):
+        """`many_writers`: the cache and the oracle are one of several workers over one global table
+        (Evict pushes deltas); `share_with`: another Pair whose global table this one works on too."""
         self.w = w
         N = max_ids or w.n
         dev = torch.device("cuda:0")
         host = (w.backing == "host") if host_backing is None else host_backing
-        self.oracle = Oracle(w.capacity, w.dim, w.s, w.policy, N, w.optimizer, w.eps, table)
-        self.cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, N, w.optimizer, w.eps)
-        V = table.shape[0]
-        if host:
-            self.W = torch.from_numpy(table.astype(np.float32)).pin_memory()
-            self.A = torch.zeros(V, w.dim).pin_memory() if w.optimizer else None
-            self.Cg = torch.zeros(V, dtype=torch.int32).pin_memory()
+        self.oracle = Oracle(w.capacity, w.dim, w.s, w.policy, N, w.optimizer, w.eps, table, many_writers=many_writers,
+                             share_with=share_with.oracle if share_with is not None else None)
+        self.cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, N, w.optimizer, w.eps, many_writers=many_writers)
+        if share_with is not None:
+            self.W, self.A, self.Cg = share_with.W, share_with.A, share_with.Cg
         else:
-            self.W = torch.from_numpy(table.astype(np.float32)).to(dev)
-            self.A = torch.zeros(V, w.dim, device=dev) if w.optimizer else None
-            self.Cg = torch.zeros(V, dtype=torch.int32, device=dev)
+            V = table.shape[0]
+            if host:
+                self.W = torch.from_numpy(table.astype(np.float32)).pin_memory()
+                self.A = torch.zeros(V, w.dim).pin_memory() if w.optimizer else None
+                self.Cg = torch.zeros(V, dtype=torch.int32).pin_memory()
+            else:
+                self.W = torch.from_numpy(table.astype(np.float32)).to(dev)
+                self.A = torch.zeros(V, w.dim, device=dev) if w.optimizer else None
+                self.Cg = torch.zeros(V, dtype=torch.int32, device=dev)
         self.cache.attach_backing(self.W, self.A, self.Cg,
                                   hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)
         self.dev = dev
@@ -107,6 +114,12 @@ class Pair:
         assert got["total"] == ototal, (got["total"], ototal)
         assert got["resident"] == self.oracle.size
         assert got["iteration"] == self.oracle.iteration
+
+    def compare_table(self):
+        close(self.W.cpu().numpy(), self.oracle.W, "global table")
+        if self.A is not None:
+            close(self.A.cpu().numpy(), self.oracle.A, "global accumulators")
+        assert np.array_equal(self.Cg.cpu().numpy().view(np.uint32), self.oracle.Cg), "global clocks differ"
 
     def flush_and_compare(self):
         rc = self.cache.flush()
