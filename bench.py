@@ -101,7 +101,7 @@ def policy_study(args, w, dev):
     table = wl.table_init(w)
     rows = []
     for frac in (0.03, 0.05, 0.10, 0.15):
-        for policy, pname in ((wl.LRU, "LRU"), (wl.LFU, "LFU")):
+        for policy, pname in ((wl.LRU, "LRU"), (wl.LFU, "LFU"), (wl.LFU_LIGHT, "LFU-light (cap 16)")):
             Wt = torch.from_numpy(table).to(dev)
             At = torch.zeros_like(Wt) if w.optimizer else None
             Cg = torch.zeros(w.vocab, dtype=torch.int32, device=dev)
@@ -157,7 +157,8 @@ def main():
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0 = auto)")
     ap.add_argument("--policy-study", action="store_true",
                     help="instead of the benchmark: miss rate and step time of the chosen config for cache sizes of "
-                         "3, 5, 10 and 15 %% of the vocabulary under LRU and LFU (the experiment of the paper's Figure 8)")
+                         "3, 5, 10 and 15 %% of the vocabulary under LRU, LFU and light-weight LFU (the experiment of the paper's "
+                         "Figure 8, and the claim of its Section 4.3)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "

@@ -46,7 +46,8 @@ typedef enum het_status {
 } het_status;
 
 enum { HET_POLICY_LRU = 0, HET_POLICY_LFU = 1,          /* Section 4.3 */
-       HET_POLICY_NONE = 2 };                            /* no cache at all: the baseline "Hybrid (w/o Cache)" of Section 5 */
+       HET_POLICY_NONE = 2,                              /* no cache at all: the baseline "Hybrid (w/o Cache)" of Section 5 */
+       HET_POLICY_LFU_LIGHT = 3 };                       /* the light-weight LFU of Section 4.3, an approximation of LFU: see het_cache_set_lfu_cap */
 enum { HET_OPT_SGD = 0, HET_OPT_ADAGRAD = 1 };
 enum { HET_BACKING_HBM = 0, HET_BACKING_PINNED_HOST = 1 };
 enum { HET_CLASS_HIT = 0, HET_CLASS_STALE = 1, HET_CLASS_MISS = 2 };
@@ -84,6 +85,18 @@ typedef struct het_stats_t {
  * HET_EINVAL: out == NULL, capacity <= 0, dim <= 0, s < 0, unknown policy.
  */
 int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, int32_t policy);
+
+/*
+ * HET_POLICY_LFU_LIGHT (Section 4.3: an embedding whose frequency is high enough is accessed
+ * directly, without the upkeep of its frequency; the paper names no threshold): LFU whose use
+ * counter stops at `cap` (default 16).  A row that has been used that often is no longer touched by
+ * lookups: neither its counter nor its last-use stamp is written, and it leaves the cache only
+ * after every row used less often.  It evicts other rows than exact LFU does where counts beyond
+ * the cap would have decided; on skewed streams the miss rate is about the same (bench.py
+ * --policy-study).  Call between het_cache_create and het_cache_configure.  HET_EINVAL: cap == 0,
+ * another policy, already configured.
+ */
+int het_cache_set_lfu_cap(het_cache *c, uint32_t cap);
 
 /*
  * Several workers over one global table (Section 3.1; Lemma 1).  Call between het_cache_create and

@@ -24,13 +24,14 @@ class Entry:
 
 
 class BruteCache:
-    def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer, eps, table, many=False, server=None):
+    def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer, eps, table, many=False, server=None, lfu_cap=16):
         """`many`: one of several workers over one server (Evict pushes what was accumulated since
         the Fetch, and the server adds it); `server`: another BruteCache whose global table is used."""
         self.C, self.D, self.s = capacity, dim, s
         self.policy, self.opt, self.eps = policy, optimizer, float(eps)
         self.P = capacity + max_batch_ids
         self.many = many
+        self.lfu_cap = lfu_cap         # policy 3, light-weight LFU: rows used this often are no longer kept track of
         if server is not None:
             self.W, self.A, self.c_g = server.W, server.A, server.c_g
         else:
@@ -107,6 +108,8 @@ class BruteCache:
                 self.classes[k] = MISS
         for k in set(ids):
             e = self.find(k)
+            if self.policy == 3 and e.freq >= self.lfu_cap:
+                continue
             e.last_use = self.t
             e.freq += 1
         return [list(self.find(k).row) for k in ids]

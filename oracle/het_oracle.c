@@ -40,6 +40,12 @@
  * het_oracle_foreign_update is a push by a worker that is not modelled otherwise: the server adds
  * a delta to the global row and advances its clock by one.
  *
+ * Light-weight LFU (Section 4.3: once an embedding's frequency is "high enough" it is accessed
+ * directly and its frequency is no longer maintained; the paper gives no threshold): LFU whose
+ * use counter stops at a cap (het_oracle_set_lfu_cap, default 16).  A row whose counter has
+ * reached the cap is no longer touched by Reads: neither its counter nor its last-use stamp moves.
+ * It is an approximation of LFU by design; tests compare its miss rate with exact LFU's.
+ *
  * Floating point is HET_REAL (double unless overridden at compile time); compile with
  * -ffp-contract=off so that every operation rounds once.
  *
@@ -63,7 +69,7 @@
 #endif
 typedef HET_REAL real;
 
-enum { POLICY_LRU = 0, POLICY_LFU = 1 };
+enum { POLICY_LRU = 0, POLICY_LFU = 1, POLICY_LFU_LIGHT = 3 };   /* (2 is the GPU library's "no cache") */
 enum { OPT_SGD = 0, OPT_ADAGRAD = 1 };
 enum { CLS_HIT = 0, CLS_STALE = 1, CLS_MISS = 2 };
 enum { ERR_NONE = 0, ERR_RANGE = 1, ERR_STATE = 2, ERR_ARG = 4 };
@@ -77,6 +83,7 @@ typedef struct het_oracle {
     int64_t C, P, max_ids, s;
     int32_t dim, policy, opt;
     int32_t many;            /* several workers write the global table: Evict pushes deltas */
+    uint32_t lfu_cap;        /* light-weight LFU: the use counter stops here */
     real eps;
     /* global table (caller's arrays) */
     real *W, *A;
@@ -111,9 +118,10 @@ het_oracle *het_oracle_create(int64_t capacity, int32_t dim, int64_t s, int32_t 
                               int64_t max_batch_ids, int32_t optimizer, double eps)
 {
     if (capacity <= 0 || dim <= 0 || s < 0 || max_batch_ids <= 0) return NULL;
-    if (policy != POLICY_LRU && policy != POLICY_LFU) return NULL;
+    if (policy != POLICY_LRU && policy != POLICY_LFU && policy != POLICY_LFU_LIGHT) return NULL;
     if (optimizer != OPT_SGD && optimizer != OPT_ADAGRAD) return NULL;
     het_oracle *o = (het_oracle *)calloc(1, sizeof(*o));
+    o->lfu_cap = 16;
     o->C = capacity; o->dim = dim; o->s = s; o->policy = policy;
     o->max_ids = max_batch_ids; o->opt = optimizer; o->eps = (real)eps;
     o->P = capacity + max_batch_ids;
@@ -151,6 +159,14 @@ void het_oracle_destroy(het_oracle *o)
     free(o->last_use); free(o->freq); free(o->slot_of);
     free(o->lk_key); free(o->lk_cls); free(o->lk_slot); free(o->ev_id);
     free(o);
+}
+
+/* Light-weight LFU: where the use counter stops (at least 1). */
+int het_oracle_set_lfu_cap(het_oracle *o, uint32_t cap)
+{
+    if (!o || cap == 0) return ERR_ARG;
+    o->lfu_cap = cap;
+    return ERR_NONE;
 }
 
 /* Call right after create: this cache is one of several workers' over one global table. */
@@ -221,7 +237,7 @@ typedef struct { uint32_t freq, last_use; int64_t slot; int32_t policy; } victim
 static int cmp_victim(const void *a, const void *b)
 {
     const victim_key *x = (const victim_key *)a, *y = (const victim_key *)b;
-    if (x->policy == POLICY_LFU && x->freq != y->freq) return x->freq < y->freq ? -1 : 1;
+    if (x->policy != POLICY_LRU && x->freq != y->freq) return x->freq < y->freq ? -1 : 1;
     if (x->last_use != y->last_use) return x->last_use < y->last_use ? -1 : 1;
     return (x->slot > y->slot) - (x->slot < y->slot);
 }
@@ -311,6 +327,7 @@ static int read_keys(het_oracle *o, const int64_t *ids, int64_t n)
     for (int64_t u = 0; u < U; ++u) {           /* one use per key per Read */
         int64_t slot = o->slot_of[K[u]];
         o->lk_slot[u] = slot;
+        if (o->policy == POLICY_LFU_LIGHT && o->freq[slot] >= o->lfu_cap) continue;   /* frequent enough: no upkeep */
         o->last_use[slot] = o->t;
         o->freq[slot] += 1;
     }

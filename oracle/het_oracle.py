@@ -41,6 +41,7 @@ def _load(real: str):
     lib.het_oracle_update_pooled.argtypes = [p, p, i64, p, p, i64, rl]
     lib.het_oracle_flush.argtypes = [p]
     lib.het_oracle_set_many_writers.argtypes = [p]
+    lib.het_oracle_set_lfu_cap.argtypes = [p, C.c_uint32]
     lib.het_oracle_foreign_update.argtypes = [p, p, p, i64]
     for f in ("export_state", "export_rows", "last_lookup", "last_evicted", "size", "iteration"):
         getattr(lib, "het_oracle_" + f).restype = i64
@@ -68,7 +69,7 @@ class Oracle:
     the oracle's own global table is `self.W` (and `self.A`, `self.Cg`)."""
 
     def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer, eps, table,
-                 real: str = "f64", many_writers: bool = False, share_with: "Oracle" = None):
+                 real: str = "f64", many_writers: bool = False, share_with: "Oracle" = None, lfu_cap: int = None):
         """`many_writers`: this cache is one of several workers' (Evict pushes deltas).
         `share_with`: another Oracle whose global table (W, A, Cg) this one works on too;
         `table` is then ignored."""
@@ -79,6 +80,8 @@ class Oracle:
                                             float(eps))
         if not self.h:
             raise ValueError("het_oracle_create rejected the arguments")
+        if lfu_cap is not None and self.lib.het_oracle_set_lfu_cap(self.h, lfu_cap):
+            raise ValueError("het_oracle_set_lfu_cap rejected the cap")
         if many_writers and self.lib.het_oracle_set_many_writers(self.h):
             raise ValueError("het_oracle_set_many_writers failed")
         if share_with is not None:

@@ -56,6 +56,7 @@ struct CacheView {
     float *rows, *acc;
     float *rows0, *acc0;  // several workers: every cached row (accumulator) as it was fetched; else null
     int many;             // several workers write the global table: Evict pushes what was accumulated since the Fetch (Section 3.1)
+    uint32_t freq_cap;    // light-weight LFU (Section 4.3): a row used this often is no longer kept track of; 0: exact policies
     uint32_t *slot_key;
     SlotMeta *meta;       // start clock, local clock, LRU stamp, LFU count: one 16-byte record per slot
     uint32_t n_slots;     // capacity + max_batch_ids
@@ -488,8 +489,9 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
                     if (slot == SLOT_NONE) miss = true;
                     else {
                         hit = valid; stale = !valid;
-                        store_meta(cv.meta, (uint32_t)slot, m.x, m.y, t_now, m.w + 1);   // one use per key per Read
-                        if (keep_h0) {
+                        const bool upkeep = !(cv.freq_cap && m.w >= cv.freq_cap);        // (light-weight LFU: frequent enough, left alone)
+                        if (upkeep) store_meta(cv.meta, (uint32_t)slot, m.x, m.y, t_now, m.w + 1);   // one use per key per Read
+                        if (keep_h0 && upkeep) {
                             const uint32_t b_old = h0_bin(tp, policy_key(tp, m)), b_new = h0_bin(tp, policy_key(tp, make_uint4(0, 0, t_now, m.w + 1)));
                             if (b_old != b_new) { atomicSub(&h0_delta[b_old], 1u); atomicAdd(&h0_delta[b_new], 1u); }
                         }

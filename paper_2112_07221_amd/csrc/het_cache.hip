@@ -46,6 +46,7 @@ struct het_cache {
     // configuration
     bool configured = false, attached = false;
     bool many = false;               // one of several workers over one global table (het_cache_set_many_writers)
+    uint32_t lfu_cap = 16;           // HET_POLICY_LFU_LIGHT: where the use counter stops
     int64_t max_ids = 0;
     int32_t optimizer = 0;
     float eps = 0.f;
@@ -305,7 +306,7 @@ void use_order(het_cache *c, int set)
 TrimPlan make_trim_plan(const het_cache *c)
 {
     TrimPlan tp = c->tp;
-    tp.lfu = c->policy == HET_POLICY_LFU;
+    tp.lfu = c->policy == HET_POLICY_LFU || c->policy == HET_POLICY_LFU_LIGHT;
     tp.bits = std::max(1, bit_width(c->t_host));
     tp.key_bits = tp.lfu ? 2 * tp.bits : tp.bits;
     tp.passes = (tp.key_bits + SEL_BITS - 1) / SEL_BITS;
@@ -488,7 +489,7 @@ int launch_apply_tile(het_cache *c, bool verify, const int64_t *ids, uint32_t n,
     int next = c->sel_next;
     int stage = -1;
     if (trim && next < tp.passes) stage = next++;
-    else if (trim && next == tp.passes && verify) { stage = next++; tp.dirty_stamp = (uint32_t)c->t_host; }
+    else if (trim && next == tp.passes && verify && !c->cv.freq_cap) { stage = next++; tp.dirty_stamp = (uint32_t)c->t_host; }    // (light-weight LFU leaves some rows of the batch unstamped)
     const uint32_t extra = stage >= 0 ? stage_blocks(c, tp, stage) : 0u;
     const Rides ride = next_rides(c);
     const uint32_t lds = lds_bytes(std::max(sizeof(TrimLds), sizeof(ApplyLds<VEC, TILE>)), ride);
@@ -581,7 +582,7 @@ extern "C" {
 int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, int32_t policy)
 {
     if (!out || capacity <= 0 || dim <= 0 || s < 0) return HET_EINVAL;
-    if (policy != HET_POLICY_LRU && policy != HET_POLICY_LFU && policy != HET_POLICY_NONE) return HET_EINVAL;
+    if (policy != HET_POLICY_LRU && policy != HET_POLICY_LFU && policy != HET_POLICY_NONE && policy != HET_POLICY_LFU_LIGHT) return HET_EINVAL;
     if (capacity >= (1ll << 30) || dim > (1 << 20)) return HET_EINVAL;
     het_cache *c = new (std::nothrow) het_cache();
     if (!c) return HET_ENOMEM;
@@ -617,6 +618,7 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
     if (!direct && (rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
     if (!direct && cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
     cv.many = c->many;
+    cv.freq_cap = c->policy == HET_POLICY_LFU_LIGHT ? c->lfu_cap : 0u;
     if (c->many && (rc = dev_alloc(c, &cv.rows0, row_elems))) return rc;
     if (c->many && cv.adagrad && (rc = dev_alloc(c, &cv.acc0, row_elems))) return rc;
     if ((rc = dev_alloc(c, &cv.slot_key, P)) || (rc = dev_alloc(c, &cv.meta, P))) return rc;
@@ -730,6 +732,13 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
     const int rc = attach_impl(c, table, state, cg, vocab, location);
     if (rc != HET_OK && c && !was) free_owned_from(c, keep);
     return rc;
+}
+
+int het_cache_set_lfu_cap(het_cache *c, uint32_t cap)
+{
+    if (!c || c->configured || c->policy != HET_POLICY_LFU_LIGHT || cap == 0) return HET_EINVAL;
+    c->lfu_cap = cap;
+    return HET_OK;
 }
 
 int het_cache_set_many_writers(het_cache *c)

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhet_cache.so")
 
 HET_OK, HET_EINVAL, HET_ENOMEM, HET_EHIP, HET_ERANGE, HET_ESTATE = 0, -1, -2, -3, -4, -5
-POLICY_LRU, POLICY_LFU, POLICY_NONE = 0, 1, 2
+POLICY_LRU, POLICY_LFU, POLICY_NONE, POLICY_LFU_LIGHT = 0, 1, 2, 3
 OPT_SGD, OPT_ADAGRAD = 0, 1
 BACKING_HBM, BACKING_PINNED_HOST = 0, 1
 CLASS_HIT, CLASS_STALE, CLASS_MISS = 0, 1, 2
@@ -29,7 +29,7 @@ EXPORTS = (
     "het_last_evicted", "het_cache_destroy", "het_strerror", "het_profile_begin",
     "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name",
     "het_lookup_nocache_static", "het_build_id", "het_cache_set_many_writers",
-    "het_backing_foreign_update",
+    "het_backing_foreign_update", "het_cache_set_lfu_cap",
 )
 
 COUNTER_FIELDS = ("n", "unique", "hit", "stale", "miss", "evicted", "evicted_dirty",
@@ -77,6 +77,7 @@ def load() -> C.CDLL:
     lib.het_prefetch.argtypes = [p, p, i64]
     lib.het_prefetch_cancel.argtypes = [p]
     lib.het_cache_set_many_writers.argtypes = [p]
+    lib.het_cache_set_lfu_cap.argtypes = [p, C.c_uint32]
     lib.het_backing_foreign_update.argtypes = [p, p, p, i64]
     lib.het_lookup_pooled.argtypes = [p, p, i64, p, i64, p]
     lib.het_update.argtypes = [p, p, p, i64, C.c_float]
@@ -151,7 +152,7 @@ class HetCache:
     Calls are enqueued on the current torch stream captured at construction."""
 
     def __init__(self, capacity, dim, s, policy, max_batch_ids, optimizer=OPT_SGD, eps=0.0,
-                 stream=None, many_writers=False):
+                 stream=None, many_writers=False, lfu_cap=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("the embedding-cache library needs a GPU; none is visible")
@@ -165,6 +166,8 @@ class HetCache:
         self.h = h
         if many_writers:
             self._rc(self.lib.het_cache_set_many_writers(h), "het_cache_set_many_writers")
+        if lfu_cap is not None:
+            self._rc(self.lib.het_cache_set_lfu_cap(h, lfu_cap), "het_cache_set_lfu_cap")
         self._rc(self.lib.het_cache_configure(h, max_batch_ids, optimizer, eps,
                                               C.c_void_p(self._stream.cuda_stream)),
                  "het_cache_configure")

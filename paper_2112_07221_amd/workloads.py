@@ -16,7 +16,7 @@ from typing import Optional
 
 import numpy as np
 
-LRU, LFU = 0, 1
+LRU, LFU, LFU_LIGHT = 0, 1, 3
 SGD, ADAGRAD = 0, 1
 
 

@@ -29,7 +29,7 @@ class Pair:
     """A HIP cache and an oracle over equal tables."""
 
     def __init__(self, w: wl.Workload, table: np.ndarray, max_ids=None, host_backing=None, many_writers=False,
-                 share_with: "Pair" = None):
+                 share_with: "Pair" = None, lfu_cap=None):
         """`many_writers`: the cache and the oracle are one of several workers over one global table
         (Evict pushes deltas); `share_with`: another Pair whose global table this one works on too."""
         self.w = w
@@ -37,8 +37,9 @@ class Pair:
         dev = torch.device("cuda:0")
         host = (w.backing == "host") if host_backing is None else host_backing
         self.oracle = Oracle(w.capacity, w.dim, w.s, w.policy, N, w.optimizer, w.eps, table, many_writers=many_writers,
-                             share_with=share_with.oracle if share_with is not None else None)
-        self.cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, N, w.optimizer, w.eps, many_writers=many_writers)
+                             share_with=share_with.oracle if share_with is not None else None, lfu_cap=lfu_cap)
+        self.cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, N, w.optimizer, w.eps, many_writers=many_writers,
+                                 lfu_cap=lfu_cap)
         if share_with is not None:
             self.W, self.A, self.Cg = share_with.W, share_with.A, share_with.Cg
         else:
@@ -138,7 +139,7 @@ class Pair:
 
 
 def run_workload(w: wl.Workload, iters: int, state_every: int = 1, table=None, ids=None, grads=None,
-                 values_every: int = 0, prefetch=False):
+                 values_every: int = 0, prefetch=False, lfu_cap=None):
     """Runs `iters` lookup+update iterations of workload `w` on both sides.  With `prefetch` the
     ids of iteration t+2 are announced before lookup t (prefetch="before", as the benchmark
     does), between lookup t and update t (prefetch=True or "between") or after update t
@@ -146,7 +147,7 @@ def run_workload(w: wl.Workload, iters: int, state_every: int = 1, table=None, i
     table = wl.table_init(w) if table is None else table
     ids = wl.IdStream(w).batches(iters) if ids is None else ids
     grads = wl.grad_pool(w) if grads is None else grads
-    p = Pair(w, table)
+    p = Pair(w, table, lfu_cap=lfu_cap)
     try:
         ids_dev = torch.from_numpy(ids).to(p.dev) if prefetch else None
         for t in range(iters):

@@ -60,6 +60,22 @@ def test_row_widths(dim):
     run_workload(w, 12, state_every=3, values_every=3)
 
 
+@pytest.mark.parametrize("cap,host", [(1, False), (4, False), (4, True), (16, False)])
+def test_light_weight_lfu(cap, host):
+    """HET_POLICY_LFU_LIGHT (Section 4.3): rows used `cap` times are no longer kept track of.  The
+    oracle applies the same rule, so the comparison is as exact as for the other policies."""
+    w = wl.WORKLOADS[1].scaled(policy=wl.LFU_LIGHT, s=3, optimizer=wl.ADAGRAD, eps=1e-8, capacity=700,
+                               backing="host" if host else "hbm")
+    st = run_workload(w, 40, state_every=1, values_every=8, prefetch="before", lfu_cap=cap)
+    assert st["total"]["evicted"] > 0 and (cap == 1 or st["total"]["stale"] > 0)      # (cap 1 is first in, first out: nothing stays long enough)
+
+
+def test_light_weight_lfu_config2_full_size():
+    w = wl.WORKLOADS[2].scaled(policy=wl.LFU_LIGHT, s=5)
+    st = run_workload(w, 20, state_every=5, values_every=10, prefetch="before", lfu_cap=4)
+    assert st["total"]["evicted_dirty"] > 0
+
+
 def test_config2_shape_reduced():
     """Config 2's structure (26 fields, Zipf 1.05, LFU, Adagrad, s = 100) at a tenth of its
     size, long enough for rows to go stale: several sort tiles, ragged last tile."""

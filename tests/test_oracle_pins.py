@@ -364,3 +364,62 @@ def test_write_of_a_key_that_was_never_read_is_skipped_and_flagged():
     assert rc & 2
     o.flush()
     assert o.W[:, 0].tolist() == [0, -1, 0, 0, 0]
+
+
+# ---------------------------------------------------------------- light-weight LFU (Section 4.3)
+@pytest.mark.parametrize("opt,s,cap", [(0, 0, 1), (1, 2, 3), (0, S_INF, 6)])
+def test_light_lfu_matches_brute_force_twin(opt, s, cap):
+    """LFU whose use counter stops at a cap (a row used that often is left alone by Reads), against
+    the list-based twin: classes, slots, evicted ids, every cached row's clocks and policy fields."""
+    V, C, D, N = 50, 6, 2, 12
+    ids, grads, table = stream(23 + cap, V, N, 150, D, alpha=1.2)
+    o = Oracle(C, D, s, 3, N, opt, 1e-8, table, lfu_cap=cap)
+    b = brute.BruteCache(C, D, s, 3, N, opt, 1e-8, table, lfu_cap=cap)
+    capped = 0
+    for i, g in zip(ids, grads):
+        out, _ = o.lookup(i)
+        assert np.array_equal(out, np.asarray(b.read(i.tolist())))
+        keys, cls, slots = o.last_lookup()
+        assert {k: CLS[c] for k, c in zip(keys.tolist(), cls.tolist())} == b.classes
+        o.update(i, g, 0.05)
+        b.write(i.tolist(), g.tolist(), 0.05)
+        assert o.last_evicted().tolist() == b.evicted
+        st = o.export_state()
+        assert list(zip(*(st[c].tolist() for c in ("key", "slot", "cs", "cc", "last_use", "freq")))) == b.state()
+        assert st["freq"].max() <= cap
+        capped += int((st["freq"] == cap).sum())
+    assert capped > 0
+    o.flush(); b.flush()
+    assert np.array_equal(o.W, np.asarray(b.W))
+
+
+def test_light_lfu_with_a_cap_never_reached_is_lfu():
+    V, C, D, N = 200, 20, 2, 40
+    ids, grads, table = stream(29, V, N, 120, D, alpha=1.1)
+    exact = Oracle(C, D, 3, 1, N, 0, 0.0, table)
+    light = Oracle(C, D, 3, 3, N, 0, 0.0, table, lfu_cap=10**9)
+    for i, g in zip(ids, grads):
+        a, _ = exact.lookup(i)
+        b, _ = light.lookup(i)
+        assert np.array_equal(a, b)
+        exact.update(i, g, 0.1); light.update(i, g, 0.1)
+        assert exact.last_evicted().tolist() == light.last_evicted().tolist()
+    se, sl = exact.export_state(), light.export_state()
+    assert all(np.array_equal(se[c], sl[c]) for c in se)
+
+
+def test_light_lfu_misses_about_as_often_as_lfu():
+    """Section 4.3: under the same workload the light-weight version has a similar miss rate."""
+    V, D, N, T = 3000, 2, 200, 300
+    ids, grads, table = stream(37, V, N, T, D, alpha=1.05)
+    miss = {}
+    for name, policy, cap in (("lru", 0, None), ("lfu", 1, None), ("light", 3, 8)):
+        o = Oracle(300, D, 5, policy, N, 0, 0.0, table, lfu_cap=cap)
+        for t, (i, g) in enumerate(zip(ids, grads)):
+            o.lookup(i)
+            o.update(i, g, 0.1)
+            if t == T // 3:
+                warm = o.stats()[1]["miss"]
+        miss[name] = o.stats()[1]["miss"] - warm
+    assert abs(miss["light"] - miss["lfu"]) <= 0.05 * miss["lfu"]
+    assert miss["light"] < miss["lru"]
