@@ -36,7 +36,12 @@ __device__ __forceinline__ void store_meta(SlotMeta *m, uint32_t slot, uint32_t 
 struct HostLink {
     float *rows[2], *acc[2];      // staging, [max_ids][dim] each; trims alternate between the two
     uint32_t *keys[2], *cg[2];    // per staged row: its key and the global clock it will carry
-    uint64_t *pend;               // [vocab]: (serial number of the trim << 32) | staging index of the key's staged row
+    uint64_t *pend;               // [vocab]: (serial number of the trim << 32) | staging index of the key's staged row,
+                                  // or (tag of a list of keys fetched ahead << 32) | place in that list; the tags' top bit tells them apart
+    // rows of the coming batch fetched ahead of its Read (Section 4.2), [max_ids] each: the listed keys, where a key's
+    // row is staged if its write-back is still to come (else KEY_NONE: it comes from the table), and the rows
+    uint32_t *pf_keys, *pf_from;
+    float *pf_rows, *pf_acc;
     // (selected, not indexed: indexing kernel arguments at run time would put them in scratch memory)
     __device__ __forceinline__ float *rows_of(int b) const { return b ? rows[1] : rows[0]; }
     __device__ __forceinline__ float *acc_of(int b) const { return b ? acc[1] : acc[0]; }
@@ -390,7 +395,7 @@ __device__ __forceinline__ void free_list_body(const CacheView &cv, const uint32
                                                uint32_t tile, uint32_t *lds)
 {
     if (threadIdx.x == 0) tile_free_idle[tile] = 0;
-    if (tile == 0 && threadIdx.x == 0) { cv.ds->ev_n[ev_idle] = 0; cv.ds->push_n[ev_idle] = 0; }
+    if (tile == 0 && threadIdx.x == 0) cv.ds->ev_n[ev_idle] = 0;      // (push_n is written by every eviction, and a write-back on its way may still read it)
     const uint32_t slot = tile * PT_TILE + threadIdx.x;
     const bool fr = slot < cv.n_slots && cv.slot_key[slot] == KEY_NONE;
     if (slot < cv.n_slots) cv.was_free[slot] = fr ? 1 : 0;
@@ -422,7 +427,7 @@ template <bool LOOKUP>
 __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
                                                            const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle,
                                                            uint32_t *zero_from, uint32_t zero_words, TrimPlan tp,
-                                                           const int64_t *__restrict__ check_ids)
+                                                           const int64_t *__restrict__ check_ids, int pf_idle = -1)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
     __shared__ uint32_t h0_delta[LOOKUP ? SEL_BINS : 1];       // rows entering (+) and leaving (-) each bin of the kept histogram
@@ -457,6 +462,7 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         cv.last->n = n;
         atomicAdd(&ds->total.n, (unsigned long long)n);
         if (LOOKUP) ds->t = t_now;
+        if (LOOKUP && pf_idle >= 0) ds->pf_n[pf_idle] = 0;    // the list of keys to fetch ahead that this lookup's second kernel may fill
     }
     bool head = false, miss = false, stale = false, hit = false, absent = false, bad = false;
     if (j < n) {
@@ -647,19 +653,44 @@ __device__ __forceinline__ void pull_row_from(const CacheView &cv, const float *
 
 // Host-backed table: writes the rows staged by trim `buf` to the global table, with their clocks.
 // Runs in `nblocks` workgroups of 256 threads; `vblock` is this one's index.
+// LINK_ROWS rows per row group are on their way at a time: a transfer over the host link takes
+// microseconds, and what keeps the link full is the number of rows in flight, not the number of
+// workgroups (few workgroups, because a compute unit that waits for the host serves its other
+// waves' memory requests behind those that wait).
+constexpr int LINK_ROWS = 4;
 template <int VEC>
 __device__ __forceinline__ void deferred_push_body(const CacheView &cv, int buf, uint32_t vblock, uint32_t nblocks)
 {
+    using V = typename VecT<VEC>::type;
     const RowGeom g = cv.geom;
     const uint32_t n = cv.ds->push_n[buf];
     const uint32_t gid = (vblock * 256u + threadIdx.x) / g.lanes, ngroups = nblocks * 256u / g.lanes;
     const int gl = threadIdx.x % g.lanes;
-    for (uint32_t r = gid; r < n; r += ngroups) {
-        const uint32_t key = cv.hl.keys_of(buf)[r];
-        if (key == KEY_NONE) continue;                   // a tied victim without updates
-        row_copy<VEC>(cv.W + (size_t)key * g.dim, cv.hl.rows_of(buf) + (size_t)r * g.dim, g.chunks, g.lanes, gl);
-        if (cv.adagrad) row_copy<VEC>(cv.A + (size_t)key * g.dim, cv.hl.acc_of(buf) + (size_t)r * g.dim, g.chunks, g.lanes, gl);
-        if (gl == 0) cv.Cg_host[key] = cv.hl.cg_of(buf)[r];
+    for (uint32_t r0 = gid * LINK_ROWS; r0 < n; r0 += ngroups * LINK_ROWS) {
+        uint32_t key[LINK_ROWS], at[LINK_ROWS];
+#pragma unroll
+        for (int k = 0; k < LINK_ROWS; ++k) {
+            at[k] = r0 + k < n ? r0 + k : r0;
+            key[k] = cv.hl.keys_of(buf)[at[k]];
+            if (r0 + k >= n) key[k] = KEY_NONE;          // (KEY_NONE within the list: a tied victim without updates)
+        }
+        for (int pass = 0; pass < (cv.adagrad ? 2 : 1); ++pass) {
+            const float *from = pass ? cv.hl.acc_of(buf) : cv.hl.rows_of(buf);
+            float *to = pass ? cv.A : cv.W;
+            for (int c = gl; c < g.chunks; c += g.lanes) {
+                V v[LINK_ROWS];
+#pragma unroll
+                for (int k = 0; k < LINK_ROWS; ++k) v[k] = reinterpret_cast<const V *>(from + (size_t)at[k] * g.dim)[c];
+#pragma unroll
+                for (int k = 0; k < LINK_ROWS; ++k)
+                    if (key[k] != KEY_NONE) reinterpret_cast<V *>(to + (size_t)key[k] * g.dim)[c] = v[k];
+            }
+        }
+        if (gl == 0) {
+#pragma unroll
+            for (int k = 0; k < LINK_ROWS; ++k)
+                if (key[k] != KEY_NONE) cv.Cg_host[key[k]] = cv.hl.cg_of(buf)[at[k]];
+        }
     }
 }
 
@@ -739,6 +770,90 @@ __device__ __forceinline__ void fetch_rows(const CacheView &cv, const float *con
     }
 }
 
+// Host-backed table: the rows the next Read will miss are fetched while the Write in between runs
+// (Section 4.2: the next minibatch's indices are known in advance; Section 4.1: communication is
+// invoked asynchronously and overlaps computation).  The second kernel of a lookup lists the keys of
+// the announced batch that are not cached (nothing is inserted before that batch's own lookup, and a
+// key evicted in between is found through `pend`); a kernel on a stream of its own then brings their
+// rows from the table into HBM, beside the last trim's write-back going the other way; the next
+// lookup's fetch kernel takes them from there.
+struct Ahead {
+    const uint32_t *skey;   // the announced batch's sorted keys (listing role), or null
+    uint32_t n;             // their number
+    uint32_t blocks;        // workgroups of the listing role in this launch
+    uint32_t list_tag;      // tag the listing role gives the keys it lists (top bit set)
+    int list_slot;          // which of ds->pf_n counts them
+    uint32_t pending_seq;   // serial number of the trim whose staged rows are still to be written back (0: none)
+    uint32_t use_tag;       // fetch role: tag of the rows that were fetched ahead for THIS lookup (0: none)
+};
+
+// Lists the keys of an announced batch that are not cached.  Workgroups of 256 threads, one sorted position each.
+__device__ __forceinline__ void ahead_list_body(const CacheView &cv, const Ahead &ah, uint32_t vblock)
+{
+    const uint32_t j = vblock * 256u + threadIdx.x;
+    bool want = false;
+    uint32_t key = KEY_NONE, from = KEY_NONE;
+    if (j < ah.n) {
+        key = ah.skey[j];
+        const bool head = key != cv.vocab && (j == 0 || ah.skey[j - 1] != key);
+        if (head && ht_find(cv.ht, key) == SLOT_NONE) {
+            want = true;
+            // a row the last trim evicted, whose write-back is still to come: the staged copy is the row
+            const uint64_t pe = cv.hl.pend[key];
+            if (ah.pending_seq && (uint32_t)(pe >> 32) == ah.pending_seq) from = (uint32_t)pe;
+        }
+    }
+    const uint64_t m = __ballot(want);
+    if (!m) return;
+    uint32_t base = 0;
+    const uint32_t first = (uint32_t)__builtin_ctzll(m);
+    if (lane_id() == first) base = atomicAdd(&cv.ds->pf_n[ah.list_slot], (uint32_t)__popcll(m));     // (the order of the list does not matter)
+    base = __shfl(base, (int)first, WAVE);
+    if (want) {
+        const uint32_t at = base + mask_rank(m);
+        cv.hl.pf_keys[at] = key;
+        cv.hl.pf_from[at] = from;
+        cv.hl.pend[key] = ((uint64_t)ah.list_tag << 32) | at;
+    }
+}
+
+// On the stream beside the main one: the first half of the workgroups write the rows a trim staged
+// back to the table (push_buf < 0: nothing to write), the second half bring the listed rows in.
+template <int VEC>
+__global__ __launch_bounds__(256) void link_kernel(CacheView cv, int push_buf, int list_slot, int staged_buf, uint32_t push_blocks)
+{
+    const uint32_t half = push_blocks;
+    if (blockIdx.x < half) { if (push_buf >= 0) deferred_push_body<VEC>(cv, push_buf, blockIdx.x, half); return; }
+    if (list_slot < 0) return;
+    const RowGeom g = cv.geom;
+    const uint32_t n = cv.ds->pf_n[list_slot];
+    const uint32_t gid = ((blockIdx.x - half) * 256u + threadIdx.x) / g.lanes, ngroups = (gridDim.x - half) * 256u / g.lanes;
+    const int gl = threadIdx.x % g.lanes;
+    using V = typename VecT<VEC>::type;
+    for (uint32_t r0 = gid * LINK_ROWS; r0 < n; r0 += ngroups * LINK_ROWS) {
+        uint32_t at[LINK_ROWS], key[LINK_ROWS], from[LINK_ROWS];
+#pragma unroll
+        for (int k = 0; k < LINK_ROWS; ++k) {
+            at[k] = r0 + k < n ? r0 + k : r0;            // (past the end: the first row again, to the same place)
+            key[k] = cv.hl.pf_keys[at[k]]; from[k] = cv.hl.pf_from[at[k]];
+        }
+        for (int pass = 0; pass < (cv.adagrad ? 2 : 1); ++pass) {
+            const float *table = pass ? cv.A : cv.W, *stage = pass ? cv.hl.acc_of(staged_buf) : cv.hl.rows_of(staged_buf);
+            float *to = pass ? cv.hl.pf_acc : cv.hl.pf_rows;
+            for (int c = gl; c < g.chunks; c += g.lanes) {
+                V v[LINK_ROWS];
+#pragma unroll
+                for (int k = 0; k < LINK_ROWS; ++k) {
+                    const float *row = from[k] != KEY_NONE ? stage + (size_t)from[k] * g.dim : table + (size_t)key[k] * g.dim;
+                    v[k] = reinterpret_cast<const V *>(row)[c];
+                }
+#pragma unroll
+                for (int k = 0; k < LINK_ROWS; ++k) reinterpret_cast<V *>(to + (size_t)at[k] * g.dim)[c] = v[k];
+            }
+        }
+    }
+}
+
 struct FillLds {
     uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
     uint32_t scan[4 + 1];
@@ -749,7 +864,7 @@ template <int VEC, bool POOLED, int RIDE>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv, SortStage ride, SortStage ride2,
-                                                          uint32_t push_blocks, int push_buf, uint32_t push_seq, int hist_pass)
+                                                          uint32_t push_blocks, int push_buf, uint32_t push_seq, int hist_pass, Ahead ah)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
@@ -757,6 +872,8 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
     if (RIDE == 2 && run_carried<false>(ride, ride2, bid, nblk)) return;
     if (bid < push_blocks) { deferred_push_body<VEC>(cv, push_buf, bid, push_blocks); return; }    // host-backed table: the last trim's write-back
     bid -= push_blocks; nblk -= push_blocks;
+    if (bid < ah.blocks) { ahead_list_body(cv, ah, bid); return; }                                 // host-backed table: what to fetch ahead for the coming batch
+    bid -= ah.blocks; nblk -= ah.blocks;
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
@@ -782,12 +899,15 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
                 slot[r] = cv.free_list[m];
                 // host-backed table: a row the last trim evicted may still be on its way to the table
                 // (its write-back travels in this very kernel); then the staged copy is the global row
-                const bool link = cv.Cg_host && push_seq;
+                // or it was fetched ahead into HBM for this very lookup
+                const bool link = cv.Cg_host && (push_seq || ah.use_tag);
                 const uint64_t pe = link ? cv.hl.pend[key] : 0ull;
-                const bool staged = link && (uint32_t)(pe >> 32) == push_seq;
+                const uint32_t tag = (uint32_t)(pe >> 32);
+                const bool staged = link && push_seq && tag == push_seq;
+                const bool ahead = link && ah.use_tag && tag == ah.use_tag;
                 const size_t at = (size_t)(uint32_t)pe * g.dim;
-                srow[r] = staged ? cv.hl.rows_of(push_buf) + at : cv.W + (size_t)key * g.dim;
-                sacc[r] = staged ? cv.hl.acc_of(push_buf) + at : cv.A + (size_t)key * g.dim;
+                srow[r] = staged ? cv.hl.rows_of(push_buf) + at : (ahead ? cv.hl.pf_rows + at : cv.W + (size_t)key * g.dim);
+                sacc[r] = staged ? cv.hl.acc_of(push_buf) + at : (ahead ? cv.hl.pf_acc + at : cv.A + (size_t)key * g.dim);
             }
             int nin = 0;                         // rows of this batch that exist (the first ones)
 #pragma unroll

@@ -34,6 +34,7 @@ struct DState {
     int32_t over;        // trim: rows above capacity when the select ran (what the eviction removes)
     int32_t pad1;
     uint32_t push_n[2];  // host-backed table: rows a trim staged for write-back; trims alternate like ev_n
+    uint32_t pf_n[2];    // host-backed table: keys of a coming batch listed for fetching ahead; the lists alternate
     Counters call[2];    // per-call counters: calls alternate between the two, the idle one is cleared meanwhile
     Counters total;
 };

@@ -20,11 +20,11 @@ using namespace het;
 // Kernels of the path, as named in profiles and by het_profile_kernel_name.
 enum KernelId {
     K_SORT_STAGE, K_PROBE, K_POOLED_INDEX, K_FILL_GATHER, K_APPLY, K_TRIM_STAGE,
-    K_TRIM_EVICT, K_DEFERRED_PUSH, K_FLUSH, K_MISC, K_NUM
+    K_TRIM_EVICT, K_DEFERRED_PUSH, K_LINK, K_FLUSH, K_MISC, K_NUM
 };
 static const char *const kKernelNames[K_NUM] = {
     "sort_stage_kernel", "probe_kernel", "pooled_index_kernel", "fill_gather_kernel",
-    "apply_kernel", "trim_stage_kernel", "trim_evict_kernel", "deferred_push_kernel", "flush_kernel", "misc"};
+    "apply_kernel", "trim_stage_kernel", "trim_evict_kernel", "deferred_push_kernel", "link_kernel", "flush_kernel", "misc"};
 
 struct ProfSpan { int id; hipEvent_t start, stop; };
 
@@ -82,6 +82,14 @@ struct het_cache {
     bool push_pending = false;
     int push_buf = 0;
     uint32_t push_seq = 0, trim_seq = 0;
+    // host-backed table: the stream beside the main one on which rows of the coming batch are fetched
+    // ahead and staged rows are written back while the update runs (Section 4.1, 4.2)
+    hipStream_t side = nullptr;
+    hipEvent_t ev_main = nullptr, ev_link = nullptr;
+    bool link_outstanding = false;   // a kernel on that stream has not been waited for yet
+    uint32_t pf_serial = 0;
+    int pf_slot_next = 0;            // which of the two list counters the next list uses
+    struct { bool ready = false; const int64_t *ids = nullptr; uint32_t n = 0, tag = 0; } pf;   // rows fetched ahead, and for which lookup
     // host-side bookkeeping
     uint64_t t_host = 0;             // non-empty lookups so far (equals the device's t)
     bool overflow_pending = false;   // a lookup ran and no trim since
@@ -321,11 +329,21 @@ uint32_t stage_blocks(const het_cache *c, const TrimPlan &tp, int stage)
 }
 
 constexpr uint32_t PUSH_BLOCKS = 256;      // few workgroups keep the host link full; more only contend
+constexpr uint32_t LINK_BLOCKS = 32;       // workgroups of the kernel that works the host link beside the update (half write back, half fetch ahead)
+
+// Host-backed table: the main stream goes on only when the kernel on the stream beside it is done.
+void wait_link(het_cache *c)
+{
+    if (!c->link_outstanding) return;
+    (void)hipStreamWaitEvent(c->stream, c->ev_link, 0);
+    c->link_outstanding = false;
+}
 
 // Host-backed table: enqueues the write-back a trim left staged, if nobody carried it yet.
 void drain_pushes(het_cache *c)
 {
     if (!c->push_pending) return;
+    wait_link(c);                // (staged copies reach the table in the order they were staged)
     if (c->cv.geom.vec == 4) LAUNCH(c, K_DEFERRED_PUSH, deferred_push_kernel<4><<<PUSH_BLOCKS, 256, 0, c->stream>>>(c->cv, c->push_buf));
     else LAUNCH(c, K_DEFERRED_PUSH, deferred_push_kernel<1><<<PUSH_BLOCKS, 256, 0, c->stream>>>(c->cv, c->push_buf));
     c->push_pending = false;
@@ -345,7 +363,7 @@ int run_trim(het_cache *c, int first_stage)
     tp.ev_slot = fill;
     tp.ev_ids = c->ev_ids[fill];
     tp.push_seq = ++c->trim_seq;
-    if (c->trim_seq == 0xFFFFFFFFu) c->trim_seq = 0;        // 0 means "none"; a wrap is harmless (see HostLink::pend)
+    if (c->trim_seq == 0x7FFFFFFFu) c->trim_seq = 0;        // 0 means "none", the top bit marks lists of keys fetched ahead; a wrap is harmless (see HostLink::pend)
     const Rides ride = next_rides(c);
     const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
     if (ride.blocks())
@@ -395,7 +413,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         const TrimPlan none{};
 #define GATHER_ONLY(POOLED, RIDE)                                                                                        \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<grid, 256, lds, c->stream>>>(                          \
-                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u, 0))
+                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u, 0, Ahead{}))
         const int kind = ride.kind();
         if (!offsets) { if (kind == 0) GATHER_ONLY(false, 0); else if (kind == 1) GATHER_ONLY(false, 1); else GATHER_ONLY(false, 2); }
         else { if (kind == 0) GATHER_ONLY(true, 0); else if (kind == 1) GATHER_ONLY(true, 1); else GATHER_ONLY(true, 2); }
@@ -416,7 +434,8 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const uint32_t kept_words = tp.h0_kept ? (uint32_t)SEL_BINS : 0u;
     LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + (match >= 0 ? ptiles : 0u) + stiles, PT_THREADS, 0, c->stream>>>(
                            c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last),
-                           c->tp.hist + kept_words, c->tp.zero_words - kept_words, tp, match >= 0 ? ids : nullptr));
+                           c->tp.hist + kept_words, c->tp.zero_words - kept_words, tp, match >= 0 ? ids : nullptr,
+                           c->side ? c->pf_slot_next : -1));
     const int hist_pass = tp.h0_kept ? 1 : 0;                  // this pass of the select rides with the fetches
     // (the update has one kernel to carry a stage: with the first pass kept, a select of two passes
     // is over when that kernel ends: second pass here, tie count there)
@@ -429,7 +448,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 #define FILL_GATHER(POOLED, RIDE, GRID, FILLB, HISTB, PUSHB)                                                              \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>(     \
                                  c->cv, c->ws, n, t_now, ptiles, FILLB, tp, HISTB, out, offsets, n_bags, c->inv, ride.a, ride.b, \
-                                 PUSHB, c->push_buf, c->push_seq, hist_pass))
+                                 PUSHB, c->push_buf, c->push_seq, hist_pass, ah))
 #define FILL_GATHER_ANY(GRID, FILLB, HISTB, PUSHB)                                                                        \
     do {                                                                                                                  \
         const int kind = ride.kind();                                                                                     \
@@ -444,6 +463,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         }                                                                                                                 \
     } while (0)
     const uint32_t gather_blocks = row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
+    Ahead ah{};
     if (c->location == HET_BACKING_HBM && !c->many) {
         // one kernel: the gather reads a missed key's row from the global table, beside the fetch
         const Rides ride = next_rides(c);
@@ -453,16 +473,60 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         // goes the other way in the same kernel; the gather follows and reads the cached copies.
         // Several workers: a row that is synchronised takes a new value (the server's row plus this
         // worker's push), which the gather must see, so it follows in a launch of its own too.
-        const uint32_t push_blocks = c->push_pending ? PUSH_BLOCKS : 0u;
+        // Host-backed table with a batch announced for the next lookup: the second kernel lists that
+        // batch's keys that are not cached, and a kernel on the stream beside this one brings their rows
+        // into HBM while the update runs, with the write-back going the other way beside them (so the
+        // fetch kernel leaves the write-back to it); the next lookup's fetch kernel finds them there.
+        const bool host = c->side != nullptr;
+        Announced *next = host && c->n_ann > 0 ? &c->ann[0] : nullptr;
+        if (host) {
+            // rows fetched ahead for this lookup; and no refresh of this lookup may overtake an older staged copy
+            wait_link(c);
+            if (c->pf.ready && c->pf.ids == ids && c->pf.n == n) ah.use_tag = c->pf.tag;
+            c->pf.ready = false;
+        }
+        const uint32_t push_blocks = c->push_pending && !next ? PUSH_BLOCKS : 0u;
         const uint32_t fetch_blocks = c->location == HET_BACKING_HBM ? fill_blocks : std::min(fill_blocks, PUSH_BLOCKS);
         {
             const Rides ride = next_rides(c);
             FILL_GATHER_ANY(ride.blocks() + push_blocks + fetch_blocks + ptiles + hist_blocks, fetch_blocks, hist_blocks, push_blocks);
         }
-        c->push_pending = false;
+        if (push_blocks) c->push_pending = false;
+        ah = Ahead{};
+        if (next) {
+            if (next->next_stage < sort_stages(c)) {         // what is left of its sort runs now
+                sort_now(c, next->ids, next->n, next->set, next->next_stage);
+                next->next_stage = sort_stages(c);
+            }
+            c->pf_serial = (c->pf_serial % 0x7FFFFFFFu) + 1;
+            ah.skey = c->keys[next->set][sort_result_buffer(c)];
+            ah.n = next->n;
+            ah.blocks = cdiv(next->n, 256);
+            ah.list_tag = 0x80000000u | c->pf_serial;
+            ah.list_slot = c->pf_slot_next;
+            ah.pending_seq = c->push_pending ? c->push_seq : 0u;
+        }
         {
             const Rides ride = next_rides(c);
-            FILL_GATHER_ANY(ride.blocks() + gather_blocks, 0u, 0u, 0u);
+            FILL_GATHER_ANY(ride.blocks() + ah.blocks + gather_blocks, 0u, 0u, 0u);
+        }
+        if (next) {
+            if ((rc = launch_ok()) != HET_OK) return rc;
+            HIP_TRY(hipEventRecord(c->ev_main, c->stream));
+            HIP_TRY(hipStreamWaitEvent(c->side, c->ev_main, 0));
+            const int pbuf = c->push_pending ? c->push_buf : -1;
+            // Few workgroups with several rows in flight each: a compute unit that waits for the host link
+            // serves its other waves' memory requests behind those that wait, so every compute unit that
+            // hosts a workgroup of this kernel is slow for the update's kernels meanwhile (measured: with
+            // 512 workgroups the optimizer step took as long as the whole transfer).
+            if (VEC == 4) LAUNCH_ON(c, c->side, K_LINK, link_kernel<4><<<LINK_BLOCKS, 256, 0, c->side>>>(c->cv, pbuf, ah.list_slot, c->push_buf, LINK_BLOCKS / 2));
+            else LAUNCH_ON(c, c->side, K_LINK, link_kernel<1><<<LINK_BLOCKS, 256, 0, c->side>>>(c->cv, pbuf, ah.list_slot, c->push_buf, LINK_BLOCKS / 2));
+            if ((rc = launch_ok()) != HET_OK) return rc;
+            HIP_TRY(hipEventRecord(c->ev_link, c->side));
+            c->link_outstanding = true;
+            c->push_pending = false;
+            c->pf.ready = true; c->pf.ids = next->ids; c->pf.n = next->n; c->pf.tag = ah.list_tag;
+            c->pf_slot_next ^= 1;
         }
     }
 #undef FILL_GATHER_ANY
@@ -551,6 +615,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 int sync_all(het_cache *c)
 {
     drain_pushes(c);
+    if (c->side) HIP_TRY(hipStreamSynchronize(c->side));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return HET_OK;
 }
@@ -719,6 +784,12 @@ static int attach_impl(het_cache *c, float *table, float *state, uint32_t *cg, i
             if ((rc = dev_alloc(c, &hl.rows[b], row_elems)) || (rc = dev_alloc(c, &hl.keys[b], N)) || (rc = dev_alloc(c, &hl.cg[b], N))) return rc;
             if (state && (rc = dev_alloc(c, &hl.acc[b], row_elems))) return rc;
         }
+        if ((rc = dev_alloc(c, &hl.pf_rows, row_elems)) || (rc = dev_alloc(c, &hl.pf_keys, N)) || (rc = dev_alloc(c, &hl.pf_from, N))) return rc;
+        if (state && (rc = dev_alloc(c, &hl.pf_acc, row_elems))) return rc;
+        // the stream beside the main one (default priority), and the two events that order them
+        HIP_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+        HIP_TRY(hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
+        HIP_TRY(hipEventCreateWithFlags(&c->ev_link, hipEventDisableTiming));
     }
     c->location = location;
     c->attached = true;
@@ -730,7 +801,12 @@ int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, i
     const size_t keep = c ? c->owned.size() : 0;
     const bool was = c && c->attached;
     const int rc = attach_impl(c, table, state, cg, vocab, location);
-    if (rc != HET_OK && c && !was) free_owned_from(c, keep);
+    if (rc != HET_OK && c && !was) {
+        free_owned_from(c, keep);
+        if (c->ev_main) { (void)hipEventDestroy(c->ev_main); c->ev_main = nullptr; }
+        if (c->ev_link) { (void)hipEventDestroy(c->ev_link); c->ev_link = nullptr; }
+        if (c->side) { (void)hipStreamDestroy(c->side); c->side = nullptr; }
+    }
     return rc;
 }
 
@@ -765,6 +841,7 @@ int het_prefetch_cancel(het_cache *c)
     // stages already enqueued read their buffer in stream order before anything enqueued from now on;
     // stages not enqueued yet never will be
     c->n_ann = 0;
+    c->pf.ready = false;             // rows fetched ahead for a withdrawn batch are not used
     return HET_OK;
 }
 
@@ -832,6 +909,8 @@ int het_flush(het_cache *c)
     if (!ready(c)) return HET_EINVAL;
     begin_call(c);
     c->n_ann = 0;                // announcements do not outlive a flush
+    c->pf.ready = false;
+    wait_link(c);                // (nothing the flush writes may be overtaken by an older staged copy)
     drain_pushes(c);             // (a staged copy of a row reaches the table before anything the flush writes)
     const uint32_t grid = row_grid(c->cv.geom, c->cv.n_slots);
     if (c->cv.geom.vec == 4) LAUNCH(c, K_FLUSH, flush_kernel<4><<<grid, 256, 0, c->stream>>>(c->cv));
@@ -1073,6 +1152,9 @@ int het_cache_destroy(het_cache *c)
     if (!c) return HET_OK;
     int rc = HET_OK;
     if (c->configured && sync_all(c) != HET_OK) rc = HET_EHIP;
+    if (c->ev_main) (void)hipEventDestroy(c->ev_main);
+    if (c->ev_link) (void)hipEventDestroy(c->ev_link);
+    if (c->side) (void)hipStreamDestroy(c->side);
     for (void *p : c->owned)
         if (hipFree(p) != hipSuccess) rc = HET_EHIP;
     delete c;

@@ -180,3 +180,42 @@ def test_withdrawn_announcements_are_not_used():
         p.flush_and_compare()
     finally:
         p.close()
+
+
+@pytest.mark.parametrize("policy,opt", [(wl.LRU, wl.SGD), (wl.LFU, wl.ADAGRAD)])
+def test_rows_fetched_ahead_are_used_only_by_the_lookup_they_were_fetched_for(policy, opt):
+    """Host-backed table: while an update runs, the rows the announced batch will miss are brought into
+    HBM on a stream beside the main one.  Here the announced batch does not come next, comes later, is
+    withdrawn, or comes after a flush; rows evicted or updated in between must come from where they
+    are then (cache, staging buffer, table), never from a copy fetched ahead that has gone stale."""
+    w = wl.WORKLOADS[1].scaled(vocab=3000, capacity=150, s=2, policy=policy, optimizer=opt, eps=1e-8, backing="host")
+    T = 12
+    ids = wl.IdStream(w).batches(T)
+    g = wl.grad_pool(w)
+    p = Pair(w, wl.table_init(w))
+    try:
+        d = torch.from_numpy(ids).to(p.dev)
+        step = lambda t, gi: (p.lookup(ids[t], ids_dev=d[t]), p.update(ids[t], g[gi % len(g)], ids_dev=d[t]))
+        p.cache.prefetch(d[1])
+        step(0, 0)                      # lists batch 1 and fetches its rows ahead
+        step(2, 1)                      # another batch comes first (and lists batch 1 again, after its own changes)
+        step(1, 2)                      # now the announced one
+        p.compare_state(values=True); p.compare_counters()
+        p.cache.prefetch(d[3])
+        step(4, 3)                      # lists batch 3
+        p.cache.prefetch_cancel()       # withdrawn: batch 3 sorts and fetches for itself
+        step(3, 4)
+        p.cache.prefetch(d[5])
+        step(6, 5)
+        assert p.cache.flush() == 0     # a flush in between: announcements are void
+        p.oracle.flush()
+        step(5, 6)
+        p.cache.prefetch(d[7]); p.cache.prefetch(d[8])
+        for t in (9, 7, 8):             # free running: nothing waits between these calls
+            p.cache.lookup(d[t], torch.empty(w.n, w.dim, device=p.dev))
+            p.cache.update(d[t], torch.from_numpy(g[t % len(g)]).to(p.dev), w.lr)
+            p.oracle.lookup(ids[t]); p.oracle.update(ids[t], g[t % len(g)], w.lr)
+        p.compare_state(values=True); p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
