@@ -36,7 +36,7 @@ class BruteCache:
             self.W, self.A, self.c_g = server.W, server.A, server.c_g
         else:
             self.W = [[float(x) for x in r] for r in table]      # global table
-            self.A = [[0.0] * dim for _ in table]
+            self.A = [[0.0] * dim for _ in table]         # (row-wise Adagrad, optimizer 2, uses the first entry only)
             self.c_g = [0] * len(table)
         self.entries = []                                      # the cache embedding table
         self.t = 0
@@ -58,7 +58,7 @@ class BruteCache:
         if self.many:
             for j in range(self.D):
                 self.W[e.key][j] = self.W[e.key][j] + (e.row[j] - e.row0[j])
-                if self.opt == 1:
+                if self.opt == 1 or (self.opt == 2 and j == 0):
                     self.A[e.key][j] = self.A[e.key][j] + (e.acc[j] - e.acc0[j])
         else:
             self.W[e.key] = list(e.row)
@@ -124,15 +124,25 @@ class BruteCache:
                 g[j] = g[j] + float(grads[i][j])
         for k in sorted(G):
             e = self.find(k)
+            if self.opt == 2:
+                e.acc[0] = e.acc[0] + self._mean_sq(G[k])
             for j in range(self.D):
                 g = G[k][j]
-                if self.opt == 0:
+                if self.opt == 2:
+                    e.row[j] = e.row[j] - (lr * g) / (math.sqrt(e.acc[0]) + self.eps)
+                elif self.opt == 0:
                     e.row[j] = e.row[j] - lr * g
                 else:
                     e.acc[j] = e.acc[j] + g * g
                     e.row[j] = e.row[j] - (lr * g) / (math.sqrt(e.acc[j]) + self.eps)
             e.c_c += 1
         self.evict_overflow()
+
+    def _mean_sq(self, g):
+        ss = 0.0
+        for v in g:
+            ss = ss + v * v
+        return ss / self.D
 
     def flush(self):
         for e in self.entries:

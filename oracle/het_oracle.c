@@ -40,6 +40,10 @@
  * het_oracle_foreign_update is a push by a worker that is not modelled otherwise: the server adds
  * a delta to the global row and advances its clock by one.
  *
+ * Row-wise Adagrad (not in the paper; a common half-state variant for embedding tables): one
+ * accumulator per row, a += mean_j(g_j^2); x_j -= lr * g_j / (sqrt(a) + eps).  The accumulator
+ * arrays then hold one value per row (A[V], one per cached row) and travel with the row as before.
+ *
  * Light-weight LFU (Section 4.3: once an embedding's frequency is "high enough" it is accessed
  * directly and its frequency is no longer maintained; the paper gives no threshold): LFU whose
  * use counter stops at a cap (het_oracle_set_lfu_cap, default 16).  A row whose counter has
@@ -70,7 +74,7 @@
 typedef HET_REAL real;
 
 enum { POLICY_LRU = 0, POLICY_LFU = 1, POLICY_LFU_LIGHT = 3 };   /* (2 is the GPU library's "no cache") */
-enum { OPT_SGD = 0, OPT_ADAGRAD = 1 };
+enum { OPT_SGD = 0, OPT_ADAGRAD = 1, OPT_ADAGRAD_ROW = 2 };
 enum { CLS_HIT = 0, CLS_STALE = 1, CLS_MISS = 2 };
 enum { ERR_NONE = 0, ERR_RANGE = 1, ERR_STATE = 2, ERR_ARG = 4 };
 
@@ -82,6 +86,7 @@ typedef struct het_oracle {
     /* configuration */
     int64_t C, P, max_ids, s;
     int32_t dim, policy, opt;
+    int32_t sdim;            /* optimizer state per row: dim (Adagrad), 1 (row-wise Adagrad); unused for SGD */
     int32_t many;            /* several workers write the global table: Evict pushes deltas */
     uint32_t lfu_cap;        /* light-weight LFU: the use counter stops here */
     real eps;
@@ -119,9 +124,10 @@ het_oracle *het_oracle_create(int64_t capacity, int32_t dim, int64_t s, int32_t 
 {
     if (capacity <= 0 || dim <= 0 || s < 0 || max_batch_ids <= 0) return NULL;
     if (policy != POLICY_LRU && policy != POLICY_LFU && policy != POLICY_LFU_LIGHT) return NULL;
-    if (optimizer != OPT_SGD && optimizer != OPT_ADAGRAD) return NULL;
+    if (optimizer != OPT_SGD && optimizer != OPT_ADAGRAD && optimizer != OPT_ADAGRAD_ROW) return NULL;
     het_oracle *o = (het_oracle *)calloc(1, sizeof(*o));
     o->lfu_cap = 16;
+    o->sdim = optimizer == OPT_ADAGRAD_ROW ? 1 : dim;
     o->C = capacity; o->dim = dim; o->s = s; o->policy = policy;
     o->max_ids = max_batch_ids; o->opt = optimizer; o->eps = (real)eps;
     o->P = capacity + max_batch_ids;
@@ -144,7 +150,7 @@ het_oracle *het_oracle_create(int64_t capacity, int32_t dim, int64_t s, int32_t 
 int het_oracle_attach(het_oracle *o, real *W, real *A, uint32_t *Cg, int64_t V)
 {
     if (!o || !W || !Cg || V <= 0) return ERR_ARG;
-    if (o->opt == OPT_ADAGRAD && !A) return ERR_ARG;
+    if (o->opt != OPT_SGD && !A) return ERR_ARG;
     o->W = W; o->A = A; o->Cg = Cg; o->V = V;
     free(o->slot_of);
     o->slot_of = (int64_t *)malloc(sizeof(int64_t) * V);
@@ -189,15 +195,15 @@ static int write_back(het_oracle *o, int64_t slot)
         for (int32_t j = 0; j < o->dim; ++j) {
             real d = o->row[(size_t)slot * o->dim + j] - o->row0[(size_t)slot * o->dim + j];
             o->W[(size_t)k * o->dim + j] = o->W[(size_t)k * o->dim + j] + d;
-            if (o->opt == OPT_ADAGRAD) {
-                real da = o->acc[(size_t)slot * o->dim + j] - o->acc0[(size_t)slot * o->dim + j];
-                o->A[(size_t)k * o->dim + j] = o->A[(size_t)k * o->dim + j] + da;
+            if (o->opt != OPT_SGD && j < o->sdim) {
+                real da = o->acc[(size_t)slot * o->sdim + j] - o->acc0[(size_t)slot * o->sdim + j];
+                o->A[(size_t)k * o->sdim + j] = o->A[(size_t)k * o->sdim + j] + da;
             }
         }
     } else {
         memcpy(o->W + (size_t)k * o->dim, o->row + (size_t)slot * o->dim, sizeof(real) * o->dim);
-        if (o->opt == OPT_ADAGRAD)
-            memcpy(o->A + (size_t)k * o->dim, o->acc + (size_t)slot * o->dim, sizeof(real) * o->dim);
+        if (o->opt != OPT_SGD)
+            memcpy(o->A + (size_t)k * o->sdim, o->acc + (size_t)slot * o->sdim, sizeof(real) * o->sdim);
     }
     if (o->cc[slot] > o->Cg[k]) o->Cg[k] = o->cc[slot];
     return 1;
@@ -208,16 +214,16 @@ static void rebase(het_oracle *o, int64_t slot)
 {
     if (!o->many) return;
     memcpy(o->row0 + (size_t)slot * o->dim, o->row + (size_t)slot * o->dim, sizeof(real) * o->dim);
-    if (o->opt == OPT_ADAGRAD)
-        memcpy(o->acc0 + (size_t)slot * o->dim, o->acc + (size_t)slot * o->dim, sizeof(real) * o->dim);
+    if (o->opt != OPT_SGD)
+        memcpy(o->acc0 + (size_t)slot * o->sdim, o->acc + (size_t)slot * o->sdim, sizeof(real) * o->sdim);
 }
 
 /* Fetch: read the global row, c_s = c_c = c_g   (Section 3.1, Fetch) */
 static void fetch_into(het_oracle *o, int64_t k, int64_t slot)
 {
     memcpy(o->row + (size_t)slot * o->dim, o->W + (size_t)k * o->dim, sizeof(real) * o->dim);
-    if (o->opt == OPT_ADAGRAD)
-        memcpy(o->acc + (size_t)slot * o->dim, o->A + (size_t)k * o->dim, sizeof(real) * o->dim);
+    if (o->opt != OPT_SGD)
+        memcpy(o->acc + (size_t)slot * o->sdim, o->A + (size_t)k * o->sdim, sizeof(real) * o->sdim);
     o->cs[slot] = o->cc[slot] = o->Cg[k];
     rebase(o, slot);
 }
@@ -393,10 +399,22 @@ static int write_keys(het_oracle *o, const int64_t *ids, int64_t n, const real *
     for (int64_t u = 0; u < U; ++u) {           /* Update + Clock */
         int64_t slot = o->slot_of[K[u]];
         if (slot < 0) { o->err |= ERR_STATE; continue; }
-        real *x = o->row + (size_t)slot * o->dim, *a = o->acc + (size_t)slot * o->dim;
+        real *x = o->row + (size_t)slot * o->dim, *a = o->acc + (size_t)slot * o->sdim;
         const real *g = G + (size_t)u * o->dim;
+        real row_denom = 0;
+        if (o->opt == OPT_ADAGRAD_ROW) {        /* one accumulator for the row: the mean of the squares */
+            real ss = 0;
+            for (int32_t j = 0; j < o->dim; ++j) { real sq = g[j] * g[j]; ss = ss + sq; }
+            ss = ss / (real)o->dim;
+            a[0] = a[0] + ss;
+            row_denom = (real)sqrt((double)a[0]) + o->eps;
+        }
         for (int32_t j = 0; j < o->dim; ++j) {
-            if (o->opt == OPT_SGD) {
+            if (o->opt == OPT_ADAGRAD_ROW) {
+                real step = lr * g[j];
+                step = step / row_denom;
+                x[j] = x[j] - step;
+            } else if (o->opt == OPT_SGD) {
                 real step = lr * g[j];
                 x[j] = x[j] - step;
             } else {
@@ -479,8 +497,8 @@ int64_t het_oracle_export_rows(const het_oracle *o, real *rows, real *acc)
     for (int64_t slot = 0; slot < o->P; ++slot)
         if (o->key[slot] >= 0) {
             memcpy(rows + (size_t)r * o->dim, o->row + (size_t)slot * o->dim, sizeof(real) * o->dim);
-            if (acc) memcpy(acc + (size_t)r * o->dim, o->acc + (size_t)slot * o->dim,
-                            sizeof(real) * o->dim);
+            if (acc) memcpy(acc + (size_t)r * o->sdim, o->acc + (size_t)slot * o->sdim,
+                            sizeof(real) * o->sdim);
             ++r;
         }
     return r;

@@ -88,7 +88,7 @@ class Oracle:
             self.W, self.A, self.Cg = share_with.W, share_with.A, share_with.Cg
         else:
             self.W = np.ascontiguousarray(table, dtype=self.dtype).copy()
-            self.A = np.zeros_like(self.W) if optimizer == 1 else None
+            self.A = np.zeros_like(self.W) if optimizer == 1 else (np.zeros((self.W.shape[0], 1), self.dtype) if optimizer == 2 else None)
             self.Cg = np.zeros(self.W.shape[0], dtype=np.uint32)
         V = self.W.shape[0]
         rc = self.lib.het_oracle_attach(self.h, _ptr(self.W), _ptr(self.A), _ptr(self.Cg), V)
@@ -148,7 +148,7 @@ class Oracle:
 
     def export_rows(self):
         rows = np.empty((self.P, self.dim), self.dtype)
-        acc = np.empty((self.P, self.dim), self.dtype) if self.A is not None else None
+        acc = np.empty((self.P, self.A.shape[1]), self.dtype) if self.A is not None else None
         r = self.lib.het_oracle_export_rows(self.h, _ptr(rows), _ptr(acc))
         return rows[:r], (acc[:r] if acc is not None else None)
 

@@ -423,3 +423,65 @@ def test_light_lfu_misses_about_as_often_as_lfu():
         miss[name] = o.stats()[1]["miss"] - warm
     assert abs(miss["light"] - miss["lfu"]) <= 0.05 * miss["lfu"]
     assert miss["light"] < miss["lru"]
+
+
+# ---------------------------------------------------------------- row-wise Adagrad (one accumulator per row)
+def test_rowwise_adagrad_with_rows_of_one_float_is_adagrad():
+    """dim = 1: the mean of the squares is the square, so the row-wise form is the element-wise one
+    (itself pinned to the library optimizer above)."""
+    V, C, N = 80, 10, 25
+    ids, grads, table = stream(43, V, N, 120, 1, alpha=1.1)
+    a = Oracle(C, 1, 2, 1, N, 1, 1e-8, table)
+    b = Oracle(C, 1, 2, 1, N, 2, 1e-8, table)
+    for i, g in zip(ids, grads):
+        x, _ = a.lookup(i); y, _ = b.lookup(i)
+        assert np.array_equal(x, y)
+        a.update(i, g, 0.05); b.update(i, g, 0.05)
+    a.flush(); b.flush()
+    assert np.array_equal(a.W, b.W) and np.array_equal(a.A, b.A)
+
+
+def test_rowwise_adagrad_matches_library_adagrad_on_rows_of_equal_gradients():
+    """If every component of a row's gradient is the same number c, the mean of the squares is c^2 and
+    every component follows plain Adagrad with gradient c: the library optimizer on the dense table."""
+    V, D, C, N, lr, eps = 40, 5, 40, 12, 0.1, 1e-10
+    rng = np.random.default_rng(47)
+    table = rng.standard_normal((V, D)) * 0.01
+    o = Oracle(C, D, 3, 1, N, 2, eps, table)
+    Wt = torch.tensor(table.copy(), dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adagrad([Wt], lr=lr, eps=eps)
+    for t in range(60):
+        ids = rng.integers(0, V, size=N).astype(np.int64)
+        c = rng.standard_normal(N)
+        grads = np.repeat(c[:, None], D, axis=1)
+        out, _ = o.lookup(ids)
+        np.testing.assert_allclose(out, Wt.detach().numpy()[ids], rtol=1e-12, atol=1e-15)
+        o.update(ids, grads, lr)
+        dense = np.zeros((V, D))
+        np.add.at(dense, ids, grads)
+        # rows that were not touched must not move: give them no gradient at all
+        Wt.grad = torch.tensor(dense)
+        before = Wt.detach().clone()
+        opt.step()
+        untouched = np.setdiff1d(np.arange(V), ids)
+        assert torch.equal(Wt.detach()[untouched], before[untouched])
+    o.flush()
+    np.testing.assert_allclose(o.W, Wt.detach().numpy(), rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("policy,s,many", [(0, 0, False), (1, 2, False), (1, 3, True)])
+def test_rowwise_adagrad_matches_brute_force_twin(policy, s, many):
+    V, C, D, N = 50, 6, 4, 12
+    ids, grads, table = stream(53 + policy, V, N, 100, D)
+    o = Oracle(C, D, s, policy, N, 2, 1e-8, table, many_writers=many)
+    b = brute.BruteCache(C, D, s, policy, N, 2, 1e-8, table, many=many)
+    for i, g in zip(ids, grads):
+        out, _ = o.lookup(i)
+        assert np.array_equal(out, np.asarray(b.read(i.tolist())))
+        o.update(i, g, 0.05)
+        b.write(i.tolist(), g.tolist(), 0.05)
+        assert o.last_evicted().tolist() == b.evicted
+        assert np.array_equal(o.W, np.asarray(b.W))
+        assert np.array_equal(o.A[:, 0], np.asarray(b.A)[:, 0])
+    o.flush(); b.flush()
+    assert np.array_equal(o.W, np.asarray(b.W)) and np.array_equal(o.A[:, 0], np.asarray(b.A)[:, 0])
