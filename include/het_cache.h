@@ -48,7 +48,8 @@ typedef enum het_status {
 enum { HET_POLICY_LRU = 0, HET_POLICY_LFU = 1,          /* Section 4.3 */
        HET_POLICY_NONE = 2,                              /* no cache at all: the baseline "Hybrid (w/o Cache)" of Section 5 */
        HET_POLICY_LFU_LIGHT = 3 };                       /* the light-weight LFU of Section 4.3, an approximation of LFU: see het_cache_set_lfu_cap */
-enum { HET_OPT_SGD = 0, HET_OPT_ADAGRAD = 1 };
+enum { HET_OPT_SGD = 0, HET_OPT_ADAGRAD = 1,
+       HET_OPT_ADAGRAD_ROWWISE = 2 };   /* one accumulator per row: a += mean_j(G_j^2); x_j -= lr * G_j / (sqrt(a) + eps) */
 enum { HET_BACKING_HBM = 0, HET_BACKING_PINNED_HOST = 1 };
 enum { HET_CLASS_HIT = 0, HET_CLASS_STALE = 1, HET_CLASS_MISS = 2 };
 #define HET_S_INFINITE INT64_MAX /* staleness bound that never invalidates a row */
@@ -118,9 +119,14 @@ int het_cache_set_many_writers(het_cache *c);
  * the cache in HBM: capacity + max_batch_ids row slots (rows fetched on a miss are added beyond
  * the capacity and the overflow is trimmed at the end of the update, Algorithm 2 / 3), the
  * id->slot hash table and the per-call workspaces.  Must be called once, before attach.
- * eps is Adagrad's epsilon (ignored for SGD).
+ * eps is Adagrad's epsilon (ignored for SGD).  HET_OPT_ADAGRAD_ROWWISE keeps one accumulator per row
+ * instead of one per element (half the optimizer state of an embedding table): `state` of
+ * het_attach_backing is then float[vocab] and het_export_rows' acc float[n_resident]; the table
+ * must be in HBM.
  * HET_EINVAL: max_batch_ids <= 0 or above 2^20, unknown optimizer, eps < 0, a second call, or
- * rows wider than the kernels take (dim above 4096, or above 1024 if dim is no multiple of 4).
+ * rows wider than the kernels take (dim above 4096, or above 1024 if dim is no multiple of 4; for
+ * HET_OPT_ADAGRAD_ROWWISE dim above 256, or above 64 if dim is no multiple of 4), row-wise Adagrad
+ * together with het_cache_set_many_writers.
  * HET_ENOMEM: the device allocation failed.
  */
 int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps,
@@ -129,7 +135,8 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
 /*
  * Names the global embedding table this cache fronts (Section 3.1):
  *   table  float[vocab][dim], row-major: the global rows;
- *   state  float[vocab][dim]: Adagrad accumulators, travelling with the rows (NULL for SGD);
+ *   state  float[vocab][dim]: Adagrad accumulators, travelling with the rows (NULL for SGD;
+ *          float[vocab] for row-wise Adagrad);
  *   cg     uint32[vocab]: global clock c_g per row, zero-initialised by the caller.
  * location HET_BACKING_HBM: device pointers.  HET_BACKING_PINNED_HOST: pointers to pinned,
  * device-mapped host memory (hipHostMalloc); kernels read and write it over the host link.

@@ -75,7 +75,8 @@ struct CacheView {
     Counters *last;       // this call's counters (one of ds->call)
     Counters *next_call;  // the other one: cleared by this call for the next
     RowGeom geom;
-    int adagrad;
+    int adagrad;          // element-wise Adagrad: an accumulator row beside every row
+    int rowwise;          // row-wise Adagrad: one accumulator per row (acc[slot], A[key]); rows of at most one piece per lane
     int direct;           // no cache: rows/acc alias the global table, a key is its own slot, there are no clocks
 };
 
@@ -591,6 +592,7 @@ __device__ __forceinline__ void push_row(const CacheView &cv, uint32_t key, uint
     row_copy<VEC>(cv.W + (size_t)key * g.dim, cv.rows + (size_t)slot * g.dim, g.chunks, g.lanes, gl);
     if (cv.adagrad)
         row_copy<VEC>(cv.A + (size_t)key * g.dim, cv.acc + (size_t)slot * g.dim, g.chunks, g.lanes, gl);
+    if (cv.rowwise && gl == 0) cv.A[key] = cv.acc[slot];
     if (gl == 0) {
         const uint32_t cc = cv.meta[slot].cc;
         if (cc > cv.Cg[key]) { cv.Cg[key] = cc; if (cv.Cg_host) cv.Cg_host[key] = cc; }
@@ -640,6 +642,7 @@ __device__ __forceinline__ void pull_row(const CacheView &cv, uint32_t key, uint
     row_copy<VEC>(cv.rows + (size_t)slot * g.dim, cv.W + (size_t)key * g.dim, g.chunks, g.lanes, gl);
     if (cv.adagrad)
         row_copy<VEC>(cv.acc + (size_t)slot * g.dim, cv.A + (size_t)key * g.dim, g.chunks, g.lanes, gl);
+    if (cv.rowwise && gl == 0) cv.acc[slot] = cv.A[key];
 }
 
 // The same from explicit sources (a staged row).
@@ -890,12 +893,13 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         // rows in flight each leave the chip to the other roles of this kernel from the start)
         for (uint32_t m0 = gid; m0 < tot_miss; m0 += ngroups * FILL_ROWS) {
             const float *srow[FILL_ROWS], *sacc[FILL_ROWS];
-            uint32_t slot[FILL_ROWS];
+            uint32_t slot[FILL_ROWS], keyr[FILL_ROWS];
 #pragma unroll
             for (int r = 0; r < FILL_ROWS; ++r) {
                 const uint32_t m = m0 + r * ngroups < tot_miss ? m0 + r * ngroups : m0;     // (beyond the end: the first row again, not stored)
                 const uint32_t tl = tile_of(fl.pre_miss, ptiles, m);
                 const uint32_t key = ws.miss_stage[tl * PT_TILE + (m - fl.pre_miss[tl])].y;
+                keyr[r] = key;
                 slot[r] = cv.free_list[m];
                 // host-backed table: a row the last trim evicted may still be on its way to the table
                 // (its write-back travels in this very kernel); then the staged copy is the global row
@@ -914,6 +918,11 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             for (int r = 0; r < FILL_ROWS; ++r) nin += m0 + r * ngroups < tot_miss ? 1 : 0;
             if (cv.adagrad) fetch_rows<VEC, true>(cv, srow, sacc, slot, nin, gl);
             else fetch_rows<VEC, false>(cv, srow, sacc, slot, nin, gl);
+            if (cv.rowwise && gl == 0) {             // (one accumulator per row; such a table is in HBM)
+#pragma unroll
+                for (int r = 0; r < FILL_ROWS; ++r)
+                    if (r < nin) cv.acc[slot[r]] = cv.A[keyr[r]];
+            }
         }                                        // (clocks, key and index entry: the workgroups below)
         for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
             const uint32_t tl = tile_of(fl.pre_stale, ptiles, m);
@@ -1060,17 +1069,38 @@ __device__ __forceinline__ float fast_sqrt(float v) { return __builtin_amdgcn_sq
 __device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
 
 // The optimizer step on one cached row for chunk c of the row, and nothing else.
+// Row-wise Adagrad's denominator for the row in `slot`: the row group adds up the squares of the
+// gradient's pieces (every lane of the group calls, lanes beyond the row with zeros; the row has one
+// piece per lane), the accumulator takes their mean, and the group's first lane stores it.
 template <int VEC>
-__device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, int c, const double *g64, float lr, float eps)
+__device__ __forceinline__ float rowwise_rcp(const CacheView &cv, uint32_t slot, const float (&G)[VEC], float eps)
+{
+    double ss = 0.0;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) ss += (double)G[k] * (double)G[k];
+    for (int o = cv.geom.lanes / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, WAVE);     // (the same tree in every lane: the same sum)
+    const float a = cv.acc[slot] + (float)(ss / (double)cv.geom.dim);
+    if (threadIdx.x % cv.geom.lanes == 0) cv.acc[slot] = a;
+    return fast_rcp(fast_sqrt(a) + eps);
+}
+
+template <int VEC>
+__device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, int c, const double *g64, float lr, float eps, bool act = true)
 {
     using V = typename VecT<VEC>::type;
     float G[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) G[k] = (float)g64[k];           // the fp64 sum is rounded to fp32 once
+    for (int k = 0; k < VEC; ++k) G[k] = act ? (float)g64[k] : 0.f;           // the fp64 sum is rounded to fp32 once
+    float row_rcp = 0.f;
+    if (cv.rowwise) row_rcp = rowwise_rcp<VEC>(cv, slot, G, eps);
+    if (!act) return;
     V *xp = reinterpret_cast<V *>(cv.rows + (size_t)slot * cv.geom.dim) + c;
     V xv = *xp;
     float *x = reinterpret_cast<float *>(&xv);
-    if (cv.adagrad) {
+    if (cv.rowwise) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) x[k] -= lr * G[k] * row_rcp;
+    } else if (cv.adagrad) {
         V *ap = reinterpret_cast<V *>(cv.acc + (size_t)slot * cv.geom.dim) + c;
         V av = *ap;
         float *a = reinterpret_cast<float *>(&av);
@@ -1181,14 +1211,21 @@ struct SegWork {
 // The optimizer step from a row already in registers.
 template <int VEC>
 __device__ __forceinline__ void apply_loaded(const CacheView &cv, uint32_t slot, int cidx, const double *g64, float lr, float eps,
-                                             typename VecT<VEC>::type xv, typename VecT<VEC>::type av)
+                                             typename VecT<VEC>::type xv, typename VecT<VEC>::type av, bool act)
 {
     using V = typename VecT<VEC>::type;
     float *x = reinterpret_cast<float *>(&xv), *a = reinterpret_cast<float *>(&av);
+    float Gs[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) Gs[e] = act ? (float)g64[e] : 0.f;          // the fp64 sum is rounded once
+    float row_rcp = 0.f;
+    if (cv.rowwise) row_rcp = rowwise_rcp<VEC>(cv, slot, Gs, eps);            // (every lane of the row group)
+    if (!act) return;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-        const float G = (float)g64[e];                                        // the fp64 sum is rounded once
-        if (cv.adagrad) { a[e] += G * G; x[e] -= lr * G * fast_rcp(fast_sqrt(a[e]) + eps); }
+        const float G = Gs[e];
+        if (cv.rowwise) x[e] -= lr * G * row_rcp;
+        else if (cv.adagrad) { a[e] += G * G; x[e] -= lr * G * fast_rcp(fast_sqrt(a[e]) + eps); }
         else x[e] -= lr * G;
     }
     reinterpret_cast<V *>(cv.rows + (size_t)slot * cv.geom.dim)[cidx] = xv;
@@ -1331,7 +1368,7 @@ __global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspa
     auto finish_piece = [&](const SegWork &w, int cidx, bool act, const double (&acc64)[VEC], V xr, V ar) {
         const bool closed = !w.is_front && !w.is_back;
         if (closed) {
-            if (act && w.slot != SLOT_NONE) apply_loaded<VEC>(cv, (uint32_t)w.slot, cidx, acc64, lr, eps, xr, ar);
+            if (w.slot != SLOT_NONE) apply_loaded<VEC>(cv, (uint32_t)w.slot, cidx, acc64, lr, eps, xr, ar, act);
         } else if (act) {
             double *mine = bd.part + ((size_t)T * 2 + (w.is_front ? 0 : 1)) * pstride + (size_t)cidx * VEC;
 #pragma unroll
@@ -1385,15 +1422,15 @@ __global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspa
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) l.share[threadIdx.x * VEC + e] = acc64[e];
                 __syncthreads();
-                if (group == 0 && act) {
+                if (group == 0) {
                     double tot[VEC];
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) tot[e] = 0.0;
                     for (uint32_t gi = 0; gi < ngroups; ++gi)
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) tot[e] += l.share[(gi * g.lanes + gl) * VEC + e];
-                    if (step) apply_loaded<VEC>(cv, (uint32_t)slot, cidx, tot, lr, eps, xr, ar);
-                    else if (!closed) {
+                    if (step) apply_loaded<VEC>(cv, (uint32_t)slot, cidx, tot, lr, eps, xr, ar, act);
+                    else if (!closed && act) {
                         double *mine = bd.part + ((size_t)T * 2 + (is_front ? 0 : 1)) * pstride + (size_t)cidx * VEC;
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) st_device(mine + e, tot[e]);
@@ -1429,7 +1466,8 @@ __global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspa
 #pragma unroll
     for (int q = 0; q < MAXC; ++q) {
         const int cidx = gl + q * g.lanes;
-        if (cidx >= g.chunks) continue;
+        const bool act = cidx < g.chunks;
+        if (!act && !cv.rowwise) continue;                  // (row-wise Adagrad: every lane of the group takes part in the row's sum)
         double sum[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
@@ -1438,16 +1476,16 @@ __global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspa
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint32_t i = i0 + u;
-                const double *pp = bd.part + ((size_t)(T0 + (i < m ? i : 0u)) * 2 + (i == 0 || i >= m ? 1 : 0)) * pstride + (size_t)cidx * VEC;
+                const double *pp = bd.part + ((size_t)(T0 + (i < m ? i : 0u)) * 2 + (i == 0 || i >= m ? 1 : 0)) * pstride + (size_t)(act ? cidx : 0) * VEC;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) part[u][e] = i < m ? ld_device(pp + e) : 0.0;
+                for (int e = 0; e < VEC; ++e) part[u][e] = i < m && act ? ld_device(pp + e) : 0.0;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
         }
-        if (slot != SLOT_NONE) apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps);
+        if (slot != SLOT_NONE) apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps, act);
     }
 }
 
@@ -1628,6 +1666,10 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
                 reinterpret_cast<V *>(dst_a + (size_t)to[2] * g.dim)[c] = a2;
                 reinterpret_cast<V *>(dst_a + (size_t)to[3] * g.dim)[c] = a3;
             }
+        }
+        if (cv.rowwise && gl == 0) {                 // (one accumulator per row; such a table is in HBM)
+#pragma unroll
+            for (int r = 0; r < PUSH_ROWS; ++r) cv.A[to[r]] = cv.acc[from[r]];
         }
     }
     if (threadIdx.x == 0) {

@@ -659,8 +659,9 @@ int het_cache_create(het_cache **out, int64_t capacity, int32_t dim, int64_t s, 
 static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps, void *hip_stream)
 {
     if (!c || c->configured || max_batch_ids <= 0 || max_batch_ids > (int64_t)MAX_PROBE_TILES * PT_TILE) return HET_EINVAL;
-    if (optimizer != HET_OPT_SGD && optimizer != HET_OPT_ADAGRAD) return HET_EINVAL;
+    if (optimizer != HET_OPT_SGD && optimizer != HET_OPT_ADAGRAD && optimizer != HET_OPT_ADAGRAD_ROWWISE) return HET_EINVAL;
     if (!(eps >= 0.f)) return HET_EINVAL;
+    if (optimizer == HET_OPT_ADAGRAD_ROWWISE && c->many) return HET_EINVAL;
     c->max_ids = max_batch_ids; c->optimizer = optimizer; c->eps = eps;
     c->stream = static_cast<hipStream_t>(hip_stream);
 
@@ -669,7 +670,7 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
     cv.direct = direct;
     const uint64_t P = direct ? 1 : (uint64_t)c->capacity + (uint64_t)max_batch_ids;
     cv.n_slots = (uint32_t)P; cv.capacity = (uint32_t)c->capacity; cv.max_ids = (uint32_t)max_batch_ids;
-    cv.s = c->s; cv.adagrad = optimizer == HET_OPT_ADAGRAD;
+    cv.s = c->s; cv.adagrad = optimizer == HET_OPT_ADAGRAD; cv.rowwise = optimizer == HET_OPT_ADAGRAD_ROWWISE;
     RowGeom g;
     g.dim = c->dim; g.vec = (c->dim % 4 == 0) ? 4 : 1; g.chunks = c->dim / g.vec;
     g.lanes = (int)std::min<uint32_t>(64u, pow2_at_least((uint64_t)g.chunks));
@@ -677,11 +678,13 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
     const int per_lane = (g.chunks + g.lanes - 1) / g.lanes;
     c->max_chunks_per_lane = per_lane <= 1 ? 1 : (per_lane <= 2 ? 2 : (per_lane <= 4 ? 4 : 16));
     if (per_lane > 16) return HET_EINVAL;               // rows wider than 64 lanes x 16 chunks
+    if (cv.rowwise && per_lane > 1) return HET_EINVAL;  // row-wise Adagrad: the row group holds the whole row's gradient at once
 
     int rc = HET_OK;
     const size_t row_elems = (size_t)P * (size_t)c->dim;
     if (!direct && (rc = dev_alloc(c, &cv.rows, row_elems))) return rc;
     if (!direct && cv.adagrad && (rc = dev_alloc(c, &cv.acc, row_elems))) return rc;
+    if (!direct && cv.rowwise && (rc = dev_alloc(c, &cv.acc, (size_t)P))) return rc;
     cv.many = c->many;
     cv.freq_cap = c->policy == HET_POLICY_LFU_LIGHT ? c->lfu_cap : 0u;
     if (c->many && (rc = dev_alloc(c, &cv.rows0, row_elems))) return rc;
@@ -751,7 +754,8 @@ static int attach_impl(het_cache *c, float *table, float *state, uint32_t *cg, i
 {
     if (!c || !c->configured || !table || !cg || vocab <= 0 || vocab >= 0xFFFFFFFFll) return HET_EINVAL;
     if (location != HET_BACKING_HBM && location != HET_BACKING_PINNED_HOST) return HET_EINVAL;
-    if (c->optimizer == HET_OPT_ADAGRAD && !state) return HET_EINVAL;
+    if (c->optimizer != HET_OPT_SGD && !state) return HET_EINVAL;
+    if (c->optimizer == HET_OPT_ADAGRAD_ROWWISE && location != HET_BACKING_HBM) return HET_EINVAL;
     if (c->attached) return HET_EINVAL;
     if (c->many && location != HET_BACKING_HBM) return HET_EINVAL;      // several workers: the shared table lives in HBM
     if (location == HET_BACKING_PINNED_HOST) {
@@ -984,15 +988,16 @@ int het_export_rows(het_cache *c, float *rows, float *acc)
         float *dst = which ? acc : rows;
         const float *src = which ? c->cv.acc : c->cv.rows;
         if (!dst || !src) continue;
+        const size_t W = which && c->cv.rowwise ? 1 : D;        // (row-wise Adagrad: one accumulator per row)
         size_t r = 0;
         for (size_t s0 = 0; s0 < P; s0 += step) {
             const size_t cnt = std::min(step, P - s0);
             bool any = false;
             for (size_t i = 0; i < cnt && !any; ++i) any = k[s0 + i] != KEY_NONE;
             if (!any) continue;
-            HIP_TRY(hipMemcpy(buf.data(), src + s0 * D, cnt * D * 4, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(buf.data(), src + s0 * W, cnt * W * 4, hipMemcpyDeviceToHost));
             for (size_t i = 0; i < cnt; ++i)
-                if (k[s0 + i] != KEY_NONE) { std::memcpy(dst + r * D, buf.data() + i * D, D * 4); ++r; }
+                if (k[s0 + i] != KEY_NONE) { std::memcpy(dst + r * W, buf.data() + i * W, W * 4); ++r; }
         }
     }
     return HET_OK;

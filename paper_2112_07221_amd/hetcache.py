@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libhet_cache.so")
 
 HET_OK, HET_EINVAL, HET_ENOMEM, HET_EHIP, HET_ERANGE, HET_ESTATE = 0, -1, -2, -3, -4, -5
 POLICY_LRU, POLICY_LFU, POLICY_NONE, POLICY_LFU_LIGHT = 0, 1, 2, 3
-OPT_SGD, OPT_ADAGRAD = 0, 1
+OPT_SGD, OPT_ADAGRAD, OPT_ADAGRAD_ROWWISE = 0, 1, 2
 BACKING_HBM, BACKING_PINNED_HOST = 0, 1
 CLASS_HIT, CLASS_STALE, CLASS_MISS = 0, 1, 2
 S_INFINITE = (1 << 63) - 1
@@ -273,7 +273,11 @@ class HetCache:
     def export_rows(self):
         r = int(self.stats()["resident"])
         rows = np.empty((r, self.dim), np.float32)
-        acc = np.empty((r, self.dim), np.float32) if self.optimizer == OPT_ADAGRAD else None
+        acc = None
+        if self.optimizer == OPT_ADAGRAD:
+            acc = np.empty((r, self.dim), np.float32)
+        elif self.optimizer == OPT_ADAGRAD_ROWWISE:
+            acc = np.empty((r, 1), np.float32)
         self._rc(self.lib.het_export_rows(self.h, _np_ptr(rows), _np_ptr(acc) if acc is not None else None),
                  "het_export_rows")
         return rows, acc

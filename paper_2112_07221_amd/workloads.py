@@ -17,7 +17,7 @@ from typing import Optional
 import numpy as np
 
 LRU, LFU, LFU_LIGHT = 0, 1, 3
-SGD, ADAGRAD = 0, 1
+SGD, ADAGRAD, ADAGRAD_ROWWISE = 0, 1, 2
 
 
 @dataclass(frozen=True)

@@ -46,11 +46,11 @@ class Pair:
             V = table.shape[0]
             if host:
                 self.W = torch.from_numpy(table.astype(np.float32)).pin_memory()
-                self.A = torch.zeros(V, w.dim).pin_memory() if w.optimizer else None
+                self.A = torch.zeros(V, w.dim if w.optimizer == 1 else 1).pin_memory() if w.optimizer else None
                 self.Cg = torch.zeros(V, dtype=torch.int32).pin_memory()
             else:
                 self.W = torch.from_numpy(table.astype(np.float32)).to(dev)
-                self.A = torch.zeros(V, w.dim, device=dev) if w.optimizer else None
+                self.A = torch.zeros(V, w.dim if w.optimizer == 1 else 1, device=dev) if w.optimizer else None    # (row-wise Adagrad: one per row)
                 self.Cg = torch.zeros(V, dtype=torch.int32, device=dev)
         self.cache.attach_backing(self.W, self.A, self.Cg,
                                   hc.BACKING_PINNED_HOST if host else hc.BACKING_HBM)

@@ -779,3 +779,79 @@ def test_update_reuses_the_lookup_order_only_for_the_same_ids():
         assert p.cache.stats()["error_bits"] & 2
     finally:
         p.close()
+
+
+@pytest.mark.parametrize("dim", [1, 4, 10, 16, 64, 256])
+def test_rowwise_adagrad_row_widths(dim):
+    """HET_OPT_ADAGRAD_ROWWISE: one accumulator per row (a += mean of the squared gradient), the row
+    group adding up the squares; rows narrower than their row group (dim 10: six idle lanes)."""
+    w = wl.WORKLOADS[1].scaled(dim=dim, optimizer=wl.ADAGRAD_ROWWISE, eps=1e-8, policy=wl.LFU, s=2)
+    st = run_workload(w, 14, state_every=2, values_every=2, prefetch="before")
+    assert st["total"]["stale_dirty"] > 0 and st["total"]["evicted_dirty"] > 0
+
+
+def test_rowwise_adagrad_config2_full_size_and_long_runs():
+    w = wl.WORKLOADS[2].scaled(optimizer=wl.ADAGRAD_ROWWISE, s=3)
+    st = run_workload(w, 10, state_every=5, values_every=5, prefetch="before")
+    assert st["total"]["stale_dirty"] > 0
+    # a few keys hold most of the batch: segments summed by the whole workgroup, and runs that cross tiles
+    w = wl.WORKLOADS[1].scaled(dim=64, capacity=400, s=2, optimizer=wl.ADAGRAD_ROWWISE, eps=1e-8, policy=wl.LFU)
+    rng = np.random.default_rng(13)
+    n = 3000
+    p = Pair(w, wl.table_init(w), max_ids=n)
+    try:
+        hot = rng.permutation(w.vocab)[:3]
+        for it in range(3):
+            u = rng.random(n)
+            ids = rng.integers(0, w.vocab, size=n)
+            ids[u < 0.85] = hot[2]; ids[u < 0.65] = hot[1]; ids[u < 0.45] = hot[0]
+            ids = ids.astype(np.int64)
+            g = rng.standard_normal((n, w.dim)).astype(np.float32)
+            p.lookup(ids); p.update(ids, g)
+            p.compare_state(values=True); p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
+def test_rowwise_adagrad_pooled_and_without_a_cache():
+    w = wl.WORKLOADS[5].scaled(vocab=50_000, dim=64, batch=128, capacity=3_000, s=3, optimizer=wl.ADAGRAD_ROWWISE)
+    st = run_workload(w, 12, state_every=3, values_every=3)
+    assert st["total"]["evicted_dirty"] > 0
+    # HET_POLICY_NONE: the step goes straight to the global table and its per-row accumulators
+    from oracle.het_oracle import Oracle
+    w = wl.WORKLOADS[1].scaled(optimizer=wl.ADAGRAD_ROWWISE, eps=1e-8)
+    table, ids_np, g_np = wl.table_init(w), wl.IdStream(w).batches(8), wl.grad_pool(w)
+    oracle = Oracle(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps, table)
+    cache = hc.HetCache(1, w.dim, 0, hc.POLICY_NONE, w.n, w.optimizer, w.eps)
+    dev = torch.device("cuda:0")
+    W = torch.from_numpy(table).to(dev); A = torch.zeros(w.vocab, device=dev); Cg = torch.zeros(w.vocab, dtype=torch.int32, device=dev)
+    cache.attach_backing(W, A, Cg)
+    try:
+        out = torch.empty(w.n, w.dim, device=dev)
+        for t in range(8):
+            d = torch.from_numpy(ids_np[t]).to(dev)
+            cache.lookup(d, out)
+            want, _ = oracle.lookup(ids_np[t])
+            close(out.cpu().numpy(), want, "lookup output")
+            cache.update(d, torch.from_numpy(g_np[t]).to(dev), w.lr)
+            oracle.update(ids_np[t], g_np[t], w.lr)
+        oracle.flush()
+        close(W.cpu().numpy(), oracle.W, "global table")
+        close(A.cpu().numpy(), oracle.A[:, 0], "global accumulators")
+    finally:
+        cache.close(); oracle.close()
+
+
+def test_rowwise_adagrad_is_refused_where_it_is_not_built():
+    with pytest.raises(hc.HetError):                       # rows of more than one piece per lane
+        hc.HetCache(100, 512, 1, hc.POLICY_LFU, 64, hc.OPT_ADAGRAD_ROWWISE, 1e-8)
+    with pytest.raises(hc.HetError):                       # several workers
+        hc.HetCache(100, 16, 1, hc.POLICY_LFU, 64, hc.OPT_ADAGRAD_ROWWISE, 1e-8, many_writers=True)
+    c = hc.HetCache(100, 16, 1, hc.POLICY_LFU, 64, hc.OPT_ADAGRAD_ROWWISE, 1e-8)
+    try:
+        with pytest.raises(hc.HetError):                   # table in host memory
+            c.attach_backing(torch.zeros(50, 16).pin_memory(), torch.zeros(50).pin_memory(),
+                             torch.zeros(50, dtype=torch.int32).pin_memory(), hc.BACKING_PINNED_HOST)
+    finally:
+        c.close()
