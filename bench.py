@@ -139,6 +139,54 @@ def policy_study(args, w, dev):
                       "rows": rows}))
 
 
+def pattern_study(args, w, dev):
+    """What plain kernels with the access patterns of the path's heavy steps reach on this GPU at
+    this config's sizes (het_profile_rows): a streaming copy, a gather of the batch's rows, and the
+    optimizer step's read-modify-write of the batch's distinct rows with and without their
+    gradients.  One JSON line."""
+    import torch
+    from paper_2112_07221_amd import hetcache as hc
+    from paper_2112_07221_amd import workloads as wl
+    rng = np.random.default_rng(20211207)
+    batch = wl.IdStream(w).batches(3)[2]
+    n, D, R = int(w.n), int(w.dim), 4 * int(w.dim)
+    U = int(np.unique(batch).size)
+    P = int(w.capacity + w.n)
+    V = int(min(w.vocab, 4_000_000))            # (a table of this many rows stands for the global one: far beyond the caches)
+    Q = 2 if w.optimizer else 1
+    src = torch.randn(V, D, device=dev)
+    outb = torch.empty(n, D, device=dev)
+    x = torch.randn(P, D, device=dev)
+    a = torch.rand(P, D, device=dev) if w.optimizer else None
+    grads = torch.randn(n, D, device=dev)
+    as_dev = lambda v: torch.from_numpy(np.ascontiguousarray(v, dtype=np.int32)).to(dev)
+    ids_zipf = as_dev(np.sort(batch % V))                         # the batch's ids in sorted order, as the gather reads them
+    ids_scattered = as_dev(rng.choice(V, size=n, replace=False))  # as many distinct rows, anywhere
+    slots = as_dev(np.sort(rng.choice(P, size=U, replace=False))) # the batch's distinct keys sit in U of the P slots
+    rows = []
+
+    def add(name, nbytes, ms):
+        rows.append({"pattern": name, "bytes": nbytes, "us": ms * 1e3, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_of_8TBps": nbytes / (ms * 1e-3) / 8e12})
+
+    big = torch.empty(1 << 20, 64, device=dev)                    # 256 MiB
+    add("streaming copy, 256 MiB", 2 * big.numel() * 4, hc.profile_rows(hc.PATTERN_COPY, torch.empty_like(big), src=big, n=big.shape[0]))
+    del big
+    add(f"streaming copy of n = {n} rows", 2 * n * R, hc.profile_rows(hc.PATTERN_COPY, outb, src=src, n=n))
+    add("gather of n distinct rows from anywhere in the table", 2 * n * R,
+        hc.profile_rows(hc.PATTERN_GATHER, outb, src=src, idx=ids_scattered))
+    add(f"gather of the batch's n rows in sorted order ({U} distinct; bytes counted as the path does: U read, n written)", (U + n) * R,
+        hc.profile_rows(hc.PATTERN_GATHER, outb, src=src, idx=ids_zipf))
+    add(f"update of U = {U} distinct cached rows ({'row and accumulator' if Q == 2 else 'row'} read and written)", 2 * U * Q * R,
+        hc.profile_rows(hc.PATTERN_UPDATE, x, a=a, idx=slots))
+    for per in (2, 3):
+        gidx = as_dev(rng.permutation(n)[: U * per] if U * per <= n else rng.integers(0, n, U * per))
+        add(f"update of U rows, each with {per} gradient rows from anywhere in the batch", (2 * U * Q + U * per) * R,
+            hc.profile_rows(hc.PATTERN_UPDATE, x, a=a, src=grads, idx=slots, gidx=gidx, per=per))
+    print(json.dumps({"study": "plain kernels with the path's access patterns", "config": w.index, "n": n, "unique": U,
+                      "dim": D, "slots": P, "build_id": hc.build_id(), "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +207,9 @@ def main():
                     help="instead of the benchmark: miss rate and step time of the chosen config for cache sizes of "
                          "3, 5, 10 and 15 %% of the vocabulary under LRU, LFU and light-weight LFU (the experiment of the paper's "
                          "Figure 8, and the claim of its Section 4.3)")
+    ap.add_argument("--pattern-study", action="store_true",
+                    help="instead of the benchmark: what plain copy, gather and read-modify-write kernels reach at the "
+                         "chosen config's sizes (reference points beside the streaming peak)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -173,6 +224,9 @@ def main():
     dev = torch.device("cuda:0")
     if args.policy_study:
         policy_study(args, w, dev)
+        return
+    if args.pattern_study:
+        pattern_study(args, w, dev)
         return
     K, W = args.steps, args.warmup
     total = W + K + args.profile_steps

@@ -289,6 +289,28 @@ int het_profile_end(het_cache *c, double *total_ms, int64_t *launches, int32_t n
 int het_profile_kernel_count(void);
 const char *het_profile_kernel_name(int index);
 
+/*
+ * Reference points for the roofline (not part of the path): runs, `reps` times in a row on
+ * hip_stream (after two launches that are not timed), a plain kernel that has the memory access
+ * pattern of one of the path's heavy steps and nothing else, and gives the average milliseconds
+ * per launch between two HIP events in *avg_ms (host).  All pointers but avg_ms are device memory;
+ * rows have `dim` floats (4, 8, 16, ... 128, or a multiple of 4 above 256); idx holds n row numbers
+ * (uint32).
+ *   HET_PATTERN_COPY    x[i] = src[i], i < n: a streaming copy (idx unused)
+ *   HET_PATTERN_GATHER  x[i] = src[idx[i]]: the gather (Get of Algorithm 2)
+ *   HET_PATTERN_UPDATE  rows idx[i] (distinct) of x, and of a unless it is NULL, read, changed and
+ *                       written back: the optimizer step on cached rows (Update of Algorithm 3).
+ *                       With per = 2 or 3 every row also reads `per` rows of src, numbers
+ *                       gidx[i * per ...]: the gradients of its key's lookups (per = 0: none)
+ * The caller owns every buffer and makes them large enough for the row numbers it passes.
+ * HET_EINVAL for a bad size or a missing pointer, HET_EHIP if the runtime refused.
+ */
+#define HET_PATTERN_COPY 0
+#define HET_PATTERN_GATHER 1
+#define HET_PATTERN_UPDATE 2
+int het_profile_rows(int32_t pattern, float *x, float *a, const float *src, const uint32_t *idx, int64_t n, int32_t dim,
+                     const uint32_t *gidx, int32_t per, int32_t reps, double *avg_ms, void *hip_stream);
+
 /* Waits for the stream, frees everything the library allocated.  NULL is allowed. */
 int het_cache_destroy(het_cache *c);
 

@@ -680,13 +680,18 @@ __device__ __forceinline__ void deferred_push_body(const CacheView &cv, int buf,
         for (int pass = 0; pass < (cv.adagrad ? 2 : 1); ++pass) {
             const float *from = pass ? cv.hl.acc_of(buf) : cv.hl.rows_of(buf);
             float *to = pass ? cv.A : cv.W;
+            static_assert(LINK_ROWS == 4, "the copy below is written out for four rows");
             for (int c = gl; c < g.chunks; c += g.lanes) {
-                V v[LINK_ROWS];
-#pragma unroll
-                for (int k = 0; k < LINK_ROWS; ++k) v[k] = reinterpret_cast<const V *>(from + (size_t)at[k] * g.dim)[c];
-#pragma unroll
-                for (int k = 0; k < LINK_ROWS; ++k)
-                    if (key[k] != KEY_NONE) reinterpret_cast<V *>(to + (size_t)key[k] * g.dim)[c] = v[k];
+                // (named values, not an array: with an array the compiler kept the rows in scratch
+                // memory and waited for each store to the host before the next)
+                const V v0 = reinterpret_cast<const V *>(from + (size_t)at[0] * g.dim)[c];
+                const V v1 = reinterpret_cast<const V *>(from + (size_t)at[1] * g.dim)[c];
+                const V v2 = reinterpret_cast<const V *>(from + (size_t)at[2] * g.dim)[c];
+                const V v3 = reinterpret_cast<const V *>(from + (size_t)at[3] * g.dim)[c];
+                if (key[0] != KEY_NONE) reinterpret_cast<V *>(to + (size_t)key[0] * g.dim)[c] = v0;
+                if (key[1] != KEY_NONE) reinterpret_cast<V *>(to + (size_t)key[1] * g.dim)[c] = v1;
+                if (key[2] != KEY_NONE) reinterpret_cast<V *>(to + (size_t)key[2] * g.dim)[c] = v2;
+                if (key[3] != KEY_NONE) reinterpret_cast<V *>(to + (size_t)key[3] * g.dim)[c] = v3;
             }
         }
         if (gl == 0) {
@@ -1251,7 +1256,8 @@ struct ApplyBorders {
 };
 
 template <int VEC, int MAXC, bool VERIFY, int AP_TILE>
-__global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
+// (rows of one piece per lane: held to 80 registers, six waves per SIMD; the compiler's own choice was 84 and five)
+__global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? 6 : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
                                                            const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                            float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
                                                            SortStage ride, SortStage ride2)

@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "cache_kernels.hpp"
+#include "pattern_kernels.hpp"
 
 using namespace het;
 
@@ -1145,6 +1146,39 @@ int het_profile_end(het_cache *c, double *total_ms, int64_t *launches, int32_t n
         (void)hipEventDestroy(sp.stop);
     }
     c->spans.clear();
+    return rc;
+}
+
+int het_profile_rows(int32_t pattern, float *x, float *a, const float *src, const uint32_t *idx, int64_t n, int32_t dim,
+                     const uint32_t *gidx, int32_t per, int32_t reps, double *avg_ms, void *hip_stream)
+{
+    if (pattern < 0 || pattern > 2 || n <= 0 || n > (int64_t)1 << 30 || dim <= 0 || dim % 4 || reps <= 0 || !avg_ms || !x) return HET_EINVAL;
+    if (pattern != HET_PATTERN_UPDATE && !src) return HET_EINVAL;
+    if (pattern != HET_PATTERN_COPY && !idx) return HET_EINVAL;
+    if (pattern == HET_PATTERN_UPDATE && (per < 0 || per > 3 || per == 1 || (per > 0 && (!src || !gidx)))) return HET_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int lanes = std::min(dim / 4, 64);
+    if (lanes & (lanes - 1)) return HET_EINVAL;          // (row groups of 1, 2, 4, ... 64 lanes: rows of 4, 8, 16, ... 128 floats, or wider)
+    const uint32_t per_block = 256u / (uint32_t)lanes;
+    const uint32_t rows_at_once = pattern == HET_PATTERN_UPDATE ? PAT_UPDATE_ROWS : PAT_ROWS;
+    const uint32_t grid = std::max(1u, std::min(cdiv(cdiv((uint64_t)n, rows_at_once), per_block), 256u * 8u));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return HET_EHIP; }
+    int rc = HET_OK;
+    for (int rep = -2; rep < reps && rc == HET_OK; ++rep) {          // (two launches first that are not timed)
+        if (rep == 0 && hipEventRecord(e0, st) != hipSuccess) rc = HET_EHIP;
+        if (pattern == HET_PATTERN_UPDATE && per == 0) pattern_update_kernel<0><<<grid, 256, 0, st>>>(x, a, idx, (uint32_t)n, dim, nullptr, nullptr);
+        else if (pattern == HET_PATTERN_UPDATE && per == 2) pattern_update_kernel<2><<<grid, 256, 0, st>>>(x, a, idx, (uint32_t)n, dim, src, gidx);
+        else if (pattern == HET_PATTERN_UPDATE) pattern_update_kernel<3><<<grid, 256, 0, st>>>(x, a, idx, (uint32_t)n, dim, src, gidx);
+        else pattern_gather_kernel<<<grid, 256, 0, st>>>(src, x, pattern == HET_PATTERN_GATHER ? idx : nullptr, (uint32_t)n, dim);
+        if (hipGetLastError() != hipSuccess) rc = HET_EHIP;
+    }
+    float ms = 0.f;
+    if (rc == HET_OK && (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                         hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) rc = HET_EHIP;
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    *avg_ms = (double)ms / reps;
     return rc;
 }
 

@@ -27,7 +27,7 @@ EXPORTS = (
     "het_lookup_pooled", "het_update", "het_update_pooled", "het_flush", "het_stats",
     "het_clear_error", "het_export_state", "het_export_rows", "het_last_lookup",
     "het_last_evicted", "het_cache_destroy", "het_strerror", "het_profile_begin",
-    "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name",
+    "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name", "het_profile_rows",
     "het_lookup_nocache_static", "het_build_id", "het_cache_set_many_writers",
     "het_backing_foreign_update", "het_cache_set_lfu_cap",
 )
@@ -98,6 +98,7 @@ def load() -> C.CDLL:
     lib.het_profile_begin.argtypes = [p]
     lib.het_profile_end.argtypes = [p, p, p, i32]
     lib.het_profile_kernel_count.argtypes = []
+    lib.het_profile_rows.argtypes = [i32, p, p, p, p, i64, i32, p, i32, i32, p, p]
     lib.het_profile_kernel_name.argtypes = [C.c_int]
     lib.het_profile_kernel_name.restype = C.c_char_p
     for name in EXPORTS:
@@ -144,6 +145,39 @@ def lookup_nocache_static(table, ids, out, err_bits=None, stream=None):
                                          ids.numel(), out.data_ptr(),
                                          err_bits.data_ptr() if err_bits is not None else None,
                                          C.c_void_p(st.cuda_stream))
+
+
+PATTERN_COPY, PATTERN_GATHER, PATTERN_UPDATE = 0, 1, 2
+
+
+def profile_rows(pattern, x, a=None, src=None, idx=None, n=None, gidx=None, per=0, reps=20, stream=None):
+    """Average milliseconds per launch of het_profile_rows' reference kernel (see the header).
+    x, a, src: fp32 matrices of equal row width on the GPU; idx: int32 row numbers on the GPU."""
+    import torch
+    lib = load()
+    _check_dev(x, torch.float32, "x")
+    dim = x.shape[1]
+    for t, what in ((a, "a"), (src, "src")):
+        if t is not None:
+            _check_dev(t, torch.float32, what)
+            if t.dim() != 2 or t.shape[1] != dim:
+                raise ValueError(f"{what} must have rows of {dim} floats")
+    for t, what in ((idx, "idx"), (gidx, "gidx")):
+        if t is not None:
+            _check_dev(t, torch.int32, what)
+    n = int(n if n is not None else (idx.numel() if idx is not None else x.shape[0]))
+    if (idx is not None and idx.numel() < n) or (pattern != PATTERN_UPDATE and x.shape[0] < n) or \
+            (per and (gidx is None or gidx.numel() < n * per)):
+        raise ValueError("a buffer is too small for n rows")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    ms = C.c_double()
+    rc = lib.het_profile_rows(pattern, x.data_ptr(), a.data_ptr() if a is not None else None,
+                              src.data_ptr() if src is not None else None, idx.data_ptr() if idx is not None else None,
+                              n, dim, gidx.data_ptr() if gidx is not None else None, per, reps, C.byref(ms),
+                              C.c_void_p(st.cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"het_profile_rows: {strerror(rc)}")
+    return ms.value
 
 
 class HetCache:

@@ -855,3 +855,37 @@ def test_rowwise_adagrad_is_refused_where_it_is_not_built():
                              torch.zeros(50, dtype=torch.int32).pin_memory(), hc.BACKING_PINNED_HOST)
     finally:
         c.close()
+
+
+@pytest.mark.gpu
+def test_reference_pattern_kernels_do_what_the_header_says():
+    """het_profile_rows' plain kernels (reference points for the roofline, not part of the path):
+    the copy copies, the gather gathers, the update changes exactly the rows it is given."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(5)
+    for dim in (4, 64, 128, 256, 520):
+        V, n = 3000, 1237
+        src = torch.randn(V, dim, device=dev)
+        out = torch.zeros(n, dim, device=dev)
+        assert hc.profile_rows(hc.PATTERN_COPY, out, src=src, n=n, reps=1) > 0
+        assert torch.equal(out, src[:n])
+        idx = torch.from_numpy(rng.integers(0, V, n).astype(np.int32)).to(dev)
+        hc.profile_rows(hc.PATTERN_GATHER, out, src=src, idx=idx, reps=1)
+        assert torch.equal(out, src[idx.long()])
+        # the update: a += 1 + sum of the row's gradients, x -= a, three launches in all (two untimed)
+        rows = torch.from_numpy(rng.choice(V, n, replace=False).astype(np.int32)).to(dev)
+        for per in (0, 2, 3):
+            x = torch.zeros(V, dim, device=dev); a = torch.zeros(V, dim, device=dev)
+            g = torch.randn(n * 3, dim, device=dev)
+            gidx = torch.from_numpy(rng.permutation(n * 3)[: n * per].astype(np.int32)).to(dev) if per else None
+            hc.profile_rows(hc.PATTERN_UPDATE, x, a=a, src=g if per else None, idx=rows, gidx=gidx, per=per, reps=1)
+            d = torch.ones(n, dim, device=dev, dtype=torch.float64)
+            if per:
+                d = d + g[gidx.long()].double().view(n, per, dim).sum(1)
+            want_a = torch.zeros(V, dim, device=dev, dtype=torch.float64); want_a[rows.long()] = 3 * d
+            want_x = torch.zeros(V, dim, device=dev, dtype=torch.float64); want_x[rows.long()] = -6 * d
+            assert torch.allclose(a.double(), want_a, rtol=1e-5, atol=1e-5)
+            assert torch.allclose(x.double(), want_x, rtol=1e-5, atol=1e-5)
+    with pytest.raises(RuntimeError):
+        hc.profile_rows(hc.PATTERN_GATHER, torch.zeros(4, 12, device=dev), src=torch.zeros(4, 12, device=dev),
+                        idx=torch.zeros(4, dtype=torch.int32, device=dev))        # row groups of three lanes
