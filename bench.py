@@ -187,6 +187,76 @@ def pattern_study(args, w, dev):
                       "dim": D, "slots": P, "build_id": hc.build_id(), "rows": rows}))
 
 
+def trace_apply(args, w, dev):
+    """Where the update kernel's time goes: per-workgroup time stamps (het_profile_trace) of one
+    update after `--warmup` steps, summarised per role and per phase.  One JSON line."""
+    import torch
+    from paper_2112_07221_amd import hetcache as hc
+    from paper_2112_07221_amd import workloads as wl
+    T = args.warmup + 8
+    table = wl.table_init(w)
+    ids = torch.from_numpy(wl.IdStream(w).batches(T)).to(dev)
+    grads = torch.from_numpy(wl.grad_pool(w)).to(dev)
+    Wt = torch.from_numpy(table).to(dev)
+    At = torch.zeros_like(Wt) if w.optimizer else None
+    Cg = torch.zeros(w.vocab, dtype=torch.int32, device=dev)
+    offsets = torch.from_numpy(wl.bag_offsets(w)).to(dev) if w.pooled else None
+    out = torch.empty(w.n_grad_rows, w.dim, device=dev)
+    cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps)
+    cache.attach_backing(Wt, At, Cg, hc.BACKING_HBM)
+    cap = 1 << 15
+    rec = torch.zeros(cap, hc.TRACE_WORDS, dtype=torch.int64, device=dev)
+
+    def step(t):
+        if t == 0:
+            cache.prefetch(ids[1])
+        if t + 2 < T:
+            cache.prefetch(ids[t + 2])
+        if w.pooled:
+            cache.lookup_pooled(ids[t], offsets, out)
+            cache.update_pooled(ids[t], offsets, grads[t % w.grad_pool], w.lr)
+        else:
+            cache.lookup(ids[t], out)
+            cache.update(ids[t], grads[t % w.grad_pool], w.lr)
+
+    for t in range(args.warmup):
+        step(t)
+    reps = []
+    for r in range(3):
+        torch.cuda.synchronize()
+        rec.zero_()
+        cache.profile_trace(rec)
+        step(args.warmup + r)
+        torch.cuda.synchronize()
+        cache.profile_trace(None)
+        a = rec.cpu().numpy()
+        used = a[:, 6] > 0
+        k0 = a[used, 0].min()
+        us = lambda x: (x - k0) / 100.0                       # 100 MHz counter
+        q = lambda v, p: float(np.percentile(v, p))
+        one = {"kernel_span_us": float(us(a[used, 5].max())), "workgroups": int(used.sum()), "roles": {}, "tile_phases_us": {}}
+        for role, name in ((1, "carried sort stage"), (2, "select stage"), (3, "id check"), (4, "update tile")):
+            m = a[:, 6] == role
+            if not m.any():
+                continue
+            st, en = us(a[m, 0]), us(a[m, 5])
+            one["roles"][name] = {"workgroups": int(m.sum()), "start_us_p50_max": [q(st, 50), float(st.max())],
+                                  "end_us_p50_p90_max": [q(en, 50), q(en, 90), float(en.max())],
+                                  "duration_us_p50_p90_max": [q(en - st, 50), q(en - st, 90), float((en - st).max())]}
+        m = a[:, 6] == 4
+        wk = a[m]
+        for i, name in ((1, "tile loaded, segments listed"), (2, "short segments"), (3, "long segments"),
+                        (4, "barrier before the border runs"), (5, "border runs finished")):
+            ok = (wk[:, i] > 0) & (wk[:, i - 1] > 0)
+            if ok.any():
+                d = (wk[ok, i] - wk[ok, i - 1]) / 100.0
+                one["tile_phases_us"][name] = {"workgroups": int(ok.sum()), "p50": q(d, 50), "p90": q(d, 90), "max": float(d.max())}
+        reps.append(one)
+    cache.close()
+    print(json.dumps({"study": "time stamps inside the update kernel", "config": w.index, "build_id": hc.build_id(),
+                      "warmup": args.warmup, "updates": reps}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -207,6 +277,9 @@ def main():
                     help="instead of the benchmark: miss rate and step time of the chosen config for cache sizes of "
                          "3, 5, 10 and 15 %% of the vocabulary under LRU, LFU and light-weight LFU (the experiment of the paper's "
                          "Figure 8, and the claim of its Section 4.3)")
+    ap.add_argument("--trace-apply", action="store_true",
+                    help="instead of the benchmark: per-workgroup time stamps of the update kernel (table in HBM), "
+                         "summarised per role and phase")
     ap.add_argument("--pattern-study", action="store_true",
                     help="instead of the benchmark: what plain copy, gather and read-modify-write kernels reach at the "
                          "chosen config's sizes (reference points beside the streaming peak)")
@@ -227,6 +300,9 @@ def main():
         return
     if args.pattern_study:
         pattern_study(args, w, dev)
+        return
+    if args.trace_apply:
+        trace_apply(args, w, dev)
         return
     K, W = args.steps, args.warmup
     total = W + K + args.profile_steps

@@ -1249,6 +1249,19 @@ __device__ __forceinline__ void st_device(int32_t *p, int32_t v) { __hip_atomic_
 __device__ __forceinline__ int32_t ld_device(const int32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void stores_acknowledged() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Optional time stamps of the update's kernel, one record of TRACE_WORDS words per workgroup
+// (het_profile_trace): [0] start, [1] tile and segments listed, [2] short segments done, [3] long
+// segments done, [4] past the barrier before the border runs, [5] end, [6] role (1 carried sort
+// stage, 2 select stage, 3 id check, 4 tile of the update).  Clock: wall_clock64(), 100 MHz.
+constexpr int TRACE_WORDS = 8;
+struct ApplyTrace {
+    unsigned long long *rec;     // nullptr: off
+    uint32_t cap;                // workgroups the buffer has room for
+    __device__ __forceinline__ void stamp(int i) const { if (rec && threadIdx.x == 0 && blockIdx.x < cap) rec[(size_t)blockIdx.x * TRACE_WORDS + i] = wall_clock64(); }
+    __device__ __forceinline__ void end() const { if (rec && lane_id() == 0 && blockIdx.x < cap) atomicMax(&rec[(size_t)blockIdx.x * TRACE_WORDS + 5], (unsigned long long)wall_clock64()); }   // (the last wave to leave)
+    __device__ __forceinline__ void role(int r) const { if (rec && threadIdx.x == 0 && blockIdx.x < cap) rec[(size_t)blockIdx.x * TRACE_WORDS + 6] = (unsigned long long)r; }
+};
+
 struct ApplyBorders {
     double *part;          // [tiles][2][dim]: sum of the segment that came in through the tile's front border / that leaves through its back border
     int32_t *slot;         // [tiles]: slot of the run that leaves through the tile's back border (it starts in this tile)
@@ -1260,15 +1273,17 @@ template <int VEC, int MAXC, bool VERIFY, int AP_TILE>
 __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? 6 : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
                                                            const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                            float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
-                                                           SortStage ride, SortStage ride2)
+                                                           SortStage ride, SortStage ride2, ApplyTrace tr)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
-    if (run_carried(ride, ride2, bid, nblk)) return;
+    tr.stamp(0);
+    if (run_carried(ride, ride2, bid, nblk)) { tr.role(1); tr.end(); return; }
     const uint32_t verify_blocks = VERIFY ? (n_ids + VERIFY_TILE - 1) / VERIFY_TILE : 0u;
     const uint32_t stage_blocks = nblk - work_blocks - verify_blocks;
     if (bid < stage_blocks) {            // extra workgroups (ahead of the others: their chain of steps is long): a stage of the coming trim's select
         trim_stage_body(cv, tp, stage, bid, stage_blocks, lds_as<TrimLds>());
+        tr.role(2); tr.end();
         return;
     }
     bid -= stage_blocks;
@@ -1283,9 +1298,11 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
             if (j < nvv) bad |= ids[ws.perm[j]] != (int64_t)ws.skey[j];
         }
         if (__any(bad) && lane_id() == 0) atomicOr(&cv.ds->err, ERRBIT_STATE);
+        tr.role(3); tr.end();
         return;
     }
     bid -= verify_blocks;
+    tr.role(4);
     const RowGeom g = cv.geom;
     const uint32_t group = threadIdx.x / g.lanes, ngroups = AP_THREADS / g.lanes;
     const int gl = threadIdx.x % g.lanes;
@@ -1359,6 +1376,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
         if (do_back || through)  // tiles behind this one that the run also leaves through their back border
             T1 = T + 1 + wave_count_leading([&](uint32_t i) { const uint64_t je = ((uint64_t)T + i + 1) * AP_TILE; return je < nv && skey[je] == key; });
     }
+    tr.stamp(1);
     // (does any segment need the whole workgroup?  every thread looks at one)
     const bool any_long = __syncthreads_or(threadIdx.x < nseg && l.seg_start[threadIdx.x + 1] - l.seg_start[threadIdx.x] > AP_SOLO) != 0;
 
@@ -1406,6 +1424,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
             finish_segment(w);
         }
     }
+    tr.stamp(2);
     if (any_long) {
         // longer segments (a popular key): all row groups together, one segment at a time
         for (uint32_t sg = 0; sg < nseg; ++sg) {
@@ -1450,7 +1469,8 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
             if (!closed && group == 0) stores_acknowledged();
         }
     }
-    if (!front_open && !back_open) return;
+    tr.stamp(3);
+    if (!front_open && !back_open) { tr.end(); return; }
 
     // Runs that cross this tile's borders.  Every tile such a run touches has stored one sum; each
     // counts itself as arrived at the run's first tile, and the one that arrives last adds the
@@ -1458,7 +1478,8 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
     // through the front border, the second to the run that leaves through the back border (a tile
     // that lies inside one run has only the former).
     __syncthreads();
-    if (!do_front && !do_back) return;
+    tr.stamp(4);
+    if (!do_front && !do_back) { tr.end(); return; }
     const uint32_t m = T1 - T0 + 1;
     uint32_t last = 0;
     if (lane_id() == 0) {
@@ -1467,7 +1488,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
         if (last) bd.arrived[T0] = 0;                       // clean for the next kernel
     }
     last = __shfl(last, 0, WAVE);
-    if (!last || lane_id() >= (uint32_t)g.lanes) return;
+    if (!last || lane_id() >= (uint32_t)g.lanes) { tr.end(); return; }
     const int32_t slot = ld_device(&bd.slot[T0]);           // (SLOT_NONE: a key that is not cached, flagged where the order was probed)
 #pragma unroll
     for (int q = 0; q < MAXC; ++q) {
@@ -1493,6 +1514,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
         }
         if (slot != SLOT_NONE) apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps, act);
     }
+    tr.end();
 }
 
 // Drops the victims among 1024 consecutive slots, four per thread: erase the key, free the slot,

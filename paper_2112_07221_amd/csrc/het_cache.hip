@@ -100,6 +100,7 @@ struct het_cache {
     bool order_valid = false;
     // optional per-kernel timing (het_profile_begin / het_profile_end)
     bool profiling = false;
+    ApplyTrace trace{};              // het_profile_trace
     std::vector<ProfSpan> spans;
 };
 
@@ -559,9 +560,9 @@ int launch_apply_tile(het_cache *c, bool verify, const int64_t *ids, uint32_t n,
     const Rides ride = next_rides(c);
     const uint32_t lds = lds_bytes(std::max(sizeof(TrimLds), sizeof(ApplyLds<VEC, TILE>)), ride);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, TILE><<<ride.blocks() + grid + extra + cdiv(n, VERIFY_TILE), AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, TILE><<<ride.blocks() + grid + extra + cdiv(n, VERIFY_TILE), AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, TILE><<<ride.blocks() + grid + extra, AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, TILE><<<ride.blocks() + grid + extra, AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace));
     return next;
 }
 
@@ -1180,6 +1181,14 @@ int het_profile_rows(int32_t pattern, float *x, float *a, const float *src, cons
     (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
     *avg_ms = (double)ms / reps;
     return rc;
+}
+
+int het_profile_trace(het_cache *c, uint64_t *records, int64_t capacity)
+{
+    if (!c || !c->configured || capacity < 0 || capacity > (int64_t)1 << 24 || (capacity > 0 && !records)) return HET_EINVAL;
+    c->trace.rec = capacity ? reinterpret_cast<unsigned long long *>(records) : nullptr;
+    c->trace.cap = (uint32_t)capacity;
+    return HET_OK;
 }
 
 int het_profile_kernel_count(void) { return K_NUM; }

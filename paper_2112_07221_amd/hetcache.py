@@ -27,7 +27,7 @@ EXPORTS = (
     "het_lookup_pooled", "het_update", "het_update_pooled", "het_flush", "het_stats",
     "het_clear_error", "het_export_state", "het_export_rows", "het_last_lookup",
     "het_last_evicted", "het_cache_destroy", "het_strerror", "het_profile_begin",
-    "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name", "het_profile_rows",
+    "het_profile_end", "het_profile_kernel_count", "het_profile_kernel_name", "het_profile_rows", "het_profile_trace",
     "het_lookup_nocache_static", "het_build_id", "het_cache_set_many_writers",
     "het_backing_foreign_update", "het_cache_set_lfu_cap",
 )
@@ -98,6 +98,7 @@ def load() -> C.CDLL:
     lib.het_profile_begin.argtypes = [p]
     lib.het_profile_end.argtypes = [p, p, p, i32]
     lib.het_profile_kernel_count.argtypes = []
+    lib.het_profile_trace.argtypes = [p, p, i64]
     lib.het_profile_rows.argtypes = [i32, p, p, p, p, i64, i32, p, i32, i32, p, p]
     lib.het_profile_kernel_name.argtypes = [C.c_int]
     lib.het_profile_kernel_name.restype = C.c_char_p
@@ -148,6 +149,7 @@ def lookup_nocache_static(table, ids, out, err_bits=None, stream=None):
 
 
 PATTERN_COPY, PATTERN_GATHER, PATTERN_UPDATE = 0, 1, 2
+TRACE_WORDS = 8
 
 
 def profile_rows(pattern, x, a=None, src=None, idx=None, n=None, gidx=None, per=0, reps=20, stream=None):
@@ -341,6 +343,17 @@ class HetCache:
         self._rc(self.lib.het_profile_end(self.h, _np_ptr(ms), _np_ptr(cnt), k), "het_profile_end")
         return {self.lib.het_profile_kernel_name(i).decode(): (float(ms[i]), int(cnt[i]))
                 for i in range(k) if cnt[i]}
+
+    def profile_trace(self, records=None):
+        """Switches the update kernel's per-workgroup time stamps on (records: zeroed int64 GPU tensor
+        of shape [workgroups, TRACE_WORDS]) or off (None)."""
+        import torch
+        if records is None:
+            self._rc(self.lib.het_profile_trace(self.h, None, 0), "het_profile_trace")
+        else:
+            _check_dev(records, torch.int64, "records")
+            self._rc(self.lib.het_profile_trace(self.h, records.data_ptr(), records.shape[0]), "het_profile_trace")
+        self._trace_records = records
 
     def close(self):
         if getattr(self, "h", None):

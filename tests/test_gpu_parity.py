@@ -889,3 +889,34 @@ def test_reference_pattern_kernels_do_what_the_header_says():
     with pytest.raises(RuntimeError):
         hc.profile_rows(hc.PATTERN_GATHER, torch.zeros(4, 12, device=dev), src=torch.zeros(4, 12, device=dev),
                         idx=torch.zeros(4, dtype=torch.int32, device=dev))        # row groups of three lanes
+
+
+@pytest.mark.gpu
+def test_time_stamps_of_the_update_kernel_change_nothing():
+    """het_profile_trace: with the stamps on, an update gives the same cache as without, every
+    workgroup of the kernel leaves a record with start <= end, and switching them off stops them."""
+    dev = torch.device("cuda:0")
+    w = wl.WORKLOADS[1].scaled(capacity=600, s=2, optimizer=wl.ADAGRAD, eps=1e-8)
+    table = wl.table_init(w)
+    ids = wl.IdStream(w).batches(6)
+    grads = wl.grad_pool(w)
+    p = Pair(w, table)
+    try:
+        rec = torch.zeros(4096, hc.TRACE_WORDS, dtype=torch.int64, device=dev)
+        for t in range(6):
+            p.lookup(ids[t])
+            if t == 3:
+                p.cache.profile_trace(rec)
+            if t == 4:
+                p.cache.profile_trace(None)
+                seen = rec.cpu().numpy().copy()
+                rec.zero_()
+            p.update(ids[t], grads[t % len(grads)])
+            p.compare_state(values=True)
+        used = seen[:, 6] > 0
+        assert used.sum() >= 1 and (seen[used, 6] <= 4).all()
+        assert (seen[used, 5] >= seen[used, 0]).all() and (seen[used, 0] > 0).all()
+        assert not rec.cpu().numpy().any()
+        p.flush_and_compare()
+    finally:
+        p.close()
