@@ -372,10 +372,13 @@ def main():
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
     e0.record()
+    enqueue_ms = 0.0
+    K_host = max(1, min(K, 100))                 # host cost of a step: over the first steps, before the launch queue fills and the host waits for the GPU
     for t in range(W, W + K):
         step(t)
+        if t + 1 == W + K_host:
+            enqueue_ms = (time.perf_counter() - wall0) * 1e3
     e1.record()
-    enqueue_ms = (time.perf_counter() - wall0) * 1e3          # host time to enqueue all K steps
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - wall0) * 1e3
     gpu_ms = e0.elapsed_time(e1)
@@ -421,7 +424,7 @@ def main():
                    "ids_per_step": w.n, "unique_per_step": per_step["unique_lookup"],
                    "miss_per_step": per_step["miss"], "stale_per_step": per_step["stale"],
                    "evicted_dirty_per_step": per_step["evicted_dirty"],
-                   "warmup_ms_per_step": warm_ms, "host_enqueue_ms_per_step": enqueue_ms / K},
+                   "warmup_ms_per_step": warm_ms, "host_enqueue_ms_per_step": enqueue_ms / K_host},
         "step_hbm": {"algorithmic_bytes": step_bytes,
                      "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
