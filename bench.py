@@ -187,9 +187,9 @@ def pattern_study(args, w, dev):
                       "dim": D, "slots": P, "build_id": hc.build_id(), "rows": rows}))
 
 
-def trace_apply(args, w, dev):
-    """Where the update kernel's time goes: per-workgroup time stamps (het_profile_trace) of one
-    update after `--warmup` steps, summarised per role and per phase.  One JSON line."""
+def trace_kernels(args, w, dev):
+    """Where the two heavy kernels' time goes: per-workgroup time stamps (het_profile_trace) of one
+    lookup and one update after `--warmup` steps, summarised per role and per phase.  One JSON line."""
     import torch
     from paper_2112_07221_amd import hetcache as hc
     from paper_2112_07221_amd import workloads as wl
@@ -205,7 +205,10 @@ def trace_apply(args, w, dev):
     cache = hc.HetCache(w.capacity, w.dim, w.s, w.policy, w.n, w.optimizer, w.eps)
     cache.attach_backing(Wt, At, Cg, hc.BACKING_HBM)
     cap = 1 << 15
-    rec = torch.zeros(cap, hc.TRACE_WORDS, dtype=torch.int64, device=dev)
+    kernels = {"apply_kernel": {1: "carried sort stage", 2: "select stage", 3: "id check", 4: "update tile"},
+               "fill_gather_kernel": {1: "carried sort stage", 2: "fetch", 3: "bookkeeping of the fetched keys", 4: "select stage",
+                                      5: "gather", 6: "host link"}}
+    rec = {k: torch.zeros(cap, hc.TRACE_WORDS, dtype=torch.int64, device=dev) for k in kernels}
 
     def step(t):
         if t == 0:
@@ -221,40 +224,46 @@ def trace_apply(args, w, dev):
 
     for t in range(args.warmup):
         step(t)
+    q = lambda v, p: float(np.percentile(v, p))
     reps = []
     for r in range(3):
         torch.cuda.synchronize()
-        rec.zero_()
-        cache.profile_trace(rec)
+        for k in kernels:
+            rec[k].zero_()
+            cache.profile_trace(rec[k], k)
         step(args.warmup + r)
         torch.cuda.synchronize()
-        cache.profile_trace(None)
-        a = rec.cpu().numpy()
-        used = a[:, 6] > 0
-        k0 = a[used, 0].min()
-        us = lambda x: (x - k0) / 100.0                       # 100 MHz counter
-        q = lambda v, p: float(np.percentile(v, p))
-        one = {"kernel_span_us": float(us(a[used, 5].max())), "workgroups": int(used.sum()), "roles": {}, "tile_phases_us": {}}
-        for role, name in ((1, "carried sort stage"), (2, "select stage"), (3, "id check"), (4, "update tile")):
-            m = a[:, 6] == role
-            if not m.any():
-                continue
-            st, en = us(a[m, 0]), us(a[m, 5])
-            one["roles"][name] = {"workgroups": int(m.sum()), "start_us_p50_max": [q(st, 50), float(st.max())],
-                                  "end_us_p50_p90_max": [q(en, 50), q(en, 90), float(en.max())],
-                                  "duration_us_p50_p90_max": [q(en - st, 50), q(en - st, 90), float((en - st).max())]}
-        m = a[:, 6] == 4
-        wk = a[m]
-        for i, name in ((1, "tile loaded, segments listed"), (2, "short segments"), (3, "long segments"),
-                        (4, "barrier before the border runs"), (5, "border runs finished")):
-            ok = (wk[:, i] > 0) & (wk[:, i - 1] > 0)
-            if ok.any():
-                d = (wk[ok, i] - wk[ok, i - 1]) / 100.0
-                one["tile_phases_us"][name] = {"workgroups": int(ok.sum()), "p50": q(d, 50), "p90": q(d, 90), "max": float(d.max())}
+        one = {}
+        for k, roles in kernels.items():
+            cache.profile_trace(None, k)
+            a = rec[k].cpu().numpy()
+            used = a[:, 6] > 0
+            k0 = a[used, 0].min()
+            us = lambda x: (x - k0) / 100.0                   # 100 MHz counter
+            d = {"kernel_span_us": float(us(a[used, 5].max())), "workgroups": int(used.sum()), "roles": {}}
+            for role, name in roles.items():
+                m = a[:, 6] == role
+                if not m.any():
+                    continue
+                st, en = us(a[m, 0]), us(a[m, 5])
+                d["roles"][name] = {"workgroups": int(m.sum()), "start_us_p50_max": [q(st, 50), float(st.max())],
+                                    "end_us_p50_p90_max": [q(en, 50), q(en, 90), float(en.max())],
+                                    "duration_us_p50_p90_max": [q(en - st, 50), q(en - st, 90), float((en - st).max())],
+                                    "sum_of_durations_us": float((en - st).sum())}
+            if k == "apply_kernel":
+                d["tile_phases_us"] = {}
+                wk = a[a[:, 6] == 4]
+                for i, name in ((1, "tile loaded, segments listed"), (2, "short segments"), (3, "long segments"),
+                                (4, "barrier before the border runs"), (5, "border runs finished")):
+                    ok = (wk[:, i] > 0) & (wk[:, i - 1] > 0)
+                    if ok.any():
+                        dd = (wk[ok, i] - wk[ok, i - 1]) / 100.0
+                        d["tile_phases_us"][name] = {"workgroups": int(ok.sum()), "p50": q(dd, 50), "p90": q(dd, 90), "max": float(dd.max())}
+            one[k] = d
         reps.append(one)
     cache.close()
-    print(json.dumps({"study": "time stamps inside the update kernel", "config": w.index, "build_id": hc.build_id(),
-                      "warmup": args.warmup, "updates": reps}))
+    print(json.dumps({"study": "time stamps inside the lookup's second kernel and the update's kernel", "config": w.index,
+                      "build_id": hc.build_id(), "warmup": args.warmup, "steps": reps}))
 
 
 def main():
@@ -277,9 +286,9 @@ def main():
                     help="instead of the benchmark: miss rate and step time of the chosen config for cache sizes of "
                          "3, 5, 10 and 15 %% of the vocabulary under LRU, LFU and light-weight LFU (the experiment of the paper's "
                          "Figure 8, and the claim of its Section 4.3)")
-    ap.add_argument("--trace-apply", action="store_true",
-                    help="instead of the benchmark: per-workgroup time stamps of the update kernel (table in HBM), "
-                         "summarised per role and phase")
+    ap.add_argument("--trace-kernels", action="store_true",
+                    help="instead of the benchmark: per-workgroup time stamps inside fill_gather_kernel and apply_kernel "
+                         "(table in HBM), summarised per role and phase")
     ap.add_argument("--pattern-study", action="store_true",
                     help="instead of the benchmark: what plain copy, gather and read-modify-write kernels reach at the "
                          "chosen config's sizes (reference points beside the streaming peak)")
@@ -301,8 +310,8 @@ def main():
     if args.pattern_study:
         pattern_study(args, w, dev)
         return
-    if args.trace_apply:
-        trace_apply(args, w, dev)
+    if args.trace_kernels:
+        trace_kernels(args, w, dev)
         return
     K, W = args.steps, args.warmup
     total = W + K + args.profile_steps

@@ -290,18 +290,22 @@ int het_profile_kernel_count(void);
 const char *het_profile_kernel_name(int index);
 
 /*
- * Time stamps inside the update's kernel, for finding out where its time goes.  While `records`
- * (device memory, HET_TRACE_WORDS uint64 per workgroup, room for `capacity` workgroups, zeroed by
- * the caller) is set, every het_update writes, per workgroup of its main kernel: [0] start,
- * [1] tile loaded and segments listed, [2] short segments done, [3] long segments done, [4] past
- * the barrier before the runs that cross tile borders, [5] the last wave's end, [6] role (1 carried
- * sort stage, 2 select stage, 3 id check, 4 tile of the update); [1]..[4] only for role 4, and only
- * as far as the workgroup got.  Clock: the GPU's constant 100 MHz counter.  A later update
- * overwrites the records.  capacity 0 (records ignored) switches the stamps off again.  The stamps
- * cost a few stores per workgroup: not for timed regions.  HET_EINVAL for a bad argument.
+ * Time stamps inside the two heavy kernels, for finding out where their time goes.  `kernel` is the
+ * index (het_profile_kernel_name) of "apply_kernel" (het_update's main kernel) or of
+ * "fill_gather_kernel" (het_lookup's second kernel).  While `records` (device memory,
+ * HET_TRACE_WORDS uint64 per workgroup, room for `capacity` workgroups, zeroed by the caller) is
+ * set, every launch of that kernel writes per workgroup: [0] start, [5] the last wave's end,
+ * [6] role.  apply_kernel: roles 1 carried sort stage, 2 select stage, 3 id check, 4 tile of the
+ * update; for role 4 also [1] tile loaded and segments listed, [2] short segments done, [3] long
+ * segments done, [4] past the barrier before the runs that cross tile borders (as far as the
+ * workgroup got).  fill_gather_kernel: roles 1 carried sort stage, 2 fetch, 3 the fetched keys'
+ * bookkeeping, 4 select stage, 5 gather, 6 host link.  Clock: the GPU's constant 100 MHz counter.
+ * A later launch overwrites the records.  capacity 0 (records ignored) switches the stamps off
+ * again.  They cost a few stores per workgroup: not for timed regions.  HET_EINVAL for a bad
+ * argument.
  */
 #define HET_TRACE_WORDS 8
-int het_profile_trace(het_cache *c, uint64_t *records, int64_t capacity);
+int het_profile_trace(het_cache *c, int32_t kernel, uint64_t *records, int64_t capacity);
 
 /*
  * Reference points for the roofline (not part of the path): runs, `reps` times in a row on

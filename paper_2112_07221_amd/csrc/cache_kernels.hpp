@@ -750,6 +750,23 @@ typedef float raw_float4 __attribute__((ext_vector_type(4)));
 template <int VEC> struct RawVecT { using type = float; };
 template <> struct RawVecT<4> { using type = raw_float4; };
 
+// Optional time stamps inside the two heavy kernels, one record of TRACE_WORDS words per workgroup
+// (het_profile_trace): [0] start, [5] the last wave's end, [6] role.
+// apply_kernel: roles 1 carried sort stage, 2 select stage, 3 id check, 4 tile of the update; for
+// role 4 also [1] tile and segments listed, [2] short segments done, [3] long segments done,
+// [4] past the barrier before the border runs.
+// fill_gather_kernel: roles 1 carried sort stage, 2 fetch, 3 the fetched keys' bookkeeping,
+// 4 select stage, 5 gather, 6 host link (write-back, list of rows to fetch ahead).
+// Clock: wall_clock64(), 100 MHz.
+constexpr int TRACE_WORDS = 8;
+struct KernelTrace {
+    unsigned long long *rec;     // nullptr: off
+    uint32_t cap;                // workgroups the buffer has room for
+    __device__ __forceinline__ void stamp(int i) const { if (rec && threadIdx.x == 0 && blockIdx.x < cap) rec[(size_t)blockIdx.x * TRACE_WORDS + i] = wall_clock64(); }
+    __device__ __forceinline__ void end() const { if (rec && lane_id() == 0 && blockIdx.x < cap) atomicMax(&rec[(size_t)blockIdx.x * TRACE_WORDS + 5], (unsigned long long)wall_clock64()); }   // (the last wave to leave)
+    __device__ __forceinline__ void role(int r) const { if (rec && threadIdx.x == 0 && blockIdx.x < cap) rec[(size_t)blockIdx.x * TRACE_WORDS + 6] = (unsigned long long)r; }
+};
+
 // Fetch's pull for FILL_ROWS rows at once (all loads first).  Called by a whole row group.
 template <int VEC, bool WITH_ACC>
 __device__ __forceinline__ void fetch_rows(const CacheView &cv, const float *const (&srow)[FILL_ROWS], const float *const (&sacc)[FILL_ROWS],
@@ -868,19 +885,24 @@ struct FillLds {
 };
 // RIDE: 0 carries no sort stage, 1 a histogram stage (cheap in registers: the gather keeps its
 // occupancy), 2 any stage.
-template <int VEC, bool POOLED, int RIDE>
+// TRACE: time stamps (het_profile_trace); a kernel of its own, because the stamps' arguments cost the
+// other one scalar registers it has no room for.
+template <int VEC, bool POOLED, int RIDE, bool TRACE>
 __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles, uint32_t fill_blocks,
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv, SortStage ride, SortStage ride2,
-                                                          uint32_t push_blocks, int push_buf, uint32_t push_seq, int hist_pass, Ahead ah)
+                                                          uint32_t push_blocks, int push_buf, uint32_t push_seq, int hist_pass, Ahead ah,
+                                                          KernelTrace tr_arg)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
-    if (RIDE == 1 && run_carried<true>(ride, ride2, bid, nblk)) return;
-    if (RIDE == 2 && run_carried<false>(ride, ride2, bid, nblk)) return;
-    if (bid < push_blocks) { deferred_push_body<VEC>(cv, push_buf, bid, push_blocks); return; }    // host-backed table: the last trim's write-back
+    const KernelTrace tr = TRACE ? tr_arg : KernelTrace{nullptr, 0u};
+    tr.stamp(0);
+    if (RIDE == 1 && run_carried<true>(ride, ride2, bid, nblk)) { tr.role(1); tr.end(); return; }
+    if (RIDE == 2 && run_carried<false>(ride, ride2, bid, nblk)) { tr.role(1); tr.end(); return; }
+    if (bid < push_blocks) { deferred_push_body<VEC>(cv, push_buf, bid, push_blocks); tr.role(6); tr.end(); return; }    // host-backed table: the last trim's write-back
     bid -= push_blocks; nblk -= push_blocks;
-    if (bid < ah.blocks) { ahead_list_body(cv, ah, bid); return; }                                 // host-backed table: what to fetch ahead for the coming batch
+    if (bid < ah.blocks) { ahead_list_body(cv, ah, bid); tr.role(6); tr.end(); return; }                                 // host-backed table: what to fetch ahead for the coming batch
     bid -= ah.blocks; nblk -= ah.blocks;
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
@@ -945,6 +967,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
                 if (cv.Cg_host && !has_updates) for (uint32_t jj = jk.x; jj < n && ws.skey[jj] == key; ++jj) ws.src[jj] = (int32_t)slot;
             }
         }
+        tr.role(2); tr.end();
         return;
     }
 
@@ -966,6 +989,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             // host-backed table: the gather runs after this kernel and reads the cached copy
             if (cv.Cg_host) for (uint32_t jj = j; jj < n && ws.skey[jj] == key; ++jj) ws.src[jj] = (int32_t)slot;
         }
+        tr.role(3); tr.end();
         return;
     }
     bid -= ins_blocks; nblk -= ins_blocks;
@@ -976,6 +1000,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         TrimLds &tl = lds_as<TrimLds>();
         const uint32_t new_rows = block_sum_array<TRIM_WAVES>(ws.tile_miss, ptiles, tl.scan);
         trim_hist_body(cv, tp, hist_pass, bid - fill_blocks, hist_blocks, tl, true, new_rows, t_now, hist_pass == 0);
+        tr.role(4); tr.end();
         return;
     }
     const uint32_t first_gather = fill_blocks + hist_blocks;
@@ -1052,6 +1077,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             }
         }
     }
+    tr.role(5); tr.end();
 }
 
 // Pooled forms: inv[perm[j]] = j (sorted position of every original position), and the bag of
@@ -1249,19 +1275,6 @@ __device__ __forceinline__ void st_device(int32_t *p, int32_t v) { __hip_atomic_
 __device__ __forceinline__ int32_t ld_device(const int32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void stores_acknowledged() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// Optional time stamps of the update's kernel, one record of TRACE_WORDS words per workgroup
-// (het_profile_trace): [0] start, [1] tile and segments listed, [2] short segments done, [3] long
-// segments done, [4] past the barrier before the border runs, [5] end, [6] role (1 carried sort
-// stage, 2 select stage, 3 id check, 4 tile of the update).  Clock: wall_clock64(), 100 MHz.
-constexpr int TRACE_WORDS = 8;
-struct ApplyTrace {
-    unsigned long long *rec;     // nullptr: off
-    uint32_t cap;                // workgroups the buffer has room for
-    __device__ __forceinline__ void stamp(int i) const { if (rec && threadIdx.x == 0 && blockIdx.x < cap) rec[(size_t)blockIdx.x * TRACE_WORDS + i] = wall_clock64(); }
-    __device__ __forceinline__ void end() const { if (rec && lane_id() == 0 && blockIdx.x < cap) atomicMax(&rec[(size_t)blockIdx.x * TRACE_WORDS + 5], (unsigned long long)wall_clock64()); }   // (the last wave to leave)
-    __device__ __forceinline__ void role(int r) const { if (rec && threadIdx.x == 0 && blockIdx.x < cap) rec[(size_t)blockIdx.x * TRACE_WORDS + 6] = (unsigned long long)r; }
-};
-
 struct ApplyBorders {
     double *part;          // [tiles][2][dim]: sum of the segment that came in through the tile's front border / that leaves through its back border
     int32_t *slot;         // [tiles]: slot of the run that leaves through the tile's back border (it starts in this tile)
@@ -1273,7 +1286,7 @@ template <int VEC, int MAXC, bool VERIFY, int AP_TILE>
 __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? 6 : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
                                                            const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                            float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
-                                                           SortStage ride, SortStage ride2, ApplyTrace tr)
+                                                           SortStage ride, SortStage ride2, KernelTrace tr)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
@@ -1530,7 +1543,9 @@ struct EvictLds {
     uint32_t v_slot[EV_SLOTS], v_key[EV_SLOTS], v_cg[EV_SLOTS], v_at[EV_SLOTS];
     uint32_t n_push;
 };
-template <int VEC, bool RIDE>
+// MANY: several workers over the table (the push adds what this worker changed to the server's row:
+// three more rows in flight per victim, which the one-worker kernel does not pay registers for).
+template <int VEC, bool RIDE, bool MANY>
 __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, TrimPlan tp, SortStage ride, SortStage ride2)
 {
     uint32_t blk = blockIdx.x, nblk_ = gridDim.x;
@@ -1664,7 +1679,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
                 a2 = reinterpret_cast<const V *>(src_a + (size_t)from[2] * g.dim)[c];
                 a3 = reinterpret_cast<const V *>(src_a + (size_t)from[3] * g.dim)[c];
             }
-            if (cv.many) {
+            if (MANY) {
                 // several workers: the server adds what this worker accumulated since its Fetch
                 // (rows past the end repeat the last one: only the first of the repeats adds)
                 const bool r1 = v0 + 1 < np, r2 = v0 + 2 < np, r3 = v0 + 3 < np;

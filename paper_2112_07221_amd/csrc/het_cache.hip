@@ -100,7 +100,7 @@ struct het_cache {
     bool order_valid = false;
     // optional per-kernel timing (het_profile_begin / het_profile_end)
     bool profiling = false;
-    ApplyTrace trace{};              // het_profile_trace
+    KernelTrace trace[2]{};          // het_profile_trace: the update's kernel, the lookup's second kernel
     std::vector<ProfSpan> spans;
 };
 
@@ -368,10 +368,12 @@ int run_trim(het_cache *c, int first_stage)
     if (c->trim_seq == 0x7FFFFFFFu) c->trim_seq = 0;        // 0 means "none", the top bit marks lists of keys fetched ahead; a wrap is harmless (see HostLink::pend)
     const Rides ride = next_rides(c);
     const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
-    if (ride.blocks())
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
+    if (c->many)
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true, true><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
+    else if (ride.blocks())
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true, false><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
     else
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false><<<ev_blocks + 1, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride.a, ride.b));
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false, false><<<ev_blocks + 1, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride.a, ride.b));
     c->tf_last = fill;
     if (c->location == HET_BACKING_PINNED_HOST) { c->push_pending = true; c->push_buf = fill; c->push_seq = tp.push_seq; }
     c->overflow_pending = false;
@@ -413,13 +415,15 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         const uint32_t grid = ride.blocks() + row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
         const uint32_t lds = lds_bytes(std::max(sizeof(FillLds), sizeof(TrimLds)), ride);
         const TrimPlan none{};
-#define GATHER_ONLY(POOLED, RIDE)                                                                                        \
-    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<grid, 256, lds, c->stream>>>(                          \
-                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u, 0, Ahead{}))
+#define GATHER_ONLY_T(POOLED, RIDE, TRACE)                                                                               \
+    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE, TRACE><<<grid, 256, lds, c->stream>>>(                   \
+                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u, 0, Ahead{}, c->trace[1]))
+#define GATHER_ONLY(POOLED, RIDE) do { if (c->trace[1].rec) GATHER_ONLY_T(POOLED, RIDE, true); else GATHER_ONLY_T(POOLED, RIDE, false); } while (0)
         const int kind = ride.kind();
         if (!offsets) { if (kind == 0) GATHER_ONLY(false, 0); else if (kind == 1) GATHER_ONLY(false, 1); else GATHER_ONLY(false, 2); }
         else { if (kind == 0) GATHER_ONLY(true, 0); else if (kind == 1) GATHER_ONLY(true, 1); else GATHER_ONLY(true, 2); }
 #undef GATHER_ONLY
+#undef GATHER_ONLY_T
         if ((rc = launch_ok()) != HET_OK) return rc;
         c->last_lookup_n = n;
         c->order_ids = ids; c->order_n = n; c->order_valid = true;
@@ -447,10 +451,15 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     if (offsets)
         LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
     const uint32_t lds_own = (uint32_t)std::max(sizeof(FillLds), sizeof(TrimLds));
-#define FILL_GATHER(POOLED, RIDE, GRID, FILLB, HISTB, PUSHB)                                                              \
-    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>(     \
+#define FILL_GATHER_T(POOLED, RIDE, TRACE, GRID, FILLB, HISTB, PUSHB)                                                     \
+    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE, TRACE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>( \
                                  c->cv, c->ws, n, t_now, ptiles, FILLB, tp, HISTB, out, offsets, n_bags, c->inv, ride.a, ride.b, \
-                                 PUSHB, c->push_buf, c->push_seq, hist_pass, ah))
+                                 PUSHB, c->push_buf, c->push_seq, hist_pass, ah, c->trace[1]))
+#define FILL_GATHER(POOLED, RIDE, GRID, FILLB, HISTB, PUSHB)                                                              \
+    do {                                                                                                                  \
+        if (c->trace[1].rec) FILL_GATHER_T(POOLED, RIDE, true, GRID, FILLB, HISTB, PUSHB);                                \
+        else FILL_GATHER_T(POOLED, RIDE, false, GRID, FILLB, HISTB, PUSHB);                                               \
+    } while (0)
 #define FILL_GATHER_ANY(GRID, FILLB, HISTB, PUSHB)                                                                        \
     do {                                                                                                                  \
         const int kind = ride.kind();                                                                                     \
@@ -533,6 +542,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     }
 #undef FILL_GATHER_ANY
 #undef FILL_GATHER
+#undef FILL_GATHER_T
     if ((rc = launch_ok()) != HET_OK) return rc;
     c->overflow_pending = true;
     c->last_lookup_n = n;
@@ -560,9 +570,9 @@ int launch_apply_tile(het_cache *c, bool verify, const int64_t *ids, uint32_t n,
     const Rides ride = next_rides(c);
     const uint32_t lds = lds_bytes(std::max(sizeof(TrimLds), sizeof(ApplyLds<VEC, TILE>)), ride);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, TILE><<<ride.blocks() + grid + extra + cdiv(n, VERIFY_TILE), AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, TILE><<<ride.blocks() + grid + extra + cdiv(n, VERIFY_TILE), AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace[0]));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, TILE><<<ride.blocks() + grid + extra, AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, TILE><<<ride.blocks() + grid + extra, AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace[0]));
     return next;
 }
 
@@ -1183,11 +1193,13 @@ int het_profile_rows(int32_t pattern, float *x, float *a, const float *src, cons
     return rc;
 }
 
-int het_profile_trace(het_cache *c, uint64_t *records, int64_t capacity)
+int het_profile_trace(het_cache *c, int32_t kernel, uint64_t *records, int64_t capacity)
 {
     if (!c || !c->configured || capacity < 0 || capacity > (int64_t)1 << 24 || (capacity > 0 && !records)) return HET_EINVAL;
-    c->trace.rec = capacity ? reinterpret_cast<unsigned long long *>(records) : nullptr;
-    c->trace.cap = (uint32_t)capacity;
+    if (kernel != K_APPLY && kernel != K_FILL_GATHER) return HET_EINVAL;
+    KernelTrace &t = c->trace[kernel == K_APPLY ? 0 : 1];
+    t.rec = capacity ? reinterpret_cast<unsigned long long *>(records) : nullptr;
+    t.cap = (uint32_t)capacity;
     return HET_OK;
 }
 

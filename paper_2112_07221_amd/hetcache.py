@@ -98,7 +98,7 @@ def load() -> C.CDLL:
     lib.het_profile_begin.argtypes = [p]
     lib.het_profile_end.argtypes = [p, p, p, i32]
     lib.het_profile_kernel_count.argtypes = []
-    lib.het_profile_trace.argtypes = [p, p, i64]
+    lib.het_profile_trace.argtypes = [p, i32, p, i64]
     lib.het_profile_rows.argtypes = [i32, p, p, p, p, i64, i32, p, i32, i32, p, p]
     lib.het_profile_kernel_name.argtypes = [C.c_int]
     lib.het_profile_kernel_name.restype = C.c_char_p
@@ -344,16 +344,19 @@ class HetCache:
         return {self.lib.het_profile_kernel_name(i).decode(): (float(ms[i]), int(cnt[i]))
                 for i in range(k) if cnt[i]}
 
-    def profile_trace(self, records=None):
-        """Switches the update kernel's per-workgroup time stamps on (records: zeroed int64 GPU tensor
-        of shape [workgroups, TRACE_WORDS]) or off (None)."""
+    def profile_trace(self, records=None, kernel="apply_kernel"):
+        """Switches the per-workgroup time stamps of `kernel` ("apply_kernel" or "fill_gather_kernel")
+        on (records: zeroed int64 GPU tensor of shape [workgroups, TRACE_WORDS]) or off (None)."""
         import torch
+        names = [self.lib.het_profile_kernel_name(i).decode() for i in range(self.lib.het_profile_kernel_count())]
+        k = names.index(kernel)
         if records is None:
-            self._rc(self.lib.het_profile_trace(self.h, None, 0), "het_profile_trace")
+            self._rc(self.lib.het_profile_trace(self.h, k, None, 0), "het_profile_trace")
         else:
             _check_dev(records, torch.int64, "records")
-            self._rc(self.lib.het_profile_trace(self.h, records.data_ptr(), records.shape[0]), "het_profile_trace")
-        self._trace_records = records
+            self._rc(self.lib.het_profile_trace(self.h, k, records.data_ptr(), records.shape[0]), "het_profile_trace")
+        self._trace_records = getattr(self, "_trace_records", {})
+        self._trace_records[kernel] = records
 
     def close(self):
         if getattr(self, "h", None):

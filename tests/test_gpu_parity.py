@@ -892,31 +892,36 @@ def test_reference_pattern_kernels_do_what_the_header_says():
 
 
 @pytest.mark.gpu
-def test_time_stamps_of_the_update_kernel_change_nothing():
-    """het_profile_trace: with the stamps on, an update gives the same cache as without, every
-    workgroup of the kernel leaves a record with start <= end, and switching them off stops them."""
+def test_time_stamps_inside_the_kernels_change_nothing():
+    """het_profile_trace: with the stamps on, a step gives the same cache as without, every
+    workgroup of the two kernels leaves a record with start <= end, and switching them off stops them."""
     dev = torch.device("cuda:0")
     w = wl.WORKLOADS[1].scaled(capacity=600, s=2, optimizer=wl.ADAGRAD, eps=1e-8)
     table = wl.table_init(w)
     ids = wl.IdStream(w).batches(6)
     grads = wl.grad_pool(w)
     p = Pair(w, table)
+    kernels = ("apply_kernel", "fill_gather_kernel")
     try:
-        rec = torch.zeros(4096, hc.TRACE_WORDS, dtype=torch.int64, device=dev)
+        rec = {k: torch.zeros(4096, hc.TRACE_WORDS, dtype=torch.int64, device=dev) for k in kernels}
+        seen = {}
         for t in range(6):
-            p.lookup(ids[t])
             if t == 3:
-                p.cache.profile_trace(rec)
+                for k in kernels:
+                    p.cache.profile_trace(rec[k], k)
             if t == 4:
-                p.cache.profile_trace(None)
-                seen = rec.cpu().numpy().copy()
-                rec.zero_()
+                for k in kernels:
+                    p.cache.profile_trace(None, k)
+                    seen[k] = rec[k].cpu().numpy().copy()
+                    rec[k].zero_()
+            p.lookup(ids[t])
             p.update(ids[t], grads[t % len(grads)])
             p.compare_state(values=True)
-        used = seen[:, 6] > 0
-        assert used.sum() >= 1 and (seen[used, 6] <= 4).all()
-        assert (seen[used, 5] >= seen[used, 0]).all() and (seen[used, 0] > 0).all()
-        assert not rec.cpu().numpy().any()
+        for k in kernels:
+            used = seen[k][:, 6] > 0
+            assert used.sum() >= 1 and (seen[k][used, 6] <= 6).all()
+            assert (seen[k][used, 5] >= seen[k][used, 0]).all() and (seen[k][used, 0] > 0).all()
+            assert not rec[k].cpu().numpy().any()
         p.flush_and_compare()
     finally:
         p.close()
