@@ -368,12 +368,17 @@ int run_trim(het_cache *c, int first_stage)
     if (c->trim_seq == 0x7FFFFFFFu) c->trim_seq = 0;        // 0 means "none", the top bit marks lists of keys fetched ahead; a wrap is harmless (see HostLink::pend)
     const Rides ride = next_rides(c);
     const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
+    // Rows of a kilobyte or more: the pushes run at the memory's limit, and a fourth workgroup per
+    // compute unit only gets in the others' way (config 5: 107 us against 97).  Asking for more LDS
+    // than a quarter of a compute unit's keeps it to three.
+    const uint32_t lds_floor = c->cv.geom.lanes == 64 && VEC == 4 ? 44u * 1024u : 0u;
+    const uint32_t lds = std::max(lds_bytes(sizeof(EvictLds), ride), lds_floor);
     if (c->many)
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true, true><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true, true><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds, c->stream>>>(c->cv, tp, ride.a, ride.b));
     else if (ride.blocks())
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true, false><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds_bytes(sizeof(EvictLds), ride), c->stream>>>(c->cv, tp, ride.a, ride.b));
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true, false><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds, c->stream>>>(c->cv, tp, ride.a, ride.b));
     else
-        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false, false><<<ev_blocks + 1, TRIM_THREADS, sizeof(EvictLds), c->stream>>>(c->cv, tp, ride.a, ride.b));
+        LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, false, false><<<ev_blocks + 1, TRIM_THREADS, lds, c->stream>>>(c->cv, tp, ride.a, ride.b));
     c->tf_last = fill;
     if (c->location == HET_BACKING_PINNED_HOST) { c->push_pending = true; c->push_buf = fill; c->push_seq = tp.push_seq; }
     c->overflow_pending = false;
