@@ -183,6 +183,12 @@ def pattern_study(args, w, dev):
         gidx = as_dev(rng.permutation(n)[: U * per] if U * per <= n else rng.integers(0, n, U * per))
         add(f"update of U rows, each with {per} gradient rows from anywhere in the batch", (2 * U * Q + U * per) * R,
             hc.profile_rows(hc.PATTERN_UPDATE, x, a=a, src=grads, idx=slots, gidx=gidx, per=per))
+    shuffled = as_dev(rng.permutation(slots.cpu().numpy()))   # the path's order: by key, which says nothing about the slot
+    add("update of U distinct cached rows, taken in random order of slot", 2 * U * Q * R,
+        hc.profile_rows(hc.PATTERN_UPDATE, x, a=a, idx=shuffled))
+    gidx = as_dev(rng.permutation(n)[: U * 2] if U * 2 <= n else rng.integers(0, n, U * 2))
+    add("update of U rows in random order of slot, each with 2 gradient rows from anywhere in the batch", (2 * U * Q + U * 2) * R,
+        hc.profile_rows(hc.PATTERN_UPDATE, x, a=a, src=grads, idx=shuffled, gidx=gidx, per=2))
     print(json.dumps({"study": "plain kernels with the path's access patterns", "config": w.index, "n": n, "unique": U,
                       "dim": D, "slots": P, "build_id": hc.build_id(), "rows": rows}))
 
