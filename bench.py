@@ -80,9 +80,10 @@ def kernel_bytes(w, c, name):
     if name == "apply_kernel":      # grads read, value (+accumulator) read and written, index arrays
         return w.n_grad_rows * R + 2 * U * Q * R + 4 * w.n + 12 * U
     if name == "fill_gather_kernel":
-        # cached rows read once per key, out written, fetched rows (and refreshed ones) read and
-        # written with their optimizer state, index arrays
-        moved = c["miss"] + c["stale"]
+        # cached rows read once per key, out written, refreshed rows read and written with their
+        # optimizer state (and the fetched ones where the table is behind the host link: with the
+        # table in HBM the update reads a missed key's row from the table itself), index arrays
+        moved = c["stale"] + (c["miss"] if w.backing == "host" else 0)
         return U * R + w.n_grad_rows * R + 2 * moved * Q * R + 8 * w.n + 4 * U
     return None
 

@@ -892,7 +892,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
                                                           TrimPlan tp, uint32_t hist_blocks, float *__restrict__ out, const int64_t *__restrict__ offsets, uint32_t n_bags,
                                                           const uint32_t *__restrict__ inv, SortStage ride, SortStage ride2,
                                                           uint32_t push_blocks, int push_buf, uint32_t push_seq, int hist_pass, Ahead ah,
-                                                          KernelTrace tr_arg)
+                                                          KernelTrace tr_arg, int fetch_mode)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
@@ -907,18 +907,22 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
-    const uint32_t ins_blocks = fill_blocks ? ptiles : 0u;
+    // fetch_mode 0: everything.  1: the missed keys' rows are left to the update that follows (it reads
+    // them from the global table and writes them to their slots with its step applied: they are
+    // neither written nor read once more); all else as usual.  2: only those rows (a call came
+    // between that is not that update).
+    const uint32_t ins_blocks = fill_blocks && fetch_mode != 2 ? ptiles : 0u;
     if (bid < fill_blocks) {
         FillLds &fl = lds_as<FillLds>();
         const uint32_t tot_miss = tile_prefix_to_lds<4>(ws.tile_miss, ptiles, fl.pre_miss, fl.scan);
         const uint32_t tot_stale = tile_prefix_to_lds<4>(ws.tile_stale, ptiles, fl.pre_stale, fl.scan);
         const uint32_t gid = bid * groups_per_block + threadIdx.x / g.lanes;
         const uint32_t ngroups = fill_blocks * groups_per_block;
-        if (bid == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // for an update that reuses this order
+        if (bid == 0 && threadIdx.x == 0 && fetch_mode != 2) cv.ds->n_unique = (uint32_t)cv.last->unique;   // for an update that reuses this order
         // Fetch(k) into a new slot, FILL_ROWS keys per row group at a time: where each row comes from
         // and goes to is asked for all of them first, then the rows (few workgroups with several
         // rows in flight each leave the chip to the other roles of this kernel from the start)
-        for (uint32_t m0 = gid; m0 < tot_miss; m0 += ngroups * FILL_ROWS) {
+        for (uint32_t m0 = gid; m0 < tot_miss && fetch_mode != 1; m0 += ngroups * FILL_ROWS) {
             const float *srow[FILL_ROWS], *sacc[FILL_ROWS];
             uint32_t slot[FILL_ROWS], keyr[FILL_ROWS];
 #pragma unroll
@@ -951,7 +955,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
                     if (r < nin) cv.acc[slot[r]] = cv.A[keyr[r]];
             }
         }                                        // (clocks, key and index entry: the workgroups below)
-        for (uint32_t m = gid; m < tot_stale; m += ngroups) {                // Evict(k); Fetch(k) in place
+        for (uint32_t m = gid; m < tot_stale && fetch_mode != 2; m += ngroups) {                // Evict(k); Fetch(k) in place
             const uint32_t tl = tile_of(fl.pre_stale, ptiles, m);
             const uint2 jk = ws.stale_stage[tl * PT_TILE + (m - fl.pre_stale[tl])];
             const uint32_t key = jk.y;
@@ -1116,7 +1120,10 @@ __device__ __forceinline__ float rowwise_rcp(const CacheView &cv, uint32_t slot,
 }
 
 template <int VEC>
-__device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, int c, const double *g64, float lr, float eps, bool act = true)
+// `from_key` other than KEY_NONE: the row has not been fetched yet (see apply_kernel, "fresh"): it is
+// read from the global table at that key and written to the slot.
+__device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, int c, const double *g64, float lr, float eps, bool act = true,
+                                           uint32_t from_key = KEY_NONE)
 {
     using V = typename VecT<VEC>::type;
     float G[VEC];
@@ -1125,15 +1132,16 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
     float row_rcp = 0.f;
     if (cv.rowwise) row_rcp = rowwise_rcp<VEC>(cv, slot, G, eps);
     if (!act) return;
+    const bool fresh = from_key != KEY_NONE;
     V *xp = reinterpret_cast<V *>(cv.rows + (size_t)slot * cv.geom.dim) + c;
-    V xv = *xp;
+    V xv = fresh ? reinterpret_cast<const V *>(cv.W + (size_t)from_key * cv.geom.dim)[c] : *xp;
     float *x = reinterpret_cast<float *>(&xv);
     if (cv.rowwise) {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) x[k] -= lr * G[k] * row_rcp;
     } else if (cv.adagrad) {
         V *ap = reinterpret_cast<V *>(cv.acc + (size_t)slot * cv.geom.dim) + c;
-        V av = *ap;
+        V av = fresh ? reinterpret_cast<const V *>(cv.A + (size_t)from_key * cv.geom.dim)[c] : *ap;
         float *a = reinterpret_cast<float *>(&av);
 #pragma unroll
         for (int k = 0; k < VEC; ++k) { a[k] += G[k] * G[k]; x[k] -= lr * G[k] * fast_rcp(fast_sqrt(a[k]) + eps); }
@@ -1159,6 +1167,10 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // fp64 partial sum per tile it touches in `ApplyBorders::part`, and the tile that arrives last at
 // the run's counter adds them up in tile order and applies the step: which tile is last varies,
 // the order of the additions does not.  Nobody waits for anybody.
+// fresh_rows: the lookup whose order this update reuses left the fetch of its missed keys' rows to
+// this kernel (table in HBM, one worker): where a run's key was a miss, the row and accumulator are
+// read from the global table instead of the slot; the step's result goes to the slot as always.
+// Fetch and Update of Algorithms 2 and 3 in one read and one write of the row.
 // VERIFY: the ids must be the ones the sorted order was built from (an update that reuses the
 // preceding lookup's order); extra workgroups compare them and flag any difference.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
@@ -1178,6 +1190,7 @@ template <int VEC, int AP_TILE> struct ApplyLds {
     int32_t slot[AP_TILE];               // slot of the key, valid at run heads
     uint32_t seg_start[AP_TILE + 1];     // first position (within the tile) of every segment, then the tile's count
     uint32_t wave_heads[AP_TILE / WAVE];
+    uint64_t fresh[AP_TILE / WAVE];      // per position: a run head whose key missed in the lookup and whose row is fetched here
 };
 
 // How many of the conditions cond(1), cond(2), ... hold before the first that does not; found by
@@ -1199,7 +1212,7 @@ __device__ __forceinline__ uint32_t wave_count_leading(F cond)
 template <int VEC>
 __device__ __forceinline__ void add_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
                                               int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
-                                              typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar)
+                                              typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar, uint32_t from_key = KEY_NONE)
 {
     using V = typename VecT<VEC>::type;
     const int dim = cv.geom.dim;
@@ -1211,8 +1224,9 @@ __device__ __forceinline__ void add_positions(const CacheView &cv, const float *
             if (act && b0 + r < hi) v[r] = reinterpret_cast<const V *>(grads + (size_t)grow[b0 + r] * dim)[cidx];
         }
         if (with_row && b0 == lo && act) {
-            xr = reinterpret_cast<const V *>(cv.rows + (size_t)slot * dim)[cidx];
-            if (cv.adagrad) ar = reinterpret_cast<const V *>(cv.acc + (size_t)slot * dim)[cidx];
+            const bool fresh = from_key != KEY_NONE;          // not fetched yet: the global row
+            xr = reinterpret_cast<const V *>(fresh ? cv.W + (size_t)from_key * dim : cv.rows + (size_t)slot * dim)[cidx];
+            if (cv.adagrad) ar = reinterpret_cast<const V *>(fresh ? cv.A + (size_t)from_key * dim : cv.acc + (size_t)slot * dim)[cidx];
         }
 #pragma unroll
         for (int r = 0; r < AP_BATCH; ++r) {
@@ -1226,16 +1240,17 @@ __device__ __forceinline__ void add_positions(const CacheView &cv, const float *
 template <int VEC>
 __device__ __forceinline__ void sum_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
                                               int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
-                                              typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar)
+                                              typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar, uint32_t from_key = KEY_NONE)
 {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
-    add_positions<VEC>(cv, grads, grow, lo, hi, cidx, act, acc64, with_row, slot, xr, ar);
+    add_positions<VEC>(cv, grads, grow, lo, hi, cidx, act, acc64, with_row, slot, xr, ar, from_key);
 }
 
 struct SegWork {
     uint32_t a, b;             // positions [a, b) of the tile
     int32_t slot;
+    uint32_t from_key;         // KEY_NONE, or the key whose row has not been fetched yet (fresh)
     bool is_front, is_back;    // the run began in an earlier tile / goes on in a later one
 };
 
@@ -1273,20 +1288,22 @@ __device__ __forceinline__ void st_device(double *p, double v) { __hip_atomic_st
 __device__ __forceinline__ double ld_device(const double *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void st_device(int32_t *p, int32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ int32_t ld_device(const int32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_device(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t ld_device(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void stores_acknowledged() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 struct ApplyBorders {
     double *part;          // [tiles][2][dim]: sum of the segment that came in through the tile's front border / that leaves through its back border
     int32_t *slot;         // [tiles]: slot of the run that leaves through the tile's back border (it starts in this tile)
+    uint32_t *from_key;    // [tiles]: that run's key if its row has not been fetched yet, else KEY_NONE
     uint32_t *arrived;     // [tiles]: how many tiles of the run that starts in this tile have stored their sums (zero between kernels)
 };
 
 template <int VEC, int MAXC, bool VERIFY, int AP_TILE>
-// (rows of one piece per lane: held to 80 registers, six waves per SIMD; the compiler's own choice was 84 and five)
-__global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? 6 : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
+__global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
                                                            const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                            float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
-                                                           SortStage ride, SortStage ride2, KernelTrace tr)
+                                                           SortStage ride, SortStage ride2, KernelTrace tr, int fresh_rows)
 {
     using V = typename VecT<VEC>::type;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
@@ -1341,10 +1358,14 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
             const uint32_t k = in ? skey[j] : KEY_NONE;
             uint32_t pm = in ? ws.perm[j] : 0u;
             const int32_t hs = in ? ws.head_slot[j] : SLOT_NONE;
+            // fresh_rows: the lookup left the fetch of its missed keys' rows to this kernel
+            const bool fresh = fresh_rows && in && ws.cls[j] == (uint8_t)CLS_MISS && (j == 0 || skey[j - 1] != k);
             if (grad_row && in) pm = grad_row[pm];
             l.key[1 + i] = j < nv ? k : KEY_NONE;
             l.grow[i] = pm;
             l.slot[i] = hs;
+            const uint64_t fm = __ballot(fresh);
+            if (lane_id() == 0) l.fresh[i / WAVE] = fm;
         } else if (i == AP_TILE) {
             l.key[0] = j0 > 0 && j0 < n_ids ? skey[j0 - 1] : KEY_NONE;
         } else if (i == AP_TILE + 1) {
@@ -1399,6 +1420,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
         w.a = l.seg_start[sg]; w.b = l.seg_start[sg + 1];
         w.is_front = sg == 0 && front_open; w.is_back = sg + 1 == nseg && back_open;
         w.slot = w.is_front ? SLOT_NONE : l.slot[w.a];
+        w.from_key = !w.is_front && ((l.fresh[w.a / WAVE] >> (w.a % WAVE)) & 1ull) ? l.key[1 + w.a] : KEY_NONE;
         return w;
     };
     // what is left to do once the segment's sum for row piece cidx is there
@@ -1414,7 +1436,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
     };
     auto finish_segment = [&](const SegWork &w) {
         if (gl == 0) {
-            if (w.is_back && !w.is_front) st_device(&bd.slot[T], w.slot);
+            if (w.is_back && !w.is_front) { st_device(&bd.slot[T], w.slot); st_device(&bd.from_key[T], w.from_key); }
             // Clock(k): once per key per Write; a run that goes on in later tiles takes it where it starts
             if (!w.is_front && w.slot != SLOT_NONE && !cv.direct) atomicAdd(&cv.meta[w.slot].cc, 1u);
         }
@@ -1431,7 +1453,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
                 const bool act = cidx < g.chunks;
                 double acc64[VEC];
                 V xr{}, ar{};
-                sum_positions<VEC>(cv, grads, l.grow, w.a, w.b, cidx, act, acc64, step, (uint32_t)w.slot, xr, ar);
+                sum_positions<VEC>(cv, grads, l.grow, w.a, w.b, cidx, act, acc64, step, (uint32_t)w.slot, xr, ar, w.from_key);
                 finish_piece(w, cidx, act, acc64, xr, ar);
             }
             finish_segment(w);
@@ -1445,6 +1467,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
             if (b - a <= AP_SOLO) continue;
             const bool is_front = sg == 0 && front_open, is_back = sg + 1 == nseg && back_open;
             const int32_t slot = is_front ? SLOT_NONE : l.slot[a];
+            const uint32_t from_key = !is_front && ((l.fresh[a / WAVE] >> (a % WAVE)) & 1ull) ? l.key[1 + a] : KEY_NONE;
             const bool closed = !is_front && !is_back;
             const bool step = closed && slot != SLOT_NONE;
             const uint32_t per = (b - a + ngroups - 1) / ngroups;
@@ -1455,7 +1478,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
                 const bool act = cidx < g.chunks;
                 double acc64[VEC];
                 V xr{}, ar{};
-                sum_positions<VEC>(cv, grads, l.grow, lo, hi, cidx, act, acc64, step && group == 0, (uint32_t)slot, xr, ar);
+                sum_positions<VEC>(cv, grads, l.grow, lo, hi, cidx, act, acc64, step && group == 0, (uint32_t)slot, xr, ar, from_key);
                 __syncthreads();                            // (the shares of the piece before have been read)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) l.share[threadIdx.x * VEC + e] = acc64[e];
@@ -1476,7 +1499,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
                 }
             }
             if (threadIdx.x == 0) {
-                if (is_back && !is_front) st_device(&bd.slot[T], slot);
+                if (is_back && !is_front) { st_device(&bd.slot[T], slot); st_device(&bd.from_key[T], from_key); }
                 if (!is_front && slot != SLOT_NONE && !cv.direct) atomicAdd(&cv.meta[slot].cc, 1u);
             }
             if (!closed && group == 0) stores_acknowledged();
@@ -1503,6 +1526,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
     last = __shfl(last, 0, WAVE);
     if (!last || lane_id() >= (uint32_t)g.lanes) { tr.end(); return; }
     const int32_t slot = ld_device(&bd.slot[T0]);           // (SLOT_NONE: a key that is not cached, flagged where the order was probed)
+    const uint32_t from_key = ld_device(&bd.from_key[T0]);
 #pragma unroll
     for (int q = 0; q < MAXC; ++q) {
         const int cidx = gl + q * g.lanes;
@@ -1525,7 +1549,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
         }
-        if (slot != SLOT_NONE) apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps, act);
+        if (slot != SLOT_NONE) apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps, act, from_key);
     }
     tr.end();
 }

@@ -101,6 +101,11 @@ struct het_cache {
     // optional per-kernel timing (het_profile_begin / het_profile_end)
     bool profiling = false;
     KernelTrace trace[2]{};          // het_profile_trace: the update's kernel, the lookup's second kernel
+    // The last lookup left the fetch of its missed keys' rows to the update that reuses its order (table in
+    // HBM, one worker): that update reads them from the global table.  Any other call that needs the rows
+    // in their slots fetches them first (settle_fetch).
+    bool fetch_owed = false;
+    uint32_t owed_n = 0, owed_t = 0;
     std::vector<ProfSpan> spans;
 };
 
@@ -330,6 +335,7 @@ uint32_t stage_blocks(const het_cache *c, const TrimPlan &tp, int stage)
     return cdiv(c->cv.n_slots, COUNT_SLOTS);
 }
 
+constexpr uint32_t STALE_BLOCKS = 128;     // fetch workgroups of a lookup that leaves the missed rows to the update: they refresh the stale rows
 constexpr uint32_t PUSH_BLOCKS = 256;      // few workgroups keep the host link full; more only contend
 constexpr uint32_t LINK_BLOCKS = 32;       // workgroups of the kernel that works the host link beside the update (half write back, half fetch ahead)
 
@@ -349,6 +355,28 @@ void drain_pushes(het_cache *c)
     if (c->cv.geom.vec == 4) LAUNCH(c, K_DEFERRED_PUSH, deferred_push_kernel<4><<<PUSH_BLOCKS, 256, 0, c->stream>>>(c->cv, c->push_buf));
     else LAUNCH(c, K_DEFERRED_PUSH, deferred_push_kernel<1><<<PUSH_BLOCKS, 256, 0, c->stream>>>(c->cv, c->push_buf));
     c->push_pending = false;
+}
+
+// A lookup left the fetch of its missed keys' rows to the update that reuses its order, and that
+// update is not what comes next: fetch them now (the lookup's lists are still in place: nothing
+// has sorted, probed or trimmed since).
+template <int VEC>
+int settle_fetch_impl(het_cache *c)
+{
+    const uint32_t n = c->owed_n, ptiles = cdiv(n, PT_TILE);
+    const uint32_t fill_blocks = std::min(cdiv(row_grid(c->cv.geom, n), (uint32_t)FILL_ROWS), FILL_MAX_BLOCKS);
+    const TrimPlan none{};
+    const SortStage no = no_stage();
+    LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, false, 0, false><<<fill_blocks, 256, sizeof(FillLds), c->stream>>>(
+                                 c->cv, c->ws, n, c->owed_t, ptiles, fill_blocks, none, 0u, nullptr, nullptr, 0u, nullptr, no, no,
+                                 0u, 0, 0u, 0, Ahead{}, KernelTrace{}, 2));
+    c->fetch_owed = false;
+    return launch_ok();
+}
+int settle_fetch(het_cache *c)
+{
+    if (!c->fetch_owed) return HET_OK;
+    return c->cv.geom.vec == 4 ? settle_fetch_impl<4>(c) : settle_fetch_impl<1>(c);
 }
 
 // Evict(): the select stages from `first_stage` on (earlier ones rode along with the update's
@@ -393,6 +421,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     begin_call(c);
     c->t_host += 1;
     int rc;
+    if ((rc = settle_fetch(c)) != HET_OK) return rc;
     if (c->overflow_pending && (rc = run_trim<VEC>(c, c->sel_next)) != HET_OK) return rc;   // a Read that follows a Read
     // The sorted order: announced by het_prefetch and sorted inside the kernels launched since
     // (what is left of it runs now), or sorted here.  Announcements older than the one used are
@@ -422,7 +451,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
         const TrimPlan none{};
 #define GATHER_ONLY_T(POOLED, RIDE, TRACE)                                                                               \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE, TRACE><<<grid, 256, lds, c->stream>>>(                   \
-                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u, 0, Ahead{}, c->trace[1]))
+                                 c->cv, c->ws, n, t_now, 0u, 0u, none, 0u, out, offsets, n_bags, c->inv, ride.a, ride.b, 0u, 0, 0u, 0, Ahead{}, c->trace[1], 0))
 #define GATHER_ONLY(POOLED, RIDE) do { if (c->trace[1].rec) GATHER_ONLY_T(POOLED, RIDE, true); else GATHER_ONLY_T(POOLED, RIDE, false); } while (0)
         const int kind = ride.kind();
         if (!offsets) { if (kind == 0) GATHER_ONLY(false, 0); else if (kind == 1) GATHER_ONLY(false, 1); else GATHER_ONLY(false, 2); }
@@ -459,7 +488,7 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
 #define FILL_GATHER_T(POOLED, RIDE, TRACE, GRID, FILLB, HISTB, PUSHB)                                                     \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE, TRACE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>( \
                                  c->cv, c->ws, n, t_now, ptiles, FILLB, tp, HISTB, out, offsets, n_bags, c->inv, ride.a, ride.b, \
-                                 PUSHB, c->push_buf, c->push_seq, hist_pass, ah, c->trace[1]))
+                                 PUSHB, c->push_buf, c->push_seq, hist_pass, ah, c->trace[1], fetch_mode))
 #define FILL_GATHER(POOLED, RIDE, GRID, FILLB, HISTB, PUSHB)                                                              \
     do {                                                                                                                  \
         if (c->trace[1].rec) FILL_GATHER_T(POOLED, RIDE, true, GRID, FILLB, HISTB, PUSHB);                                \
@@ -480,10 +509,18 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     } while (0)
     const uint32_t gather_blocks = row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
     Ahead ah{};
+    int fetch_mode = 0;
     if (c->location == HET_BACKING_HBM && !c->many) {
-        // one kernel: the gather reads a missed key's row from the global table, beside the fetch
+        // one kernel: the gather reads a missed key's row from the global table, beside the fetch.
+        // The missed keys' rows themselves are left to the update that is expected to follow (it reads
+        // them from the global table and writes them to their slots with its step applied); the fetch
+        // workgroups that remain refresh the stale rows.
         const Rides ride = next_rides(c);
-        FILL_GATHER_ANY(ride.blocks() + fill_blocks + ptiles + hist_blocks + gather_blocks, fill_blocks, hist_blocks, 0u);
+        const bool owe = !c->cv.rowwise;
+        fetch_mode = owe ? 1 : 0;
+        const uint32_t fb = owe ? std::min(fill_blocks, STALE_BLOCKS) : fill_blocks;
+        FILL_GATHER_ANY(ride.blocks() + fb + ptiles + hist_blocks + gather_blocks, fb, hist_blocks, 0u);
+        if (owe) { c->fetch_owed = true; c->owed_n = n; c->owed_t = t_now; }
     } else {
         // Host-backed table: the fetches come over the host link, and the last trim's write-back
         // goes the other way in the same kernel; the gather follows and reads the cached copies.
@@ -573,11 +610,13 @@ int launch_apply_tile(het_cache *c, bool verify, const int64_t *ids, uint32_t n,
     else if (trim && next == tp.passes && verify && !c->cv.freq_cap) { stage = next++; tp.dirty_stamp = (uint32_t)c->t_host; }    // (light-weight LFU leaves some rows of the batch unstamped)
     const uint32_t extra = stage >= 0 ? stage_blocks(c, tp, stage) : 0u;
     const Rides ride = next_rides(c);
+    const int fresh = verify && c->fetch_owed ? 1 : 0;          // (verify: this update reuses the lookup's order)
+    if (fresh) c->fetch_owed = false;
     const uint32_t lds = lds_bytes(std::max(sizeof(TrimLds), sizeof(ApplyLds<VEC, TILE>)), ride);
     if (verify)
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, TILE><<<ride.blocks() + grid + extra + cdiv(n, VERIFY_TILE), AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace[0]));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, true, TILE><<<ride.blocks() + grid + extra + cdiv(n, VERIFY_TILE), AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace[0], fresh));
     else
-        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, TILE><<<ride.blocks() + grid + extra, AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace[0]));
+        LAUNCH(c, K_APPLY, apply_kernel<VEC, MAXC, false, TILE><<<ride.blocks() + grid + extra, AP_THREADS, lds, c->stream>>>(c->cv, c->ws, c->bd, ids, grads, grad_row, lr, c->eps, n, grid, tp, stage, ride.a, ride.b, c->trace[0], fresh));
     return next;
 }
 
@@ -602,6 +641,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     // set of sort buffers (announced batches use the other sets).
     const bool reuse = c->order_valid && ids == c->order_ids && n == c->order_n;
     if (!reuse) {
+        if ((rc = settle_fetch(c)) != HET_OK) return rc;
         sort_now(c, ids, n, c->sort_set, 0);
         use_order(c, c->sort_set);
         if (c->cv.direct)
@@ -735,7 +775,7 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
         (rc = dev_alloc(c, &ws.miss_stage, ptiles * PT_TILE)) || (rc = dev_alloc(c, &ws.stale_stage, ptiles * PT_TILE)) ||
         (rc = dev_alloc(c, &c->inv, N)) || (rc = dev_alloc(c, &ws.bag_of, N)) ||
         (rc = dev_alloc(c, &c->bd.part, ap_tiles * 2 * (size_t)c->dim)) || (rc = dev_alloc(c, &c->bd.slot, ap_tiles)) ||
-        (rc = dev_alloc(c, &c->bd.arrived, ap_tiles)))
+        (rc = dev_alloc(c, &c->bd.arrived, ap_tiles)) || (rc = dev_alloc(c, &c->bd.from_key, ap_tiles)))
         return rc;
     const size_t slot_tiles = cdiv(P, TRIM_TILE), ev_blocks = cdiv(P, EV_SLOTS), ev_supers = cdiv(ev_blocks, EV_SUPER);
     c->tp.zero_words = (uint32_t)(SEL_MAX_PASSES * SEL_BINS + 4 * ev_supers);
@@ -933,6 +973,7 @@ int het_flush(het_cache *c)
     c->pf.ready = false;
     wait_link(c);                // (nothing the flush writes may be overtaken by an older staged copy)
     drain_pushes(c);             // (a staged copy of a row reaches the table before anything the flush writes)
+    { int rc0 = settle_fetch(c); if (rc0) return rc0; }
     const uint32_t grid = row_grid(c->cv.geom, c->cv.n_slots);
     if (c->cv.geom.vec == 4) LAUNCH(c, K_FLUSH, flush_kernel<4><<<grid, 256, 0, c->stream>>>(c->cv));
     else LAUNCH(c, K_FLUSH, flush_kernel<1><<<grid, 256, 0, c->stream>>>(c->cv));
@@ -992,6 +1033,7 @@ int het_export_state(het_cache *c, int64_t *keys, int32_t *slots, uint32_t *cs, 
 int het_export_rows(het_cache *c, float *rows, float *acc)
 {
     if (!c || !c->configured) return HET_EINVAL;
+    { int rc0 = settle_fetch(c); if (rc0) return rc0; }
     { int rc0 = sync_all(c); if (rc0) return rc0; }
     const size_t P = c->cv.n_slots, D = (size_t)c->dim;
     if (c->cv.direct) return HET_OK;                 // no cache: nothing is ever cached

@@ -925,3 +925,40 @@ def test_time_stamps_inside_the_kernels_change_nothing():
         p.flush_and_compare()
     finally:
         p.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("opt", [wl.SGD, wl.ADAGRAD])
+def test_rows_a_lookup_leaves_to_the_update_are_fetched_by_whoever_needs_them_first(opt):
+    """With the table in HBM a lookup leaves the fetch of its missed keys' rows to the update that
+    reuses its order.  Whatever comes instead (a flush, an export of the rows, another lookup, an
+    update with other ids or with the same ids in another buffer) must find the rows in their slots."""
+    w = wl.WORKLOADS[1].scaled(capacity=500, s=2, optimizer=opt, eps=1e-8, policy=wl.LFU)
+    table = wl.table_init(w)
+    ids = wl.IdStream(w).batches(12)
+    grads = wl.grad_pool(w)
+    p = Pair(w, table)
+    try:
+        g = lambda t: grads[t % len(grads)]
+        p.lookup(ids[0]); p.update(ids[0], g(0))                       # the ordinary case: the update fetches
+        p.compare_state(values=True)
+        p.lookup(ids[1]); p.compare_state(values=True)                 # an export of the rows comes first
+        p.update(ids[1], g(1)); p.compare_state(values=True)
+        p.lookup(ids[2]); p.flush_and_compare()                        # a flush comes first
+        p.update(ids[2], g(2)); p.compare_state(values=True)
+        p.lookup(ids[3]); p.lookup(ids[4])                             # another lookup comes first
+        p.update(ids[4], g(4)); p.compare_state(values=True)
+        p.lookup(ids[5])                                               # an update with other ids comes first
+        p.update(ids[6], g(6)); p.compare_state(values=True)
+        p.lookup(ids[7])                                               # the same ids in another buffer: sorted afresh
+        p.update(ids[7].copy(), g(7)); p.compare_state(values=True)
+        dev_ids = torch.from_numpy(ids[8]).to(p.dev)                   # and the ordinary case again, free-running
+        for t in range(8, 12):
+            dev_ids = torch.from_numpy(ids[t]).to(p.dev)
+            p.lookup(ids[t], ids_dev=dev_ids)
+            p.update(ids[t], g(t), ids_dev=dev_ids)
+        p.compare_state(values=True)
+        p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
