@@ -948,11 +948,13 @@ def test_rows_a_lookup_leaves_to_the_update_are_fetched_by_whoever_needs_them_fi
         p.update(ids[2], g(2)); p.compare_state(values=True)
         p.lookup(ids[3]); p.lookup(ids[4])                             # another lookup comes first
         p.update(ids[4], g(4)); p.compare_state(values=True)
-        p.lookup(ids[5])                                               # an update with other ids comes first
-        p.update(ids[6], g(6)); p.compare_state(values=True)
-        p.lookup(ids[7])                                               # the same ids in another buffer: sorted afresh
-        p.update(ids[7].copy(), g(7)); p.compare_state(values=True)
-        dev_ids = torch.from_numpy(ids[8]).to(p.dev)                   # and the ordinary case again, free-running
+        p.lookup(ids[5])                                               # an update of a part of the ids comes first
+        half = len(ids[5]) // 2
+        p.update(ids[5][:half].copy(), g(5)[:half].copy()); p.compare_state(values=True)
+        a = torch.from_numpy(ids[7]).to(p.dev); b = a.clone()          # the same ids in another buffer: sorted afresh
+        p.lookup(ids[7], ids_dev=a)
+        p.update(ids[7], g(7), ids_dev=b); p.compare_state(values=True)
+        # and the ordinary case again, free-running
         for t in range(8, 12):
             dev_ids = torch.from_numpy(ids[t]).to(p.dev)
             p.lookup(ids[t], ids_dev=dev_ids)
