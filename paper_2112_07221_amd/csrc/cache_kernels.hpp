@@ -1175,7 +1175,7 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // preceding lookup's order); extra workgroups compare them and flag any difference.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
 constexpr int AP_THREADS = 256;
-constexpr int AP_BATCH = 8;
+constexpr int AP_BATCH = 6;            // gradient rows in flight per row group (with eight the kernel needs 87 registers: five waves per SIMD instead of six)
 constexpr int AP_SOLO = 32;
 // Positions per tile (template parameter AP_TILE): 64 where a workgroup has eight row groups or
 // more (rows up to 128 floats), 128 for wider rows, whose fewer row groups would otherwise stand
@@ -1300,7 +1300,8 @@ struct ApplyBorders {
 };
 
 template <int VEC, int MAXC, bool VERIFY, int AP_TILE>
-__global__ __launch_bounds__(AP_THREADS) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
+// (rows of one piece per lane: held to 80 registers, six waves per SIMD)
+__global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? 6 : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
                                                            const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                            float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
                                                            SortStage ride, SortStage ride2, KernelTrace tr, int fresh_rows)
