@@ -741,7 +741,7 @@ constexpr int MAX_PROBE_TILES = 1024;     // max_batch_ids <= 2^20 per call
 // values the fetch copies), so it does not wait for the fetch: the first `fill_blocks`
 // workgroups fetch, the others gather, side by side.
 // POOLED: out[b] = sum of the bag's rows in bag order; else out[perm[j]] = row of position j.
-constexpr int GATHER_ROWS = 4;
+constexpr int GATHER_ROWS = 8;
 constexpr int POOL_ROWS = 8;
 constexpr int FILL_ROWS = 2;              // missed keys a row group fetches at a time
 // A row chunk as the compiler's own vector type (arrays of these stay in registers where arrays
