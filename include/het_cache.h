@@ -141,7 +141,10 @@ int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, 
  * location HET_BACKING_HBM: device pointers.  HET_BACKING_PINNED_HOST: pointers to pinned,
  * device-mapped host memory (hipHostMalloc); kernels read and write it over the host link.
  * The caller owns the arrays; the library reads and writes them during lookup/update/flush and
- * they must outlive the cache.  vocab must be below 2^32 - 1.
+ * they must outlive the cache.  Between a lookup and the update that follows it the caller must
+ * not write them (with the table in HBM the rows a lookup misses are read from it for the output
+ * at once and for the cache by that update); writes by other workers go through
+ * het_backing_foreign_update.  vocab must be below 2^32 - 1.
  */
 int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, int64_t vocab,
                        int32_t location);
