@@ -339,7 +339,7 @@ def test_long_runs_that_cover_whole_workgroups(dim, n):
 FUZZ_ITERATIONS = 36
 
 
-@pytest.mark.parametrize("seed,host", [(1, False), (2, False), (3, True), (4, False)])
+@pytest.mark.parametrize("seed,host", [(1, False), (2, False), (3, True), (4, False), (5, False), (6, False), (7, False)])
 def test_random_call_sequences(seed, host):
     """Seeded random mixes of the calls: batches of random size and skew, announcements of coming
     (and of never used) batches, lookups that no update follows, updates that sort their own ids,
