@@ -60,6 +60,12 @@ struct CacheView {
     // cache slots
     float *rows, *acc;
     float *rows0, *acc0;  // several workers: every cached row (accumulator) as it was fetched; else null
+    // Early push (table in HBM, one worker): the update that fetches a missed key's row (see apply_kernel,
+    // fresh rows) writes its result to the global table as well as to the slot, and early_cc[slot] is the
+    // c_c at which the two are equal.  A victim whose c_c is still that, and whose global clock is still
+    // the c_s it was fetched at (nobody else pushed), is evicted without copying its row: Evict's push
+    // has already travelled.  0: not equal at any c_c a row with updates can have.  nullptr: not in use.
+    uint32_t *early_cc;
     int many;             // several workers write the global table: Evict pushes what was accumulated since the Fetch (Section 3.1)
     uint32_t freq_cap;    // light-weight LFU (Section 4.3): a row used this often is no longer kept track of; 0: exact policies
     uint32_t *slot_key;
@@ -949,6 +955,11 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             for (int r = 0; r < FILL_ROWS; ++r) nin += m0 + r * ngroups < tot_miss ? 1 : 0;
             if (cv.adagrad) fetch_rows<VEC, true>(cv, srow, sacc, slot, nin, gl);
             else fetch_rows<VEC, false>(cv, srow, sacc, slot, nin, gl);
+            if (fetch_mode == 2 && cv.early_cc && gl == 0) {        // the update that would have pushed early is not coming
+#pragma unroll
+                for (int r = 0; r < FILL_ROWS; ++r)
+                    if (r < nin) cv.early_cc[slot[r]] = 0u;
+            }
             if (cv.rowwise && gl == 0) {             // (one accumulator per row; such a table is in HBM)
 #pragma unroll
                 for (int r = 0; r < FILL_ROWS; ++r)
@@ -987,6 +998,7 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
             const uint32_t j = jk.x, key = jk.y;
             const uint32_t cg = cv.Cg[key];
             store_meta(cv.meta, slot, cg, cg, t_now, 1u);                    // c_s = c_c = c_g; first use
+            if (cv.early_cc) cv.early_cc[slot] = fetch_mode == 1 ? cg + 1u : 0u;    // (the update that fetches the row will make it c_g + 1)
             cv.slot_key[slot] = key;
             ws.head_slot[j] = (int32_t)slot;
             if (!ht_insert(cv.ht, key, slot)) atomicOr(&cv.ds->err, ERRBIT_INTERNAL);
@@ -1119,9 +1131,9 @@ __device__ __forceinline__ float rowwise_rcp(const CacheView &cv, uint32_t slot,
     return fast_rcp(fast_sqrt(a) + eps);
 }
 
-template <int VEC>
 // `from_key` other than KEY_NONE: the row has not been fetched yet (see apply_kernel, "fresh"): it is
-// read from the global table at that key and written to the slot.
+// read from the global table at that key and written to the slot (EARLY: and to the global table).
+template <int VEC, bool EARLY = false>
 __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, int c, const double *g64, float lr, float eps, bool act = true,
                                            uint32_t from_key = KEY_NONE)
 {
@@ -1146,11 +1158,13 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 #pragma unroll
         for (int k = 0; k < VEC; ++k) { a[k] += G[k] * G[k]; x[k] -= lr * G[k] * fast_rcp(fast_sqrt(a[k]) + eps); }
         *ap = av;
+        if (EARLY && fresh) reinterpret_cast<V *>(cv.A + (size_t)from_key * cv.geom.dim)[c] = av;
     } else {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) x[k] -= lr * G[k];
     }
     *xp = xv;
+    if (EARLY && fresh) reinterpret_cast<V *>(cv.W + (size_t)from_key * cv.geom.dim)[c] = xv;     // early push
 }
 
 // Update + Clock (Algorithm 3) in one kernel.  A workgroup takes a tile of AP_TILE consecutive
@@ -1176,6 +1190,7 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
 constexpr int AP_THREADS = 256;
 constexpr int AP_BATCH = 6;            // gradient rows in flight per row group (with eight the kernel needs 87 registers: five waves per SIMD instead of six)
+constexpr int AP_BATCH_EARLY = 4;      // ... where the kernel also pushes early (EARLY: two more row addresses to keep)
 constexpr int AP_SOLO = 32;
 // Positions per tile (template parameter AP_TILE): 64 where a workgroup has eight row groups or
 // more (rows up to 128 floats), 128 for wider rows, whose fewer row groups would otherwise stand
@@ -1209,17 +1224,17 @@ __device__ __forceinline__ uint32_t wave_count_leading(F cond)
 // Adds the gradient rows of tile positions [lo, hi) for row piece cidx to acc64, in order, in fp64.
 // If `with_row`, the cached row (and accumulator) of `slot` is requested together with the first
 // batch of gradients.
-template <int VEC>
+template <int VEC, int BATCH = AP_BATCH>
 __device__ __forceinline__ void add_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
                                               int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
                                               typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar, uint32_t from_key = KEY_NONE)
 {
     using V = typename VecT<VEC>::type;
     const int dim = cv.geom.dim;
-    for (uint32_t b0 = lo; b0 < hi; b0 += AP_BATCH) {
-        V v[AP_BATCH];
+    for (uint32_t b0 = lo; b0 < hi; b0 += BATCH) {
+        V v[BATCH];
 #pragma unroll
-        for (int r = 0; r < AP_BATCH; ++r) {
+        for (int r = 0; r < BATCH; ++r) {
             v[r] = V{};
             if (act && b0 + r < hi) v[r] = reinterpret_cast<const V *>(grads + (size_t)grow[b0 + r] * dim)[cidx];
         }
@@ -1229,7 +1244,7 @@ __device__ __forceinline__ void add_positions(const CacheView &cv, const float *
             if (cv.adagrad) ar = reinterpret_cast<const V *>(fresh ? cv.A + (size_t)from_key * dim : cv.acc + (size_t)slot * dim)[cidx];
         }
 #pragma unroll
-        for (int r = 0; r < AP_BATCH; ++r) {
+        for (int r = 0; r < BATCH; ++r) {
             const float *vf = reinterpret_cast<const float *>(&v[r]);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc64[e] += (double)vf[e];          // zero where there is no position
@@ -1237,14 +1252,14 @@ __device__ __forceinline__ void add_positions(const CacheView &cv, const float *
     }
 }
 
-template <int VEC>
+template <int VEC, int BATCH = AP_BATCH>
 __device__ __forceinline__ void sum_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
                                               int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
                                               typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar, uint32_t from_key = KEY_NONE)
 {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc64[e] = 0.0;
-    add_positions<VEC>(cv, grads, grow, lo, hi, cidx, act, acc64, with_row, slot, xr, ar, from_key);
+    add_positions<VEC, BATCH>(cv, grads, grow, lo, hi, cidx, act, acc64, with_row, slot, xr, ar, from_key);
 }
 
 struct SegWork {
@@ -1255,9 +1270,9 @@ struct SegWork {
 };
 
 // The optimizer step from a row already in registers.
-template <int VEC>
+template <int VEC, bool EARLY = false>
 __device__ __forceinline__ void apply_loaded(const CacheView &cv, uint32_t slot, int cidx, const double *g64, float lr, float eps,
-                                             typename VecT<VEC>::type xv, typename VecT<VEC>::type av, bool act)
+                                             typename VecT<VEC>::type xv, typename VecT<VEC>::type av, bool act, uint32_t from_key = KEY_NONE)
 {
     using V = typename VecT<VEC>::type;
     float *x = reinterpret_cast<float *>(&xv), *a = reinterpret_cast<float *>(&av);
@@ -1276,6 +1291,10 @@ __device__ __forceinline__ void apply_loaded(const CacheView &cv, uint32_t slot,
     }
     reinterpret_cast<V *>(cv.rows + (size_t)slot * cv.geom.dim)[cidx] = xv;
     if (cv.adagrad) reinterpret_cast<V *>(cv.acc + (size_t)slot * cv.geom.dim)[cidx] = av;
+    if (EARLY && from_key != KEY_NONE) {                // early push: a row fetched by this update goes to the global table as well
+        reinterpret_cast<V *>(cv.W + (size_t)from_key * cv.geom.dim)[cidx] = xv;
+        if (cv.adagrad) reinterpret_cast<V *>(cv.A + (size_t)from_key * cv.geom.dim)[cidx] = av;
+    }
 }
 
 // What the tiles of one run tell each other inside the kernel goes through loads, stores and
@@ -1299,7 +1318,7 @@ struct ApplyBorders {
     uint32_t *arrived;     // [tiles]: how many tiles of the run that starts in this tile have stored their sums (zero between kernels)
 };
 
-template <int VEC, int MAXC, bool VERIFY, int AP_TILE>
+template <int VEC, int MAXC, bool VERIFY, int AP_TILE, bool EARLY>
 // (rows of one piece per lane: held to 80 registers, six waves per SIMD)
 __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? 6 : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
                                                            const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
@@ -1307,6 +1326,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
                                                            SortStage ride, SortStage ride2, KernelTrace tr, int fresh_rows)
 {
     using V = typename VecT<VEC>::type;
+    constexpr int BATCH = EARLY ? AP_BATCH_EARLY : AP_BATCH;
     uint32_t bid = blockIdx.x, nblk = gridDim.x;
     tr.stamp(0);
     if (run_carried(ride, ride2, bid, nblk)) { tr.role(1); tr.end(); return; }
@@ -1428,7 +1448,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
     auto finish_piece = [&](const SegWork &w, int cidx, bool act, const double (&acc64)[VEC], V xr, V ar) {
         const bool closed = !w.is_front && !w.is_back;
         if (closed) {
-            if (w.slot != SLOT_NONE) apply_loaded<VEC>(cv, (uint32_t)w.slot, cidx, acc64, lr, eps, xr, ar, act);
+            if (w.slot != SLOT_NONE) apply_loaded<VEC, EARLY>(cv, (uint32_t)w.slot, cidx, acc64, lr, eps, xr, ar, act, w.from_key);
         } else if (act) {
             double *mine = bd.part + ((size_t)T * 2 + (w.is_front ? 0 : 1)) * pstride + (size_t)cidx * VEC;
 #pragma unroll
@@ -1454,7 +1474,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
                 const bool act = cidx < g.chunks;
                 double acc64[VEC];
                 V xr{}, ar{};
-                sum_positions<VEC>(cv, grads, l.grow, w.a, w.b, cidx, act, acc64, step, (uint32_t)w.slot, xr, ar, w.from_key);
+                sum_positions<VEC, BATCH>(cv, grads, l.grow, w.a, w.b, cidx, act, acc64, step, (uint32_t)w.slot, xr, ar, w.from_key);
                 finish_piece(w, cidx, act, acc64, xr, ar);
             }
             finish_segment(w);
@@ -1479,7 +1499,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
                 const bool act = cidx < g.chunks;
                 double acc64[VEC];
                 V xr{}, ar{};
-                sum_positions<VEC>(cv, grads, l.grow, lo, hi, cidx, act, acc64, step && group == 0, (uint32_t)slot, xr, ar, from_key);
+                sum_positions<VEC, BATCH>(cv, grads, l.grow, lo, hi, cidx, act, acc64, step && group == 0, (uint32_t)slot, xr, ar, from_key);
                 __syncthreads();                            // (the shares of the piece before have been read)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) l.share[threadIdx.x * VEC + e] = acc64[e];
@@ -1491,7 +1511,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
                     for (uint32_t gi = 0; gi < ngroups; ++gi)
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) tot[e] += l.share[(gi * g.lanes + gl) * VEC + e];
-                    if (step) apply_loaded<VEC>(cv, (uint32_t)slot, cidx, tot, lr, eps, xr, ar, act);
+                    if (step) apply_loaded<VEC, EARLY>(cv, (uint32_t)slot, cidx, tot, lr, eps, xr, ar, act, from_key);
                     else if (!closed && act) {
                         double *mine = bd.part + ((size_t)T * 2 + (is_front ? 0 : 1)) * pstride + (size_t)cidx * VEC;
 #pragma unroll
@@ -1550,7 +1570,7 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
         }
-        if (slot != SLOT_NONE) apply_step<VEC>(cv, (uint32_t)slot, cidx, sum, lr, eps, act, from_key);
+        if (slot != SLOT_NONE) apply_step<VEC, EARLY>(cv, (uint32_t)slot, cidx, sum, lr, eps, act, from_key);
     }
     tr.end();
 }
@@ -1646,6 +1666,7 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
         const uint32_t slot = slot0 + i, k = key[i], my_cc = meta[i].y;
         tp.ev_ids[ev_at++] = k;
         const uint32_t cg = dirty[i] ? cv.Cg[k] : 0u;                         // in flight together with the erase's loads
+        const uint32_t early = dirty[i] && cv.early_cc ? cv.early_cc[slot] : 0u;
         ht_erase(cv.ht, k);
         cv.slot_key[slot] = KEY_NONE;
         // host-backed table: rows below tau that hold updates are staged in slot order, then one
@@ -1653,8 +1674,12 @@ __global__ __launch_bounds__(TRIM_THREADS) void trim_evict_kernel(CacheView cv, 
         const uint32_t stage_at = lt[i] ? dlt_at : dlt_total + eq_at[i];
         if (dirty[i]) {
             if (my_cc > cg) cv.Cg[k] = my_cc;                                 // c_g = max(c_g, c_c)
-            const uint32_t at = atomicAdd(&el.n_push, 1u);
-            v_slot[at] = slot; v_key[at] = k; v_cg[at] = my_cc > cg ? my_cc : cg; v_at[at] = stage_at;
+            // (pushed early by the update that fetched it, not updated since, and nobody else has pushed: the row is there already)
+            const bool travelled = early == my_cc && cg == meta[i].x;
+            if (!travelled) {
+                const uint32_t at = atomicAdd(&el.n_push, 1u);
+                v_slot[at] = slot; v_key[at] = k; v_cg[at] = my_cc > cg ? my_cc : cg; v_at[at] = stage_at;
+            }
             dlt_at += lt[i];
         } else if (cv.Cg_host && eq[i]) {
             cv.hl.keys_of(buf)[stage_at] = KEY_NONE;

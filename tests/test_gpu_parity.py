@@ -346,7 +346,7 @@ def test_random_call_sequences(seed, host):
     flushes in between.  State and counters are compared after every iteration."""
     rng = np.random.default_rng(100 + seed)
     N = 6000
-    w = wl.WORKLOADS[1].scaled(dim=int(rng.choice([8, 16, 48])), capacity=int(rng.choice([150, 700, 3000])),
+    w = wl.WORKLOADS[1].scaled(dim=int(rng.choice([8, 16, 48, 128])), capacity=int(rng.choice([150, 700, 3000])),
                                s=int(rng.choice([0, 2, 50])), policy=int(rng.choice([wl.LRU, wl.LFU])),
                                optimizer=int(rng.choice([wl.SGD, wl.ADAGRAD])), eps=1e-8)
     table = wl.table_init(w)
@@ -566,13 +566,16 @@ def test_update_with_part_or_a_reordering_of_the_looked_up_ids(opt):
         p.close()
 
 
+@pytest.mark.parametrize("dim", [16, 128])
 @pytest.mark.parametrize("opt", [wl.SGD, wl.ADAGRAD])
-def test_checkvalid_condition_two_after_another_writers_pushes(opt):
+def test_checkvalid_condition_two_after_another_writers_pushes(opt, dim):
     """CheckValid's second condition (c_g <= c_c + s, Section 3.1) never fails with one worker.
     Another worker's pushes are emulated by changing global rows and advancing their c_g behind
     the cache's back: cached rows without updates of their own are refetched and show the new
-    values, rows with updates are pushed first."""
-    w = wl.WORKLOADS[1].scaled(capacity=600, s=2, policy=wl.LFU, optimizer=opt, eps=1e-8)
+    values, rows with updates are pushed first.  (With rows of 128 floats the update pushes the
+    rows it fetches early; a row the other worker has overwritten since must still be pushed at
+    its eviction.)"""
+    w = wl.WORKLOADS[1].scaled(dim=dim, capacity=600, s=2, policy=wl.LFU, optimizer=opt, eps=1e-8)
     T = 18
     table = wl.table_init(w)
     ids = wl.IdStream(w).batches(T)
@@ -928,12 +931,13 @@ def test_time_stamps_inside_the_kernels_change_nothing():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("dim", [16, 128])
 @pytest.mark.parametrize("opt", [wl.SGD, wl.ADAGRAD])
-def test_rows_a_lookup_leaves_to_the_update_are_fetched_by_whoever_needs_them_first(opt):
+def test_rows_a_lookup_leaves_to_the_update_are_fetched_by_whoever_needs_them_first(opt, dim):
     """With the table in HBM a lookup leaves the fetch of its missed keys' rows to the update that
     reuses its order.  Whatever comes instead (a flush, an export of the rows, another lookup, an
     update with other ids or with the same ids in another buffer) must find the rows in their slots."""
-    w = wl.WORKLOADS[1].scaled(capacity=500, s=2, optimizer=opt, eps=1e-8, policy=wl.LFU)
+    w = wl.WORKLOADS[1].scaled(dim=dim, capacity=500, s=2, optimizer=opt, eps=1e-8, policy=wl.LFU)     # (dim 128: with the early push)
     table = wl.table_init(w)
     ids = wl.IdStream(w).batches(12)
     grads = wl.grad_pool(w)
