@@ -434,7 +434,8 @@ template <bool LOOKUP>
 __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
                                                            const uint32_t *tile_free, uint32_t *tile_free_idle, uint32_t ev_idle,
                                                            uint32_t *zero_from, uint32_t zero_words, TrimPlan tp,
-                                                           const int64_t *__restrict__ check_ids, int pf_idle = -1)
+                                                           const int64_t *__restrict__ check_ids, int pf_idle = -1,
+                                                           uint32_t *__restrict__ inv = nullptr)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
     __shared__ uint32_t h0_delta[LOOKUP ? SEL_BINS : 1];       // rows entering (+) and leaving (-) each bin of the kept histogram
@@ -457,6 +458,7 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
     const uint32_t vocab = cv.vocab;
     const uint32_t j = tile * PT_TILE + threadIdx.x;
     DState *ds = cv.ds;
+    if (LOOKUP && inv && j < n) inv[ws.perm[j]] = j;         // pooled lookup: the sorted position of every original position
     const bool keep_h0 = LOOKUP && tp.h0_kept;
     if (keep_h0) {
         for (int b = threadIdx.x; b < SEL_BINS; b += PT_THREADS) h0_delta[b] = 0;
@@ -554,11 +556,12 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
 // the global table.  The sorted order is used as it is; a key stands for its own row.
 template <bool LOOKUP>
 __global__ __launch_bounds__(PT_THREADS) void direct_probe_kernel(CacheView cv, Workspace ws, uint32_t n, uint32_t t_now, uint32_t ptiles,
-                                                                  const int64_t *__restrict__ check_ids)
+                                                                  const int64_t *__restrict__ check_ids, uint32_t *__restrict__ inv = nullptr)
 {
     __shared__ uint32_t lds[PT_WAVES + 1];
     if (blockIdx.x >= ptiles) { check_order_body(cv, ws, check_ids, n, blockIdx.x - ptiles); return; }     // (an order sorted ahead, see probe_kernel)
     const uint32_t j = blockIdx.x * PT_TILE + threadIdx.x;
+    if (LOOKUP && inv && j < n) inv[ws.perm[j]] = j;         // pooled lookup (see probe_kernel)
     const uint32_t vocab = cv.vocab;
     DState *ds = cv.ds;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -885,6 +888,75 @@ __global__ __launch_bounds__(256) void link_kernel(CacheView cv, int push_buf, i
     }
 }
 
+// Get for bags (sum pooling): one row group adds up one bag at a time, in bag order, in fp64, rounded
+// once (a bag may hold hundreds of rows).  Where the rows are is found for as many ids of the bag
+// as the group has lanes at once, one id per lane (its sorted position, then source and key there:
+// two steps for the whole stretch, not two per POOL_ROWS rows), and handed from lane to lane
+// for the row loads; the next stretch is asked for behind the first rows of the present one.
+// A row's address carries "does not count" (an id outside the vocabulary) in its lowest bit.
+template <int VEC>
+__device__ __forceinline__ void pooled_gather_body(const CacheView &cv, const Workspace &ws, uint32_t n, float *__restrict__ out,
+                                                   const int64_t *__restrict__ offsets, uint32_t n_bags, const uint32_t *__restrict__ inv,
+                                                   uint32_t gid, uint32_t ngroups)
+{
+    using V = typename VecT<VEC>::type;
+    const RowGeom g = cv.geom;
+    const int gl = threadIdx.x % g.lanes;
+    const int first_lane = (int)(threadIdx.x % WAVE) - gl;
+    auto where = [&](uint32_t jj, bool in) -> unsigned long long {
+        const int32_t sr = ws.src[jj];
+        const uint32_t ky = ws.skey[jj];
+        const float *row = sr == SRC_BACKING ? cv.W + (size_t)ky * g.dim : cv.rows + (size_t)(uint32_t)(sr < 0 ? 0 : sr) * g.dim;
+        return (unsigned long long)(uintptr_t)row | (in && sr != SRC_ZERO ? 0ull : 1ull);
+    };
+    for (uint32_t b = gid; b < n_bags; b += ngroups) {
+        int64_t lo = offsets[b], hi = offsets[b + 1];
+        lo = lo < 0 ? 0 : lo; hi = hi > (int64_t)n ? (int64_t)n : hi;
+        for (int c0 = 0; c0 < g.chunks; c0 += g.lanes) {
+            const bool mine = c0 + gl < g.chunks;
+            const int c = mine ? c0 + gl : 0;    // (a lane beyond the row reads its first piece and stores nothing: every lane hands addresses on)
+            double sum[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
+            if (lo < hi) {
+                int64_t i0 = lo;
+                unsigned long long cur = where(inv[i0 + gl < hi ? i0 + gl : hi - 1], i0 + gl < hi);
+                while (i0 < hi) {
+                    const int cnt = hi - i0 < (int64_t)g.lanes ? (int)(hi - i0) : g.lanes;
+                    const int64_t i1 = i0 + g.lanes;
+                    const bool more = i1 < hi;
+                    const uint32_t jj1 = more ? inv[i1 + gl < hi ? i1 + gl : hi - 1] : 0u;
+                    unsigned long long nxt = 0ull;
+                    for (int r0 = 0; r0 < cnt; r0 += POOL_ROWS) {
+                        V v[POOL_ROWS];
+                        bool counts[POOL_ROWS];
+#pragma unroll
+                        for (int r = 0; r < POOL_ROWS; ++r) {
+                            const int rr = r0 + r < cnt ? r0 + r : cnt - 1;
+                            const unsigned long long p = __shfl(cur, first_lane + rr, WAVE);
+                            counts[r] = r0 + r < cnt && !(p & 1ull);
+                            v[r] = reinterpret_cast<const V *>((uintptr_t)(p & ~1ull))[c];
+                        }
+                        if (r0 == 0 && more) nxt = where(jj1, i1 + gl < hi);
+#pragma unroll
+                        for (int r = 0; r < POOL_ROWS; ++r) {
+                            const float *vf = reinterpret_cast<const float *>(&v[r]);
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) sum[e] += counts[r] ? (double)vf[e] : 0.0;
+                        }
+                    }
+                    cur = nxt; i0 = i1;
+                }
+            }
+            V res;
+            float *rf = reinterpret_cast<float *>(&res);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) rf[e] = (float)sum[e];
+            if (mine) reinterpret_cast<V *>(out + (size_t)b * g.dim)[c] = res;
+        }
+    }
+}
+
 struct FillLds {
     uint32_t pre_miss[MAX_PROBE_TILES], pre_stale[MAX_PROBE_TILES];
     uint32_t scan[4 + 1];
@@ -913,6 +985,19 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
     const RowGeom g = cv.geom;
     const int gl = threadIdx.x % g.lanes;
     const uint32_t groups_per_block = 256u / g.lanes;
+    if (POOLED) {
+        // Get for bags.  These workgroups live longest (a row group adds up a whole bag), so they take
+        // the first places; all the other roles' workgroups follow.
+        const uint32_t others = fill_blocks + (fill_blocks && fetch_mode != 2 ? ptiles : 0u) + hist_blocks;
+        const uint32_t bag_blocks = nblk - others;
+        if (bid < bag_blocks) {
+            if (fill_blocks == 0 && bid == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // (no fetch workgroup does)
+            pooled_gather_body<VEC>(cv, ws, n, out, offsets, n_bags, inv, bid * groups_per_block + threadIdx.x / g.lanes, bag_blocks * groups_per_block);
+            tr.role(5); tr.end();
+            return;
+        }
+        bid -= bag_blocks; nblk -= bag_blocks;
+    }
     // fetch_mode 0: everything.  1: the missed keys' rows are left to the update that follows (it reads
     // them from the global table and writes them to their slots with its step applied: they are
     // neither written nor read once more); all else as usual.  2: only those rows (a call came
@@ -1019,11 +1104,12 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
         tr.role(4); tr.end();
         return;
     }
+    if (POOLED) return;                  // (never reached: the bags' workgroups came first)
     const uint32_t first_gather = fill_blocks + hist_blocks;
     if (fill_blocks == 0 && bid == 0 && threadIdx.x == 0) cv.ds->n_unique = (uint32_t)cv.last->unique;   // (no fetch workgroup did)
     const uint32_t gid = (bid - first_gather) * groups_per_block + threadIdx.x / g.lanes;
     const uint32_t ngroups = (nblk - first_gather) * groups_per_block;
-    if (!POOLED) {
+    {
         // Get, GATHER_ROWS positions per row group at a time: where each row comes from is asked
         // for all of them first, then the rows themselves, so that a group has several rows in
         // flight (one row per group at a time leaves the memory system idle most of the time)
@@ -1053,56 +1139,14 @@ __global__ __launch_bounds__(256) void fill_gather_kernel(CacheView cv, Workspac
                 }
             }
         }
-    } else {
-        for (uint32_t b = gid; b < n_bags; b += ngroups) {
-            int64_t lo = offsets[b], hi = offsets[b + 1];
-            lo = lo < 0 ? 0 : lo; hi = hi > (int64_t)n ? (int64_t)n : hi;
-            // POOL_ROWS ids of the bag at a time: their sorted positions, then where their rows come
-            // from, then the rows, each step for all of them at once; added in bag order
-            for (int c = gl; c < g.chunks; c += g.lanes) {
-                double sum[VEC];                 // summed wide and rounded once: a bag may hold hundreds of rows
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
-                for (int64_t i0 = lo; i0 < hi; i0 += POOL_ROWS) {
-                    uint32_t jj[POOL_ROWS];
-#pragma unroll
-                    for (int r = 0; r < POOL_ROWS; ++r) jj[r] = inv[i0 + r < hi ? i0 + r : hi - 1];
-                    int32_t sr[POOL_ROWS];
-                    uint32_t ky[POOL_ROWS];
-#pragma unroll
-                    for (int r = 0; r < POOL_ROWS; ++r) { sr[r] = ws.src[jj[r]]; ky[r] = ws.skey[jj[r]]; }
-                    V v[POOL_ROWS];
-#pragma unroll
-                    for (int r = 0; r < POOL_ROWS; ++r) {
-                        const float *row = sr[r] == SRC_BACKING ? cv.W + (size_t)ky[r] * g.dim : cv.rows + (size_t)(uint32_t)(sr[r] < 0 ? 0 : sr[r]) * g.dim;
-                        v[r] = reinterpret_cast<const V *>(row)[c];
-                    }
-#pragma unroll
-                    for (int r = 0; r < POOL_ROWS; ++r) {
-                        const bool counts = i0 + r < hi && sr[r] != SRC_ZERO;
-                        const float *vf = reinterpret_cast<const float *>(&v[r]);
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) sum[e] += counts ? (double)vf[e] : 0.0;
-                    }
-                }
-                V res;
-                float *rf = reinterpret_cast<float *>(&res);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) rf[e] = (float)sum[e];
-                reinterpret_cast<V *>(out + (size_t)b * g.dim)[c] = res;
-            }
-        }
     }
     tr.role(5); tr.end();
 }
 
-// Pooled forms: inv[perm[j]] = j (sorted position of every original position), and the bag of
-// every original position.
-__global__ __launch_bounds__(256) void pooled_index_kernel(Workspace ws, uint32_t n, uint32_t *__restrict__ inv,
-                                                           const int64_t *__restrict__ offsets, uint32_t n_bags)
+// Pooled update: the bag of every original position (its gradient row).
+__global__ __launch_bounds__(256) void pooled_index_kernel(Workspace ws, uint32_t n, const int64_t *__restrict__ offsets, uint32_t n_bags)
 {
     for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) {
-        inv[ws.perm[i]] = i;
         uint32_t lo = 0, hi = n_bags;            // largest b with offsets[b] <= i
         while (hi - lo > 1) { const uint32_t mid = (lo + hi) / 2; if (offsets[mid] <= (int64_t)i) lo = mid; else hi = mid; }
         ws.bag_of[i] = lo;

@@ -442,9 +442,8 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     const uint32_t t_now = (uint32_t)c->t_host;
     if (c->cv.direct) {
         // no cache: mark the runs, then gather straight from the global table
-        LAUNCH(c, K_PROBE, direct_probe_kernel<true><<<cdiv(n, PT_TILE) * (match >= 0 ? 2u : 1u), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now, cdiv(n, PT_TILE), match >= 0 ? ids : nullptr));
-        if (offsets)
-            LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
+        LAUNCH(c, K_PROBE, direct_probe_kernel<true><<<cdiv(n, PT_TILE) * (match >= 0 ? 2u : 1u), PT_THREADS, 0, c->stream>>>(c->cv, c->ws, n, t_now, cdiv(n, PT_TILE), match >= 0 ? ids : nullptr,
+                                                                                                                              offsets ? c->inv : nullptr));
         const Rides ride = next_rides(c);
         const uint32_t grid = ride.blocks() + row_grid(c->cv.geom, offsets ? n_bags : cdiv(n, GATHER_ROWS));
         const uint32_t lds = lds_bytes(std::max(sizeof(FillLds), sizeof(TrimLds)), ride);
@@ -475,15 +474,13 @@ int run_lookup(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     LAUNCH(c, K_PROBE, probe_kernel<true><<<ptiles + (match >= 0 ? ptiles : 0u) + stiles, PT_THREADS, 0, c->stream>>>(
                            c->cv, c->ws, n, t_now, ptiles, c->tile_free[c->tf_last], c->tile_free[1 - c->tf_last], (uint32_t)(1 - c->tf_last),
                            c->tp.hist + kept_words, c->tp.zero_words - kept_words, tp, match >= 0 ? ids : nullptr,
-                           c->side ? c->pf_slot_next : -1));
+                           c->side ? c->pf_slot_next : -1, offsets ? c->inv : nullptr));
     const int hist_pass = tp.h0_kept ? 1 : 0;                  // this pass of the select rides with the fetches
     // (the update has one kernel to carry a stage: with the first pass kept, a select of two passes
     // is over when that kernel ends: second pass here, tie count there)
     const uint32_t hist_blocks = hist_pass < tp.passes ? stage_blocks(c, tp, hist_pass) : 0u;
     c->sel_next = hist_blocks ? hist_pass + 1 : hist_pass;     // (a select of one pass whose histogram is kept: only the tie count is left)
         const uint32_t fill_blocks = std::min(cdiv(row_grid(c->cv.geom, n), (uint32_t)FILL_ROWS), FILL_MAX_BLOCKS);     // they come first: theirs is the longer chain
-    if (offsets)
-        LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
     const uint32_t lds_own = (uint32_t)std::max(sizeof(FillLds), sizeof(TrimLds));
 #define FILL_GATHER_T(POOLED, RIDE, TRACE, GRID, FILLB, HISTB, PUSHB)                                                     \
     LAUNCH(c, K_FILL_GATHER, fill_gather_kernel<VEC, POOLED, RIDE, TRACE><<<GRID, 256, lds_bytes(lds_own, ride), c->stream>>>( \
@@ -662,7 +659,7 @@ int run_update(het_cache *c, const int64_t *ids, uint32_t n, const int64_t *offs
     }
     const uint32_t *grad_row = nullptr;
     if (offsets) {
-        LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, c->inv, offsets, n_bags));
+        LAUNCH(c, K_POOLED_INDEX, pooled_index_kernel<<<std::min(cdiv(n, 256), 4096u), 256, 0, c->stream>>>(c->ws, n, offsets, n_bags));
         grad_row = c->ws.bag_of;
     }
     // Only a lookup leaves rows above capacity; an update that follows no lookup has nothing to trim.

@@ -484,10 +484,12 @@ def test_largest_batch_the_library_accepts():
         hc.HetCache(w.capacity, w.dim, w.s, w.policy, n + 1, w.optimizer, w.eps)
 
 
-def test_pooled_with_bags_of_uneven_size_and_empty_bags():
+@pytest.mark.parametrize("dim", [24, 7, 320])
+def test_pooled_with_bags_of_uneven_size_and_empty_bags(dim):
     """Bags of 0 to several hundred ids (the regular layouts have equal bags): pooled gather in bag
-    order, bag gradients spread to the bag's ids."""
-    w = wl.WORKLOADS[5].scaled(vocab=20_000, dim=24, batch=300, width=10, capacity=1_500, s=3)
+    order, bag gradients spread to the bag's ids.  Rows narrower than their row group (24 floats: six
+    pieces for eight lanes), rows moved float by float (7), rows of more pieces than a wave has lanes (320)."""
+    w = wl.WORKLOADS[5].scaled(vocab=20_000, dim=dim, batch=300, width=10, capacity=1_500, s=3)
     n = w.n
     table = wl.table_init(w)
     rng = np.random.default_rng(31)
