@@ -1215,7 +1215,7 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // sorted positions, brings their keys, gradient rows' numbers and slots into LDS and lists the
 // tile's segments (stretches of equal keys; a run of equal keys is one segment unless it crosses a
 // tile border).  Work then goes by segment, not by position:
-//   - a segment of up to AP_SOLO positions is summed by one row group, AP_BATCH gradient rows in
+//   - a segment of up to AP_SOLO positions is summed by one row group, a few gradient rows (ap_batch) in
 //     flight at a time, in order of position, in fp64 (the kernel is bound by reading the
 //     gradients; summing wide makes a long run of a popular key lose no digits), rounded once;
 //   - a longer one by all row groups of the workgroup together: contiguous shares, added in group
@@ -1233,8 +1233,13 @@ __device__ __forceinline__ void apply_step(const CacheView &cv, uint32_t slot, i
 // preceding lookup's order); extra workgroups compare them and flag any difference.
 // MAXC: row pieces per lane (dim / VEC / lanes, rounded up).
 constexpr int AP_THREADS = 256;
-constexpr int AP_BATCH = 6;            // gradient rows in flight per row group (with eight the kernel needs 87 registers: five waves per SIMD instead of six)
-constexpr int AP_BATCH_EARLY = 4;      // ... where the kernel also pushes early (EARLY: two more row addresses to keep)
+// Gradient rows in flight per row group, and waves per SIMD the kernel is held to (rows of one piece
+// per lane).  Tiles of 64 positions: seven waves (72 registers), so that all tiles of a batch of
+// config 2's or 4's size are resident from the start, with four rows in flight (three where the
+// kernel also pushes early: two more row addresses to keep).  Tiles of 128 positions (rows of more
+// than 128 floats): six waves and six rows (four with the early push); seven waves were slower there.
+__host__ __device__ constexpr int ap_batch(int ap_tile, bool early) { return ap_tile == 64 ? (early ? 3 : 4) : (early ? 4 : 6); }
+__host__ __device__ constexpr int ap_waves(int ap_tile) { return ap_tile == 64 ? 7 : 6; }
 constexpr int AP_SOLO = 32;
 // Positions per tile (template parameter AP_TILE): 64 where a workgroup has eight row groups or
 // more (rows up to 128 floats), 128 for wider rows, whose fewer row groups would otherwise stand
@@ -1268,7 +1273,7 @@ __device__ __forceinline__ uint32_t wave_count_leading(F cond)
 // Adds the gradient rows of tile positions [lo, hi) for row piece cidx to acc64, in order, in fp64.
 // If `with_row`, the cached row (and accumulator) of `slot` is requested together with the first
 // batch of gradients.
-template <int VEC, int BATCH = AP_BATCH>
+template <int VEC, int BATCH>
 __device__ __forceinline__ void add_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
                                               int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
                                               typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar, uint32_t from_key = KEY_NONE)
@@ -1296,7 +1301,7 @@ __device__ __forceinline__ void add_positions(const CacheView &cv, const float *
     }
 }
 
-template <int VEC, int BATCH = AP_BATCH>
+template <int VEC, int BATCH>
 __device__ __forceinline__ void sum_positions(const CacheView &cv, const float *__restrict__ grads, const uint32_t *grow, uint32_t lo, uint32_t hi,
                                               int cidx, bool act, double (&acc64)[VEC], bool with_row, uint32_t slot,
                                               typename VecT<VEC>::type &xr, typename VecT<VEC>::type &ar, uint32_t from_key = KEY_NONE)
@@ -1363,14 +1368,13 @@ struct ApplyBorders {
 };
 
 template <int VEC, int MAXC, bool VERIFY, int AP_TILE, bool EARLY>
-// (rows of one piece per lane: held to 80 registers, six waves per SIMD)
-__global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? 6 : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
+__global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? ap_waves(AP_TILE) : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
                                                            const float *__restrict__ grads, const uint32_t *__restrict__ grad_row,
                                                            float lr, float eps, uint32_t n_ids, uint32_t work_blocks, TrimPlan tp, int stage,
                                                            SortStage ride, SortStage ride2, KernelTrace tr, int fresh_rows)
 {
     using V = typename VecT<VEC>::type;
-    constexpr int BATCH = EARLY ? AP_BATCH_EARLY : AP_BATCH;
+    constexpr int BATCH = ap_batch(AP_TILE, EARLY);
     // The tiles' workgroups live longest, so they take the first places; the carried stages, the select
     // stage and the id check follow in the places they leave (the other way round the step was 1 to 2 %
     // longer on every config).
