@@ -1365,7 +1365,13 @@ struct ApplyBorders {
     int32_t *slot;         // [tiles]: slot of the run that leaves through the tile's back border (it starts in this tile)
     uint32_t *from_key;    // [tiles]: that run's key if its row has not been fetched yet, else KEY_NONE
     uint32_t *arrived;     // [tiles]: how many tiles of the run that starts in this tile have stored their sums (zero between kernels)
+    // A run over more than AP_GROUP tiles is summed in two levels (see apply_kernel).  A group is named like
+    // a sum in `part`, by its first tile and the border through which the run leaves or enters that tile (a
+    // run's first group starts at the run's first tile, back border; a tile may end one long run and start
+    // another).  The groups' sums lie behind the tiles' sums in `part` ([tiles][2][dim] more), their counters
+    // behind the runs' counters in `arrived` ([tiles][2] more): no further kernel arguments.
 };
+constexpr uint32_t AP_GROUP = 16;
 
 template <int VEC, int MAXC, bool VERIFY, int AP_TILE, bool EARLY>
 __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC == 1 ? ap_waves(AP_TILE) : 1))) void apply_kernel(CacheView cv, Workspace ws, ApplyBorders bd, const int64_t *__restrict__ ids,
@@ -1589,14 +1595,63 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
     tr.stamp(4);
     if (!do_front && !do_back) { tr.end(); return; }
     const uint32_t m = T1 - T0 + 1;
-    uint32_t last = 0;
-    if (lane_id() == 0) {
-        // (this tile's sums were acknowledged before the barrier above)
-        last = __hip_atomic_fetch_add(&bd.arrived[T0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == m - 1 ? 1u : 0u;
-        if (last) bd.arrived[T0] = 0;                       // clean for the next kernel
+    // Sum of `count` stored sums, four in flight at a time, in order; where(i) is the i-th one's address for row piece 0.
+    auto add_up = [&](uint32_t count, auto where, int cidx, bool act, double (&sum)[VEC]) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
+        for (uint32_t i0 = 0; i0 < count; i0 += 4) {
+            double part[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t i = i0 + u;
+                const double *pp = where(i < count ? i : 0u) + (size_t)(act ? cidx : 0) * VEC;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) part[u][e] = i < count && act ? ld_device(pp + e) : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
+        }
+    };
+    // the i-th tile of the run: its first tile holds the run's sum at its back border, the others at their front border
+    auto tile_sum = [&](uint32_t i) { return bd.part + ((size_t)(T0 + i) * 2 + (i == 0 ? 1 : 0)) * pstride; };
+    auto arrive = [&](uint32_t *counter, uint32_t expected) {
+        uint32_t last = 0;
+        if (lane_id() == 0) {
+            // (this tile's sums were acknowledged before)
+            last = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1 ? 1u : 0u;
+            if (last) *counter = 0;                         // clean for the next kernel
+        }
+        return __shfl(last, 0, WAVE) != 0;
+    };
+    // A run over more than AP_GROUP tiles (a very popular key) would keep its last tile adding for as
+    // long as the rest of the kernel takes: two levels instead.  The tile that arrives last in its
+    // group of AP_GROUP consecutive tiles adds the group's sums in tile order and stores the result;
+    // the group that arrives last adds the groups' results in group order.  Still a fixed order.
+    const bool grouped = m > AP_GROUP;
+    const uint32_t ngroups_run = (m + AP_GROUP - 1) / AP_GROUP;
+    if (grouped) {
+        const uint32_t first = (T - T0) / AP_GROUP * AP_GROUP;          // the group's first tile, counted from T0
+        const uint32_t gs = min(AP_GROUP, m - first);
+        const size_t gname = (size_t)(T0 + first) * 2 + (first == 0 ? 1 : 0);
+        if (!arrive(&bd.arrived[work_blocks + gname], gs)) { tr.end(); return; }
+        if (lane_id() < (uint32_t)g.lanes) {
+#pragma unroll
+            for (int q = 0; q < MAXC; ++q) {
+                const int cidx = gl + q * g.lanes;
+                const bool act = cidx < g.chunks;
+                if (!act) continue;
+                double sum[VEC];
+                add_up(gs, [&](uint32_t i) { return tile_sum(first + i); }, cidx, act, sum);
+                double *mine = bd.part + ((size_t)work_blocks * 2 + gname) * pstride + (size_t)cidx * VEC;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) st_device(mine + e, sum[e]);
+            }
+        }
+        stores_acknowledged();
     }
-    last = __shfl(last, 0, WAVE);
-    if (!last || lane_id() >= (uint32_t)g.lanes) { tr.end(); return; }
+    if (!arrive(&bd.arrived[T0], grouped ? ngroups_run : m) || lane_id() >= (uint32_t)g.lanes) { tr.end(); return; }
     const int32_t slot = ld_device(&bd.slot[T0]);           // (SLOT_NONE: a key that is not cached, flagged where the order was probed)
     const uint32_t from_key = ld_device(&bd.from_key[T0]);
 #pragma unroll
@@ -1605,22 +1660,8 @@ __global__ __launch_bounds__(AP_THREADS) __attribute__((amdgpu_waves_per_eu(MAXC
         const bool act = cidx < g.chunks;
         if (!act && !cv.rowwise) continue;                  // (row-wise Adagrad: every lane of the group takes part in the row's sum)
         double sum[VEC];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) sum[e] = 0.0;
-        for (uint32_t i0 = 0; i0 < m; i0 += 4) {
-            double part[4][VEC];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t i = i0 + u;
-                const double *pp = bd.part + ((size_t)(T0 + (i < m ? i : 0u)) * 2 + (i == 0 || i >= m ? 1 : 0)) * pstride + (size_t)(act ? cidx : 0) * VEC;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) part[u][e] = i < m && act ? ld_device(pp + e) : 0.0;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) sum[e] += part[u][e];
-        }
+        if (grouped) add_up(ngroups_run, [&](uint32_t i) { return (const double *)bd.part + ((size_t)work_blocks * 2 + (size_t)(T0 + i * AP_GROUP) * 2 + (i == 0 ? 1 : 0)) * pstride; }, cidx, act, sum);
+        else add_up(m, [&](uint32_t i) { return (const double *)tile_sum(i); }, cidx, act, sum);
         if (slot != SLOT_NONE) apply_step<VEC, EARLY>(cv, (uint32_t)slot, cidx, sum, lr, eps, act, from_key);
     }
     tr.end();

@@ -79,6 +79,8 @@ struct het_cache {
     uint32_t n_buckets = 0;
     int max_chunks_per_lane = 1;     // row chunks one lane handles in the apply kernel
     std::vector<void *> owned;       // every device allocation, for destroy
+    char *arena = nullptr;           // one allocation that holds all the small arrays side by side (see dev_alloc)
+    size_t arena_used = 0;
     // host-backed table: write-back of the last trim's victims still to be enqueued
     bool push_pending = false;
     int push_buf = 0;
@@ -123,17 +125,43 @@ void report(const char *what, hipError_t e)
         if (e_ != hipSuccess) { report(#expr, e_); return HET_EHIP; } \
     } while (0)
 
-// Frees the device allocations made after the first `keep` (a call that fails midway leaves none behind).
-void free_owned_from(het_cache *c, size_t keep)
+// Frees the device allocations made after the first `keep`, and what was taken from the arena after
+// `arena_mark` (a call that fails midway leaves nothing behind).
+void free_owned_from(het_cache *c, size_t keep, size_t arena_mark)
 {
-    while (c->owned.size() > keep) { (void)hipFree(c->owned.back()); c->owned.pop_back(); }
+    while (c->owned.size() > keep) {
+        if (c->owned.back() == c->arena) { c->arena = nullptr; c->arena_used = 0; }
+        (void)hipFree(c->owned.back());
+        c->owned.pop_back();
+    }
+    if (c->arena) c->arena_used = arena_mark;
 }
 
+constexpr size_t ARENA_BYTES = (size_t)128 << 20, ARENA_ITEM_MAX = 8u << 20;
+
+// Arrays of up to 8 MB lie side by side in one allocation of 128 MB; larger ones, and whatever does
+// not fit, get their own.  With an allocation per array the probe kernel's time on config 2 depended
+// on how many arrays had been allocated before (13.0 or 14.5 us: two more small arrays were enough);
+// side by side it does not.
 template <typename T>
 int dev_alloc(het_cache *c, T **p, size_t count)
 {
+    const size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+    if (ARENA_BYTES && bytes <= ARENA_ITEM_MAX) {
+        if (!c->arena) {
+            void *a = nullptr;
+            if (hipMalloc(&a, ARENA_BYTES) == hipSuccess) { c->arena = static_cast<char *>(a); c->arena_used = 0; c->owned.push_back(a); }
+            else (void)hipGetLastError();
+        }
+        const size_t at = (c->arena_used + 255) / 256 * 256;
+        if (c->arena && at + bytes <= ARENA_BYTES) {
+            *p = reinterpret_cast<T *>(c->arena + at);
+            c->arena_used = at + bytes;
+            return HET_OK;
+        }
+    }
     void *q = nullptr;
-    const hipError_t e = hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T));
+    const hipError_t e = hipMalloc(&q, bytes);
     if (e != hipSuccess) { report("hipMalloc", e); return HET_ENOMEM; }
     c->owned.push_back(q);
     *p = static_cast<T *>(q);
@@ -787,8 +815,8 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
         (rc = dev_alloc(c, &ws.tile_miss, ptiles)) || (rc = dev_alloc(c, &ws.tile_stale, ptiles)) ||
         (rc = dev_alloc(c, &ws.miss_stage, ptiles * PT_TILE)) || (rc = dev_alloc(c, &ws.stale_stage, ptiles * PT_TILE)) ||
         (rc = dev_alloc(c, &c->inv, N)) || (rc = dev_alloc(c, &ws.bag_of, N)) ||
-        (rc = dev_alloc(c, &c->bd.part, ap_tiles * 2 * (size_t)c->dim)) || (rc = dev_alloc(c, &c->bd.slot, ap_tiles)) ||
-        (rc = dev_alloc(c, &c->bd.arrived, ap_tiles)) || (rc = dev_alloc(c, &c->bd.from_key, ap_tiles)))
+        (rc = dev_alloc(c, &c->bd.part, ap_tiles * 4 * (size_t)c->dim)) || (rc = dev_alloc(c, &c->bd.slot, ap_tiles)) ||      // (tiles' sums, then groups' sums: see ApplyBorders)
+        (rc = dev_alloc(c, &c->bd.arrived, ap_tiles * 3)) || (rc = dev_alloc(c, &c->bd.from_key, ap_tiles)))
         return rc;
     const size_t slot_tiles = cdiv(P, TRIM_TILE), ev_blocks = cdiv(P, EV_SLOTS), ev_supers = cdiv(ev_blocks, EV_SUPER);
     c->tp.zero_words = (uint32_t)(SEL_MAX_PASSES * SEL_BINS + 4 * ev_supers);
@@ -803,7 +831,7 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
     }
     HIP_TRY(hipMemsetAsync(c->tile_free[1], 0, slot_tiles * sizeof(uint32_t), c->stream));
 
-    HIP_TRY(hipMemsetAsync(c->bd.arrived, 0, ap_tiles * sizeof(uint32_t), c->stream));
+    HIP_TRY(hipMemsetAsync(c->bd.arrived, 0, ap_tiles * 3 * sizeof(uint32_t), c->stream));
     HIP_TRY(hipMemsetAsync(cv.ds, 0, sizeof(DState), c->stream));
     init_cache_kernel<<<1024, 256, 0, c->stream>>>(cv, c->n_buckets * BUCKET_ENTRIES, c->n_buckets);
     if ((rc = launch_ok())) return rc;
@@ -814,9 +842,9 @@ static int configure_impl(het_cache *c, int64_t max_batch_ids, int32_t optimizer
 
 int het_cache_configure(het_cache *c, int64_t max_batch_ids, int32_t optimizer, float eps, void *hip_stream)
 {
-    const size_t keep = c ? c->owned.size() : 0;
+    const size_t keep = c ? c->owned.size() : 0, mark = c ? c->arena_used : 0;
     const int rc = configure_impl(c, max_batch_ids, optimizer, eps, hip_stream);
-    if (rc != HET_OK && c && !c->configured) free_owned_from(c, keep);     // a retry starts from nothing
+    if (rc != HET_OK && c && !c->configured) free_owned_from(c, keep, mark);     // a retry starts from nothing
     return rc;
 }
 
@@ -873,11 +901,11 @@ static int attach_impl(het_cache *c, float *table, float *state, uint32_t *cg, i
 
 int het_attach_backing(het_cache *c, float *table, float *state, uint32_t *cg, int64_t vocab, int32_t location)
 {
-    const size_t keep = c ? c->owned.size() : 0;
+    const size_t keep = c ? c->owned.size() : 0, mark = c ? c->arena_used : 0;
     const bool was = c && c->attached;
     const int rc = attach_impl(c, table, state, cg, vocab, location);
     if (rc != HET_OK && c && !was) {
-        free_owned_from(c, keep);
+        free_owned_from(c, keep, mark);
         if (c->ev_main) { (void)hipEventDestroy(c->ev_main); c->ev_main = nullptr; }
         if (c->ev_link) { (void)hipEventDestroy(c->ev_link); c->ev_link = nullptr; }
         if (c->side) { (void)hipStreamDestroy(c->side); c->side = nullptr; }

@@ -311,7 +311,34 @@ def test_ragged_and_degenerate_batches():
         p.close()
 
 
-@pytest.mark.parametrize("dim,n", [(10, 3000), (64, 3000), (260, 2000), (64, 300_000)])
+@pytest.mark.parametrize("dim,tile", [(64, 64), (128, 64), (256, 128), (520, 128)])
+def test_two_very_long_runs_next_to_each_other(dim, tile):
+    """Two neighbouring keys that each fill dozens of the update's tiles (sums of such runs are added
+    up in groups of tiles first).  The second run starts in the middle of the tile in which the first
+    ends, and that tile is the first of a group of the first run: both runs' group sums meet there."""
+    w = wl.WORKLOADS[1].scaled(dim=dim, capacity=300, s=2, optimizer=wl.ADAGRAD, eps=1e-8, policy=wl.LFU)
+    table = wl.table_init(w)
+    rng = np.random.default_rng(17)
+    a, b = 500, 501
+    before = rng.integers(0, a, size=tile // 2)                 # keys below both: the first run starts in the middle of tile 0
+    n_a, n_b, n_rest = tile * 32, tile * 20 + 7, 300
+    n = len(before) + n_a + n_b + n_rest
+    p = Pair(w, table, max_ids=n)
+    try:
+        for it in range(3):
+            ids = np.concatenate([before, np.full(n_a, a), np.full(n_b, b), rng.integers(b + 1, w.vocab, size=n_rest)]).astype(np.int64)
+            ids = ids[rng.permutation(n)]
+            g = rng.standard_normal((n, w.dim)).astype(np.float32)
+            p.lookup(ids)
+            p.update(ids, g)
+            p.compare_state(values=True)
+            p.compare_counters()
+        p.flush_and_compare()
+    finally:
+        p.close()
+
+
+@pytest.mark.parametrize("dim,n", [(10, 3000), (64, 3000), (260, 2000), (260, 40_000), (64, 300_000)])
 def test_long_runs_that_cover_whole_workgroups(dim, n):
     """A few keys hold most of the batch: the optimizer step's workgroups that lie inside one run
     leave one partial sum each (row groups of 1, 16 and 64 lanes; both chunk sizes)."""
