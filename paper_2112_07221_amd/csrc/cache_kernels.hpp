@@ -473,7 +473,11 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         if (LOOKUP) ds->t = t_now;
         if (LOOKUP && pf_idle >= 0) ds->pf_n[pf_idle] = 0;    // the list of keys to fetch ahead that this lookup's second kernel may fill
     }
-    bool head = false, miss = false, stale = false, hit = false, absent = false, bad = false;
+    // Find runs once per key, not once per position: by the head of every run of equal keys, and by
+    // each wave's first lane (its run may have begun in the wave before); the other positions of a
+    // run take where their row comes from from the nearest such lane below them.
+    bool head = false, miss = false, stale = false, hit = false, absent = false, bad = false, finder = false;
+    int32_t my_src = SRC_ZERO;
     if (j < n) {
         const uint32_t key = ws.skey[j];
         if (key == vocab) {                                   // id outside the vocabulary
@@ -484,39 +488,48 @@ __global__ __launch_bounds__(PT_THREADS) void probe_kernel(CacheView cv, Workspa
         } else {
             head = j == 0 || ws.skey[j - 1] != key;
             if (j + 1 == n || ws.skey[j + 1] == vocab) ds->n_valid = j + 1;    // one writer: the last valid position
-            const uint32_t cg = LOOKUP ? cv.Cg[key] : 0u;        // in flight together with the probe's loads
-            const int32_t slot = ht_find(cv.ht, key);
-            int32_t src = slot == SLOT_NONE ? SRC_BACKING : slot;
-            bool valid = true;
-            uint4 m = make_uint4(0, 0, 0, 0);
-            if (LOOKUP && slot != SLOT_NONE) {
-                m = load_meta(cv.meta, (uint32_t)slot);
-                const uint32_t cs = m.x, cc = m.y;
-                valid = check_valid(cs, cc, cg, cv.s);
-                // A stale row that holds no updates of its own is refetched: its value is the
-                // global row.  (One with updates is pushed first, so its own value stays current.)
-                if (!valid && !(cc > cs)) src = SRC_BACKING;
-            }
-            if (LOOKUP) ws.src[j] = src;
-            if (head) {
-                ws.head_slot[j] = slot;
-                if (LOOKUP) {
-                    if (slot == SLOT_NONE) miss = true;
-                    else {
-                        hit = valid; stale = !valid;
-                        const bool upkeep = !(cv.freq_cap && m.w >= cv.freq_cap);        // (light-weight LFU: frequent enough, left alone)
-                        if (upkeep) store_meta(cv.meta, (uint32_t)slot, m.x, m.y, t_now, m.w + 1);   // one use per key per Read
-                        if (keep_h0 && upkeep) {
-                            const uint32_t b_old = h0_bin(tp, policy_key(tp, m)), b_new = h0_bin(tp, policy_key(tp, make_uint4(0, 0, t_now, m.w + 1)));
-                            if (b_old != b_new) { atomicSub(&h0_delta[b_old], 1u); atomicAdd(&h0_delta[b_new], 1u); }
+            finder = head || (LOOKUP && lane_id() == 0);
+            if (finder) {
+                const uint32_t cg = LOOKUP ? cv.Cg[key] : 0u;        // in flight together with the probe's loads
+                const int32_t slot = ht_find(cv.ht, key);
+                int32_t src = slot == SLOT_NONE ? SRC_BACKING : slot;
+                bool valid = true;
+                uint4 m = make_uint4(0, 0, 0, 0);
+                if (LOOKUP && slot != SLOT_NONE) {
+                    m = load_meta(cv.meta, (uint32_t)slot);
+                    const uint32_t cs = m.x, cc = m.y;
+                    valid = check_valid(cs, cc, cg, cv.s);
+                    // A stale row that holds no updates of its own is refetched: its value is the
+                    // global row.  (One with updates is pushed first, so its own value stays current.)
+                    if (!valid && !(cc > cs)) src = SRC_BACKING;
+                }
+                my_src = src;
+                if (head) {
+                    ws.head_slot[j] = slot;
+                    if (LOOKUP) {
+                        if (slot == SLOT_NONE) miss = true;
+                        else {
+                            hit = valid; stale = !valid;
+                            const bool upkeep = !(cv.freq_cap && m.w >= cv.freq_cap);        // (light-weight LFU: frequent enough, left alone)
+                            if (upkeep) store_meta(cv.meta, (uint32_t)slot, m.x, m.y, t_now, m.w + 1);   // one use per key per Read
+                            if (keep_h0 && upkeep) {
+                                const uint32_t b_old = h0_bin(tp, policy_key(tp, m)), b_new = h0_bin(tp, policy_key(tp, make_uint4(0, 0, t_now, m.w + 1)));
+                                if (b_old != b_new) { atomicSub(&h0_delta[b_old], 1u); atomicAdd(&h0_delta[b_new], 1u); }
+                            }
                         }
+                        ws.cls[j] = (uint8_t)(miss ? CLS_MISS : (stale ? CLS_STALE : CLS_HIT));
+                    } else {
+                        absent = slot == SLOT_NONE;
                     }
-                    ws.cls[j] = (uint8_t)(miss ? CLS_MISS : (stale ? CLS_STALE : CLS_HIT));
-                } else {
-                    absent = slot == SLOT_NONE;
                 }
             }
         }
+    }
+    if (LOOKUP) {
+        const uint64_t below = __ballot(finder) & (~0ull >> (63u - lane_id()));
+        const int from = below ? 63 - __builtin_clzll(below) : 0;
+        const int32_t src = __shfl(my_src, from, WAVE);           // (a valid key has a finder at or below its lane: sorted keys, the invalid ones last)
+        if (j < n && !bad) ws.src[j] = src;
     }
 
     if (__any(bad) && lane_id() == 0) atomicOr(&ds->err, ERRBIT_RANGE);
