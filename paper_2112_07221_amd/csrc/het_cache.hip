@@ -426,8 +426,10 @@ int run_trim(het_cache *c, int first_stage)
     const uint32_t ev_blocks = cdiv(c->cv.n_slots, EV_SLOTS);
     // Rows of a kilobyte or more: the pushes run at the memory's limit, and a fourth workgroup per
     // compute unit only gets in the others' way (config 5: 107 us against 97).  Asking for more LDS
-    // than a quarter of a compute unit's keeps it to three.
-    const uint32_t lds_floor = c->cv.geom.lanes == 64 && VEC == 4 ? 44u * 1024u : 0u;
+    // than a quarter of a compute unit's keeps it to three.  Not where the update pushes the rows it
+    // fetches early: then few victims are left to copy, and the fourth workgroup pays (config 5:
+    // 25.9 -> 23.5 us).
+    const uint32_t lds_floor = c->cv.geom.lanes == 64 && VEC == 4 && !c->cv.early_cc ? 44u * 1024u : 0u;
     const uint32_t lds = std::max(lds_bytes(sizeof(EvictLds), ride), lds_floor);
     if (c->many)
         LAUNCH(c, K_TRIM_EVICT, trim_evict_kernel<VEC, true, true><<<ride.blocks() + ev_blocks + 1, TRIM_THREADS, lds, c->stream>>>(c->cv, tp, ride.a, ride.b));
